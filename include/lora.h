@@ -1,0 +1,212 @@
+/*
+ * liblora_gfx950 -- co-batched heterogeneous-rank LoRA delta for one MI355X (gfx950).
+ *
+ *     v[t, :] = x[t, :] * A_a          (shrink,  A_a is in x r_a)
+ *     y[t, :] += s_a * v[t, :] * B_a   (expand,  B_a is r_a x out)
+ *
+ * for every token t of a batch, where a = token_adapter[t] may differ from token to token and the
+ * ranks r_a of the adapters that share the batch differ too.  This is the operation behind the
+ * paper's problem statement: LoRA adds a pair of low-rank matrices to a frozen layer, the rank
+ * being the adapter's size (Background, "Low-Rank Adaptation"); serving systems run requests of
+ * different adapters and ranks in one batched kernel (Background, "Kernel Optimizations"); and
+ * kernels that size their tiles to the largest rank in the batch make low-rank requests pay for
+ * the high-rank ones (Motivation, "Effect of Co-serving Adapters of Different Ranks").  Here every
+ * unit of work is sized by the bytes of its own adapter, never by the largest rank present.
+ *
+ * Conventions
+ *   - bf16 storage (x, y, adapter weights), fp32 accumulation, one round-to-nearest-even to bf16
+ *     when y is written.  The shrink result v is fp32 and is never rounded to bf16 in memory.
+ *   - "device" pointers are HIP device memory of the current device; "host" pointers are ordinary
+ *     host memory.  The caller owns every device buffer it passes in (arena, x, y, v, workspace).
+ *     The library owns its opaque host objects and one small device table per segment object.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernel launches and
+ *     copies are asynchronous on it unless a function says otherwise.
+ *   - Every function validates its arguments on the host before touching the device and returns a
+ *     status; nothing throws, aborts or exits.  lora_last_error() gives a thread-local detail line
+ *     for the last non-OK status returned on this thread.
+ *   - in_features and out_features must be multiples of 64; ranks are 1..LORA_MAX_RANK.
+ */
+#ifndef LORA_GFX950_H
+#define LORA_GFX950_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LORA_MAX_RANK 256
+#define LORA_BF16 1
+
+typedef enum {
+    LORA_OK = 0,
+    LORA_ERR_INVALID_ARG = 1,    /* NULL pointer, negative count, id out of range, bad flag        */
+    LORA_ERR_SHAPE = 2,          /* feature size or rank outside what the kernels support         */
+    LORA_ERR_OOM = 3,            /* arena / host / device allocation too small or failed          */
+    LORA_ERR_NOT_RESIDENT = 4,   /* a token is routed to an adapter that is not loaded            */
+    LORA_ERR_STALE_SEGMENTS = 5, /* segment object built for another pool or an older generation  */
+    LORA_ERR_WORKSPACE = 6,      /* workspace missing, misaligned or smaller than required        */
+    LORA_ERR_DEVICE = 7          /* a HIP call failed (no device, launch error, copy error)       */
+} lora_status_t;
+
+typedef struct lora_pool lora_pool_t;         /* opaque: ragged adapter pool of one projection */
+typedef struct lora_segments lora_segments_t; /* opaque: one batch's token grouping + work units */
+
+/* Adapters of one projection (one weight matrix of one layer).  `ranks` and `scales` are host
+ * arrays of n_adapters entries, copied by lora_pool_create. */
+typedef struct {
+    int32_t in_features;
+    int32_t out_features;
+    int32_t n_adapters;
+    const int32_t *ranks;
+    const float *scales;
+    int32_t dtype; /* LORA_BF16 */
+} lora_pool_desc_t;
+
+/* Where one adapter lives inside the arena (element = one bf16).  The packed form is
+ *   A^T : [rank_padded][in_features]   at a_offset   (rows rank..rank_padded-1 are zero)
+ *   B^T : [out_features][rank_padded]  at b_offset   (columns rank..rank_padded-1 are zero)
+ * with rank_padded = rank rounded up to a multiple of 8 (no padding for ranks 8,16,...,256).
+ * Both matrices are stored with the contracted index contiguous, so a rank-r adapter costs
+ * 2*r_padded*(in+out) bytes whatever the other adapters' ranks are. */
+typedef struct {
+    uint64_t a_offset;
+    uint64_t b_offset;
+    int32_t rank;
+    int32_t rank_padded;
+    float scale;
+    int32_t resident;
+} lora_adapter_info_t;
+
+/* Sizes of a built segment object. */
+typedef struct {
+    int32_t n_tokens;        /* T as passed in                                          */
+    int32_t n_active;        /* tokens with an adapter (token_adapter >= 0)             */
+    int32_t n_segments;      /* distinct adapters used by the batch                     */
+    int32_t n_shrink_units;  /* work groups of the shrink launch                        */
+    int32_t n_expand_units;  /* work groups of the expand launch                        */
+    int32_t n_k_slices;      /* split-K partial sums per v element (1 = none)           */
+    int64_t v_floats;        /* length of v in floats: sum over active tokens of rank_padded */
+    int64_t weight_bytes;    /* packed bytes of the distinct adapters the batch touches */
+} lora_segments_info_t;
+
+/* ---- pool: the ragged, rank-packed adapter arena (set-up time, not on the per-step path) ---- */
+
+/* Bytes of device memory the arena needs for this description.  Host only. */
+lora_status_t lora_pool_bytes(const lora_pool_desc_t *desc, size_t *arena_bytes);
+
+/* Lay the adapters of `desc` out in `dev_arena` (device memory, 256-byte aligned, at least
+ * lora_pool_bytes() long, owned by the caller and alive as long as the pool).  Host only: it
+ * records offsets; no adapter is resident until lora_pool_load.  LORA_ERR_SHAPE for unsupported
+ * feature sizes or ranks, LORA_ERR_OOM if arena_bytes is too small. */
+lora_status_t lora_pool_create(const lora_pool_desc_t *desc, void *dev_arena, size_t arena_bytes,
+                               lora_pool_t **out);
+
+/* Copy adapter `adapter` into the pool and mark it resident.  A is [in][rank] and B is [rank][out],
+ * row-major bf16, in host memory (src_is_device = 0) or device memory (1).  The packed, transposed
+ * form is written by a device kernel on `stream`.  With a host source the call allocates a device
+ * staging buffer and returns after the copy has completed; with a device source it is asynchronous
+ * and the source must stay valid until the stream reaches it.  Bumps the pool's generation. */
+lora_status_t lora_pool_load(lora_pool_t *pool, int32_t adapter, const void *A_in_by_r,
+                             const void *B_r_by_out, int src_is_device, void *stream);
+
+/* Mark an adapter non-resident (its bytes stay where they are).  Bumps the generation. */
+lora_status_t lora_pool_evict(lora_pool_t *pool, int32_t adapter);
+
+/* Declare an adapter resident without copying: for callers that wrote its packed form into the
+ * arena themselves (a device-to-device copy of another pool's arena, a restored snapshot).  Host
+ * only.  Bumps the generation. */
+lora_status_t lora_pool_mark_resident(lora_pool_t *pool, int32_t adapter);
+
+/* Host only: layout and residency of one adapter. */
+lora_status_t lora_pool_adapter_info(const lora_pool_t *pool, int32_t adapter, lora_adapter_info_t *info);
+
+lora_status_t lora_pool_destroy(lora_pool_t *pool);
+
+/* ---- segments: per-batch grouping of tokens by adapter and the byte-balanced work-unit lists ---- */
+
+/* Host-only half of lora_segments_build: group the T tokens by adapter (stable: tokens of one
+ * adapter keep their order), and cut every group into work units whose cost follows that adapter's
+ * own bytes.  token_adapter_host[t] in [0, n_adapters) or -1 for "no adapter" (row left untouched).
+ * LORA_ERR_INVALID_ARG for ids out of range, LORA_ERR_NOT_RESIDENT for an id that is not loaded.
+ * T = 0 and batches without any active token are valid.  The result cannot be launched until
+ * lora_segments_upload has run. */
+lora_status_t lora_segments_plan(const lora_pool_t *pool, const int32_t *token_adapter_host, int32_t T,
+                                 lora_segments_t **out);
+
+/* Same, from contiguous ranges: tokens seg_start_host[i] .. seg_start_host[i+1]-1 use adapter
+ * seg_adapter_host[i] (or none if it is -1); seg_start_host has S+1 non-decreasing entries starting
+ * at 0 and T = seg_start_host[S].  Ranges that name the same adapter are merged into one group. */
+lora_status_t lora_segments_plan_ranges(const lora_pool_t *pool, const int32_t *seg_start_host,
+                                        const int32_t *seg_adapter_host, int32_t S, lora_segments_t **out);
+
+/* Allocate the segment object's device table (library-owned, freed by lora_segments_destroy) and
+ * enqueue one host-to-device copy of it on `stream`. */
+lora_status_t lora_segments_upload(lora_segments_t *seg, void *stream);
+
+/* plan + upload. */
+lora_status_t lora_segments_build(const lora_pool_t *pool, const int32_t *token_adapter_host, int32_t T,
+                                  void *stream, lora_segments_t **out);
+lora_status_t lora_segments_build_ranges(const lora_pool_t *pool, const int32_t *seg_start_host,
+                                         const int32_t *seg_adapter_host, int32_t S, void *stream,
+                                         lora_segments_t **out);
+
+/* Re-plan an existing object for a new batch of the same pool and upload it, re-using its host and
+ * device storage when it is large enough (the per-step call of a decode loop).  The previous
+ * table must no longer be in use by work enqueued on another stream. */
+lora_status_t lora_segments_rebuild(lora_segments_t *seg, const int32_t *token_adapter_host, int32_t T,
+                                    void *stream);
+
+lora_status_t lora_segments_info(const lora_segments_t *seg, lora_segments_info_t *info);
+
+/* Host copies of the grouping, for callers that want to read v and for tests.  Any output may be
+ * NULL.  perm[n_active]: token index at each sorted position; seg_start[n_segments+1]: sorted
+ * positions where each group starts; seg_adapter[n_segments]; v_offset[T]: float offset of token
+ * t's row inside v (rank_padded floats long), -1 for tokens without adapter. */
+lora_status_t lora_segments_export(const lora_segments_t *seg, int32_t *perm, int32_t *seg_start,
+                                   int32_t *seg_adapter, int64_t *v_offset);
+
+/* Host copies of the work-unit lists, 6 int32 per unit: {segment, first token (relative to the
+ * group), token count, first row (shrink) or first column (expand), row or column count,
+ * k-slice (shrink) or 0}.  Either output may be NULL. */
+lora_status_t lora_segments_export_units(const lora_segments_t *seg, int32_t *shrink_units,
+                                         int32_t *expand_units);
+
+lora_status_t lora_segments_destroy(lora_segments_t *seg);
+
+/* ---- the hot path ---- */
+
+/* Bytes of device workspace lora_shrink / lora_apply need for this batch (split-K partial sums of
+ * v; 0 is possible).  The workspace must be 256-byte aligned. */
+lora_status_t lora_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *seg, size_t *bytes);
+
+/* Shrink: v[t, j] = sum_k x[t, k] * A_a(t)[k, j] for every active token.
+ * x: device, bf16, [T][in] with row stride ldx elements (ldx >= in, ldx % 8 == 0, 16-byte aligned).
+ * v: device, fp32, info.v_floats long, 16-byte aligned; token t's row starts at v_offset[t] and is
+ *    rank_padded long (entries beyond the rank are written as 0).
+ * LORA_ERR_STALE_SEGMENTS if the pool changed since `seg` was built, LORA_ERR_WORKSPACE if the
+ * workspace is too small. */
+lora_status_t lora_shrink(const lora_pool_t *pool, const lora_segments_t *seg, const void *x, int64_t ldx,
+                          float *v, void *workspace, size_t ws_bytes, void *stream);
+
+/* Expand: y[t, o] = bf16(y[t, o] + s_a(t) * sum_j v[t, j] * B_a(t)[j, o]) for every active token,
+ * in place.  y: device, bf16, [T][out] with row stride ldy (ldy >= out, ldy % 8 == 0, 16-byte
+ * aligned).  Rows of tokens without adapter are neither read nor written. */
+lora_status_t lora_expand(const lora_pool_t *pool, const lora_segments_t *seg, const float *v, void *y,
+                          int64_t ldy, void *stream);
+
+/* Shrink then expand on one stream.  v never leaves the workspace, whose size
+ * lora_apply_workspace_bytes gives (the k-slices' partial sums of v; the expand adds them up, in
+ * slice order, while it loads them). */
+lora_status_t lora_apply_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *seg, size_t *bytes);
+lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *seg, const void *x, int64_t ldx,
+                         void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream);
+
+const char *lora_status_string(lora_status_t status);
+const char *lora_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORA_GFX950_H */

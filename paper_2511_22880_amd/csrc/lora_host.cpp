@@ -1,0 +1,717 @@
+// Host side of liblora_gfx950: the ragged adapter pool, the per-batch planner (grouping of tokens
+// by adapter, byte-balanced work units) and the C boundary declared in include/lora.h.
+#include "../../include/lora.h"
+#include "lora_internal.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using lora::SegRec;
+using lora::Unit;
+
+// ------------------------------------------------------------------------------------------------
+// errors
+// ------------------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+static lora_status_t fail(lora_status_t st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+static lora_status_t hip_fail(hipError_t e, const char *what)
+{
+    return fail(LORA_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(call)                                         \
+    do {                                                      \
+        hipError_t e_ = (call);                               \
+        if (e_ != hipSuccess) return hip_fail(e_, #call);     \
+    } while (0)
+
+static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+static inline size_t round_up_sz(size_t v, size_t m) { return (v + m - 1) / m * m; }
+
+// ------------------------------------------------------------------------------------------------
+// objects
+// ------------------------------------------------------------------------------------------------
+struct lora_pool {
+    uint32_t magic;
+    int in_features, out_features, n_adapters;
+    std::vector<int32_t> rank, r8;
+    std::vector<float> scale;
+    std::vector<uint64_t> a_off, b_off;  // element offsets
+    std::vector<uint8_t> resident;
+    uint16_t *arena;
+    size_t arena_bytes;
+    uint64_t generation;
+    uint64_t id;
+};
+
+struct lora_segments {
+    uint32_t magic;
+    const lora_pool *pool;
+    uint64_t pool_id, pool_generation;
+    int32_t T, n_active;
+    int n_k_slices, k_slice_len;
+    int64_t v_floats, weight_bytes;
+    std::vector<int32_t> perm, seg_start, seg_adapter;
+    std::vector<int64_t> v_offset;
+    std::vector<SegRec> segs;
+    std::vector<Unit> shrink_units, expand_units;
+    // device table: [perm | segs | shrink units | expand units], one allocation
+    char *dev;
+    size_t dev_capacity;
+    char *staging;  // pinned host copy of the table
+    size_t staging_capacity;
+    size_t off_perm, off_segs, off_shrink, off_expand, table_bytes;
+    hipEvent_t copied;  // recorded after the upload; guards re-use of `staging`
+    bool uploaded;
+};
+
+static const uint32_t kPoolMagic = 0x4C505231u, kSegMagic = 0x4C534731u;
+static uint64_t g_next_pool_id = 1;
+
+static bool pool_ok(const lora_pool *p) { return p && p->magic == kPoolMagic; }
+static bool seg_ok(const lora_segments *s) { return s && s->magic == kSegMagic; }
+
+// ------------------------------------------------------------------------------------------------
+// pool
+// ------------------------------------------------------------------------------------------------
+static lora_status_t check_desc(const lora_pool_desc_t *d)
+{
+    if (!d) return fail(LORA_ERR_INVALID_ARG, "desc is NULL");
+    if (d->n_adapters < 0) return fail(LORA_ERR_INVALID_ARG, "n_adapters = %d", d->n_adapters);
+    if (d->n_adapters > 0 && (!d->ranks || !d->scales)) return fail(LORA_ERR_INVALID_ARG, "ranks/scales is NULL");
+    if (d->dtype != LORA_BF16) return fail(LORA_ERR_INVALID_ARG, "dtype %d is not LORA_BF16", d->dtype);
+    if (d->in_features <= 0 || d->out_features <= 0 || d->in_features % 64 || d->out_features % 64)
+        return fail(LORA_ERR_SHAPE, "in_features (%d) and out_features (%d) must be positive multiples of 64",
+                    d->in_features, d->out_features);
+    for (int a = 0; a < d->n_adapters; ++a)
+        if (d->ranks[a] < 1 || d->ranks[a] > LORA_MAX_RANK)
+            return fail(LORA_ERR_SHAPE, "adapter %d: rank %d outside 1..%d", a, d->ranks[a], LORA_MAX_RANK);
+    return LORA_OK;
+}
+
+static size_t adapter_elems(const lora_pool_desc_t *d, int a)
+{
+    const size_t r8 = (size_t)round_up(d->ranks[a], 8);
+    return r8 * ((size_t)d->in_features + (size_t)d->out_features);
+}
+
+extern "C" lora_status_t lora_pool_bytes(const lora_pool_desc_t *desc, size_t *arena_bytes)
+{
+    lora_status_t st = check_desc(desc);
+    if (st != LORA_OK) return st;
+    if (!arena_bytes) return fail(LORA_ERR_INVALID_ARG, "arena_bytes is NULL");
+    size_t elems = 0;
+    for (int a = 0; a < desc->n_adapters; ++a) elems += adapter_elems(desc, a);
+    *arena_bytes = round_up_sz(elems * 2, 256);
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_pool_create(const lora_pool_desc_t *desc, void *dev_arena, size_t arena_bytes,
+                                          lora_pool_t **out)
+{
+    if (!out) return fail(LORA_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    size_t need = 0;
+    lora_status_t st = lora_pool_bytes(desc, &need);
+    if (st != LORA_OK) return st;
+    if (need > 0 && !dev_arena) return fail(LORA_ERR_INVALID_ARG, "dev_arena is NULL");
+    if (((uintptr_t)dev_arena) % 256) return fail(LORA_ERR_INVALID_ARG, "dev_arena is not 256-byte aligned");
+    if (arena_bytes < need)
+        return fail(LORA_ERR_OOM, "arena of %zu bytes is smaller than the %zu bytes the pool needs", arena_bytes, need);
+    lora_pool *p = new (std::nothrow) lora_pool();
+    if (!p) return fail(LORA_ERR_OOM, "host allocation failed");
+    p->magic = kPoolMagic;
+    p->in_features = desc->in_features;
+    p->out_features = desc->out_features;
+    p->n_adapters = desc->n_adapters;
+    p->arena = (uint16_t *)dev_arena;
+    p->arena_bytes = arena_bytes;
+    p->generation = 1;
+    p->id = g_next_pool_id++;
+    uint64_t off = 0;
+    for (int a = 0; a < desc->n_adapters; ++a) {
+        const int r8 = round_up(desc->ranks[a], 8);
+        p->rank.push_back(desc->ranks[a]);
+        p->r8.push_back(r8);
+        p->scale.push_back(desc->scales[a]);
+        p->a_off.push_back(off);
+        p->b_off.push_back(off + (uint64_t)r8 * desc->in_features);
+        p->resident.push_back(0);
+        off += (uint64_t)adapter_elems(desc, a);
+    }
+    *out = p;
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_pool_adapter_info(const lora_pool_t *pool, int32_t adapter, lora_adapter_info_t *info)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (!info) return fail(LORA_ERR_INVALID_ARG, "info is NULL");
+    if (adapter < 0 || adapter >= pool->n_adapters)
+        return fail(LORA_ERR_INVALID_ARG, "adapter %d outside 0..%d", adapter, pool->n_adapters - 1);
+    info->a_offset = pool->a_off[adapter];
+    info->b_offset = pool->b_off[adapter];
+    info->rank = pool->rank[adapter];
+    info->rank_padded = pool->r8[adapter];
+    info->scale = pool->scale[adapter];
+    info->resident = pool->resident[adapter];
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_pool_load(lora_pool_t *pool, int32_t adapter, const void *A, const void *B,
+                                        int src_is_device, void *stream)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (adapter < 0 || adapter >= pool->n_adapters)
+        return fail(LORA_ERR_INVALID_ARG, "adapter %d outside 0..%d", adapter, pool->n_adapters - 1);
+    if (!A || !B) return fail(LORA_ERR_INVALID_ARG, "A or B is NULL");
+    if (src_is_device != 0 && src_is_device != 1) return fail(LORA_ERR_INVALID_ARG, "src_is_device = %d", src_is_device);
+    hipStream_t s = (hipStream_t)stream;
+    const int r = pool->rank[adapter], r8 = pool->r8[adapter];
+    const int in = pool->in_features, out = pool->out_features;
+    uint16_t *dstA = pool->arena + pool->a_off[adapter];
+    uint16_t *dstB = pool->arena + pool->b_off[adapter];
+    const size_t nA = (size_t)in * r, nB = (size_t)r * out;
+    if (src_is_device) {
+        HIP_TRY(lora::launch_pack_transpose((const uint16_t *)A, in, r, dstA, r8, in, s));
+        HIP_TRY(lora::launch_pack_transpose((const uint16_t *)B, r, out, dstB, out, r8, s));
+    } else {
+        uint16_t *tmp = nullptr;
+        hipError_t e = hipMalloc((void **)&tmp, (nA + nB) * 2);
+        if (e != hipSuccess) return hip_fail(e, "hipMalloc(staging for lora_pool_load)");
+        lora_status_t st = LORA_OK;
+        do {
+            if ((e = hipMemcpyAsync(tmp, A, nA * 2, hipMemcpyHostToDevice, s)) != hipSuccess) break;
+            if ((e = hipMemcpyAsync(tmp + nA, B, nB * 2, hipMemcpyHostToDevice, s)) != hipSuccess) break;
+            if ((e = lora::launch_pack_transpose(tmp, in, r, dstA, r8, in, s)) != hipSuccess) break;
+            if ((e = lora::launch_pack_transpose(tmp + nA, r, out, dstB, out, r8, s)) != hipSuccess) break;
+            e = hipStreamSynchronize(s);
+        } while (0);
+        if (e != hipSuccess) st = hip_fail(e, "lora_pool_load copy/pack");
+        hipError_t e2 = hipFree(tmp);
+        if (st == LORA_OK && e2 != hipSuccess) st = hip_fail(e2, "hipFree(staging)");
+        if (st != LORA_OK) return st;
+    }
+    pool->resident[adapter] = 1;
+    pool->generation++;
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_pool_evict(lora_pool_t *pool, int32_t adapter)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (adapter < 0 || adapter >= pool->n_adapters)
+        return fail(LORA_ERR_INVALID_ARG, "adapter %d outside 0..%d", adapter, pool->n_adapters - 1);
+    pool->resident[adapter] = 0;
+    pool->generation++;
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_pool_mark_resident(lora_pool_t *pool, int32_t adapter)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (adapter < 0 || adapter >= pool->n_adapters)
+        return fail(LORA_ERR_INVALID_ARG, "adapter %d outside 0..%d", adapter, pool->n_adapters - 1);
+    pool->resident[adapter] = 1;
+    pool->generation++;
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_pool_destroy(lora_pool_t *pool)
+{
+    if (!pool) return LORA_OK;
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "not a pool");
+    pool->magic = 0;
+    delete pool;
+    return LORA_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// planner
+// ------------------------------------------------------------------------------------------------
+// Split-K of the shrink: up to 4 k-slices, each at least 1024 long, each a multiple of 128 so that a
+// wavefront's quarter of a slice is a whole number of 32-wide MFMA k steps.
+static void choose_k_slices(int in, int *n_slices, int *slice_len)
+{
+    int n = in / 1024;
+    n = std::max(1, std::min(4, n));
+    int len = round_up((in + n - 1) / n, 128);
+    n = (in + len - 1) / len;
+    *n_slices = n;
+    *slice_len = len;
+}
+
+// Output columns per expand unit: about 32 KiB of B^T, a multiple of 64 (four 16-column tiles, one
+// per wavefront), at least 64.
+static int expand_cols_per_unit(int r8, int out)
+{
+    int cols = (32 * 1024) / (2 * r8);
+    cols = std::max(64, cols / 64 * 64);
+    return std::min(cols, out);
+}
+
+static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const int32_t *ta, int32_t T)
+{
+    const int N = pool->n_adapters;
+    std::vector<int32_t> count(N, 0);
+    int32_t n_active = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        const int32_t a = ta[t];
+        if (a == -1) continue;
+        if (a < 0 || a >= N) return fail(LORA_ERR_INVALID_ARG, "token %d: adapter id %d outside -1..%d", t, a, N - 1);
+        if (!pool->resident[a]) return fail(LORA_ERR_NOT_RESIDENT, "token %d: adapter %d is not loaded", t, a);
+        ++count[a];
+        ++n_active;
+    }
+    sg->pool = pool;
+    sg->pool_id = pool->id;
+    sg->pool_generation = pool->generation;
+    sg->T = T;
+    sg->n_active = n_active;
+    sg->uploaded = false;
+    choose_k_slices(pool->in_features, &sg->n_k_slices, &sg->k_slice_len);
+
+    sg->seg_start.clear();
+    sg->seg_adapter.clear();
+    sg->segs.clear();
+    std::vector<int32_t> seg_of(N, -1), cursor(N, 0);
+    int32_t pos = 0;
+    int64_t voff = 0, wbytes = 0;
+    for (int a = 0; a < N; ++a) {
+        if (!count[a]) continue;
+        SegRec r;
+        memset(&r, 0, sizeof r);
+        r.a_off = pool->a_off[a];
+        r.b_off = pool->b_off[a];
+        r.v_off = voff;
+        r.rank = pool->rank[a];
+        r.r8 = pool->r8[a];
+        r.scale = pool->scale[a];
+        r.tok_start = pos;
+        r.ntok = count[a];
+        seg_of[a] = (int32_t)sg->segs.size();
+        cursor[a] = pos;
+        sg->segs.push_back(r);
+        sg->seg_start.push_back(pos);
+        sg->seg_adapter.push_back(a);
+        pos += count[a];
+        voff += (int64_t)count[a] * r.r8;
+        wbytes += 2LL * r.r8 * ((int64_t)pool->in_features + pool->out_features);
+    }
+    sg->seg_start.push_back(pos);
+    sg->v_floats = voff;
+    sg->weight_bytes = wbytes;
+
+    sg->perm.assign(n_active, 0);
+    sg->v_offset.assign(T, -1);
+    for (int32_t t = 0; t < T; ++t) {
+        const int32_t a = ta[t];
+        if (a < 0) continue;
+        const SegRec &r = sg->segs[seg_of[a]];
+        const int32_t p = cursor[a]++;
+        sg->perm[p] = t;
+        sg->v_offset[t] = r.v_off + (int64_t)(p - r.tok_start) * r.r8;
+    }
+
+    // work units, heaviest adapters first so the launch's tail is made of small units
+    std::vector<int32_t> order(sg->segs.size());
+    for (size_t i = 0; i < order.size(); ++i) order[i] = (int32_t)i;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t x, int32_t y) { return sg->segs[x].r8 > sg->segs[y].r8; });
+    sg->shrink_units.clear();
+    sg->expand_units.clear();
+    const int out = pool->out_features;
+    for (int32_t si : order) {
+        const SegRec &r = sg->segs[si];
+        for (int row0 = 0; row0 < r.r8; row0 += lora::kRowTile)
+            for (int ks = 0; ks < sg->n_k_slices; ++ks)
+                for (int tok0 = 0; tok0 < r.ntok; tok0 += lora::kTokTile) {
+                    Unit u;
+                    memset(&u, 0, sizeof u);
+                    u.seg = si;
+                    u.tok0 = tok0;
+                    u.ntok = std::min(lora::kTokTile, r.ntok - tok0);
+                    u.p0 = row0;
+                    u.pn = std::min(lora::kRowTile, r.r8 - row0);
+                    u.ks = ks;
+                    sg->shrink_units.push_back(u);
+                }
+        const int cols = expand_cols_per_unit(r.r8, out);
+        for (int c0 = 0; c0 < out; c0 += cols)
+            for (int tok0 = 0; tok0 < r.ntok; tok0 += lora::kTokTile) {
+                Unit u;
+                memset(&u, 0, sizeof u);
+                u.seg = si;
+                u.tok0 = tok0;
+                u.ntok = std::min(lora::kTokTile, r.ntok - tok0);
+                u.p0 = c0;
+                u.pn = std::min(cols, out - c0);
+                sg->expand_units.push_back(u);
+            }
+    }
+
+    sg->off_perm = 0;
+    sg->off_segs = round_up_sz(sg->off_perm + sg->perm.size() * sizeof(int32_t), 256);
+    sg->off_shrink = round_up_sz(sg->off_segs + sg->segs.size() * sizeof(SegRec), 256);
+    sg->off_expand = round_up_sz(sg->off_shrink + sg->shrink_units.size() * sizeof(Unit), 256);
+    sg->table_bytes = round_up_sz(sg->off_expand + sg->expand_units.size() * sizeof(Unit), 256);
+    return LORA_OK;
+}
+
+static lora_segments *new_segments()
+{
+    lora_segments *sg = new (std::nothrow) lora_segments();
+    if (!sg) return nullptr;
+    sg->magic = kSegMagic;
+    sg->dev = nullptr;
+    sg->dev_capacity = 0;
+    sg->staging = nullptr;
+    sg->staging_capacity = 0;
+    sg->copied = nullptr;
+    sg->uploaded = false;
+    return sg;
+}
+
+extern "C" lora_status_t lora_segments_destroy(lora_segments_t *seg)
+{
+    if (!seg) return LORA_OK;
+    if (!seg_ok(seg)) return fail(LORA_ERR_INVALID_ARG, "not a segment object");
+    lora_status_t st = LORA_OK;
+    if (seg->copied) {
+        (void)hipEventSynchronize(seg->copied);
+        (void)hipEventDestroy(seg->copied);
+    }
+    if (seg->dev) {
+        hipError_t e = hipFree(seg->dev);
+        if (e != hipSuccess) st = hip_fail(e, "hipFree(segment table)");
+    }
+    if (seg->staging) {
+        hipError_t e = hipHostFree(seg->staging);
+        if (e != hipSuccess) st = hip_fail(e, "hipHostFree(segment staging)");
+    }
+    seg->magic = 0;
+    delete seg;
+    return st;
+}
+
+extern "C" lora_status_t lora_segments_plan(const lora_pool_t *pool, const int32_t *ta, int32_t T,
+                                            lora_segments_t **out)
+{
+    if (!out) return fail(LORA_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (T < 0) return fail(LORA_ERR_INVALID_ARG, "T = %d", T);
+    if (T > 0 && !ta) return fail(LORA_ERR_INVALID_ARG, "token_adapter_host is NULL");
+    lora_segments *sg = new_segments();
+    if (!sg) return fail(LORA_ERR_OOM, "host allocation failed");
+    lora_status_t st = plan_into(sg, pool, ta, T);
+    if (st != LORA_OK) {
+        lora_segments_destroy(sg);
+        return st;
+    }
+    *out = sg;
+    return LORA_OK;
+}
+
+static lora_status_t ranges_to_tokens(const lora_pool_t *pool, const int32_t *start, const int32_t *adapter,
+                                      int32_t S, std::vector<int32_t> *ta)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (S < 0) return fail(LORA_ERR_INVALID_ARG, "S = %d", S);
+    if (!start || (S > 0 && !adapter)) return fail(LORA_ERR_INVALID_ARG, "seg_start_host or seg_adapter_host is NULL");
+    if (start[0] != 0) return fail(LORA_ERR_INVALID_ARG, "seg_start_host[0] = %d, must be 0", start[0]);
+    for (int32_t i = 0; i < S; ++i)
+        if (start[i + 1] < start[i]) return fail(LORA_ERR_INVALID_ARG, "seg_start_host decreases at %d", i + 1);
+    ta->assign((size_t)start[S], -1);
+    for (int32_t i = 0; i < S; ++i)
+        for (int32_t t = start[i]; t < start[i + 1]; ++t) (*ta)[t] = adapter[i];
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_segments_plan_ranges(const lora_pool_t *pool, const int32_t *start,
+                                                   const int32_t *adapter, int32_t S, lora_segments_t **out)
+{
+    if (!out) return fail(LORA_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    std::vector<int32_t> ta;
+    lora_status_t st = ranges_to_tokens(pool, start, adapter, S, &ta);
+    if (st != LORA_OK) return st;
+    return lora_segments_plan(pool, ta.data(), (int32_t)ta.size(), out);
+}
+
+extern "C" lora_status_t lora_segments_upload(lora_segments_t *sg, void *stream)
+{
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    hipStream_t s = (hipStream_t)stream;
+    if (!sg->copied) HIP_TRY(hipEventCreateWithFlags(&sg->copied, hipEventDisableTiming));
+    // the previous upload may still be reading the staging buffer
+    HIP_TRY(hipEventSynchronize(sg->copied));
+    if (sg->table_bytes > sg->staging_capacity) {
+        if (sg->staging) HIP_TRY(hipHostFree(sg->staging));
+        sg->staging = nullptr;
+        sg->staging_capacity = 0;
+        const size_t cap = round_up_sz(sg->table_bytes * 2, 4096);
+        HIP_TRY(hipHostMalloc((void **)&sg->staging, cap, hipHostMallocDefault));
+        sg->staging_capacity = cap;
+    }
+    if (sg->table_bytes > sg->dev_capacity) {
+        if (sg->dev) HIP_TRY(hipFree(sg->dev));
+        sg->dev = nullptr;
+        sg->dev_capacity = 0;
+        const size_t cap = round_up_sz(sg->table_bytes * 2, 4096);
+        HIP_TRY(hipMalloc((void **)&sg->dev, cap));
+        sg->dev_capacity = cap;
+    }
+    if (!sg->perm.empty()) memcpy(sg->staging + sg->off_perm, sg->perm.data(), sg->perm.size() * sizeof(int32_t));
+    if (!sg->segs.empty()) memcpy(sg->staging + sg->off_segs, sg->segs.data(), sg->segs.size() * sizeof(SegRec));
+    if (!sg->shrink_units.empty())
+        memcpy(sg->staging + sg->off_shrink, sg->shrink_units.data(), sg->shrink_units.size() * sizeof(Unit));
+    if (!sg->expand_units.empty())
+        memcpy(sg->staging + sg->off_expand, sg->expand_units.data(), sg->expand_units.size() * sizeof(Unit));
+    if (sg->table_bytes) HIP_TRY(hipMemcpyAsync(sg->dev, sg->staging, sg->table_bytes, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipEventRecord(sg->copied, s));
+    sg->uploaded = true;
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_segments_build(const lora_pool_t *pool, const int32_t *ta, int32_t T, void *stream,
+                                             lora_segments_t **out)
+{
+    lora_status_t st = lora_segments_plan(pool, ta, T, out);
+    if (st != LORA_OK) return st;
+    st = lora_segments_upload(*out, stream);
+    if (st != LORA_OK) {
+        lora_segments_destroy(*out);
+        *out = nullptr;
+    }
+    return st;
+}
+
+extern "C" lora_status_t lora_segments_build_ranges(const lora_pool_t *pool, const int32_t *start,
+                                                    const int32_t *adapter, int32_t S, void *stream,
+                                                    lora_segments_t **out)
+{
+    lora_status_t st = lora_segments_plan_ranges(pool, start, adapter, S, out);
+    if (st != LORA_OK) return st;
+    st = lora_segments_upload(*out, stream);
+    if (st != LORA_OK) {
+        lora_segments_destroy(*out);
+        *out = nullptr;
+    }
+    return st;
+}
+
+extern "C" lora_status_t lora_segments_rebuild(lora_segments_t *sg, const int32_t *ta, int32_t T, void *stream)
+{
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (!pool_ok(sg->pool) || sg->pool->id != sg->pool_id)
+        return fail(LORA_ERR_STALE_SEGMENTS, "the pool this segment object was built for no longer exists");
+    if (T < 0) return fail(LORA_ERR_INVALID_ARG, "T = %d", T);
+    if (T > 0 && !ta) return fail(LORA_ERR_INVALID_ARG, "token_adapter_host is NULL");
+    lora_status_t st = plan_into(sg, sg->pool, ta, T);
+    if (st != LORA_OK) {
+        sg->uploaded = false;
+        return st;
+    }
+    return lora_segments_upload(sg, stream);
+}
+
+extern "C" lora_status_t lora_segments_info(const lora_segments_t *sg, lora_segments_info_t *info)
+{
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (!info) return fail(LORA_ERR_INVALID_ARG, "info is NULL");
+    info->n_tokens = sg->T;
+    info->n_active = sg->n_active;
+    info->n_segments = (int32_t)sg->segs.size();
+    info->n_shrink_units = (int32_t)sg->shrink_units.size();
+    info->n_expand_units = (int32_t)sg->expand_units.size();
+    info->n_k_slices = sg->n_k_slices;
+    info->v_floats = sg->v_floats;
+    info->weight_bytes = sg->weight_bytes;
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_segments_export(const lora_segments_t *sg, int32_t *perm, int32_t *seg_start,
+                                              int32_t *seg_adapter, int64_t *v_offset)
+{
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (perm && !sg->perm.empty()) memcpy(perm, sg->perm.data(), sg->perm.size() * sizeof(int32_t));
+    if (seg_start) memcpy(seg_start, sg->seg_start.data(), sg->seg_start.size() * sizeof(int32_t));
+    if (seg_adapter && !sg->seg_adapter.empty())
+        memcpy(seg_adapter, sg->seg_adapter.data(), sg->seg_adapter.size() * sizeof(int32_t));
+    if (v_offset && !sg->v_offset.empty()) memcpy(v_offset, sg->v_offset.data(), sg->v_offset.size() * sizeof(int64_t));
+    return LORA_OK;
+}
+
+static void export_units(const std::vector<Unit> &units, int32_t *dst)
+{
+    for (size_t i = 0; i < units.size(); ++i) {
+        const Unit &u = units[i];
+        int32_t *d = dst + 6 * i;
+        d[0] = u.seg; d[1] = u.tok0; d[2] = u.ntok; d[3] = u.p0; d[4] = u.pn; d[5] = u.ks;
+    }
+}
+
+extern "C" lora_status_t lora_segments_export_units(const lora_segments_t *sg, int32_t *shrink_units,
+                                                    int32_t *expand_units)
+{
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (shrink_units) export_units(sg->shrink_units, shrink_units);
+    if (expand_units) export_units(sg->expand_units, expand_units);
+    return LORA_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// hot path
+// ------------------------------------------------------------------------------------------------
+static lora_status_t check_launchable(const lora_pool *pool, const lora_segments *sg)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (sg->pool != pool || sg->pool_id != pool->id)
+        return fail(LORA_ERR_STALE_SEGMENTS, "segment object was built for a different pool");
+    if (sg->pool_generation != pool->generation)
+        return fail(LORA_ERR_STALE_SEGMENTS, "pool changed (generation %llu -> %llu) after the segment object was built",
+                    (unsigned long long)sg->pool_generation, (unsigned long long)pool->generation);
+    if (!sg->uploaded) return fail(LORA_ERR_INVALID_ARG, "segment object was planned but not uploaded");
+    return LORA_OK;
+}
+
+static lora_status_t check_matrix(const void *p, int64_t ld, int cols, const char *name)
+{
+    if (!p) return fail(LORA_ERR_INVALID_ARG, "%s is NULL", name);
+    if (((uintptr_t)p) % 16) return fail(LORA_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
+    if (ld < cols || ld % 8) return fail(LORA_ERR_INVALID_ARG, "row stride of %s (%lld) must be >= %d and a multiple of 8",
+                                         name, (long long)ld, cols);
+    return LORA_OK;
+}
+
+static size_t partial_bytes(const lora_segments *sg)
+{
+    if (sg->n_k_slices <= 1) return 0;
+    return round_up_sz((size_t)sg->n_k_slices * (size_t)sg->v_floats * 4, 256);
+}
+
+static lora::LaunchCtx ctx_for(const lora_pool *pool, const lora_segments *sg, bool shrink)
+{
+    lora::LaunchCtx c;
+    c.units = (const Unit *)(sg->dev + (shrink ? sg->off_shrink : sg->off_expand));
+    c.segs = (const SegRec *)(sg->dev + sg->off_segs);
+    c.perm = (const int32_t *)(sg->dev + sg->off_perm);
+    c.arena = pool->arena;
+    c.n_units = (int)(shrink ? sg->shrink_units.size() : sg->expand_units.size());
+    c.in_features = pool->in_features;
+    c.out_features = pool->out_features;
+    return c;
+}
+
+extern "C" lora_status_t lora_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *sg, size_t *bytes)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (!bytes) return fail(LORA_ERR_INVALID_ARG, "bytes is NULL");
+    *bytes = partial_bytes(sg);
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_apply_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *sg, size_t *bytes)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (!bytes) return fail(LORA_ERR_INVALID_ARG, "bytes is NULL");
+    *bytes = round_up_sz((size_t)std::max(1, sg->n_k_slices) * (size_t)sg->v_floats * 4, 256);
+    return LORA_OK;
+}
+
+static lora_status_t check_workspace(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return LORA_OK;
+    if (!ws) return fail(LORA_ERR_WORKSPACE, "workspace is NULL but %zu bytes are required", need);
+    if (((uintptr_t)ws) % 256) return fail(LORA_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+    if (have < need) return fail(LORA_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu required", have, need);
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_shrink(const lora_pool_t *pool, const lora_segments_t *sg, const void *x, int64_t ldx,
+                                     float *v, void *workspace, size_t ws_bytes, void *stream)
+{
+    lora_status_t st = check_launchable(pool, sg);
+    if (st != LORA_OK) return st;
+    if (sg->n_active == 0) return LORA_OK;
+    if ((st = check_matrix(x, ldx, pool->in_features, "x")) != LORA_OK) return st;
+    if (!v || ((uintptr_t)v) % 16) return fail(LORA_ERR_INVALID_ARG, "v is NULL or not 16-byte aligned");
+    if ((st = check_workspace(workspace, ws_bytes, partial_bytes(sg))) != LORA_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const lora::LaunchCtx c = ctx_for(pool, sg, true);
+    if (sg->n_k_slices <= 1) {
+        HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, v, 0, s));
+    } else {
+        float *parts = (float *)workspace;
+        HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, parts, sg->v_floats, s));
+        HIP_TRY(lora::launch_reduce_slices(parts, sg->n_k_slices, sg->v_floats, v, sg->v_floats, s));
+    }
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_expand(const lora_pool_t *pool, const lora_segments_t *sg, const float *v, void *y,
+                                     int64_t ldy, void *stream)
+{
+    lora_status_t st = check_launchable(pool, sg);
+    if (st != LORA_OK) return st;
+    if (sg->n_active == 0) return LORA_OK;
+    if ((st = check_matrix(y, ldy, pool->out_features, "y")) != LORA_OK) return st;
+    if (!v || ((uintptr_t)v) % 16) return fail(LORA_ERR_INVALID_ARG, "v is NULL or not 16-byte aligned");
+    const lora::LaunchCtx c = ctx_for(pool, sg, false);
+    HIP_TRY(lora::launch_expand(c, v, 1, 0, (uint16_t *)y, ldy, (hipStream_t)stream));
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *sg, const void *x, int64_t ldx,
+                                    void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream)
+{
+    lora_status_t st = check_launchable(pool, sg);
+    if (st != LORA_OK) return st;
+    if (sg->n_active == 0) return LORA_OK;
+    if ((st = check_matrix(x, ldx, pool->in_features, "x")) != LORA_OK) return st;
+    if ((st = check_matrix(y, ldy, pool->out_features, "y")) != LORA_OK) return st;
+    size_t need = 0;
+    lora_apply_workspace_bytes(pool, sg, &need);
+    if ((st = check_workspace(workspace, ws_bytes, need)) != LORA_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    float *parts = (float *)workspace;
+    const int nsl = std::max(1, sg->n_k_slices);
+    const int64_t stride = nsl > 1 ? sg->v_floats : 0;
+    HIP_TRY(lora::launch_shrink(ctx_for(pool, sg, true), (const uint16_t *)x, ldx, sg->k_slice_len, parts, stride, s));
+    HIP_TRY(lora::launch_expand(ctx_for(pool, sg, false), parts, nsl, stride, (uint16_t *)y, ldy, s));
+    return LORA_OK;
+}
+
+extern "C" const char *lora_status_string(lora_status_t status)
+{
+    switch (status) {
+    case LORA_OK: return "LORA_OK";
+    case LORA_ERR_INVALID_ARG: return "LORA_ERR_INVALID_ARG";
+    case LORA_ERR_SHAPE: return "LORA_ERR_SHAPE";
+    case LORA_ERR_OOM: return "LORA_ERR_OOM";
+    case LORA_ERR_NOT_RESIDENT: return "LORA_ERR_NOT_RESIDENT";
+    case LORA_ERR_STALE_SEGMENTS: return "LORA_ERR_STALE_SEGMENTS";
+    case LORA_ERR_WORKSPACE: return "LORA_ERR_WORKSPACE";
+    case LORA_ERR_DEVICE: return "LORA_ERR_DEVICE";
+    }
+    return "LORA_ERR_UNKNOWN";
+}
+
+extern "C" const char *lora_last_error(void) { return g_err; }

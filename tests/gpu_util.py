@@ -1,0 +1,93 @@
+"""Helpers for the GPU parity tests: put a seeded co-batch on the device, run the C-ABI path through
+the Python binding, and compare with the CPU oracle.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2511_22880_amd import binding as L
+from paper_2511_22880_amd import workloads as wl
+
+TOL = 5e-3  # max per-row relative L2 error against the fp64 oracle (bf16 inputs, fp32 accumulation)
+
+
+def bits_to_dev(bits: np.ndarray) -> torch.Tensor:
+    """uint16 bf16 patterns -> bf16 tensor on the GPU (bit copy, no conversion)."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def dev_to_bits(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+class DevicePool:
+    """A pool for one CoBatch with the adapters the batch uses (or all of them) loaded from host."""
+
+    def __init__(self, batch: wl.CoBatch, load="used", stream=None):
+        self.batch = batch
+        n = L.lora_pool_bytes(batch.in_features, batch.out_features, batch.ranks, batch.scales)
+        self.arena = torch.zeros(max(n, 256), dtype=torch.uint8, device="cuda")
+        self.pool = L.lora_pool_create(batch.in_features, batch.out_features, batch.ranks, batch.scales, self.arena)
+        self.A = [None] * batch.n_adapters
+        self.B = [None] * batch.n_adapters
+        ids = batch.used_adapters() if load == "used" else range(batch.n_adapters)
+        for a in ids:
+            A, B = batch.adapter_bits(int(a))
+            self.A[int(a)], self.B[int(a)] = A, B
+            L.lora_pool_load(self.pool, int(a), A, B, stream=stream)
+
+    def close(self):
+        L.lora_pool_destroy(self.pool)
+
+
+def row_rel_l2(y_gpu: np.ndarray, y_ref: np.ndarray) -> np.ndarray:
+    num = np.sqrt(((y_gpu - y_ref) ** 2).sum(axis=1))
+    den = np.sqrt((y_ref ** 2).sum(axis=1))
+    out = np.zeros_like(num)
+    nz = den > 0
+    out[nz] = num[nz] / den[nz]
+    out[~nz] = np.where(num[~nz] == 0, 0.0, np.inf)
+    return out
+
+
+def apply_on_gpu(dp: DevicePool, x_bits: np.ndarray, y0_bits: np.ndarray, token_adapter=None, ranges=None):
+    """Runs lora_segments_build + lora_apply; returns y as bf16 bits [T][out]."""
+    b = dp.batch
+    x = bits_to_dev(x_bits)
+    y = bits_to_dev(y0_bits)
+    ta = b.token_adapter if token_adapter is None else token_adapter
+    if ranges is not None:
+        seg = L.lora_segments_build_ranges(dp.pool, ranges[0], ranges[1])
+    else:
+        seg = L.lora_segments_build(dp.pool, ta)
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+    L.lora_apply(dp.pool, seg, x, y, ws)
+    torch.cuda.synchronize()
+    L.lora_segments_destroy(seg)
+    return dev_to_bits(y)
+
+
+def oracle_apply(dp: DevicePool, x_bits, y0_bits, token_adapter=None, rows=None):
+    b = dp.batch
+    ta = b.token_adapter if token_adapter is None else token_adapter
+    y0 = wl.bf16_bits_to_f64(y0_bits)
+    if rows is not None:
+        y0 = y0[np.asarray(rows)]
+    return oracle.lora_apply(x_bits, ta, b.ranks, b.scales, dp.A, dp.B, y0=y0, rows=rows)
+
+
+def check_parity(y_bits: np.ndarray, y_ref: np.ndarray, y0_bits: np.ndarray, token_adapter: np.ndarray, rows=None,
+                 tol: float = TOL):
+    """Rows with an adapter: relative L2 <= tol.  Rows without: bitwise equal to y0."""
+    ta = np.asarray(token_adapter)
+    if rows is not None:
+        rows = np.asarray(rows)
+        y_bits, y0_bits, ta = y_bits[rows], y0_bits[rows], ta[rows]
+    yg = wl.bf16_bits_to_f64(y_bits)
+    act = ta >= 0
+    assert np.array_equal(y_bits[~act], y0_bits[~act]), "rows without adapter were written"
+    err = row_rel_l2(yg[act], y_ref[act])
+    worst = float(err.max()) if err.size else 0.0
+    assert worst <= tol, f"max per-row relative L2 error {worst:.3e} > {tol:.1e}"
+    return worst

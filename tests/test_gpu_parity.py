@@ -1,0 +1,197 @@
+"""GPU parity: the HIP path (through the C-ABI) against the fp64 CPU oracle on the same seeded bf16
+inputs.  Bar: max per-row relative L2 error <= 5e-3 on rows with an adapter (y0 = 0, so the error is
+measured on the delta itself); rows without an adapter bitwise untouched."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_22880_amd import binding as L
+from paper_2511_22880_amd import workloads as wl
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _full_parity(batch, y0_kind="zero", ranges=None, tol=G.TOL):
+    print(f"[case] {batch.name} T={batch.T} in={batch.in_features} out={batch.out_features} y0={y0_kind}", flush=True)
+    dp = G.DevicePool(batch)
+    x_bits, y0_bits = batch.x_bits(), batch.y0_bits(y0_kind)
+    y_bits = G.apply_on_gpu(dp, x_bits, y0_bits, ranges=ranges)
+    y_ref = G.oracle_apply(dp, x_bits, y0_bits)
+    worst = G.check_parity(y_bits, y_ref, y0_bits, batch.token_adapter, tol=tol)
+    dp.close()
+    print(f"[ok] {batch.name}: max row rel-L2 {worst:.3e}", flush=True)
+    return worst
+
+
+def test_cfg0_tiny():
+    _full_parity(wl.cfg0_tiny())
+
+
+def test_cfg0_tiny_accumulates_into_small_y0():
+    _full_parity(wl.cfg0_tiny(), y0_kind="small")
+
+
+def test_small_mixed_ragged():
+    """Odd ranks (1, 3, 12, 100 ...), tokens without adapter, prefill runs of awkward lengths and
+    scattered decode tokens: several token tiles, row tiles and column tiles plus ragged tails."""
+    _full_parity(wl.small_mixed())
+    _full_parity(wl.small_mixed(seed=3, in_features=1280, out_features=192), y0_kind="small")
+
+
+def test_unit_y0_rounds_once():
+    """With y0 ~ N(0,1) the delta is below one bf16 ulp of most outputs: the result must be the
+    oracle's value rounded to bf16, within one bf16 ulp per element."""
+    b = wl.cfg0_tiny()
+    dp = G.DevicePool(b)
+    x_bits, y0_bits = b.x_bits(), b.y0_bits("unit")
+    y_bits = G.apply_on_gpu(dp, x_bits, y0_bits)
+    y_ref = G.oracle_apply(dp, x_bits, y0_bits)
+    want = wl.f32_to_bf16_bits(y_ref.astype(np.float32))
+    diff = np.abs(y_bits.astype(np.int32) - want.astype(np.int32))
+    # same sign assumed for the ulp distance; values that straddle zero are tiny and compared in value
+    same_sign = (y_bits >> 15) == (want >> 15)
+    assert np.all(diff[same_sign] <= 1)
+    assert np.allclose(wl.bf16_bits_to_f64(y_bits)[~same_sign], y_ref[~same_sign], atol=1e-2)
+    assert (diff == 0).mean() > 0.9
+    dp.close()
+
+
+def test_cfg1_decode_full_size():
+    _full_parity(wl.cfg1_decode())
+
+
+def test_shrink_and_expand_separately():
+    b = wl.small_mixed(seed=1)
+    dp = G.DevicePool(b)
+    x_bits = b.x_bits()
+    seg = L.lora_segments_build(dp.pool, b.token_adapter)
+    info = L.lora_segments_info(seg)
+    ex = L.lora_segments_export(seg)
+    x = G.bits_to_dev(x_bits)
+    v = torch.full((max(info["v_floats"], 1),), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(L.lora_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+    L.lora_shrink(dp.pool, seg, x, v, ws)
+    torch.cuda.synchronize()
+    vh = v.cpu().numpy().astype(np.float64)
+    v_ref = oracle.lora_shrink(x_bits, b.token_adapter, b.ranks, dp.A)
+    worst = 0.0
+    for t in range(b.T):
+        a = b.token_adapter[t]
+        if a < 0:
+            assert ex["v_offset"][t] == -1
+            continue
+        r, r8 = int(b.ranks[a]), (int(b.ranks[a]) + 7) // 8 * 8
+        row = vh[ex["v_offset"][t]: ex["v_offset"][t] + r8]
+        assert not row[r:].any(), "padding entries of v must be zero"
+        err = np.linalg.norm(row[:r] - v_ref[t, :r]) / np.linalg.norm(v_ref[t, :r])
+        worst = max(worst, err)
+    assert worst < 1e-5, worst  # fp32 accumulation of exact bf16 products
+    # expand from the oracle's v (rounded to fp32), into y0 = 0
+    v_in = np.zeros(max(info["v_floats"], 1), dtype=np.float32)
+    for t in range(b.T):
+        a = b.token_adapter[t]
+        if a >= 0:
+            v_in[ex["v_offset"][t]: ex["v_offset"][t] + int(b.ranks[a])] = v_ref[t, : int(b.ranks[a])]
+    y0_bits = b.y0_bits("zero")
+    y = G.bits_to_dev(y0_bits)
+    L.lora_expand(dp.pool, seg, torch.from_numpy(v_in).cuda(), y)
+    torch.cuda.synchronize()
+    y_ref = oracle.lora_expand(v_ref, b.token_adapter, b.ranks, b.scales, dp.B, b.out_features)
+    G.check_parity(G.dev_to_bits(y), y_ref, y0_bits, b.token_adapter)
+    L.lora_segments_destroy(seg)
+    dp.close()
+
+
+def test_ranges_entry_point_matches_token_list():
+    b = wl.cfg2_prefill(0, length_scale=0.02)
+    b.in_features, b.out_features = 512, 256
+    starts = np.array([s for s, _, _ in b.requests] + [b.T], dtype=np.int32)
+    ads = np.array([a for _, _, a in b.requests], dtype=np.int32)
+    dp = G.DevicePool(b)
+    x_bits, y0_bits = b.x_bits(), b.y0_bits("zero")
+    y1 = G.apply_on_gpu(dp, x_bits, y0_bits)
+    y2 = G.apply_on_gpu(dp, x_bits, y0_bits, ranges=(starts, ads))
+    assert np.array_equal(y1, y2)
+    y_ref = G.oracle_apply(dp, x_bits, y0_bits)
+    G.check_parity(y1, y_ref, y0_bits, b.token_adapter)
+    dp.close()
+
+
+def test_token_order_invariance_on_gpu():
+    """Permuting the batch permutes the result: each row's arithmetic does not depend on where the
+    token sits in the batch, only on its group-mates' count (tile shapes), so compare to tolerance
+    and require bitwise equality for a permutation that keeps every group's internal order."""
+    b = wl.small_mixed(seed=2)
+    dp = G.DevicePool(b)
+    x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
+    y = G.apply_on_gpu(dp, x_bits, y0_bits)
+    # stable: sort tokens by adapter id (keeps order inside every group)
+    p = np.argsort(b.token_adapter, kind="stable")
+    yp = G.apply_on_gpu(dp, x_bits[p], y0_bits[p], token_adapter=b.token_adapter[p])
+    assert np.array_equal(yp, y[p])
+    q = np.random.default_rng(0).permutation(b.T)
+    yq = G.apply_on_gpu(dp, x_bits[q], y0_bits[q], token_adapter=b.token_adapter[q])
+    act = b.token_adapter[q] >= 0
+    err = G.row_rel_l2(wl.bf16_bits_to_f64(yq)[act], wl.bf16_bits_to_f64(y[q])[act])
+    assert err.max() < 5e-3
+    dp.close()
+
+
+def test_empty_and_all_inactive_batches():
+    b = wl.cfg0_tiny()
+    dp = G.DevicePool(b)
+    y0_bits = b.y0_bits("small")
+    none = np.full(b.T, -1, dtype=np.int32)
+    y = G.apply_on_gpu(dp, b.x_bits(), y0_bits, token_adapter=none)
+    assert np.array_equal(y, y0_bits)
+    seg = L.lora_segments_build(dp.pool, np.zeros(0, dtype=np.int32))
+    assert L.lora_segments_info(seg)["n_active"] == 0
+    L.lora_apply(dp.pool, seg, None, None, None)  # nothing to do: no pointer is touched
+    L.lora_segments_destroy(seg)
+    dp.close()
+
+
+def test_rebuild_reuses_the_object():
+    b = wl.cfg0_tiny()
+    dp = G.DevicePool(b)
+    x_bits, y0_bits = b.x_bits(), b.y0_bits("zero")
+    x = G.bits_to_dev(x_bits)
+    seg = L.lora_segments_build(dp.pool, b.token_adapter)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(5)
+    for it in range(4):
+        ta = rng.integers(-1, 4, size=b.T).astype(np.int32) if it else b.token_adapter
+        L.lora_segments_rebuild(seg, ta)
+        y = G.bits_to_dev(y0_bits)
+        L.lora_apply(dp.pool, seg, x, y, ws)
+        torch.cuda.synchronize()
+        y_ref = G.oracle_apply(dp, x_bits, y0_bits, token_adapter=ta)
+        G.check_parity(G.dev_to_bits(y), y_ref, y0_bits, ta)
+    L.lora_segments_destroy(seg)
+    dp.close()
+
+
+def test_device_source_load_and_stale_segments():
+    b = wl.cfg0_tiny()
+    dp = G.DevicePool(b)
+    seg = L.lora_segments_build(dp.pool, b.token_adapter)
+    # reload adapter 2 from device memory with different weights: old segments must be refused
+    other = wl.cfg0_tiny(seed=1)
+    A2, B2 = other.adapter_bits(2)
+    L.lora_pool_load(dp.pool, 2, G.bits_to_dev(A2), G.bits_to_dev(B2))
+    torch.cuda.synchronize()
+    x = G.bits_to_dev(b.x_bits())
+    y = G.bits_to_dev(b.y0_bits("zero"))
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply(dp.pool, seg, x, y, ws)
+    assert e.value.status_name == "LORA_ERR_STALE_SEGMENTS"
+    L.lora_segments_destroy(seg)
+    dp.A[2], dp.B[2] = A2, B2
+    y_bits = G.apply_on_gpu(dp, b.x_bits(), b.y0_bits("zero"))
+    y_ref = G.oracle_apply(dp, b.x_bits(), b.y0_bits("zero"))
+    G.check_parity(y_bits, y_ref, b.y0_bits("zero"), b.token_adapter)
+    dp.close()
