@@ -181,6 +181,12 @@ lora_status_t lora_segments_destroy(lora_segments_t *seg);
  * v; 0 is possible).  The workspace must be 256-byte aligned. */
 lora_status_t lora_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *seg, size_t *bytes);
 
+/* A segment object can be launched on the pool it was built for and on any other pool with the same
+ * layout (equal in_features, out_features, ranks and scales, hence equal offsets) in which every
+ * adapter the batch uses is resident: the layers of a model share one token->adapter map, so one
+ * object serves all layers of one projection shape.  On its own pool it is refused with
+ * LORA_ERR_STALE_SEGMENTS once the pool's generation has moved on. */
+
 /* Shrink: v[t, j] = sum_k x[t, k] * A_a(t)[k, j] for every active token.
  * x: device, bf16, [T][in] with row stride ldx elements (ldx >= in, ldx % 8 == 0, 16-byte aligned).
  * v: device, fp32, info.v_floats long, 16-byte aligned; token t's row starts at v_offset[t] and is
@@ -202,6 +208,11 @@ lora_status_t lora_expand(const lora_pool_t *pool, const lora_segments_t *seg, c
 lora_status_t lora_apply_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *seg, size_t *bytes);
 lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *seg, const void *x, int64_t ldx,
                          void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream);
+
+/* Measurement hook.  The next lora_apply on the calling thread records the given hipEvent_t handles
+ * (passed as void*, any may be NULL) on its stream: `before` ahead of the shrink launch, `between`
+ * after it, `after` behind the expand launch.  The hook clears itself after that call. */
+lora_status_t lora_profile_next_apply(void *before, void *between, void *after);
 
 const char *lora_status_string(lora_status_t status);
 const char *lora_last_error(void);

@@ -27,7 +27,8 @@ EXPORTS = (
     "lora_pool_destroy", "lora_segments_plan", "lora_segments_plan_ranges", "lora_segments_upload",
     "lora_segments_build", "lora_segments_build_ranges", "lora_segments_rebuild", "lora_segments_info",
     "lora_segments_export", "lora_segments_export_units", "lora_segments_destroy", "lora_workspace_bytes",
-    "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_status_string",
+    "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_profile_next_apply",
+    "lora_status_string",
     "lora_last_error",
 )
 
@@ -82,6 +83,8 @@ def _ptr(obj) -> ctypes.c_void_p:
     """Address of a torch tensor, a numpy array, or an integer address; None -> NULL."""
     if obj is None:
         return ctypes.c_void_p(None)
+    if isinstance(obj, ctypes.c_void_p):
+        return obj
     if isinstance(obj, int):
         return ctypes.c_void_p(obj)
     if isinstance(obj, np.ndarray):
@@ -295,6 +298,11 @@ def lora_apply(pool: Pool, seg: Segments, x, y, workspace, stream=None, ldx: Opt
     _check(lib().lora_apply(pool.handle, seg.handle, _ptr(x), ctypes.c_int64(_ld(x, ldx)), _ptr(y),
                             ctypes.c_int64(_ld(y, ldy)), _ptr(workspace),
                             ctypes.c_size_t(_nbytes(workspace) if ws_bytes is None else ws_bytes), _stream(stream)))
+
+
+def lora_profile_next_apply(before=None, between=None, after=None) -> None:
+    """hipEvent_t handles (integers) recorded around the two launches of the next lora_apply."""
+    _check(lib().lora_profile_next_apply(_ptr(before), _ptr(between), _ptr(after)))
 
 
 def lora_status_string(status: int) -> str:

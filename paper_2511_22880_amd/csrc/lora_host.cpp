@@ -66,14 +66,18 @@ struct lora_segments {
     int64_t v_floats, weight_bytes;
     std::vector<int32_t> perm, seg_start, seg_adapter;
     std::vector<int64_t> v_offset;
+    // layout of the pool the plan was made for (for launches on sibling pools)
+    int layout_in, layout_out;
+    std::vector<int32_t> layout_rank;
+    std::vector<float> layout_scale;
     std::vector<SegRec> segs;
     std::vector<Unit> shrink_units, expand_units;
-    // device table: [perm | segs | shrink units | expand units], one allocation
+    // device table: [shrink units | expand units], one allocation
     char *dev;
     size_t dev_capacity;
     char *staging;  // pinned host copy of the table
     size_t staging_capacity;
-    size_t off_perm, off_segs, off_shrink, off_expand, table_bytes;
+    size_t off_shrink, off_expand, table_bytes;
     hipEvent_t copied;  // recorded after the upload; guards re-use of `staging`
     bool uploaded;
 };
@@ -255,11 +259,12 @@ static void choose_k_slices(int in, int *n_slices, int *slice_len)
 }
 
 // Output columns per expand unit: about 32 KiB of B^T, a multiple of 64 (four 16-column tiles, one
-// per wavefront), at least 64.
+// per wavefront), between 64 and 512: a unit's time is its bytes plus a per-tile cost (the y
+// update), so low-rank units are capped by tile count rather than by bytes.
 static int expand_cols_per_unit(int r8, int out)
 {
     int cols = (32 * 1024) / (2 * r8);
-    cols = std::max(64, cols / 64 * 64);
+    cols = std::min(512, std::max(64, cols / 64 * 64));
     return std::min(cols, out);
 }
 
@@ -279,6 +284,10 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     sg->pool = pool;
     sg->pool_id = pool->id;
     sg->pool_generation = pool->generation;
+    sg->layout_in = pool->in_features;
+    sg->layout_out = pool->out_features;
+    sg->layout_rank = pool->rank;
+    sg->layout_scale = pool->scale;
     sg->T = T;
     sg->n_active = n_active;
     sg->uploaded = false;
@@ -334,6 +343,9 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     sg->shrink_units.clear();
     sg->expand_units.clear();
     const int out = pool->out_features;
+    auto fill_tokens = [&](Unit &u, const SegRec &r) {
+        for (int q = 0; q < 16; ++q) u.tok[q] = sg->perm[r.tok_start + u.tok0 + (q < u.ntok ? q : 0)];
+    };
     for (int32_t si : order) {
         const SegRec &r = sg->segs[si];
         for (int row0 = 0; row0 < r.r8; row0 += lora::kRowTile)
@@ -347,6 +359,11 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                     u.p0 = row0;
                     u.pn = std::min(lora::kRowTile, r.r8 - row0);
                     u.ks = ks;
+                    u.r8 = r.r8;
+                    u.scale = r.scale;
+                    u.w_off = r.a_off + (uint64_t)row0 * pool->in_features;
+                    u.v_off = r.v_off + (int64_t)tok0 * r.r8 + row0;
+                    fill_tokens(u, r);
                     sg->shrink_units.push_back(u);
                 }
         const int cols = expand_cols_per_unit(r.r8, out);
@@ -359,13 +376,16 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                 u.ntok = std::min(lora::kTokTile, r.ntok - tok0);
                 u.p0 = c0;
                 u.pn = std::min(cols, out - c0);
+                u.r8 = r.r8;
+                u.scale = r.scale;
+                u.w_off = r.b_off + (uint64_t)c0 * r.r8;
+                u.v_off = r.v_off + (int64_t)tok0 * r.r8;
+                fill_tokens(u, r);
                 sg->expand_units.push_back(u);
             }
     }
 
-    sg->off_perm = 0;
-    sg->off_segs = round_up_sz(sg->off_perm + sg->perm.size() * sizeof(int32_t), 256);
-    sg->off_shrink = round_up_sz(sg->off_segs + sg->segs.size() * sizeof(SegRec), 256);
+    sg->off_shrink = 0;
     sg->off_expand = round_up_sz(sg->off_shrink + sg->shrink_units.size() * sizeof(Unit), 256);
     sg->table_bytes = round_up_sz(sg->off_expand + sg->expand_units.size() * sizeof(Unit), 256);
     return LORA_OK;
@@ -475,8 +495,6 @@ extern "C" lora_status_t lora_segments_upload(lora_segments_t *sg, void *stream)
         HIP_TRY(hipMalloc((void **)&sg->dev, cap));
         sg->dev_capacity = cap;
     }
-    if (!sg->perm.empty()) memcpy(sg->staging + sg->off_perm, sg->perm.data(), sg->perm.size() * sizeof(int32_t));
-    if (!sg->segs.empty()) memcpy(sg->staging + sg->off_segs, sg->segs.data(), sg->segs.size() * sizeof(SegRec));
     if (!sg->shrink_units.empty())
         memcpy(sg->staging + sg->off_shrink, sg->shrink_units.data(), sg->shrink_units.size() * sizeof(Unit));
     if (!sg->expand_units.empty())
@@ -577,15 +595,27 @@ extern "C" lora_status_t lora_segments_export_units(const lora_segments_t *sg, i
 // ------------------------------------------------------------------------------------------------
 // hot path
 // ------------------------------------------------------------------------------------------------
+// A segment object may be launched on the pool it was planned for, or on another pool with the same
+// layout (same feature sizes and ranks, hence the same offsets): the layers of a model that share a
+// projection shape and an adapter set.  On such a sibling pool every adapter the batch uses must be
+// resident.
 static lora_status_t check_launchable(const lora_pool *pool, const lora_segments *sg)
 {
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
-    if (sg->pool != pool || sg->pool_id != pool->id)
-        return fail(LORA_ERR_STALE_SEGMENTS, "segment object was built for a different pool");
-    if (sg->pool_generation != pool->generation)
-        return fail(LORA_ERR_STALE_SEGMENTS, "pool changed (generation %llu -> %llu) after the segment object was built",
-                    (unsigned long long)sg->pool_generation, (unsigned long long)pool->generation);
+    if (sg->pool_id == pool->id) {
+        if (sg->pool_generation != pool->generation)
+            return fail(LORA_ERR_STALE_SEGMENTS,
+                        "pool changed (generation %llu -> %llu) after the segment object was built",
+                        (unsigned long long)sg->pool_generation, (unsigned long long)pool->generation);
+    } else {
+        if (sg->layout_in != pool->in_features || sg->layout_out != pool->out_features ||
+            sg->layout_rank != pool->rank || sg->layout_scale != pool->scale)
+            return fail(LORA_ERR_STALE_SEGMENTS, "segment object was built for a pool with a different layout");
+        for (int32_t a : sg->seg_adapter)
+            if (!pool->resident[a])
+                return fail(LORA_ERR_NOT_RESIDENT, "adapter %d is used by the batch but not loaded in this pool", a);
+    }
     if (!sg->uploaded) return fail(LORA_ERR_INVALID_ARG, "segment object was planned but not uploaded");
     return LORA_OK;
 }
@@ -609,8 +639,6 @@ static lora::LaunchCtx ctx_for(const lora_pool *pool, const lora_segments *sg, b
 {
     lora::LaunchCtx c;
     c.units = (const Unit *)(sg->dev + (shrink ? sg->off_shrink : sg->off_expand));
-    c.segs = (const SegRec *)(sg->dev + sg->off_segs);
-    c.perm = (const int32_t *)(sg->dev + sg->off_perm);
     c.arena = pool->arena;
     c.n_units = (int)(shrink ? sg->shrink_units.size() : sg->expand_units.size());
     c.in_features = pool->in_features;
@@ -679,6 +707,16 @@ extern "C" lora_status_t lora_expand(const lora_pool_t *pool, const lora_segment
     return LORA_OK;
 }
 
+static thread_local hipEvent_t g_prof[3] = {nullptr, nullptr, nullptr};
+
+extern "C" lora_status_t lora_profile_next_apply(void *before, void *between, void *after)
+{
+    g_prof[0] = (hipEvent_t)before;
+    g_prof[1] = (hipEvent_t)between;
+    g_prof[2] = (hipEvent_t)after;
+    return LORA_OK;
+}
+
 extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *sg, const void *x, int64_t ldx,
                                     void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream)
 {
@@ -694,8 +732,13 @@ extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments
     float *parts = (float *)workspace;
     const int nsl = std::max(1, sg->n_k_slices);
     const int64_t stride = nsl > 1 ? sg->v_floats : 0;
+    hipEvent_t ev[3] = {g_prof[0], g_prof[1], g_prof[2]};
+    g_prof[0] = g_prof[1] = g_prof[2] = nullptr;
+    if (ev[0]) HIP_TRY(hipEventRecord(ev[0], s));
     HIP_TRY(lora::launch_shrink(ctx_for(pool, sg, true), (const uint16_t *)x, ldx, sg->k_slice_len, parts, stride, s));
+    if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
     HIP_TRY(lora::launch_expand(ctx_for(pool, sg, false), parts, nsl, stride, (uint16_t *)y, ldy, s));
+    if (ev[2]) HIP_TRY(hipEventRecord(ev[2], s));
     return LORA_OK;
 }
 

@@ -7,7 +7,7 @@
 
 namespace lora {
 
-// One group of tokens that share an adapter.  64 bytes, read with scalar loads.
+// One group of tokens that share an adapter (host-side planning record).
 struct SegRec {
     uint64_t a_off;     // element offset of A^T [r8][in] in the arena
     uint64_t b_off;     // element offset of B^T [out][r8] in the arena
@@ -21,26 +21,33 @@ struct SegRec {
 };
 static_assert(sizeof(SegRec) == 64, "SegRec is 64 bytes");
 
-// One work group's share.  32 bytes.
+// One work group's share, self-contained so that a work group needs a single round trip to memory
+// before it can issue its weight loads.  128 bytes: the first 64 are read with scalar loads, the
+// token list with one vector load.
 struct Unit {
+    uint64_t w_off;   // element offset of the unit's first weight row (A^T row p0 / B^T row p0)
+    int64_t v_off;    // float offset of the unit's first v element (shrink: row tok0, column p0;
+                      // expand: row tok0, column 0)
+    int32_t r8;       // padded rank = row length of v and of B^T
+    int32_t ntok;     // tokens in this unit (1..16)
+    int32_t p0;       // shrink: first rank row; expand: first output column
+    int32_t pn;       // shrink: valid rank rows (1..16, multiple of 8 except the tail); expand: columns
+    int32_t ks;       // shrink: k-slice index
+    float scale;
     int32_t seg;
-    int32_t tok0;  // first token, relative to the group
-    int32_t ntok;  // tokens in this unit
-    int32_t p0;    // shrink: first rank row; expand: first output column
-    int32_t pn;    // shrink: rank rows;      expand: output columns
-    int32_t ks;    // shrink: k-slice index
-    int32_t pad[2];
+    int32_t tok0;     // first token, relative to the group
+    int32_t pad[4];
+    int32_t tok[16];  // batch row index of each token; entries >= ntok repeat tok[0]
 };
-static_assert(sizeof(Unit) == 32, "Unit is 32 bytes");
+static_assert(sizeof(Unit) == 128, "Unit is 128 bytes");
 
+#define LORA_MAX_RANK_PADDED 256
 constexpr int kTokTile = 16;   // tokens per MFMA tile (the N of a 16x16x32 MFMA)
 constexpr int kRowTile = 16;   // rank rows / output columns per MFMA tile (the M)
 constexpr int kThreads = 256;  // 4 wavefronts per work group
 
 struct LaunchCtx {
     const Unit *units;
-    const SegRec *segs;
-    const int32_t *perm;
     const uint16_t *arena;
     int n_units;
     int in_features;

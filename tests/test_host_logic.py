@@ -1,0 +1,221 @@
+"""Host side of the C-ABI library, no GPU: the library loads and exports every symbol the header
+declares, argument errors are reported before the device is touched, pool offsets follow the ragged
+layout, and the planner's grouping and work units match a brute-force grouping."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2511_22880_amd import binding as L
+from paper_2511_22880_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_ARENA = 0x7F0000000000  # 256-byte aligned address that is never dereferenced on the host
+
+
+def make_pool(in_f=512, out_f=256, ranks=(8, 16, 3, 128), resident=True):
+    ranks = np.asarray(ranks, dtype=np.int32)
+    scales = (2.0 / np.maximum(ranks, 1)).astype(np.float32)
+    n = L.lora_pool_bytes(in_f, out_f, ranks, scales)
+    pool = L.lora_pool_create(in_f, out_f, ranks, scales, FAKE_ARENA, n)
+    if resident:
+        for a in range(len(ranks)):
+            L.lora_pool_mark_resident(pool, a)
+    return pool
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "lora.h")).read()
+    declared = set(re.findall(r"\b(lora_[a-z_]+)\s*\(", header))
+    assert declared == set(L.EXPORTS), declared ^ set(L.EXPORTS)
+    lib = L.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert L.lora_status_string(0) == "LORA_OK" and L.lora_status_string(4) == "LORA_ERR_NOT_RESIDENT"
+
+
+def test_pool_bytes_and_offsets_are_ragged():
+    ranks = np.array([8, 16, 3, 128, 256], dtype=np.int32)
+    in_f, out_f = 4096, 1024
+    n = L.lora_pool_bytes(in_f, out_f, ranks, 2.0 / ranks)
+    r8 = (ranks + 7) // 8 * 8
+    assert n == int(2 * r8.sum() * (in_f + out_f))          # no padding to the largest rank
+    assert n < 2 * 256 * len(ranks) * (in_f + out_f) / 2
+    pool = L.lora_pool_create(in_f, out_f, ranks, 2.0 / ranks, FAKE_ARENA, n)
+    off = 0
+    for a, r in enumerate(ranks):
+        info = L.lora_pool_adapter_info(pool, a)
+        assert info["a_offset"] == off and info["b_offset"] == off + r8[a] * in_f
+        assert info["rank"] == r and info["rank_padded"] == r8[a] and info["resident"] == 0
+        assert info["scale"] == pytest.approx(2.0 / r)
+        off += r8[a] * (in_f + out_f)
+    L.lora_pool_destroy(pool)
+
+
+@pytest.mark.parametrize("kwargs,status", [
+    (dict(in_f=100), "LORA_ERR_SHAPE"),
+    (dict(out_f=4097), "LORA_ERR_SHAPE"),
+    (dict(ranks=(8, 0)), "LORA_ERR_SHAPE"),
+    (dict(ranks=(8, 257)), "LORA_ERR_SHAPE"),
+])
+def test_pool_shape_errors(kwargs, status):
+    with pytest.raises(L.LoraError) as e:
+        make_pool(**kwargs)
+    assert e.value.status_name == status and e.value.detail
+
+
+def test_pool_argument_errors():
+    ranks = np.array([8], dtype=np.int32)
+    n = L.lora_pool_bytes(256, 256, ranks, [0.25])
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_create(256, 256, ranks, [0.25], FAKE_ARENA, n - 1)
+    assert e.value.status_name == "LORA_ERR_OOM"
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_create(256, 256, ranks, [0.25], FAKE_ARENA + 8, n)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_create(256, 256, ranks, [0.25], 0, n)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+    pool = make_pool()
+    for bad in (-1, 4):
+        with pytest.raises(L.LoraError) as e:
+            L.lora_pool_evict(pool, bad)
+        assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+        with pytest.raises(L.LoraError):
+            L.lora_pool_adapter_info(pool, bad)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_load(pool, 0, None, None, src_is_device=True)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+    L.lora_pool_destroy(pool)
+
+
+def test_plan_rejects_bad_routing_before_touching_the_device():
+    pool = make_pool(resident=False)
+    L.lora_pool_mark_resident(pool, 0)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_segments_plan(pool, [0, 1])
+    assert e.value.status_name == "LORA_ERR_NOT_RESIDENT" and "adapter 1" in e.value.detail
+    for bad in ([0, 4], [0, -2]):
+        with pytest.raises(L.LoraError) as e:
+            L.lora_segments_plan(pool, bad)
+        assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+    seg = L.lora_segments_plan(pool, [0, -1, 0])   # -1 is "no adapter", not an error
+    assert L.lora_segments_info(seg)["n_active"] == 2
+    L.lora_pool_evict(pool, 0)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_segments_plan(pool, [0])
+    assert e.value.status_name == "LORA_ERR_NOT_RESIDENT"
+    with pytest.raises(L.LoraError) as e:
+        L.lora_segments_plan_ranges(pool, [1, 2], [0])
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+    with pytest.raises(L.LoraError) as e:
+        L.lora_segments_plan_ranges(pool, [0, 5, 3], [-1, -1])
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+    L.lora_segments_destroy(seg)
+    L.lora_pool_destroy(pool)
+
+
+def test_launch_checks_happen_on_the_host():
+    pool = make_pool()
+    seg = L.lora_segments_plan(pool, [0, 1, 3])
+    # planned but never uploaded: refused, nothing is launched
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply(pool, seg, FAKE_ARENA, FAKE_ARENA, FAKE_ARENA, ldx=512, ldy=256, ws_bytes=1 << 20)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG" and "upload" in e.value.detail
+    # a pool change makes the object stale
+    L.lora_pool_evict(pool, 2)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_shrink(pool, seg, FAKE_ARENA, FAKE_ARENA, FAKE_ARENA, ldx=512, ws_bytes=1 << 20)
+    assert e.value.status_name == "LORA_ERR_STALE_SEGMENTS"
+    # another layout is refused too
+    other = make_pool(ranks=(8, 16, 4, 128))
+    with pytest.raises(L.LoraError) as e:
+        L.lora_expand(other, seg, FAKE_ARENA, FAKE_ARENA, ldy=256)
+    assert e.value.status_name == "LORA_ERR_STALE_SEGMENTS"
+    assert L.lora_apply_workspace_bytes(pool, seg) >= 4 * L.lora_segments_info(seg)["v_floats"]
+    for o in (seg,):
+        L.lora_segments_destroy(o)
+    L.lora_pool_destroy(pool)
+    L.lora_pool_destroy(other)
+
+
+def brute_force_groups(ta):
+    groups = {}
+    for t, a in enumerate(ta):
+        if a >= 0:
+            groups.setdefault(int(a), []).append(t)
+    return groups
+
+
+@pytest.mark.parametrize("maker", [
+    lambda: wl.cfg0_tiny(), lambda: wl.cfg1_decode(), lambda: wl.small_mixed(),
+    lambda: wl.cfg4_skew(0, "9:1"), lambda: wl.cfg3_stack(length_scale=0.05),
+])
+def test_planner_matches_brute_force_grouping(maker):
+    b = maker()
+    n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
+    pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
+    for a in range(b.n_adapters):
+        L.lora_pool_mark_resident(pool, a)
+    seg = L.lora_segments_plan(pool, b.token_adapter)
+    info, ex, units = L.lora_segments_info(seg), L.lora_segments_export(seg), L.lora_segments_export_units(seg)
+    groups = brute_force_groups(b.token_adapter)
+    r8 = (b.ranks + 7) // 8 * 8
+    assert info["n_tokens"] == b.T and info["n_active"] == sum(len(g) for g in groups.values())
+    assert info["n_segments"] == len(groups)
+    assert list(ex["seg_adapter"]) == sorted(groups)
+    # stable grouping: each group's tokens in batch order
+    for s, a in enumerate(ex["seg_adapter"]):
+        assert list(ex["perm"][ex["seg_start"][s]: ex["seg_start"][s + 1]]) == groups[int(a)]
+    assert info["v_floats"] == sum(len(g) * int(r8[a]) for a, g in groups.items())
+    assert info["weight_bytes"] == sum(2 * int(r8[a]) * (b.in_features + b.out_features) for a in groups)
+    # v rows are disjoint and tile [0, v_floats)
+    spans = sorted((int(ex["v_offset"][t]), int(r8[b.token_adapter[t]])) for t in range(b.T) if b.token_adapter[t] >= 0)
+    pos = 0
+    for off, ln in spans:
+        assert off == pos
+        pos += ln
+    assert pos == info["v_floats"] and np.all(ex["v_offset"][b.token_adapter < 0] == -1)
+    # shrink units cover every (token, rank row, k-slice) exactly once; expand units every (token, column)
+    nsl = info["n_k_slices"]
+    for s, a in enumerate(ex["seg_adapter"]):
+        ntok, rr = len(groups[int(a)]), int(r8[a])
+        cover = np.zeros((ntok, rr, nsl), dtype=np.int32)
+        for seg_i, tok0, nt, p0, pn, ks in units["shrink"][units["shrink"][:, 0] == s]:
+            assert 1 <= nt <= 16 and 1 <= pn <= 16
+            cover[tok0:tok0 + nt, p0:p0 + pn, ks] += 1
+        assert np.all(cover == 1)
+        ecover = np.zeros((ntok, b.out_features), dtype=np.int32)
+        for seg_i, tok0, nt, p0, pn, ks in units["expand"][units["expand"][:, 0] == s]:
+            assert pn % 64 == 0 and 1 <= nt <= 16
+            ecover[tok0:tok0 + nt, p0:p0 + pn] += 1
+        assert np.all(ecover == 1)
+    # no unit's size depends on another adapter's rank: expand bytes per unit bounded by its own rank
+    eu = units["expand"]
+    ub = eu[:, 4] * 2 * r8[ex["seg_adapter"][eu[:, 0]]]
+    assert ub.max() <= 64 * 1024
+    L.lora_segments_destroy(seg)
+    L.lora_pool_destroy(pool)
+
+
+def test_ranges_merge_requests_of_the_same_adapter():
+    pool = make_pool()
+    seg = L.lora_segments_plan_ranges(pool, [0, 3, 5, 9, 12], [1, -1, 0, 1])
+    ex, info = L.lora_segments_export(seg), L.lora_segments_info(seg)
+    assert info["n_tokens"] == 12 and info["n_active"] == 10 and info["n_segments"] == 2
+    assert list(ex["seg_adapter"]) == [0, 1]
+    assert list(ex["perm"]) == [5, 6, 7, 8, 0, 1, 2, 9, 10, 11]
+    L.lora_segments_destroy(seg)
+    L.lora_pool_destroy(pool)
+
+
+def test_empty_batches_plan():
+    pool = make_pool()
+    for ta in ([], [-1, -1, -1]):
+        seg = L.lora_segments_plan(pool, np.asarray(ta, dtype=np.int32))
+        info = L.lora_segments_info(seg)
+        assert info["n_active"] == 0 and info["n_segments"] == 0 and info["v_floats"] == 0
+        assert info["n_shrink_units"] == 0 and info["n_expand_units"] == 0
+        L.lora_segments_destroy(seg)
+    L.lora_pool_destroy(pool)
