@@ -24,7 +24,7 @@
  *   - Every function validates its arguments on the host before touching the device and returns a
  *     status; nothing throws, aborts or exits.  lora_last_error() gives a thread-local detail line
  *     for the last non-OK status returned on this thread.
- *   - in_features and out_features must be multiples of 64; ranks are 1..LORA_MAX_RANK.
+ *   - in_features must be a multiple of 64 and out_features of 128; ranks are 1..LORA_MAX_RANK.
  */
 #ifndef LORA_GFX950_H
 #define LORA_GFX950_H
@@ -209,9 +209,24 @@ lora_status_t lora_apply_workspace_bytes(const lora_pool_t *pool, const lora_seg
 lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *seg, const void *x, int64_t ldx,
                          void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream);
 
+/* lora_apply is two launches by default (shrink units, then expand units).  In both forms the shrink
+ * unit that completes a token tile (found through per-tile counters in the segment object's device
+ * table) adds the k-slices up and leaves the tile's v for the expand units.
+ * lora_set_fused_apply(1) selects a single launch in which shrink and expand units share the grid
+ * and the expand units poll, with a bounded number of polls, until their tile's v is complete.  The
+ * counters' epoch is host state of the segment object, so applies that share one object must be
+ * issued by one thread at a time and ordered on one stream, and must not be captured into a graph
+ * that is replayed.  The setting is process-wide. */
+lora_status_t lora_set_fused_apply(int enabled);
+
+/* Synchronises `stream` and reports LORA_ERR_DEVICE if an expand unit of an earlier fused lora_apply
+ * on this object ran into its (bounded) wait limit, in which case that apply's y is not valid. */
+lora_status_t lora_segments_check(const lora_segments_t *seg, void *stream);
+
 /* Measurement hook.  The next lora_apply on the calling thread records the given hipEvent_t handles
  * (passed as void*, any may be NULL) on its stream: `before` ahead of the shrink launch, `between`
- * after it, `after` behind the expand launch.  The hook clears itself after that call. */
+ * after it, `after` behind the expand launch (a fused apply records `between` and `after` together,
+ * behind its single launch).  The hook clears itself after that call. */
 lora_status_t lora_profile_next_apply(void *before, void *between, void *after);
 
 const char *lora_status_string(lora_status_t status);

@@ -28,6 +28,7 @@ EXPORTS = (
     "lora_segments_build", "lora_segments_build_ranges", "lora_segments_rebuild", "lora_segments_info",
     "lora_segments_export", "lora_segments_export_units", "lora_segments_destroy", "lora_workspace_bytes",
     "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_profile_next_apply",
+    "lora_set_fused_apply", "lora_segments_check",
     "lora_status_string",
     "lora_last_error",
 )
@@ -298,6 +299,14 @@ def lora_apply(pool: Pool, seg: Segments, x, y, workspace, stream=None, ldx: Opt
     _check(lib().lora_apply(pool.handle, seg.handle, _ptr(x), ctypes.c_int64(_ld(x, ldx)), _ptr(y),
                             ctypes.c_int64(_ld(y, ldy)), _ptr(workspace),
                             ctypes.c_size_t(_nbytes(workspace) if ws_bytes is None else ws_bytes), _stream(stream)))
+
+
+def lora_set_fused_apply(enabled: bool) -> None:
+    _check(lib().lora_set_fused_apply(ctypes.c_int(1 if enabled else 0)))
+
+
+def lora_segments_check(seg: Segments, stream=None) -> None:
+    _check(lib().lora_segments_check(seg.handle, _stream(stream)))
 
 
 def lora_profile_next_apply(before=None, between=None, after=None) -> None:

@@ -72,12 +72,14 @@ struct lora_segments {
     std::vector<float> layout_scale;
     std::vector<SegRec> segs;
     std::vector<Unit> shrink_units, expand_units;
-    // device table: [shrink units | expand units], one allocation
+    // device table: [shrink units | expand units | arrival counters, ready counters, time-out flag]
     char *dev;
     size_t dev_capacity;
     char *staging;  // pinned host copy of the table
     size_t staging_capacity;
-    size_t off_shrink, off_expand, table_bytes;
+    size_t off_shrink, off_expand, off_sync, table_bytes;
+    int n_sync;             // counters: one per (group, token tile), then the time-out flag
+    unsigned launches;      // fused launches since the table was uploaded (the counters' epoch)
     hipEvent_t copied;  // recorded after the upload; guards re-use of `staging`
     bool uploaded;
 };
@@ -97,8 +99,8 @@ static lora_status_t check_desc(const lora_pool_desc_t *d)
     if (d->n_adapters < 0) return fail(LORA_ERR_INVALID_ARG, "n_adapters = %d", d->n_adapters);
     if (d->n_adapters > 0 && (!d->ranks || !d->scales)) return fail(LORA_ERR_INVALID_ARG, "ranks/scales is NULL");
     if (d->dtype != LORA_BF16) return fail(LORA_ERR_INVALID_ARG, "dtype %d is not LORA_BF16", d->dtype);
-    if (d->in_features <= 0 || d->out_features <= 0 || d->in_features % 64 || d->out_features % 64)
-        return fail(LORA_ERR_SHAPE, "in_features (%d) and out_features (%d) must be positive multiples of 64",
+    if (d->in_features <= 0 || d->out_features <= 0 || d->in_features % 64 || d->out_features % 128)
+        return fail(LORA_ERR_SHAPE, "in_features (%d) must be a positive multiple of 64 and out_features (%d) of 128",
                     d->in_features, d->out_features);
     for (int a = 0; a < d->n_adapters; ++a)
         if (d->ranks[a] < 1 || d->ranks[a] > LORA_MAX_RANK)
@@ -258,13 +260,13 @@ static void choose_k_slices(int in, int *n_slices, int *slice_len)
     *slice_len = len;
 }
 
-// Output columns per expand unit: about 32 KiB of B^T, a multiple of 64 (four 16-column tiles, one
-// per wavefront), between 64 and 512: a unit's time is its bytes plus a per-tile cost (the y
-// update), so low-rank units are capped by tile count rather than by bytes.
+// Output columns per expand unit.  A work group's four wavefronts take 128-column strips of B^T,
+// splitting a strip by rank when the rank is large: one pass covers 512 columns for ranks up to
+// 32, 256 for ranks up to 64 and 128 beyond.  A unit is one pass for ranks above 32 (<= 32 KiB of
+// B^T, 64 KiB for ranks above 128) and 512 columns (one pass, <= 32 KiB) below.
 static int expand_cols_per_unit(int r8, int out)
 {
-    int cols = (32 * 1024) / (2 * r8);
-    cols = std::min(512, std::max(64, cols / 64 * 64));
+    const int cols = r8 <= 32 ? 512 : (r8 <= 64 ? 256 : 128);
     return std::min(cols, out);
 }
 
@@ -346,8 +348,17 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     auto fill_tokens = [&](Unit &u, const SegRec &r) {
         for (int q = 0; q < 16; ++q) u.tok[q] = sg->perm[r.tok_start + u.tok0 + (q < u.ntok ? q : 0)];
     };
+    // counters of the fused launch: one per (group, token tile)
+    std::vector<int32_t> sync_base(sg->segs.size(), 0);
+    int n_sync = 0;
+    for (size_t si = 0; si < sg->segs.size(); ++si) {
+        sync_base[si] = n_sync;
+        n_sync += (sg->segs[si].ntok + lora::kTokTile - 1) / lora::kTokTile;
+    }
+    sg->n_sync = n_sync;
     for (int32_t si : order) {
         const SegRec &r = sg->segs[si];
+        const int sync_n = ((r.r8 + lora::kRowTile - 1) / lora::kRowTile) * sg->n_k_slices;
         for (int row0 = 0; row0 < r.r8; row0 += lora::kRowTile)
             for (int ks = 0; ks < sg->n_k_slices; ++ks)
                 for (int tok0 = 0; tok0 < r.ntok; tok0 += lora::kTokTile) {
@@ -363,6 +374,8 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                     u.scale = r.scale;
                     u.w_off = r.a_off + (uint64_t)row0 * pool->in_features;
                     u.v_off = r.v_off + (int64_t)tok0 * r.r8 + row0;
+                    u.sync_idx = sync_base[si] + tok0 / lora::kTokTile;
+                    u.sync_n = sync_n;
                     fill_tokens(u, r);
                     sg->shrink_units.push_back(u);
                 }
@@ -380,6 +393,8 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                 u.scale = r.scale;
                 u.w_off = r.b_off + (uint64_t)c0 * r.r8;
                 u.v_off = r.v_off + (int64_t)tok0 * r.r8;
+                u.sync_idx = sync_base[si] + tok0 / lora::kTokTile;
+                u.sync_n = sync_n;
                 fill_tokens(u, r);
                 sg->expand_units.push_back(u);
             }
@@ -387,7 +402,8 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
 
     sg->off_shrink = 0;
     sg->off_expand = round_up_sz(sg->off_shrink + sg->shrink_units.size() * sizeof(Unit), 256);
-    sg->table_bytes = round_up_sz(sg->off_expand + sg->expand_units.size() * sizeof(Unit), 256);
+    sg->off_sync = round_up_sz(sg->off_expand + sg->expand_units.size() * sizeof(Unit), 256);
+    sg->table_bytes = round_up_sz(sg->off_sync + (size_t)(2 * sg->n_sync + 1) * sizeof(unsigned), 256);
     return LORA_OK;
 }
 
@@ -402,6 +418,8 @@ static lora_segments *new_segments()
     sg->staging_capacity = 0;
     sg->copied = nullptr;
     sg->uploaded = false;
+    sg->n_sync = 0;
+    sg->launches = 0;
     return sg;
 }
 
@@ -499,6 +517,8 @@ extern "C" lora_status_t lora_segments_upload(lora_segments_t *sg, void *stream)
         memcpy(sg->staging + sg->off_shrink, sg->shrink_units.data(), sg->shrink_units.size() * sizeof(Unit));
     if (!sg->expand_units.empty())
         memcpy(sg->staging + sg->off_expand, sg->expand_units.data(), sg->expand_units.size() * sizeof(Unit));
+    memset(sg->staging + sg->off_sync, 0, sg->table_bytes - sg->off_sync);
+    sg->launches = 0;
     if (sg->table_bytes) HIP_TRY(hipMemcpyAsync(sg->dev, sg->staging, sg->table_bytes, hipMemcpyHostToDevice, s));
     HIP_TRY(hipEventRecord(sg->copied, s));
     sg->uploaded = true;
@@ -635,6 +655,13 @@ static size_t partial_bytes(const lora_segments *sg)
     return round_up_sz((size_t)sg->n_k_slices * (size_t)sg->v_floats * 4, 256);
 }
 
+// lora_apply's workspace: [k-slices' fp32 partial sums of v | v as bf16 hi | v as bf16 lo]
+static size_t apply_parts_bytes(const lora_segments *sg)
+{
+    return round_up_sz((size_t)std::max(1, sg->n_k_slices) * (size_t)sg->v_floats * 4, 256);
+}
+static size_t apply_packed_bytes(const lora_segments *sg) { return round_up_sz((size_t)sg->v_floats * 2, 256); }
+
 static lora::LaunchCtx ctx_for(const lora_pool *pool, const lora_segments *sg, bool shrink)
 {
     lora::LaunchCtx c;
@@ -660,7 +687,7 @@ extern "C" lora_status_t lora_apply_workspace_bytes(const lora_pool_t *pool, con
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     if (!bytes) return fail(LORA_ERR_INVALID_ARG, "bytes is NULL");
-    *bytes = round_up_sz((size_t)std::max(1, sg->n_k_slices) * (size_t)sg->v_floats * 4, 256);
+    *bytes = apply_parts_bytes(sg) + 2 * apply_packed_bytes(sg);
     return LORA_OK;
 }
 
@@ -685,10 +712,11 @@ extern "C" lora_status_t lora_shrink(const lora_pool_t *pool, const lora_segment
     hipStream_t s = (hipStream_t)stream;
     const lora::LaunchCtx c = ctx_for(pool, sg, true);
     if (sg->n_k_slices <= 1) {
-        HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, v, 0, s));
+        HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, v, 1, 0, nullptr, s));
     } else {
         float *parts = (float *)workspace;
-        HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, parts, sg->v_floats, s));
+        HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, parts, sg->n_k_slices,
+                                    sg->v_floats, nullptr, s));
         HIP_TRY(lora::launch_reduce_slices(parts, sg->n_k_slices, sg->v_floats, v, sg->v_floats, s));
     }
     return LORA_OK;
@@ -703,11 +731,31 @@ extern "C" lora_status_t lora_expand(const lora_pool_t *pool, const lora_segment
     if ((st = check_matrix(y, ldy, pool->out_features, "y")) != LORA_OK) return st;
     if (!v || ((uintptr_t)v) % 16) return fail(LORA_ERR_INVALID_ARG, "v is NULL or not 16-byte aligned");
     const lora::LaunchCtx c = ctx_for(pool, sg, false);
-    HIP_TRY(lora::launch_expand(c, v, 1, 0, (uint16_t *)y, ldy, (hipStream_t)stream));
+    HIP_TRY(lora::launch_expand(c, v, 1, 0, (uint16_t *)y, ldy, nullptr, (hipStream_t)stream));
     return LORA_OK;
 }
 
 static thread_local hipEvent_t g_prof[3] = {nullptr, nullptr, nullptr};
+static int g_fused_apply = 0;
+static const unsigned kSpinLimit = 1u << 18;  // polls of a waiting expand unit before it gives up
+
+extern "C" lora_status_t lora_set_fused_apply(int enabled)
+{
+    g_fused_apply = enabled ? 1 : 0;
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_segments_check(const lora_segments_t *sg, void *stream)
+{
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (!sg->uploaded || !sg->dev) return LORA_OK;
+    unsigned flag = 0;
+    HIP_TRY(hipMemcpyAsync(&flag, sg->dev + sg->off_sync + (size_t)2 * sg->n_sync * sizeof(unsigned), sizeof flag,
+                           hipMemcpyDeviceToHost, (hipStream_t)stream));
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    if (flag) return fail(LORA_ERR_DEVICE, "an expand unit of a fused lora_apply gave up waiting for its shrink units");
+    return LORA_OK;
+}
 
 extern "C" lora_status_t lora_profile_next_apply(void *before, void *between, void *after)
 {
@@ -734,10 +782,28 @@ extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments
     const int64_t stride = nsl > 1 ? sg->v_floats : 0;
     hipEvent_t ev[3] = {g_prof[0], g_prof[1], g_prof[2]};
     g_prof[0] = g_prof[1] = g_prof[2] = nullptr;
+    // The counters' epoch lives in the segment object, so applies that share an object must be issued
+    // by one thread at a time and ordered on one stream.
+    lora_segments *msg = const_cast<lora_segments *>(sg);
+    lora::SyncArgs sa;
+    sa.counters = (unsigned *)(sg->dev + sg->off_sync);
+    sa.ready = sa.counters + sg->n_sync;
+    sa.timeout_flag = sa.counters + 2 * sg->n_sync;
+    sa.v_hi = (uint16_t *)((char *)workspace + apply_parts_bytes(sg));
+    sa.v_lo = (uint16_t *)((char *)workspace + apply_parts_bytes(sg) + apply_packed_bytes(sg));
+    sa.epoch = ++msg->launches;
+    sa.spin_limit = kSpinLimit;
+    const lora::LaunchCtx cs = ctx_for(pool, sg, true), ce = ctx_for(pool, sg, false);
     if (ev[0]) HIP_TRY(hipEventRecord(ev[0], s));
-    HIP_TRY(lora::launch_shrink(ctx_for(pool, sg, true), (const uint16_t *)x, ldx, sg->k_slice_len, parts, stride, s));
-    if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
-    HIP_TRY(lora::launch_expand(ctx_for(pool, sg, false), parts, nsl, stride, (uint16_t *)y, ldy, s));
+    if (g_fused_apply) {
+        HIP_TRY(lora::launch_apply_fused(cs, ce, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride,
+                                         (uint16_t *)y, ldy, &sa, s));
+        if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
+    } else {
+        HIP_TRY(lora::launch_shrink(cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride, &sa, s));
+        if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
+        HIP_TRY(lora::launch_expand(ce, parts, nsl, stride, (uint16_t *)y, ldy, &sa, s));
+    }
     if (ev[2]) HIP_TRY(hipEventRecord(ev[2], s));
     return LORA_OK;
 }

@@ -36,7 +36,9 @@ struct Unit {
     float scale;
     int32_t seg;
     int32_t tok0;     // first token, relative to the group
-    int32_t pad[4];
+    int32_t sync_idx; // counter of this unit's (group, token tile) in a fused launch
+    int32_t sync_n;   // shrink units that feed that counter per launch
+    int32_t pad[2];
     int32_t tok[16];  // batch row index of each token; entries >= ntok repeat tok[0]
 };
 static_assert(sizeof(Unit) == 128, "Unit is 128 bytes");
@@ -54,14 +56,34 @@ struct LaunchCtx {
     int out_features;
 };
 
-// v_out[ks * slice_stride + ...] receives k-slice ks's partial sums (slice_stride = 0 when there is
-// a single slice and v_out is v itself).
-hipError_t launch_shrink(const LaunchCtx &c, const uint16_t *x, int64_t ldx, int k_slice_len,
-                         float *v_out, int64_t slice_stride, hipStream_t stream);
+// Hand-over of v through the segment table's counters (see the kernels): arrivals and ready counters
+// per (group, token tile), the complete v as bf16 hi + lo, the launch epoch and the poll limit.
+struct SyncArgs {
+    unsigned *counters;
+    unsigned *ready;
+    unsigned *timeout_flag;
+    uint16_t *v_hi;
+    uint16_t *v_lo;
+    unsigned epoch;
+    unsigned spin_limit;
+};
 
-// v_in holds n_slices partial sums slice_stride floats apart (n_slices = 1: v itself).
+// v_out[ks * slice_stride + ...] receives k-slice ks's partial sums (slice_stride = 0 when there is
+// a single slice).  With `sync`, the unit that completes a token tile also writes the tile's summed v
+// as bf16 hi + lo.
+hipError_t launch_shrink(const LaunchCtx &c, const uint16_t *x, int64_t ldx, int k_slice_len, float *v_out,
+                         int n_slices, int64_t slice_stride, const SyncArgs *sync, hipStream_t stream);
+
+// Without `sync`: v_in holds n_slices fp32 partial sums slice_stride floats apart (n_slices = 1: v
+// itself).  With `sync`: v comes from sync->v_hi / v_lo (written by a shrink launch of the same epoch).
 hipError_t launch_expand(const LaunchCtx &c, const float *v_in, int n_slices, int64_t slice_stride,
-                         uint16_t *y, int64_t ldy, hipStream_t stream);
+                         uint16_t *y, int64_t ldy, const SyncArgs *sync, hipStream_t stream);
+
+// Both halves in one launch (shrink units first); the expand units poll `ready` of their token tile,
+// at most spin_limit times each.
+hipError_t launch_apply_fused(const LaunchCtx &shrink, const LaunchCtx &expand, const uint16_t *x, int64_t ldx,
+                              int k_slice_len, float *parts, int n_slices, int64_t slice_stride, uint16_t *y,
+                              int64_t ldy, const SyncArgs *sync, hipStream_t stream);
 
 // v[i] = sum over slices, in slice order.
 hipError_t launch_reduce_slices(const float *parts, int n_slices, int64_t slice_stride, float *v,

@@ -64,6 +64,7 @@ def apply_on_gpu(dp: DevicePool, x_bits: np.ndarray, y0_bits: np.ndarray, token_
     ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
     L.lora_apply(dp.pool, seg, x, y, ws)
     torch.cuda.synchronize()
+    L.lora_segments_check(seg)
     L.lora_segments_destroy(seg)
     return dev_to_bits(y)
 

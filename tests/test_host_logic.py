@@ -188,7 +188,7 @@ def test_planner_matches_brute_force_grouping(maker):
         assert np.all(cover == 1)
         ecover = np.zeros((ntok, b.out_features), dtype=np.int32)
         for seg_i, tok0, nt, p0, pn, ks in units["expand"][units["expand"][:, 0] == s]:
-            assert pn % 64 == 0 and 1 <= nt <= 16
+            assert pn % 128 == 0 and 1 <= nt <= 16
             ecover[tok0:tok0 + nt, p0:p0 + pn] += 1
         assert np.all(ecover == 1)
     # no unit's size depends on another adapter's rank: expand bytes per unit bounded by its own rank
