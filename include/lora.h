@@ -169,7 +169,10 @@ lora_status_t lora_segments_export(const lora_segments_t *seg, int32_t *perm, in
 
 /* Host copies of the work-unit lists, 6 int32 per unit: {segment, first token (relative to the
  * group), token count, first row (shrink) or first column (expand), row or column count,
- * k-slice (shrink) or 0}.  Either output may be NULL. */
+ * k-slice (shrink) or 0}.  Groups of fewer than 32 tokens are cut into shrink units of <= 16 tokens x
+ * 16 rank rows x one k-slice; token-heavy groups into shrink units of up to 32 tokens x all rank
+ * rows x all of k (listed after the others, k-slice 0) and into expand units of up to 64 tokens.
+ * Either output may be NULL. */
 lora_status_t lora_segments_export_units(const lora_segments_t *seg, int32_t *shrink_units,
                                          int32_t *expand_units);
 

@@ -71,13 +71,15 @@ struct lora_segments {
     std::vector<int32_t> layout_rank;
     std::vector<float> layout_scale;
     std::vector<SegRec> segs;
-    std::vector<Unit> shrink_units, expand_units;
-    // device table: [shrink units | expand units | arrival counters, ready counters, time-out flag]
+    std::vector<Unit> shrink_units, prefill_units, expand_units, expand_big_units;
+    // device table: [perm | shrink units | prefill shrink units | expand units | arrival counters,
+    // ready counters, time-out flag]
     char *dev;
     size_t dev_capacity;
     char *staging;  // pinned host copy of the table
     size_t staging_capacity;
-    size_t off_shrink, off_expand, off_sync, table_bytes;
+    size_t off_perm, off_shrink, off_prefill, off_expand, off_expand_big, off_sync, table_bytes;
+    bool has_big_units;     // some unit holds more than 16 tokens (token-heavy groups)
     int n_sync;             // counters: one per (group, token tile), then the time-out flag
     unsigned launches;      // fused launches since the table was uploaded (the counters' epoch)
     hipEvent_t copied;  // recorded after the upload; guards re-use of `staging`
@@ -270,6 +272,14 @@ static int expand_cols_per_unit(int r8, int out)
     return std::min(cols, out);
 }
 
+// Groups with at least this many tokens are token-heavy: their shrink runs on token tiles that read x
+// once (instead of once per 16 rank rows), their expand units hold up to kExpandBigTokens tokens.
+// Only in batches of at least kPrefillMinBatch tokens: a 128-token tile streams about 1 MB of x, far
+// longer than a whole decode-sized launch lasts.
+static const int kPrefillMinTokens = 32;
+static const int kPrefillMinBatch = 1024;
+static const int kExpandBigTokens = 64;
+
 static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const int32_t *ta, int32_t T)
 {
     const int N = pool->n_adapters;
@@ -343,12 +353,15 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     std::stable_sort(order.begin(), order.end(),
                      [&](int32_t x, int32_t y) { return sg->segs[x].r8 > sg->segs[y].r8; });
     sg->shrink_units.clear();
+    sg->prefill_units.clear();
     sg->expand_units.clear();
+    sg->expand_big_units.clear();
     const int out = pool->out_features;
     auto fill_tokens = [&](Unit &u, const SegRec &r) {
+        u.perm_off = r.tok_start + u.tok0;
         for (int q = 0; q < 16; ++q) u.tok[q] = sg->perm[r.tok_start + u.tok0 + (q < u.ntok ? q : 0)];
     };
-    // counters of the fused launch: one per (group, token tile)
+    // counters of the hand-over of v: one per (group, token tile)
     std::vector<int32_t> sync_base(sg->segs.size(), 0);
     int n_sync = 0;
     for (size_t si = 0; si < sg->segs.size(); ++si) {
@@ -356,37 +369,62 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
         n_sync += (sg->segs[si].ntok + lora::kTokTile - 1) / lora::kTokTile;
     }
     sg->n_sync = n_sync;
+    sg->has_big_units = false;
     for (int32_t si : order) {
         const SegRec &r = sg->segs[si];
+        const bool token_heavy = r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch;
         const int sync_n = ((r.r8 + lora::kRowTile - 1) / lora::kRowTile) * sg->n_k_slices;
-        for (int row0 = 0; row0 < r.r8; row0 += lora::kRowTile)
-            for (int ks = 0; ks < sg->n_k_slices; ++ks)
-                for (int tok0 = 0; tok0 < r.ntok; tok0 += lora::kTokTile) {
-                    Unit u;
-                    memset(&u, 0, sizeof u);
-                    u.seg = si;
-                    u.tok0 = tok0;
-                    u.ntok = std::min(lora::kTokTile, r.ntok - tok0);
-                    u.p0 = row0;
-                    u.pn = std::min(lora::kRowTile, r.r8 - row0);
-                    u.ks = ks;
-                    u.r8 = r.r8;
-                    u.scale = r.scale;
-                    u.w_off = r.a_off + (uint64_t)row0 * pool->in_features;
-                    u.v_off = r.v_off + (int64_t)tok0 * r.r8 + row0;
-                    u.sync_idx = sync_base[si] + tok0 / lora::kTokTile;
-                    u.sync_n = sync_n;
-                    fill_tokens(u, r);
-                    sg->shrink_units.push_back(u);
-                }
-        const int cols = expand_cols_per_unit(r.r8, out);
-        for (int c0 = 0; c0 < out; c0 += cols)
-            for (int tok0 = 0; tok0 < r.ntok; tok0 += lora::kTokTile) {
+        if (token_heavy) {
+            // shrink: tiles of 32 tokens (16 above rank 128), all rank rows, all of k
+            sg->has_big_units = true;
+            const int tile = r.r8 <= 128 ? 32 : 16;
+            for (int tok0 = 0; tok0 < r.ntok; tok0 += tile) {
                 Unit u;
                 memset(&u, 0, sizeof u);
                 u.seg = si;
                 u.tok0 = tok0;
-                u.ntok = std::min(lora::kTokTile, r.ntok - tok0);
+                u.ntok = std::min(tile, r.ntok - tok0);
+                u.p0 = 0;
+                u.pn = r.r8;
+                u.r8 = r.r8;
+                u.scale = r.scale;
+                u.w_off = r.a_off;
+                u.v_off = r.v_off + (int64_t)tok0 * r.r8;
+                fill_tokens(u, r);
+                sg->prefill_units.push_back(u);
+            }
+        } else {
+            for (int row0 = 0; row0 < r.r8; row0 += lora::kRowTile)
+                for (int ks = 0; ks < sg->n_k_slices; ++ks)
+                    for (int tok0 = 0; tok0 < r.ntok; tok0 += lora::kTokTile) {
+                        Unit u;
+                        memset(&u, 0, sizeof u);
+                        u.seg = si;
+                        u.tok0 = tok0;
+                        u.ntok = std::min(lora::kTokTile, r.ntok - tok0);
+                        u.p0 = row0;
+                        u.pn = std::min(lora::kRowTile, r.r8 - row0);
+                        u.ks = ks;
+                        u.r8 = r.r8;
+                        u.scale = r.scale;
+                        u.w_off = r.a_off + (uint64_t)row0 * pool->in_features;
+                        u.v_off = r.v_off + (int64_t)tok0 * r.r8 + row0;
+                        u.sync_idx = sync_base[si] + tok0 / lora::kTokTile;
+                        u.sync_n = sync_n;
+                        fill_tokens(u, r);
+                        sg->shrink_units.push_back(u);
+                    }
+        }
+        // expand: token-heavy groups keep a column pass's weights in registers for 4 token blocks
+        const int cols = expand_cols_per_unit(r.r8, out);
+        const int etile = token_heavy ? kExpandBigTokens : lora::kTokTile;
+        for (int c0 = 0; c0 < out; c0 += cols)
+            for (int tok0 = 0; tok0 < r.ntok; tok0 += etile) {
+                Unit u;
+                memset(&u, 0, sizeof u);
+                u.seg = si;
+                u.tok0 = tok0;
+                u.ntok = std::min(etile, r.ntok - tok0);
                 u.p0 = c0;
                 u.pn = std::min(cols, out - c0);
                 u.r8 = r.r8;
@@ -396,13 +434,16 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                 u.sync_idx = sync_base[si] + tok0 / lora::kTokTile;
                 u.sync_n = sync_n;
                 fill_tokens(u, r);
-                sg->expand_units.push_back(u);
+                (token_heavy ? sg->expand_big_units : sg->expand_units).push_back(u);
             }
     }
 
-    sg->off_shrink = 0;
-    sg->off_expand = round_up_sz(sg->off_shrink + sg->shrink_units.size() * sizeof(Unit), 256);
-    sg->off_sync = round_up_sz(sg->off_expand + sg->expand_units.size() * sizeof(Unit), 256);
+    sg->off_perm = 0;
+    sg->off_shrink = round_up_sz(sg->perm.size() * sizeof(int32_t), 256);
+    sg->off_prefill = round_up_sz(sg->off_shrink + sg->shrink_units.size() * sizeof(Unit), 256);
+    sg->off_expand = round_up_sz(sg->off_prefill + sg->prefill_units.size() * sizeof(Unit), 256);
+    sg->off_expand_big = round_up_sz(sg->off_expand + sg->expand_units.size() * sizeof(Unit), 256);
+    sg->off_sync = round_up_sz(sg->off_expand_big + sg->expand_big_units.size() * sizeof(Unit), 256);
     sg->table_bytes = round_up_sz(sg->off_sync + (size_t)(2 * sg->n_sync + 1) * sizeof(unsigned), 256);
     return LORA_OK;
 }
@@ -513,6 +554,12 @@ extern "C" lora_status_t lora_segments_upload(lora_segments_t *sg, void *stream)
         HIP_TRY(hipMalloc((void **)&sg->dev, cap));
         sg->dev_capacity = cap;
     }
+    if (!sg->perm.empty()) memcpy(sg->staging + sg->off_perm, sg->perm.data(), sg->perm.size() * sizeof(int32_t));
+    if (!sg->expand_big_units.empty())
+        memcpy(sg->staging + sg->off_expand_big, sg->expand_big_units.data(),
+               sg->expand_big_units.size() * sizeof(Unit));
+    if (!sg->prefill_units.empty())
+        memcpy(sg->staging + sg->off_prefill, sg->prefill_units.data(), sg->prefill_units.size() * sizeof(Unit));
     if (!sg->shrink_units.empty())
         memcpy(sg->staging + sg->off_shrink, sg->shrink_units.data(), sg->shrink_units.size() * sizeof(Unit));
     if (!sg->expand_units.empty())
@@ -574,8 +621,8 @@ extern "C" lora_status_t lora_segments_info(const lora_segments_t *sg, lora_segm
     info->n_tokens = sg->T;
     info->n_active = sg->n_active;
     info->n_segments = (int32_t)sg->segs.size();
-    info->n_shrink_units = (int32_t)sg->shrink_units.size();
-    info->n_expand_units = (int32_t)sg->expand_units.size();
+    info->n_shrink_units = (int32_t)(sg->shrink_units.size() + sg->prefill_units.size());
+    info->n_expand_units = (int32_t)(sg->expand_units.size() + sg->expand_big_units.size());
     info->n_k_slices = sg->n_k_slices;
     info->v_floats = sg->v_floats;
     info->weight_bytes = sg->weight_bytes;
@@ -607,8 +654,14 @@ extern "C" lora_status_t lora_segments_export_units(const lora_segments_t *sg, i
                                                     int32_t *expand_units)
 {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
-    if (shrink_units) export_units(sg->shrink_units, shrink_units);
-    if (expand_units) export_units(sg->expand_units, expand_units);
+    if (shrink_units) {
+        export_units(sg->shrink_units, shrink_units);
+        export_units(sg->prefill_units, shrink_units + 6 * sg->shrink_units.size());
+    }
+    if (expand_units) {
+        export_units(sg->expand_units, expand_units);
+        export_units(sg->expand_big_units, expand_units + 6 * sg->expand_units.size());
+    }
     return LORA_OK;
 }
 
@@ -662,12 +715,23 @@ static size_t apply_parts_bytes(const lora_segments *sg)
 }
 static size_t apply_packed_bytes(const lora_segments *sg) { return round_up_sz((size_t)sg->v_floats * 2, 256); }
 
-static lora::LaunchCtx ctx_for(const lora_pool *pool, const lora_segments *sg, bool shrink)
+enum UnitKind { kShrink, kPrefill, kExpand, kExpandBig };
+
+static lora::LaunchCtx ctx_for(const lora_pool *pool, const lora_segments *sg, UnitKind kind)
 {
     lora::LaunchCtx c;
-    c.units = (const Unit *)(sg->dev + (shrink ? sg->off_shrink : sg->off_expand));
+    const size_t off = kind == kShrink    ? sg->off_shrink
+                       : kind == kPrefill ? sg->off_prefill
+                       : kind == kExpand  ? sg->off_expand
+                                          : sg->off_expand_big;
+    const std::vector<Unit> &list = kind == kShrink    ? sg->shrink_units
+                                    : kind == kPrefill ? sg->prefill_units
+                                    : kind == kExpand  ? sg->expand_units
+                                                       : sg->expand_big_units;
+    c.units = (const Unit *)(sg->dev + off);
+    c.perm = (const int32_t *)(sg->dev + sg->off_perm);
     c.arena = pool->arena;
-    c.n_units = (int)(shrink ? sg->shrink_units.size() : sg->expand_units.size());
+    c.n_units = (int)list.size();
     c.in_features = pool->in_features;
     c.out_features = pool->out_features;
     return c;
@@ -710,13 +774,16 @@ extern "C" lora_status_t lora_shrink(const lora_pool_t *pool, const lora_segment
     if (!v || ((uintptr_t)v) % 16) return fail(LORA_ERR_INVALID_ARG, "v is NULL or not 16-byte aligned");
     if ((st = check_workspace(workspace, ws_bytes, partial_bytes(sg))) != LORA_OK) return st;
     hipStream_t s = (hipStream_t)stream;
-    const lora::LaunchCtx c = ctx_for(pool, sg, true);
+    const lora::LaunchCtx c = ctx_for(pool, sg, kShrink), cp = ctx_for(pool, sg, kPrefill);
     if (sg->n_k_slices <= 1) {
         HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, v, 1, 0, nullptr, s));
+        HIP_TRY(lora::launch_shrink_prefill(cp, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, s));
     } else {
         float *parts = (float *)workspace;
         HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, parts, sg->n_k_slices,
                                     sg->v_floats, nullptr, s));
+        HIP_TRY(lora::launch_shrink_prefill(cp, (const uint16_t *)x, ldx, nullptr, nullptr, parts, sg->n_k_slices,
+                                            sg->v_floats, s));
         HIP_TRY(lora::launch_reduce_slices(parts, sg->n_k_slices, sg->v_floats, v, sg->v_floats, s));
     }
     return LORA_OK;
@@ -730,8 +797,10 @@ extern "C" lora_status_t lora_expand(const lora_pool_t *pool, const lora_segment
     if (sg->n_active == 0) return LORA_OK;
     if ((st = check_matrix(y, ldy, pool->out_features, "y")) != LORA_OK) return st;
     if (!v || ((uintptr_t)v) % 16) return fail(LORA_ERR_INVALID_ARG, "v is NULL or not 16-byte aligned");
-    const lora::LaunchCtx c = ctx_for(pool, sg, false);
-    HIP_TRY(lora::launch_expand(c, v, 1, 0, (uint16_t *)y, ldy, nullptr, (hipStream_t)stream));
+    HIP_TRY(lora::launch_expand(ctx_for(pool, sg, kExpand), false, v, 1, 0, (uint16_t *)y, ldy, nullptr,
+                                (hipStream_t)stream));
+    HIP_TRY(lora::launch_expand(ctx_for(pool, sg, kExpandBig), true, v, 1, 0, (uint16_t *)y, ldy, nullptr,
+                                (hipStream_t)stream));
     return LORA_OK;
 }
 
@@ -793,16 +862,21 @@ extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments
     sa.v_lo = (uint16_t *)((char *)workspace + apply_parts_bytes(sg) + apply_packed_bytes(sg));
     sa.epoch = ++msg->launches;
     sa.spin_limit = kSpinLimit;
-    const lora::LaunchCtx cs = ctx_for(pool, sg, true), ce = ctx_for(pool, sg, false);
+    const lora::LaunchCtx cs = ctx_for(pool, sg, kShrink), cp = ctx_for(pool, sg, kPrefill),
+                          ce = ctx_for(pool, sg, kExpand);
     if (ev[0]) HIP_TRY(hipEventRecord(ev[0], s));
-    if (g_fused_apply) {
+    // units of more than 16 tokens span several counters: such batches always take separate launches
+    if (g_fused_apply && !sg->has_big_units) {
         HIP_TRY(lora::launch_apply_fused(cs, ce, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride,
                                          (uint16_t *)y, ldy, &sa, s));
         if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
     } else {
+        HIP_TRY(lora::launch_shrink_prefill(cp, (const uint16_t *)x, ldx, sa.v_hi, sa.v_lo, nullptr, nsl, stride, s));
         HIP_TRY(lora::launch_shrink(cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride, &sa, s));
         if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
-        HIP_TRY(lora::launch_expand(ce, parts, nsl, stride, (uint16_t *)y, ldy, &sa, s));
+        HIP_TRY(lora::launch_expand(ce, false, parts, nsl, stride, (uint16_t *)y, ldy, &sa, s));
+        HIP_TRY(lora::launch_expand(ctx_for(pool, sg, kExpandBig), true, parts, nsl, stride, (uint16_t *)y, ldy, &sa,
+                                    s));
     }
     if (ev[2]) HIP_TRY(hipEventRecord(ev[2], s));
     return LORA_OK;

@@ -29,7 +29,7 @@ struct Unit {
     int64_t v_off;    // float offset of the unit's first v element (shrink: row tok0, column p0;
                       // expand: row tok0, column 0)
     int32_t r8;       // padded rank = row length of v and of B^T
-    int32_t ntok;     // tokens in this unit (1..16)
+    int32_t ntok;     // tokens in this unit: 1..16 (decode units), up to 64 (expand) or 32 (prefill shrink)
     int32_t p0;       // shrink: first rank row; expand: first output column
     int32_t pn;       // shrink: valid rank rows (1..16, multiple of 8 except the tail); expand: columns
     int32_t ks;       // shrink: k-slice index
@@ -38,8 +38,10 @@ struct Unit {
     int32_t tok0;     // first token, relative to the group
     int32_t sync_idx; // counter of this unit's (group, token tile) in a fused launch
     int32_t sync_n;   // shrink units that feed that counter per launch
-    int32_t pad[2];
-    int32_t tok[16];  // batch row index of each token; entries >= ntok repeat tok[0]
+    int32_t perm_off; // position of the unit's first token in the device copy of perm
+    int32_t pad[1];
+    int32_t tok[16];  // batch row index of each token; entries >= ntok repeat tok[0] (units of <= 16
+                      // tokens; larger units read perm[perm_off + i])
 };
 static_assert(sizeof(Unit) == 128, "Unit is 128 bytes");
 
@@ -50,6 +52,7 @@ constexpr int kThreads = 256;  // 4 wavefronts per work group
 
 struct LaunchCtx {
     const Unit *units;
+    const int32_t *perm;
     const uint16_t *arena;
     int n_units;
     int in_features;
@@ -76,8 +79,16 @@ hipError_t launch_shrink(const LaunchCtx &c, const uint16_t *x, int64_t ldx, int
 
 // Without `sync`: v_in holds n_slices fp32 partial sums slice_stride floats apart (n_slices = 1: v
 // itself).  With `sync`: v comes from sync->v_hi / v_lo (written by a shrink launch of the same epoch).
-hipError_t launch_expand(const LaunchCtx &c, const float *v_in, int n_slices, int64_t slice_stride,
+// `big`: the list holds units of up to 64 tokens (token indices through perm).
+hipError_t launch_expand(const LaunchCtx &c, bool big, const float *v_in, int n_slices, int64_t slice_stride,
                          uint16_t *y, int64_t ldy, const SyncArgs *sync, hipStream_t stream);
+
+// Shrink of token-heavy groups: one unit = (group, up to 32 tokens, all rank rows, the whole of k).
+// Writes complete v: as bf16 hi + lo into v_hi / v_lo, or (v_f32 != NULL) as fp32 into v_f32 with the
+// other n_slices - 1 slices of the same rows set to zero.
+hipError_t launch_shrink_prefill(const LaunchCtx &c, const uint16_t *x, int64_t ldx, uint16_t *v_hi,
+                                 uint16_t *v_lo, float *v_f32, int n_slices, int64_t slice_stride,
+                                 hipStream_t stream);
 
 // Both halves in one launch (shrink units first); the expand units poll `ready` of their token tile,
 // at most spin_limit times each.

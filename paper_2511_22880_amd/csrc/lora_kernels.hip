@@ -260,6 +260,175 @@ static __device__ __forceinline__ void shrink_body(const Unit &u, const uint16_t
 }
 
 // ------------------------------------------------------------------------------------------------
+// shrink of token-heavy groups (prefill): one unit = (group, 16*TB tokens, all rank rows, all of k).
+// The four wavefronts split k into quarters; each streams its quarter of the tokens' x rows exactly
+// once, 16 bytes per lane straight into the MFMA's token operand, XD steps ahead (x comes from
+// HBM).  The rows of A^T come from L2 (every token tile of the group re-reads them), one step
+// ahead, and are shared by the TB token blocks in registers.  The four partial tiles are summed
+// through LDS in a fixed order (3+1, 2+0, then 1+0) and v leaves complete: as bf16 hi + lo for the
+// expand, or as fp32.  JB = 16-row blocks of A^T (padded rank / 16 rounded up to 1, 2, 4, 8, 16).
+// ------------------------------------------------------------------------------------------------
+constexpr int kPrefillLds = 2 * 16 * 64 * 16;  // two wavefronts' worth of up to 16 accumulator tiles
+
+template <int JB, int TB>
+static __device__ __forceinline__ void shrink_prefill_body(const Unit &u, const int32_t *__restrict__ perm,
+                                                           const uint16_t *__restrict__ arena,
+                                                           const uint16_t *__restrict__ x, int64_t ldx, int in,
+                                                           uint16_t *__restrict__ v_hi, uint16_t *__restrict__ v_lo,
+                                                           float *__restrict__ v_f32, int n_slices,
+                                                           int64_t slice_stride, char *lds)
+{
+    constexpr int XD = 4;
+    constexpr int NT = JB * TB;
+    static_assert(NT <= 16, "accumulator tiles per wavefront");
+    f32x4(*red)[NT][64] = reinterpret_cast<f32x4(*)[NT][64]>(lds);
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int n = lane & 15;
+    const int kq = lane >> 4;
+    const int r8 = u.r8;
+    const int ntok = u.ntok;
+    const uint4 zero = {0u, 0u, 0u, 0u};
+
+    const uint16_t *xrow[TB];
+    bool t_ok[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        const int t = 16 * tb + n;
+        t_ok[tb] = t < ntok;
+        xrow[tb] = x + (int64_t)perm[u.perm_off + (t_ok[tb] ? t : 0)] * ldx + 8 * kq;
+    }
+    const uint16_t *wbase = arena + u.w_off + 8 * kq;
+    int woff[JB];  // element offset of this lane's row in block jb (rows beyond the rank read row r8-1, then zeroed)
+    bool w_ok[JB];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+        const int j = 16 * jb + n;
+        w_ok[jb] = j < r8;
+        woff[jb] = (w_ok[jb] ? j : r8 - 1) * in;
+    }
+
+    f32x4 acc[JB][TB];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) acc[jb][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // this wavefront's quarter of k
+    const int kquarter = ((in + 3) / 4 + 31) & ~31;
+    const int kbeg = wave * kquarter;
+    const int kend = min(in, kbeg + kquarter);
+
+    uint4 xq[XD][TB], w[JB];
+#pragma unroll
+    for (int d = 0; d < XD; ++d)
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) xq[d][tb] = (kbeg + 32 * d < kend) ? ld16(xrow[tb] + kbeg + 32 * d) : zero;
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) w[jb] = (16 * jb < r8 && kbeg < kend) ? ld16(wbase + woff[jb] + kbeg) : zero;
+
+    for (int k0 = kbeg; k0 < kend; k0 += 32 * XD) {
+#pragma unroll
+        for (int d = 0; d < XD; ++d) {
+            const int k = k0 + 32 * d;
+            if (k < kend) {
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb) {
+                    if (16 * jb < r8) {
+                        const bf16x8 ww = as_bf16x8(w_ok[jb] ? w[jb] : zero);
+#pragma unroll
+                        for (int tb = 0; tb < TB; ++tb)
+                            acc[jb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                ww, as_bf16x8(t_ok[tb] ? xq[d][tb] : zero), acc[jb][tb], 0, 0, 0);
+                        if (k + 32 < kend) w[jb] = ld16(wbase + woff[jb] + k + 32);
+                    }
+                }
+                if (k + 32 * XD < kend) {
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb) xq[d][tb] = ld16(xrow[tb] + k + 32 * XD);
+                }
+            }
+        }
+    }
+
+    // sum the four k-quarters: (wave 2 -> 0, wave 3 -> 1), then (wave 1 -> 0)
+    if (wave >= 2) {
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) red[wave - 2][jb * TB + tb][lane] = acc[jb][tb];
+    }
+    __syncthreads();
+    if (wave < 2) {
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) acc[jb][tb] += red[wave][jb * TB + tb][lane];
+    }
+    __syncthreads();
+    if (wave == 1) {
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) red[0][jb * TB + tb][lane] = acc[jb][tb];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+
+    // lane (n, kq) holds, for token block tb and row block jb, v[token n][16*jb + 4*kq + e]
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        if (!t_ok[tb]) continue;
+        const int64_t row = u.v_off + (int64_t)(16 * tb + n) * r8;
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) {
+            const int j = 16 * jb + 4 * kq;
+            if (j < r8) {
+                const f32x4 f = acc[jb][tb] + red[0][jb * TB + tb][lane];
+                if (v_f32) {
+                    *reinterpret_cast<f32x4 *>(v_f32 + row + j) = f;
+                    for (int sl = 1; sl < n_slices; ++sl)
+                        *reinterpret_cast<f32x4 *>(v_f32 + (int64_t)sl * slice_stride + row + j) =
+                            f32x4{0.f, 0.f, 0.f, 0.f};
+                } else {
+                    uint2 h, l;
+                    h.x = pack_bf16_rne(f[0], f[1]);
+                    h.y = pack_bf16_rne(f[2], f[3]);
+                    l.x = pack_bf16_rne(f[0] - bf16_bits_to_f32(h.x & 0xFFFFu), f[1] - __uint_as_float(h.x & 0xFFFF0000u));
+                    l.y = pack_bf16_rne(f[2] - bf16_bits_to_f32(h.y & 0xFFFFu), f[3] - __uint_as_float(h.y & 0xFFFF0000u));
+                    *reinterpret_cast<uint2 *>(v_hi + row + j) = h;
+                    *reinterpret_cast<uint2 *>(v_lo + row + j) = l;
+                }
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads, 2) void k_shrink_prefill(const Unit *__restrict__ units,
+                                                                const int32_t *__restrict__ perm,
+                                                                const uint16_t *__restrict__ arena,
+                                                                const uint16_t *__restrict__ x, int64_t ldx, int in,
+                                                                uint16_t *__restrict__ v_hi,
+                                                                uint16_t *__restrict__ v_lo,
+                                                                float *__restrict__ v_f32, int n_slices,
+                                                                int64_t slice_stride)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kPrefillLds];
+    const Unit &u = units[blockIdx.x];
+    const int r8 = u.r8;
+    if (r8 <= 16)
+        shrink_prefill_body<1, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    else if (r8 <= 32)
+        shrink_prefill_body<2, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    else if (r8 <= 64)
+        shrink_prefill_body<4, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    else if (r8 <= 128)
+        shrink_prefill_body<8, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    else
+        shrink_prefill_body<16, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+}
+
+// ------------------------------------------------------------------------------------------------
 // expand: one unit = (group, <=16 tokens, a run of output columns made of 128-column strips).
 // MFMA orientation: tokens down (operand from v), output columns across (operand straight from
 // 16-byte loads of B^T rows).  Inside a strip, MFMA b (0..7) takes column 8*n + b for its column
@@ -290,9 +459,11 @@ static __device__ __forceinline__ void load_v_operand(const float *__restrict__ 
     vlo = as_bf16x8(pl);
 }
 
-// KSTEPS: 32-wide steps that cover the padded rank (1, 2, 4 or 8).
-template <int KSTEPS>
-static __device__ __forceinline__ void expand_body(const Unit &u, const uint16_t *__restrict__ arena,
+// KSTEPS: 32-wide steps that cover the padded rank (1, 2, 4 or 8).  A unit may hold several blocks
+// of 16 tokens; the weights of a column pass stay in registers while the token blocks go by.
+template <int KSTEPS, bool BIG, bool VF32>
+static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t *__restrict__ perm,
+                                                   const uint16_t *__restrict__ arena,
                                                    const float *__restrict__ v_in, int n_slices,
                                                    int64_t slice_stride, uint16_t *__restrict__ y,
                                                    int64_t ldy, char *lds, const Sync &sy)
@@ -307,17 +478,16 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const uint16_t
     const int n = lane & 15;
     const int kq = lane >> 4;
     const int r8 = u.r8;
-    const int ntok = u.ntok;
+    const int ntok_all = u.ntok;
     const int ncols = u.pn;
     const uint4 zero = {0u, 0u, 0u, 0u};
     const int my_strip = wave / P;
     const int my_part = wave % P;
+    const int32_t *toks = BIG ? perm + u.perm_off : u.tok;
 
-    // epilogue role of this thread: token e_tok, 8 columns starting at 8*e_cg of every strip
+    // epilogue role of this thread: token e_tok of the block, 8 columns starting at 8*e_cg of every strip
     const int e_tok = tid >> 4;
     const int e_cg = tid & 15;
-    const bool e_ok = e_tok < ntok;
-    uint16_t *e_y = y + (int64_t)u.tok[e_ok ? e_tok : 0] * ldy + u.p0 + 8 * e_cg;
     const float scale = u.scale;
 
     int jc[ITEMS];
@@ -328,119 +498,148 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const uint16_t
         j_ok[it] = j < r8;
         jc[it] = j_ok[it] ? j : 0;
     }
-    bf16x8 vhi[ITEMS], vlo[ITEMS];
+    bool first = true;
 
     for (int c0 = 0; c0 < ncols; c0 += S * kStrip) {
         const int cs = c0 + my_strip * kStrip;  // this wavefront's strip
         const bool strip_ok = cs < ncols;
         const uint16_t *brow = arena + u.w_off + (int64_t)((strip_ok ? cs : 0) + 8 * n) * r8;
-        // first k step's weights: row (column of y) cs + 8*n + b, 16 bytes at jc
+        // weights: row (column of y) cs + 8*n + b, 16 bytes at jc.  One k step per wavefront: they stay
+        // in registers for all token blocks; two (rank > 128): each block re-reads them (L1 / L2 hits).
         uint4 w[8];
+        if (ITEMS == 1) {
 #pragma unroll
-        for (int b = 0; b < 8; ++b) w[b] = ld16(brow + (int64_t)b * r8 + jc[0]);
-        // y of this thread's epilogue share
-        uint4 yv[S];
-#pragma unroll
-        for (int s = 0; s < S; ++s)
-            yv[s] = (e_ok && c0 + s * kStrip < ncols) ? *reinterpret_cast<const uint4 *>(e_y + c0 + s * kStrip) : zero;
+            for (int b = 0; b < 8; ++b) w[b] = ld16(brow + (int64_t)b * r8 + jc[0]);
+        }
 
-        if (c0 == 0) {
-            // the weights above are in flight; now v has to be there
-            if (sy.counters && sy.wait) wait_for(sy, u.sync_idx);
+        // one block of 16 tokens: this thread's share of y and this wavefront's v operand
+        struct Blk {
+            uint4 yv[S];
+            uint4 vh[ITEMS], vl[ITEMS];
+            uint16_t *e_y;
+            int ntok;
+        };
+        auto load_blk = [&](int t0, Blk &bk) {
+            bk.ntok = min(kTokTile, ntok_all - t0);
+            const bool e_ok = e_tok < bk.ntok;
+            bk.e_y = y + (int64_t)toks[e_ok ? t0 + e_tok : 0] * ldy + u.p0 + 8 * e_cg;
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+                bk.yv[s] = (e_ok && c0 + s * kStrip < ncols)
+                               ? *reinterpret_cast<const uint4 *>(bk.e_y + c0 + s * kStrip)
+                               : zero;
 #pragma unroll
             for (int it = 0; it < ITEMS; ++it) {
-                const bool ok = (n < ntok) && j_ok[it];
-                const int64_t off = u.v_off + (int64_t)(ok ? n : 0) * r8 + jc[it];
-                if (sy.counters) {
-                    const uint4 ph = ld_through_u16x8(sy.v_hi + off);
-                    const uint4 pl = ld_through_u16x8(sy.v_lo + off);
-                    vhi[it] = as_bf16x8(ok ? ph : zero);
-                    vlo[it] = as_bf16x8(ok ? pl : zero);
-                } else {
-                    load_v_operand(v_in + off, ok, n_slices, slice_stride, vhi[it], vlo[it]);
-                }
-            }
-        } else {
-            __syncthreads();  // the previous pass's partial tiles have been consumed
-        }
-
-        f32x4 acc[8];
-#pragma unroll
-        for (int b = 0; b < 8; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int it = 0; it < ITEMS; ++it) {
-            uint4 wn[8];
-            if (it + 1 < ITEMS) {
-#pragma unroll
-                for (int b = 0; b < 8; ++b) wn[b] = ld16(brow + (int64_t)b * r8 + jc[it + 1 < ITEMS ? it + 1 : 0]);
-            }
-#pragma unroll
-            for (int b = 0; b < 8; ++b) {
-                const bf16x8 ww = as_bf16x8(j_ok[it] ? w[b] : zero);
-                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vhi[it], ww, acc[b], 0, 0, 0);
-                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vlo[it], ww, acc[b], 0, 0, 0);
-            }
-            if (it + 1 < ITEMS) {
-#pragma unroll
-                for (int b = 0; b < 8; ++b) w[b] = wn[b];
-            }
-        }
-        if (strip_ok) {
-            // lane (n, kq) holds tokens 4*kq + e, columns 8*n + b
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int tok = 4 * kq + e;
-                if (tok < ntok) {
-                    const f32x4 lo = {acc[0][e], acc[1][e], acc[2][e], acc[3][e]};
-                    const f32x4 hi = {acc[4][e], acc[5][e], acc[6][e], acc[7][e]};
-                    *reinterpret_cast<f32x4 *>(&part[wave][tok][8 * n]) = lo;
-                    *reinterpret_cast<f32x4 *>(&part[wave][tok][8 * n + 4]) = hi;
-                }
-            }
-        }
-        __syncthreads();
-        if (e_ok) {
-#pragma unroll
-            for (int s = 0; s < S; ++s) {
-                if (c0 + s * kStrip < ncols) {
-                    f32x4 d0 = *reinterpret_cast<const f32x4 *>(&part[s * P][e_tok][8 * e_cg]);
-                    f32x4 d1 = *reinterpret_cast<const f32x4 *>(&part[s * P][e_tok][8 * e_cg + 4]);
-#pragma unroll
-                    for (int p = 1; p < P; ++p) {
-                        d0 += *reinterpret_cast<const f32x4 *>(&part[s * P + p][e_tok][8 * e_cg]);
-                        d1 += *reinterpret_cast<const f32x4 *>(&part[s * P + p][e_tok][8 * e_cg + 4]);
+                const bool ok = (n < bk.ntok) && j_ok[it];
+                const int64_t off = u.v_off + (int64_t)(ok ? t0 + n : 0) * r8 + jc[it];
+                uint4 ph, pl;
+                if (!VF32) {
+                    if (!BIG && sy.wait) {  // written earlier in this very launch: read through to memory
+                        ph = ld_through_u16x8(sy.v_hi + off);
+                        pl = ld_through_u16x8(sy.v_lo + off);
+                    } else {
+                        ph = ld16(sy.v_hi + off);
+                        pl = ld16(sy.v_lo + off);
                     }
-                    const uint4 yy = yv[s];
-                    uint4 o;
-                    o.x = pack_bf16_rne(bf16_bits_to_f32(yy.x & 0xFFFFu) + scale * d0[0],
-                                        __uint_as_float(yy.x & 0xFFFF0000u) + scale * d0[1]);
-                    o.y = pack_bf16_rne(bf16_bits_to_f32(yy.y & 0xFFFFu) + scale * d0[2],
-                                        __uint_as_float(yy.y & 0xFFFF0000u) + scale * d0[3]);
-                    o.z = pack_bf16_rne(bf16_bits_to_f32(yy.z & 0xFFFFu) + scale * d1[0],
-                                        __uint_as_float(yy.z & 0xFFFF0000u) + scale * d1[1]);
-                    o.w = pack_bf16_rne(bf16_bits_to_f32(yy.w & 0xFFFFu) + scale * d1[2],
-                                        __uint_as_float(yy.w & 0xFFFF0000u) + scale * d1[3]);
-                    *reinterpret_cast<uint4 *>(e_y + c0 + s * kStrip) = o;
+                } else {
+                    bf16x8 h, l;
+                    load_v_operand(v_in + off, ok, n_slices, slice_stride, h, l);
+                    ph = __builtin_bit_cast(uint4, h);
+                    pl = __builtin_bit_cast(uint4, l);
+                }
+                bk.vh[it] = ok ? ph : zero;
+                bk.vl[it] = ok ? pl : zero;
+            }
+        };
+
+        if (!BIG && !VF32 && first && sy.counters && sy.wait) wait_for(sy, u.sync_idx);  // weights are in flight
+        Blk cur, nxt;
+        load_blk(0, cur);
+        for (int t0 = 0; t0 < ntok_all; t0 += kTokTile) {
+            const bool has_next = BIG && t0 + kTokTile < ntok_all;
+            if (has_next) load_blk(t0 + kTokTile, nxt);  // next block's y and v travel while this one computes
+            if (!first) __syncthreads();                 // the previous block's partial tiles have been consumed
+            first = false;
+            const int ntok = cur.ntok;
+            const bool e_ok = e_tok < ntok;
+
+            f32x4 acc[8];
+#pragma unroll
+            for (int b = 0; b < 8; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int it = 0; it < ITEMS; ++it) {
+                if (ITEMS > 1) {
+#pragma unroll
+                    for (int b = 0; b < 8; ++b) w[b] = ld16(brow + (int64_t)b * r8 + jc[it]);
+                }
+#pragma unroll
+                for (int b = 0; b < 8; ++b) {
+                    const bf16x8 ww = as_bf16x8(j_ok[it] ? w[b] : zero);
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur.vh[it]), ww, acc[b], 0, 0, 0);
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur.vl[it]), ww, acc[b], 0, 0, 0);
                 }
             }
+            if (strip_ok) {
+                // lane (n, kq) holds tokens 4*kq + e, columns 8*n + b
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int tok = 4 * kq + e;
+                    if (tok < ntok) {
+                        const f32x4 lo = {acc[0][e], acc[1][e], acc[2][e], acc[3][e]};
+                        const f32x4 hi = {acc[4][e], acc[5][e], acc[6][e], acc[7][e]};
+                        *reinterpret_cast<f32x4 *>(&part[wave][tok][8 * n]) = lo;
+                        *reinterpret_cast<f32x4 *>(&part[wave][tok][8 * n + 4]) = hi;
+                    }
+                }
+            }
+            __syncthreads();
+            if (e_ok) {
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    if (c0 + s * kStrip < ncols) {
+                        f32x4 d0 = *reinterpret_cast<const f32x4 *>(&part[s * P][e_tok][8 * e_cg]);
+                        f32x4 d1 = *reinterpret_cast<const f32x4 *>(&part[s * P][e_tok][8 * e_cg + 4]);
+#pragma unroll
+                        for (int p = 1; p < P; ++p) {
+                            d0 += *reinterpret_cast<const f32x4 *>(&part[s * P + p][e_tok][8 * e_cg]);
+                            d1 += *reinterpret_cast<const f32x4 *>(&part[s * P + p][e_tok][8 * e_cg + 4]);
+                        }
+                        const uint4 yy = cur.yv[s];
+                        uint4 o;
+                        o.x = pack_bf16_rne(bf16_bits_to_f32(yy.x & 0xFFFFu) + scale * d0[0],
+                                            __uint_as_float(yy.x & 0xFFFF0000u) + scale * d0[1]);
+                        o.y = pack_bf16_rne(bf16_bits_to_f32(yy.y & 0xFFFFu) + scale * d0[2],
+                                            __uint_as_float(yy.y & 0xFFFF0000u) + scale * d0[3]);
+                        o.z = pack_bf16_rne(bf16_bits_to_f32(yy.z & 0xFFFFu) + scale * d1[0],
+                                            __uint_as_float(yy.z & 0xFFFF0000u) + scale * d1[1]);
+                        o.w = pack_bf16_rne(bf16_bits_to_f32(yy.w & 0xFFFFu) + scale * d1[2],
+                                            __uint_as_float(yy.w & 0xFFFF0000u) + scale * d1[3]);
+                        *reinterpret_cast<uint4 *>(cur.e_y + c0 + s * kStrip) = o;
+                    }
+                }
+            }
+            if (has_next) cur = nxt;
+            if (!BIG) break;  // units of the small kind hold one block
         }
     }
 }
 
-static __device__ __forceinline__ void expand_dispatch(const Unit &u, const uint16_t *__restrict__ arena,
+template <bool BIG, bool VF32>
+static __device__ __forceinline__ void expand_dispatch(const Unit &u, const int32_t *__restrict__ perm,
+                                                       const uint16_t *__restrict__ arena,
                                                        const float *__restrict__ v_in, int n_slices,
                                                        int64_t slice_stride, uint16_t *__restrict__ y,
                                                        int64_t ldy, char *lds, const Sync &sy)
 {
     const int r8 = u.r8;
     if (r8 <= 32)
-        expand_body<1>(u, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+        expand_body<1, BIG, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
     else if (r8 <= 64)
-        expand_body<2>(u, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+        expand_body<2, BIG, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
     else if (r8 <= 128)
-        expand_body<4>(u, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+        expand_body<4, BIG, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
     else
-        expand_body<8>(u, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+        expand_body<8, BIG, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
 }
 
 constexpr int kFusedLds = kShrinkLds > kExpandLds ? kShrinkLds : kExpandLds;
@@ -455,20 +654,25 @@ __global__ __launch_bounds__(kThreads) void k_shrink(const Unit *__restrict__ un
     shrink_body(units[blockIdx.x], arena, x, ldx, in, k_slice_len, v_out, n_slices, slice_stride, lds, sy);
 }
 
-__global__ __launch_bounds__(kThreads, 4) void k_expand(const Unit *__restrict__ units,
-                                                     const uint16_t *__restrict__ arena,
-                                                     const float *__restrict__ v_in, int n_slices,
-                                                     int64_t slice_stride, uint16_t *__restrict__ y,
-                                                     int64_t ldy, Sync sy)
+// BIG: units of up to 64 tokens (token-heavy groups), token indices from perm, the next token block's
+// loads in flight while the current one computes.  VF32: v is fp32 from the caller (stand-alone expand).
+template <bool BIG, bool VF32>
+__global__ __launch_bounds__(kThreads, BIG ? 2 : 4) void k_expand(const Unit *__restrict__ units,
+                                                                  const int32_t *__restrict__ perm,
+                                                                  const uint16_t *__restrict__ arena,
+                                                                  const float *__restrict__ v_in, int n_slices,
+                                                                  int64_t slice_stride, uint16_t *__restrict__ y,
+                                                                  int64_t ldy, Sync sy)
 {
     __shared__ __attribute__((aligned(16))) char lds[kExpandLds];
-    expand_dispatch(units[blockIdx.x], arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+    expand_dispatch<BIG, VF32>(units[blockIdx.x], perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
 }
 
 // Both halves in one launch: blocks [0, n_shrink) are shrink units, the rest expand units that wait
 // for their tokens' v through the counters.
 __global__ __launch_bounds__(kThreads, 4) void k_apply_fused(const Unit *__restrict__ shrink_units, int n_shrink,
                                                           const Unit *__restrict__ expand_units,
+                                                          const int32_t *__restrict__ perm,
                                                           const uint16_t *__restrict__ arena,
                                                           const uint16_t *__restrict__ x, int64_t ldx, int in,
                                                           int k_slice_len, float *__restrict__ parts, int n_slices,
@@ -480,7 +684,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_apply_fused(const Unit *__restr
     if (b < n_shrink)
         shrink_body(shrink_units[b], arena, x, ldx, in, k_slice_len, parts, n_slices, slice_stride, lds, sy);
     else
-        expand_dispatch(expand_units[b - n_shrink], arena, parts, n_slices, slice_stride, y, ldy, lds, sy);
+        expand_dispatch<false, false>(expand_units[b - n_shrink], perm, arena, parts, n_slices, slice_stride, y, ldy,
+                                      lds, sy);
 }
 
 __global__ __launch_bounds__(256) void k_reduce_slices(const float *__restrict__ parts, int n_slices,
@@ -528,12 +733,24 @@ hipError_t launch_shrink(const LaunchCtx &c, const uint16_t *x, int64_t ldx, int
     return hipGetLastError();
 }
 
-hipError_t launch_expand(const LaunchCtx &c, const float *v_in, int n_slices, int64_t slice_stride, uint16_t *y,
-                         int64_t ldy, const SyncArgs *sync, hipStream_t stream)
+hipError_t launch_expand(const LaunchCtx &c, bool big, const float *v_in, int n_slices, int64_t slice_stride,
+                         uint16_t *y, int64_t ldy, const SyncArgs *sync, hipStream_t stream)
 {
     if (c.n_units <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_expand, dim3(c.n_units), dim3(kThreads), 0, stream, c.units, c.arena, v_in, n_slices,
-                       slice_stride, y, ldy, make_sync(sync, 0));
+    const Sync sy = make_sync(sync, 0);
+    const dim3 g(c.n_units), b(kThreads);
+    if (big && sync)
+        hipLaunchKernelGGL((k_expand<true, false>), g, b, 0, stream, c.units, c.perm, c.arena, v_in, n_slices,
+                           slice_stride, y, ldy, sy);
+    else if (big)
+        hipLaunchKernelGGL((k_expand<true, true>), g, b, 0, stream, c.units, c.perm, c.arena, v_in, n_slices,
+                           slice_stride, y, ldy, sy);
+    else if (sync)
+        hipLaunchKernelGGL((k_expand<false, false>), g, b, 0, stream, c.units, c.perm, c.arena, v_in, n_slices,
+                           slice_stride, y, ldy, sy);
+    else
+        hipLaunchKernelGGL((k_expand<false, true>), g, b, 0, stream, c.units, c.perm, c.arena, v_in, n_slices,
+                           slice_stride, y, ldy, sy);
     return hipGetLastError();
 }
 
@@ -544,8 +761,18 @@ hipError_t launch_apply_fused(const LaunchCtx &cs, const LaunchCtx &ce, const ui
     const int total = cs.n_units + ce.n_units;
     if (total <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_apply_fused, dim3(total), dim3(kThreads), 0, stream, cs.units, cs.n_units, ce.units,
-                       cs.arena, x, ldx, cs.in_features, k_slice_len, parts, n_slices, slice_stride, y, ldy,
+                       ce.perm, cs.arena, x, ldx, cs.in_features, k_slice_len, parts, n_slices, slice_stride, y, ldy,
                        make_sync(sync, 1));
+    return hipGetLastError();
+}
+
+hipError_t launch_shrink_prefill(const LaunchCtx &c, const uint16_t *x, int64_t ldx, uint16_t *v_hi,
+                                 uint16_t *v_lo, float *v_f32, int n_slices, int64_t slice_stride,
+                                 hipStream_t stream)
+{
+    if (c.n_units <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_shrink_prefill, dim3(c.n_units), dim3(kThreads), 0, stream, c.units, c.perm, c.arena, x,
+                       ldx, c.in_features, v_hi, v_lo, v_f32, n_slices, slice_stride);
     return hipGetLastError();
 }
 

@@ -121,8 +121,31 @@ def _repeated_on_one_table():
     dp.close()
 
 
-def test_shrink_and_expand_separately():
-    b = wl.small_mixed(seed=1)
+def test_token_heavy_batches_small():
+    """Batches of >= 1024 tokens with groups of >= 32 tokens take the token-tile shrink and the
+    64-token expand units; sized so the oracle finishes in seconds, with ragged tiles (lengths that
+    are no multiple of 16, 64 or 128), every rank bucket, and decode tokens mixed in."""
+    b = wl.cfg2_prefill(0, length_scale=0.08)
+    b.in_features, b.out_features = 1024, 640
+    assert b.T >= 1024
+    _full_parity(b)
+    b3 = wl.cfg3_stack(layer=1, projection=1, length_scale=0.12)   # k_proj: 4096 -> 1024
+    b3.in_features = 512
+    assert b3.T >= 1024
+    _full_parity(b3, y0_kind="small")
+    big = wl.small_mixed(seed=8, in_features=576, out_features=384, ranks=(1, 3, 4, 8, 12, 16, 24, 40, 100, 128, 200, 256),
+                         decode_tokens=45, prefill_lens=(33, 130, 257, 64, 700, 31, 129))
+    _full_parity(big)
+
+
+@pytest.mark.parametrize("big", [False, True])
+def test_shrink_and_expand_separately(big):
+    if big:
+        b = wl.small_mixed(seed=9, in_features=576, out_features=384, decode_tokens=40,
+                           prefill_lens=(200, 470, 33, 350, 17))
+        assert b.T >= 1024
+    else:
+        b = wl.small_mixed(seed=1)
     dp = G.DevicePool(b)
     x_bits = b.x_bits()
     seg = L.lora_segments_build(dp.pool, b.token_adapter)
@@ -146,7 +169,9 @@ def test_shrink_and_expand_separately():
         assert not row[r:].any(), "padding entries of v must be zero"
         err = np.linalg.norm(row[:r] - v_ref[t, :r]) / np.linalg.norm(v_ref[t, :r])
         worst = max(worst, err)
-    assert worst < 1e-5, worst  # fp32 accumulation of exact bf16 products
+    # fp32 accumulation of exact bf16 products: error ~ sqrt(in) * 2^-24 * sum|terms| / |sum|, which a
+    # rank-1 row with cancellation can push to a few 1e-5
+    assert worst < 2e-4, worst
     # expand from the oracle's v (rounded to fp32), into y0 = 0
     v_in = np.zeros(max(info["v_floats"], 1), dtype=np.float32)
     for t in range(b.T):

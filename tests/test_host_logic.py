@@ -150,7 +150,8 @@ def brute_force_groups(ta):
 
 @pytest.mark.parametrize("maker", [
     lambda: wl.cfg0_tiny(), lambda: wl.cfg1_decode(), lambda: wl.small_mixed(),
-    lambda: wl.cfg4_skew(0, "9:1"), lambda: wl.cfg3_stack(length_scale=0.05),
+    lambda: wl.cfg4_skew(0, "9:1"), lambda: wl.cfg3_stack(length_scale=0.05), lambda: wl.cfg3_stack(length_scale=0.3),
+    lambda: wl.cfg2_prefill(0, length_scale=0.1),
 ])
 def test_planner_matches_brute_force_grouping(maker):
     b = maker()
@@ -182,13 +183,18 @@ def test_planner_matches_brute_force_grouping(maker):
     for s, a in enumerate(ex["seg_adapter"]):
         ntok, rr = len(groups[int(a)]), int(r8[a])
         cover = np.zeros((ntok, rr, nsl), dtype=np.int32)
+        token_heavy = ntok >= 32 and info["n_active"] >= 1024
         for seg_i, tok0, nt, p0, pn, ks in units["shrink"][units["shrink"][:, 0] == s]:
-            assert 1 <= nt <= 16 and 1 <= pn <= 16
-            cover[tok0:tok0 + nt, p0:p0 + pn, ks] += 1
+            if token_heavy:       # token tiles: all rank rows, all of k
+                assert 1 <= nt <= 32 and (p0, pn, ks) == (0, rr, 0)
+                cover[tok0:tok0 + nt, :, :] += 1
+            else:
+                assert 1 <= nt <= 16 and 1 <= pn <= 16
+                cover[tok0:tok0 + nt, p0:p0 + pn, ks] += 1
         assert np.all(cover == 1)
         ecover = np.zeros((ntok, b.out_features), dtype=np.int32)
         for seg_i, tok0, nt, p0, pn, ks in units["expand"][units["expand"][:, 0] == s]:
-            assert pn % 128 == 0 and 1 <= nt <= 16
+            assert pn % 128 == 0 and 1 <= nt <= (64 if token_heavy else 16)
             ecover[tok0:tok0 + nt, p0:p0 + pn] += 1
         assert np.all(ecover == 1)
     # no unit's size depends on another adapter's rank: expand bytes per unit bounded by its own rank
