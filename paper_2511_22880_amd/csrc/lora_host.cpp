@@ -194,8 +194,7 @@ extern "C" lora_status_t lora_pool_load(lora_pool_t *pool, int32_t adapter, cons
     uint16_t *dstB = pool->arena + pool->b_off[adapter];
     const size_t nA = (size_t)in * r, nB = (size_t)r * out;
     if (src_is_device) {
-        HIP_TRY(lora::launch_pack_transpose((const uint16_t *)A, in, r, dstA, r8, in, s));
-        HIP_TRY(lora::launch_pack_transpose((const uint16_t *)B, r, out, dstB, out, r8, s));
+        HIP_TRY(lora::launch_pack_adapter((const uint16_t *)A, (const uint16_t *)B, in, out, r, r8, dstA, dstB, s));
     } else {
         uint16_t *tmp = nullptr;
         hipError_t e = hipMalloc((void **)&tmp, (nA + nB) * 2);
@@ -204,8 +203,7 @@ extern "C" lora_status_t lora_pool_load(lora_pool_t *pool, int32_t adapter, cons
         do {
             if ((e = hipMemcpyAsync(tmp, A, nA * 2, hipMemcpyHostToDevice, s)) != hipSuccess) break;
             if ((e = hipMemcpyAsync(tmp + nA, B, nB * 2, hipMemcpyHostToDevice, s)) != hipSuccess) break;
-            if ((e = lora::launch_pack_transpose(tmp, in, r, dstA, r8, in, s)) != hipSuccess) break;
-            if ((e = lora::launch_pack_transpose(tmp + nA, r, out, dstB, out, r8, s)) != hipSuccess) break;
+            if ((e = lora::launch_pack_adapter(tmp, tmp + nA, in, out, r, r8, dstA, dstB, s)) != hipSuccess) break;
             e = hipStreamSynchronize(s);
         } while (0);
         if (e != hipSuccess) st = hip_fail(e, "lora_pool_load copy/pack");

@@ -100,10 +100,9 @@ hipError_t launch_apply_fused(const LaunchCtx &shrink, const LaunchCtx &expand, 
 hipError_t launch_reduce_slices(const float *parts, int n_slices, int64_t slice_stride, float *v,
                                 int64_t n, hipStream_t stream);
 
-// dst[p][q] = q_src_valid ? src[q * src_ld + p] : 0 for p < P, q < Q; used to write A^T (P = r8,
-// Q = in, src = A [in][r], rows p >= r zero) and B^T (P = out, Q = r8, src = B [r][out], columns
-// q >= r zero).
-hipError_t launch_pack_transpose(const uint16_t *src, int src_rows, int src_cols, uint16_t *dst, int P,
-                                 int Q, hipStream_t stream);
+// Writes adapter (A [in][r], B [r][out], row-major bf16, device memory) in the pool's packed,
+// MFMA-operand-major form: dst_a gets r8*in elements, dst_b out*r8.
+hipError_t launch_pack_adapter(const uint16_t *A, const uint16_t *B, int in, int out, int r, int r8,
+                               uint16_t *dst_a, uint16_t *dst_b, hipStream_t stream);
 
 }  // namespace lora

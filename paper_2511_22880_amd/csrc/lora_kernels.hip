@@ -1,11 +1,17 @@
 // gfx950 kernels of the co-batched LoRA delta (shrink: v = x A_a, expand: y += s_a v B_a).
 //
-// Both adapter matrices are stored with the contracted index contiguous (A^T [r8][in],
-// B^T [out][r8]), so a 16x16x32 bf16 MFMA can take its weight operand straight from 16-byte global
-// loads: lane l supplies row (l & 15) of a 16-row weight tile and the 8 consecutive k values
-// 8*(l >> 4) .. +7 of a 32-wide k step.  The token operand uses the same lane->k mapping, so the
-// order of k inside a step is irrelevant to the result.  The 16x16 fp32 result tile has
-// D[4*(l >> 4) + i][l & 15] in register i of lane l: weight row down, token across.
+// Both adapter matrices are stored the way a 16x16x32 bf16 MFMA reads its weight operand: lane l
+// supplies row (l & 15) of a 16-row weight tile and the 8 consecutive k values 8*(l >> 4) .. +7 of a
+// 32-wide k step, so the pool keeps, for every 16-row tile and every k step, the 64 lanes' 16-byte
+// pieces back to back.  One wavefront load of an operand is then 1 KB of consecutive bytes (a
+// row-major matrix would make it 16 pieces of 64 bytes, which costs the address path of a CU about
+// 3.7 times as many cycles):
+//   A^T: 16-row block jb (the last block has 8 rows when the padded rank is 8 mod 16), k step s,
+//        piece (kq, row n): element offset  16*jb*in + s*(32*h) + (kq*h + n)*8,  h = rows in the block
+//   B^T: 128-column strip, sub-block b (the 16 columns 8*n + b), rank piece kp (8 values), column
+//        slot n: element offset  128*strip*r8 + ((b*(r8/8) + kp)*16 + n)*8
+// The token operand uses the same lane->k mapping, so the order of k inside a step is irrelevant to
+// the result.  The 16x16 fp32 result tile has D[4*(l >> 4) + i][l & 15] in register i of lane l.
 //
 // Work is cut on the host into units of roughly equal adapter bytes; one work group (4 wavefronts)
 // takes one unit.  No unit ever depends on another adapter's rank.
@@ -175,7 +181,8 @@ static __device__ __forceinline__ void shrink_body(const Unit &u, const uint16_t
     const int ntok = u.ntok, pn = u.pn, ks = u.ks;
     const bool w_ok = i < pn;
     const bool x_ok = i < ntok;
-    const uint16_t *wrow = arena + u.w_off + (int64_t)(w_ok ? i : 0) * in;
+    // this lane's 16-byte piece of a k step of the unit's row block (pn = rows in the block: 16 or 8)
+    const uint16_t *wrow = arena + u.w_off + (kq * pn + (w_ok ? i : 0)) * 8;
     // slab staging: thread tid copies 16-byte chunk (tid & 127) of tokens (tid >> 7), +2, +4, ...
     const int s_chunk = tid & 127;
     const int s_tok0 = __builtin_amdgcn_readfirstlane(tid >> 7);  // wavefront-uniform
@@ -193,7 +200,7 @@ static __device__ __forceinline__ void shrink_body(const Unit &u, const uint16_t
 #pragma unroll
         for (int q = 0; q < kShrinkSteps; ++q) {
             const int k = kbeg + 32 * q;
-            a[q] = (k < kslice_end) ? ld16(wrow + k + 8 * kq) : zero;
+            a[q] = (k < kslice_end) ? ld16(wrow + (int64_t)k * pn) : zero;
         }
         if (kp != kslice_beg) __syncthreads();  // previous pass's slab is no longer being read
         {
@@ -298,14 +305,16 @@ static __device__ __forceinline__ void shrink_prefill_body(const Unit &u, const 
         t_ok[tb] = t < ntok;
         xrow[tb] = x + (int64_t)perm[u.perm_off + (t_ok[tb] ? t : 0)] * ldx + 8 * kq;
     }
-    const uint16_t *wbase = arena + u.w_off + 8 * kq;
-    int woff[JB];  // element offset of this lane's row in block jb (rows beyond the rank read row r8-1, then zeroed)
+    const uint16_t *wbase = arena + u.w_off;
+    int woff[JB];  // element offset of this lane's 16-byte piece in k step 0 of row block jb
+    int wh[JB];    // rows in block jb (16, or 8 for the last block of a padded rank that is 8 mod 16)
     bool w_ok[JB];
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) {
-        const int j = 16 * jb + n;
-        w_ok[jb] = j < r8;
-        woff[jb] = (w_ok[jb] ? j : r8 - 1) * in;
+        const int h = min(16, r8 - 16 * jb);
+        wh[jb] = h > 0 ? h : 16;
+        w_ok[jb] = n < h;
+        woff[jb] = 16 * jb * in + (kq * wh[jb] + (w_ok[jb] ? n : 0)) * 8;
     }
 
     f32x4 acc[JB][TB];
@@ -325,7 +334,8 @@ static __device__ __forceinline__ void shrink_prefill_body(const Unit &u, const 
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) xq[d][tb] = (kbeg + 32 * d < kend) ? ld16(xrow[tb] + kbeg + 32 * d) : zero;
 #pragma unroll
-    for (int jb = 0; jb < JB; ++jb) w[jb] = (16 * jb < r8 && kbeg < kend) ? ld16(wbase + woff[jb] + kbeg) : zero;
+    for (int jb = 0; jb < JB; ++jb)
+        w[jb] = (16 * jb < r8 && kbeg < kend) ? ld16(wbase + woff[jb] + (int64_t)kbeg * wh[jb]) : zero;
 
     for (int k0 = kbeg; k0 < kend; k0 += 32 * XD) {
 #pragma unroll
@@ -340,7 +350,7 @@ static __device__ __forceinline__ void shrink_prefill_body(const Unit &u, const 
                         for (int tb = 0; tb < TB; ++tb)
                             acc[jb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                                 ww, as_bf16x8(t_ok[tb] ? xq[d][tb] : zero), acc[jb][tb], 0, 0, 0);
-                        if (k + 32 < kend) w[jb] = ld16(wbase + woff[jb] + k + 32);
+                        if (k + 32 < kend) w[jb] = ld16(wbase + woff[jb] + (int64_t)(k + 32) * wh[jb]);
                     }
                 }
                 if (k + 32 * XD < kend) {
@@ -503,13 +513,15 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
     for (int c0 = 0; c0 < ncols; c0 += S * kStrip) {
         const int cs = c0 + my_strip * kStrip;  // this wavefront's strip
         const bool strip_ok = cs < ncols;
-        const uint16_t *brow = arena + u.w_off + (int64_t)((strip_ok ? cs : 0) + 8 * n) * r8;
+        // this lane's piece of sub-block 0, rank piece 0 of the wavefront's strip; sub-block b is
+        // 16*r8 elements further, rank piece kp 128 elements further
+        const uint16_t *brow = arena + u.w_off + (int64_t)(strip_ok ? cs : 0) * r8 + n * 8;
         // weights: row (column of y) cs + 8*n + b, 16 bytes at jc.  One k step per wavefront: they stay
         // in registers for all token blocks; two (rank > 128): each block re-reads them (L1 / L2 hits).
         uint4 w[8];
         if (ITEMS == 1) {
 #pragma unroll
-            for (int b = 0; b < 8; ++b) w[b] = ld16(brow + (int64_t)b * r8 + jc[0]);
+            for (int b = 0; b < 8; ++b) w[b] = ld16(brow + b * 16 * r8 + jc[0] * 16);
         }
 
         // one block of 16 tokens: this thread's share of y and this wavefront's v operand
@@ -570,7 +582,7 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
             for (int it = 0; it < ITEMS; ++it) {
                 if (ITEMS > 1) {
 #pragma unroll
-                    for (int b = 0; b < 8; ++b) w[b] = ld16(brow + (int64_t)b * r8 + jc[it]);
+                    for (int b = 0; b < 8; ++b) w[b] = ld16(brow + b * 16 * r8 + jc[it] * 16);
                 }
 #pragma unroll
                 for (int b = 0; b < 8; ++b) {
@@ -698,16 +710,42 @@ __global__ __launch_bounds__(256) void k_reduce_slices(const float *__restrict__
     v[idx] = acc;
 }
 
-__global__ __launch_bounds__(256) void k_pack_transpose(const uint16_t *__restrict__ src, int src_rows,
-                                                        int src_cols, uint16_t *__restrict__ dst, int P, int Q)
+// Writes an adapter's packed form (see the top of this file).  One thread per destination element.
+// A: [in][r] row-major -> dst of r8*in elements.
+__global__ __launch_bounds__(256) void k_pack_a(const uint16_t *__restrict__ A, int in, int r, int r8,
+                                                uint16_t *__restrict__ dst)
 {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (int64_t)P * Q) return;
-    const int p = (int)(idx / Q);
-    const int q = (int)(idx % Q);
-    uint16_t val = 0;
-    if (q < src_rows && p < src_cols) val = src[(int64_t)q * src_cols + p];
-    dst[idx] = val;
+    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (d >= (int64_t)r8 * in) return;
+    const int jb = (int)(d / (16 * (int64_t)in));
+    const int h = min(16, r8 - 16 * jb);
+    const int64_t idx = d - (int64_t)jb * 16 * in;
+    const int s = (int)(idx / (32 * h));
+    const int rem = (int)(idx % (32 * h));
+    const int kq = rem / (8 * h);
+    const int n = (rem % (8 * h)) / 8;
+    const int e = rem % 8;
+    const int j = 16 * jb + n;
+    const int k = 32 * s + 8 * kq + e;
+    dst[d] = j < r ? A[(int64_t)k * r + j] : (uint16_t)0;
+}
+
+// B: [r][out] row-major -> dst of out*r8 elements.
+__global__ __launch_bounds__(256) void k_pack_b(const uint16_t *__restrict__ B, int out, int r, int r8,
+                                                uint16_t *__restrict__ dst)
+{
+    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (d >= (int64_t)out * r8) return;
+    const int strip = (int)(d / (128 * r8));
+    const int idx = (int)(d % (128 * r8));
+    const int b = idx / (16 * r8);
+    const int rem = idx % (16 * r8);
+    const int kp = rem / 128;
+    const int n = (rem % 128) / 8;
+    const int e = rem % 8;
+    const int c = 128 * strip + 8 * n + b;
+    const int j = 8 * kp + e;
+    dst[d] = j < r ? B[(int64_t)j * out + c] : (uint16_t)0;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -786,14 +824,12 @@ hipError_t launch_reduce_slices(const float *parts, int n_slices, int64_t slice_
     return hipGetLastError();
 }
 
-hipError_t launch_pack_transpose(const uint16_t *src, int src_rows, int src_cols, uint16_t *dst, int P, int Q,
-                                 hipStream_t stream)
+hipError_t launch_pack_adapter(const uint16_t *A, const uint16_t *B, int in, int out, int r, int r8,
+                               uint16_t *dst_a, uint16_t *dst_b, hipStream_t stream)
 {
-    const int64_t n = (int64_t)P * Q;
-    if (n <= 0) return hipSuccess;
-    const int64_t blocks = (n + 255) / 256;
-    hipLaunchKernelGGL(k_pack_transpose, dim3((unsigned)blocks), dim3(256), 0, stream, src, src_rows, src_cols,
-                       dst, P, Q);
+    const int64_t na = (int64_t)r8 * in, nb = (int64_t)out * r8;
+    hipLaunchKernelGGL(k_pack_a, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, stream, A, in, r, r8, dst_a);
+    hipLaunchKernelGGL(k_pack_b, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, stream, B, out, r, r8, dst_b);
     return hipGetLastError();
 }
 
