@@ -278,3 +278,66 @@ def test_device_source_load_and_stale_segments():
     y_ref = G.oracle_apply(dp, b.x_bits(), b.y0_bits("zero"))
     G.check_parity(y_bits, y_ref, b.y0_bits("zero"), b.token_adapter)
     dp.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# Full sizes, in the launch configuration bench.py times (lora_segments_build + lora_apply, two
+# launches), checked on sampled rows the oracle computes one by one, plus the property that rows
+# without an adapter and rows outside the sample's groups are untouched where that applies.
+# ------------------------------------------------------------------------------------------------
+def _sampled_parity(batch, n_rows=48, y0_kind="zero", seed=0):
+    print(f"[case] {batch.name} T={batch.T} in={batch.in_features} out={batch.out_features} (sampled)", flush=True)
+    dp = G.DevicePool(batch)
+    x_bits, y0_bits = batch.x_bits(), batch.y0_bits(y0_kind)
+    y_bits = G.apply_on_gpu(dp, x_bits, y0_bits)
+    rng = np.random.default_rng(seed)
+    # sample across groups: first / last token of some groups (tile edges) plus random tokens
+    rows = set(rng.integers(0, batch.T, size=n_rows).tolist())
+    for a in batch.used_adapters()[:: max(1, len(batch.used_adapters()) // 12)]:
+        idx = np.nonzero(batch.token_adapter == a)[0]
+        rows.update([int(idx[0]), int(idx[-1]), int(idx[len(idx) // 2])])
+    rows = np.array(sorted(rows), dtype=np.int32)
+    y_ref = G.oracle_apply(dp, x_bits, y0_bits, rows=rows)
+    ta = batch.token_adapter[rows]
+    yg = wl.bf16_bits_to_f64(y_bits[rows])
+    act = ta >= 0
+    assert np.array_equal(y_bits[rows][~act], y0_bits[rows][~act])
+    err = G.row_rel_l2(yg[act], y_ref[act])
+    assert err.max() <= G.TOL, f"max per-row relative L2 error {err.max():.3e}"
+    # no row is left undone: every active row of a zero y0 must have become non-zero
+    if y0_kind == "zero":
+        active_rows = batch.token_adapter >= 0
+        assert np.all(y_bits[active_rows].any(axis=1)) and not y_bits[~active_rows].any()
+    dp.close()
+    print(f"[ok] {batch.name}: max row rel-L2 {err.max():.3e} on {act.sum()} sampled rows", flush=True)
+
+
+@pytest.mark.parametrize("shape", [0, 1, 2])
+def test_cfg2_prefill_full_size(shape):
+    _sampled_parity(wl.cfg2_prefill(shape))
+
+
+@pytest.mark.parametrize("layer,projection", [(0, 0), (5, 1), (17, 4), (31, 6)])
+def test_cfg3_stack_full_size(layer, projection):
+    """The mixed batch (8 prefills + 384 decode tokens, 256 adapters) on q, k, gate and down
+    projections of four layers; all 224 projections share the token -> adapter map."""
+    _sampled_parity(wl.cfg3_stack(layer=layer, projection=projection), seed=layer)
+
+
+@pytest.mark.parametrize("shape,split", [(0, "9:1"), (0, "1:1"), (0, "1:9"), (1, "1:1"), (2, "1:1")])
+def test_cfg4_skew_full_size(shape, split):
+    _sampled_parity(wl.cfg4_skew(shape, split), n_rows=64)
+
+
+def test_cfg4_isolated_class_equals_mixed_rows():
+    """Rank-8 tokens get bitwise the same result whether or not rank-256 tokens share the batch:
+    no unit of work of one adapter depends on another adapter's rank."""
+    mixed = wl.cfg4_skew(0, "1:1")
+    iso = wl.cfg4_skew(0, "1:1", only_class=0)
+    dp = G.DevicePool(mixed)
+    x_bits, y0_bits = mixed.x_bits(), mixed.y0_bits("zero")
+    y_mixed = G.apply_on_gpu(dp, x_bits, y0_bits)
+    y_iso = G.apply_on_gpu(dp, x_bits, y0_bits, token_adapter=iso.token_adapter)
+    lo = iso.token_adapter >= 0
+    assert lo.sum() == 256 and np.array_equal(y_mixed[lo], y_iso[lo]) and not y_iso[~lo].any()
+    dp.close()
