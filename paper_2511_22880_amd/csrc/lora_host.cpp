@@ -271,12 +271,11 @@ static int expand_cols_per_unit(int r8, int out)
 }
 
 // Groups with at least this many tokens are token-heavy: their shrink runs on token tiles that read x
-// once (instead of once per 16 rank rows), their expand units hold up to kExpandBigTokens tokens.
+// once (instead of once per 16 rank rows), their expand units hold up to 64 tokens and several column passes.
 // Only in batches of at least kPrefillMinBatch tokens: a 128-token tile streams about 1 MB of x, far
 // longer than a whole decode-sized launch lasts.
 static const int kPrefillMinTokens = 32;
 static const int kPrefillMinBatch = 1024;
-static const int kExpandBigTokens = 64;
 
 static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const int32_t *ta, int32_t T)
 {
@@ -413,9 +412,15 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                         sg->shrink_units.push_back(u);
                     }
         }
-        // expand: token-heavy groups keep a column pass's weights in registers for 4 token blocks
-        const int cols = expand_cols_per_unit(r.r8, out);
-        const int etile = token_heavy ? kExpandBigTokens : lora::kTokTile;
+        // expand: small groups one column pass and <= 16 tokens per unit; token-heavy groups four
+        // passes and 64 / (strips per pass) tokens, so that v stays in registers and the next pass's
+        // weights and y travel while the current pass computes
+        int cols = expand_cols_per_unit(r.r8, out);
+        int etile = lora::kTokTile;
+        if (token_heavy) {
+            etile = r.r8 <= 32 ? 16 : (r.r8 <= 64 ? 32 : 64);
+            cols = std::min(out, 4 * cols);
+        }
         for (int c0 = 0; c0 < out; c0 += cols)
             for (int tok0 = 0; tok0 < r.ntok; tok0 += etile) {
                 Unit u;

@@ -565,12 +565,18 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
         };
 
         if (!BIG && !VF32 && first && sy.counters && sy.wait) wait_for(sy, u.sync_idx);  // weights are in flight
-        Blk cur, nxt;
-        load_blk(0, cur);
-        for (int t0 = 0; t0 < ntok_all; t0 += kTokTile) {
-            const bool has_next = BIG && t0 + kTokTile < ntok_all;
-            if (has_next) load_blk(t0 + kTokTile, nxt);  // next block's y and v travel while this one computes
-            if (!first) __syncthreads();                 // the previous block's partial tiles have been consumed
+        // all of the unit's y and v go out at once (up to 4 blocks of 16 tokens), so that the HBM
+        // latency of y is paid once per column pass, not once per block
+        constexpr int NB = BIG ? 4 : 1;
+        Blk blk[NB];
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib)
+            if (ib * kTokTile < ntok_all) load_blk(ib * kTokTile, blk[ib]);
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib) {
+            if (ib * kTokTile >= ntok_all) break;
+            Blk &cur = blk[ib];
+            if (!first) __syncthreads();  // the previous block's partial tiles have been consumed
             first = false;
             const int ntok = cur.ntok;
             const bool e_ok = e_tok < ntok;
@@ -630,8 +636,189 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
                     }
                 }
             }
-            if (has_next) cur = nxt;
-            if (!BIG) break;  // units of the small kind hold one block
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// expand of token-heavy groups: one unit = (group, NB blocks of 16 tokens, several column passes).
+// Same tiles as above; what differs is what stays put and what streams.  The unit's v operands are
+// loaded once and kept for all its column passes; the weights and this thread's y pieces of the
+// next pass are requested before the current pass computes, so that y (from HBM) and B^T (from L2)
+// travel while the MFMAs, the LDS hand-over and the y stores of the current pass run.  NB = 4 / S
+// (S = strips per pass), which keeps a pass's y at four 16-byte pieces per thread for every rank.
+// ------------------------------------------------------------------------------------------------
+template <int KSTEPS, bool VF32>
+static __device__ __forceinline__ void expand_big_body(const Unit &u, const int32_t *__restrict__ perm,
+                                                       const uint16_t *__restrict__ arena,
+                                                       const float *__restrict__ v_in, int n_slices,
+                                                       int64_t slice_stride, uint16_t *__restrict__ y,
+                                                       int64_t ldy, char *lds, const Sync &sy)
+{
+    constexpr int P = KSTEPS < 4 ? KSTEPS : 4;
+    constexpr int S = 4 / P;
+    constexpr int ITEMS = KSTEPS / P;
+    constexpr int NB = 4 / S;
+    constexpr int PASS = S * kStrip;
+    float(*part)[kTokTile][kPartRow] = reinterpret_cast<float(*)[kTokTile][kPartRow]>(lds);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int n = lane & 15;
+    const int kq = lane >> 4;
+    const int r8 = u.r8;
+    const int ntok_all = u.ntok;
+    const int ncols = u.pn;
+    const uint4 zero = {0u, 0u, 0u, 0u};
+    const int my_strip = wave / P;
+    const int my_part = wave % P;
+    const int32_t *toks = perm + u.perm_off;
+    const int e_tok = tid >> 4;
+    const int e_cg = tid & 15;
+    const float scale = u.scale;
+
+    int jc[ITEMS];
+    bool j_ok[ITEMS];
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const int j = 32 * (my_part + P * it) + 8 * kq;
+        j_ok[it] = j < r8;
+        jc[it] = j_ok[it] ? j : 0;
+    }
+
+    // this thread's y rows (one per token block) and the unit's v operands
+    uint16_t *e_y[NB];
+    bool e_ok[NB];
+    uint4 vh[NB][ITEMS], vl[NB][ITEMS];
+#pragma unroll
+    for (int ib = 0; ib < NB; ++ib) {
+        const int nt = min(kTokTile, ntok_all - kTokTile * ib);  // may be <= 0
+        e_ok[ib] = e_tok < nt;
+        e_y[ib] = y + (int64_t)toks[e_ok[ib] ? kTokTile * ib + e_tok : 0] * ldy + u.p0 + 8 * e_cg;
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const bool ok = (n < nt) && j_ok[it];
+            const int64_t off = u.v_off + (int64_t)(ok ? kTokTile * ib + n : 0) * r8 + jc[it];
+            uint4 ph, pl;
+            if (!VF32) {
+                ph = ld16(sy.v_hi + off);
+                pl = ld16(sy.v_lo + off);
+            } else {
+                bf16x8 h, l;
+                load_v_operand(v_in + off, ok, n_slices, slice_stride, h, l);
+                ph = __builtin_bit_cast(uint4, h);
+                pl = __builtin_bit_cast(uint4, l);
+            }
+            vh[ib][it] = ok ? ph : zero;
+            vl[ib][it] = ok ? pl : zero;
+        }
+    }
+
+    const uint16_t *bbase = arena + u.w_off + n * 8;
+    auto load_w = [&](int c0, uint4 (&w)[ITEMS][8]) {
+        const int cs = c0 + my_strip * kStrip;
+        const uint16_t *brow = bbase + (int64_t)(cs < ncols ? cs : 0) * r8;
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it)
+#pragma unroll
+            for (int b = 0; b < 8; ++b) w[it][b] = ld16(brow + b * 16 * r8 + jc[it] * 16);
+    };
+    auto load_y = [&](int c0, uint4 (&yv)[NB][S]) {
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib)
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+                yv[ib][s] = (e_ok[ib] && c0 + s * kStrip < ncols)
+                                ? *reinterpret_cast<const uint4 *>(e_y[ib] + c0 + s * kStrip)
+                                : zero;
+    };
+    bool first = true;
+    auto compute = [&](int c0, const uint4 (&w)[ITEMS][8], const uint4 (&yv)[NB][S]) {
+        const bool strip_ok = c0 + my_strip * kStrip < ncols;
+#pragma unroll
+        for (int ib = 0; ib < NB; ++ib) {
+            const int nt = min(kTokTile, ntok_all - kTokTile * ib);
+            if (nt <= 0) break;  // uniform
+            if (!first) __syncthreads();  // the previous block's partial tiles have been consumed
+            first = false;
+            f32x4 acc[8];
+#pragma unroll
+            for (int b = 0; b < 8; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int it = 0; it < ITEMS; ++it)
+#pragma unroll
+                for (int b = 0; b < 8; ++b) {
+                    const bf16x8 ww = as_bf16x8(j_ok[it] ? w[it][b] : zero);
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vh[ib][it]), ww, acc[b], 0, 0, 0);
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vl[ib][it]), ww, acc[b], 0, 0, 0);
+                }
+            if (strip_ok) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int tok = 4 * kq + e;
+                    if (tok < nt) {
+                        const f32x4 lo = {acc[0][e], acc[1][e], acc[2][e], acc[3][e]};
+                        const f32x4 hi = {acc[4][e], acc[5][e], acc[6][e], acc[7][e]};
+                        *reinterpret_cast<f32x4 *>(&part[wave][tok][8 * n]) = lo;
+                        *reinterpret_cast<f32x4 *>(&part[wave][tok][8 * n + 4]) = hi;
+                    }
+                }
+            }
+            __syncthreads();
+            if (e_ok[ib]) {
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    if (c0 + s * kStrip < ncols) {
+                        f32x4 d0 = *reinterpret_cast<const f32x4 *>(&part[s * P][e_tok][8 * e_cg]);
+                        f32x4 d1 = *reinterpret_cast<const f32x4 *>(&part[s * P][e_tok][8 * e_cg + 4]);
+#pragma unroll
+                        for (int p = 1; p < P; ++p) {
+                            d0 += *reinterpret_cast<const f32x4 *>(&part[s * P + p][e_tok][8 * e_cg]);
+                            d1 += *reinterpret_cast<const f32x4 *>(&part[s * P + p][e_tok][8 * e_cg + 4]);
+                        }
+                        const uint4 yy = yv[ib][s];
+                        uint4 o;
+                        o.x = pack_bf16_rne(bf16_bits_to_f32(yy.x & 0xFFFFu) + scale * d0[0],
+                                            __uint_as_float(yy.x & 0xFFFF0000u) + scale * d0[1]);
+                        o.y = pack_bf16_rne(bf16_bits_to_f32(yy.y & 0xFFFFu) + scale * d0[2],
+                                            __uint_as_float(yy.y & 0xFFFF0000u) + scale * d0[3]);
+                        o.z = pack_bf16_rne(bf16_bits_to_f32(yy.z & 0xFFFFu) + scale * d1[0],
+                                            __uint_as_float(yy.z & 0xFFFF0000u) + scale * d1[1]);
+                        o.w = pack_bf16_rne(bf16_bits_to_f32(yy.w & 0xFFFFu) + scale * d1[2],
+                                            __uint_as_float(yy.w & 0xFFFF0000u) + scale * d1[3]);
+                        *reinterpret_cast<uint4 *>(e_y[ib] + c0 + s * kStrip) = o;
+                    }
+                }
+            }
+        }
+    };
+
+    // two register sets in turn; above rank 128 (two k steps per wavefront, 64 registers of weights per
+    // pass) only y is requested a pass ahead and the weights come in at the start of their pass
+    constexpr bool WDB = ITEMS == 1;
+    uint4 wa[ITEMS][8], wb[WDB ? ITEMS : 1][8];
+    uint4 ya[NB][S], yb[NB][S];
+    load_w(0, wa);
+    load_y(0, ya);
+    for (int c0 = 0; c0 < ncols; c0 += 2 * PASS) {
+        if (c0 + PASS < ncols) {
+            if constexpr (WDB) load_w(c0 + PASS, wb);
+            load_y(c0 + PASS, yb);
+        }
+        compute(c0, wa, ya);
+        if (c0 + PASS >= ncols) break;
+        if constexpr (WDB) {
+            if (c0 + 2 * PASS < ncols) load_w(c0 + 2 * PASS, wa);
+        } else {
+            load_w(c0 + PASS, wa);
+        }
+        if (c0 + 2 * PASS < ncols) load_y(c0 + 2 * PASS, ya);
+        if constexpr (WDB)
+            compute(c0 + PASS, wb, yb);
+        else
+            compute(c0 + PASS, wa, yb);
+        if constexpr (!WDB) {
+            if (c0 + 2 * PASS < ncols) load_w(c0 + 2 * PASS, wa);
         }
     }
 }
@@ -644,14 +831,25 @@ static __device__ __forceinline__ void expand_dispatch(const Unit &u, const int3
                                                        int64_t ldy, char *lds, const Sync &sy)
 {
     const int r8 = u.r8;
-    if (r8 <= 32)
-        expand_body<1, BIG, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
-    else if (r8 <= 64)
-        expand_body<2, BIG, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
-    else if (r8 <= 128)
-        expand_body<4, BIG, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
-    else
-        expand_body<8, BIG, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+    if (BIG) {
+        if (r8 <= 32)
+            expand_big_body<1, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+        else if (r8 <= 64)
+            expand_big_body<2, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+        else if (r8 <= 128)
+            expand_big_body<4, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+        else
+            expand_big_body<8, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+    } else {
+        if (r8 <= 32)
+            expand_body<1, false, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+        else if (r8 <= 64)
+            expand_body<2, false, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+        else if (r8 <= 128)
+            expand_body<4, false, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+        else
+            expand_body<8, false, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+    }
 }
 
 constexpr int kFusedLds = kShrinkLds > kExpandLds ? kShrinkLds : kExpandLds;

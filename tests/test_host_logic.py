@@ -197,10 +197,13 @@ def test_planner_matches_brute_force_grouping(maker):
             assert pn % 128 == 0 and 1 <= nt <= (64 if token_heavy else 16)
             ecover[tok0:tok0 + nt, p0:p0 + pn] += 1
         assert np.all(ecover == 1)
-    # no unit's size depends on another adapter's rank: expand bytes per unit bounded by its own rank
+    # no unit's size depends on another adapter's rank: the bytes of B^T per unit are bounded by a
+    # constant (one column pass of <= 64 KiB for small groups, four passes for token-heavy ones)
     eu = units["expand"]
-    ub = eu[:, 4] * 2 * r8[ex["seg_adapter"][eu[:, 0]]]
-    assert ub.max() <= 64 * 1024
+    ub = eu[:, 4].astype(np.int64) * 2 * r8[ex["seg_adapter"][eu[:, 0]]]
+    seg_tokens = np.diff(ex["seg_start"])[eu[:, 0]]
+    heavy = (seg_tokens >= 32) & (info["n_active"] >= 1024)
+    assert ub[~heavy].max(initial=0) <= 64 * 1024 and ub[heavy].max(initial=0) <= 256 * 1024
     L.lora_segments_destroy(seg)
     L.lora_pool_destroy(pool)
 
