@@ -412,14 +412,13 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                         sg->shrink_units.push_back(u);
                     }
         }
-        // expand: small groups one column pass and <= 16 tokens per unit; token-heavy groups four
-        // passes and 64 / (strips per pass) tokens, so that v stays in registers and the next pass's
-        // weights and y travel while the current pass computes
+        // expand: small groups one column pass and <= 16 tokens per unit; token-heavy groups 64 tokens
+        // (16 per wavefront, v kept in registers) and a quarter of the columns, at least 512
         int cols = expand_cols_per_unit(r.r8, out);
         int etile = lora::kTokTile;
         if (token_heavy) {
-            etile = r.r8 <= 32 ? 16 : (r.r8 <= 64 ? 32 : 64);
-            cols = std::min(out, 4 * cols);
+            etile = 64;
+            cols = std::min(out, std::max(512, (out / 4 + 127) / 128 * 128));
         }
         for (int c0 = 0; c0 < out; c0 += cols)
             for (int tok0 = 0; tok0 < r.ntok; tok0 += etile) {

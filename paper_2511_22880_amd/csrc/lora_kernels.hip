@@ -531,7 +531,7 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
             uint16_t *e_y;
             int ntok;
         };
-        auto load_blk = [&](int t0, Blk &bk) {
+        auto load_blk = [&](int t0, Blk &bk) __attribute__((always_inline)) {
             bk.ntok = min(kTokTile, ntok_all - t0);
             const bool e_ok = e_tok < bk.ntok;
             bk.e_y = y + (int64_t)toks[e_ok ? t0 + e_tok : 0] * ldy + u.p0 + 8 * e_cg;
@@ -641,13 +641,18 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
 }
 
 // ------------------------------------------------------------------------------------------------
-// expand of token-heavy groups: one unit = (group, NB blocks of 16 tokens, several column passes).
-// Same tiles as above; what differs is what stays put and what streams.  The unit's v operands are
-// loaded once and kept for all its column passes; the weights and this thread's y pieces of the
-// next pass are requested before the current pass computes, so that y (from HBM) and B^T (from L2)
-// travel while the MFMAs, the LDS hand-over and the y stores of the current pass run.  NB = 4 / S
-// (S = strips per pass), which keeps a pass's y at four 16-byte pieces per thread for every rank.
+// expand of token-heavy groups: one unit = (group, up to 64 tokens, a run of 128-column strips).
+// Each wavefront owns 16 of the tokens for the whole unit and all of the rank, so nothing is summed
+// across wavefronts and there is no barrier per token block: its v operands (bf16 hi + lo, every
+// k step) are loaded once and stay in registers; a strip's B^T tile (128 columns x rank, one
+// contiguous piece of the pool) is copied into LDS once per work group and read from there by the
+// four wavefronts; the MFMA result (token x column, lane n holding 8 consecutive columns of 4
+// tokens) goes straight to the y update, 16 bytes per lane, four 256-byte row pieces per store.
+// While a strip computes, the next strip's B^T tile and this lane's y pieces are already on their
+// way (the tile waits in registers, then goes into the other half of the LDS buffer).
 // ------------------------------------------------------------------------------------------------
+constexpr int kBigLds = 64 * 1024;
+
 template <int KSTEPS, bool VF32>
 static __device__ __forceinline__ void expand_big_body(const Unit &u, const int32_t *__restrict__ perm,
                                                        const uint16_t *__restrict__ arena,
@@ -655,12 +660,9 @@ static __device__ __forceinline__ void expand_big_body(const Unit &u, const int3
                                                        int64_t slice_stride, uint16_t *__restrict__ y,
                                                        int64_t ldy, char *lds, const Sync &sy)
 {
-    constexpr int P = KSTEPS < 4 ? KSTEPS : 4;
-    constexpr int S = 4 / P;
-    constexpr int ITEMS = KSTEPS / P;
-    constexpr int NB = 4 / S;
-    constexpr int PASS = S * kStrip;
-    float(*part)[kTokTile][kPartRow] = reinterpret_cast<float(*)[kTokTile][kPartRow]>(lds);
+    // the tile of one strip is 128 * r8 * 2 bytes <= 32 KiB up to rank 128: two buffers; above: one
+    constexpr bool DB = KSTEPS <= 4;
+    constexpr int WREG = 2 * KSTEPS;  // 16-byte pieces of a tile per thread (256 threads): 128*32*KSTEPS*2 / 4096
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -670,157 +672,137 @@ static __device__ __forceinline__ void expand_big_body(const Unit &u, const int3
     const int ntok_all = u.ntok;
     const int ncols = u.pn;
     const uint4 zero = {0u, 0u, 0u, 0u};
-    const int my_strip = wave / P;
-    const int my_part = wave % P;
     const int32_t *toks = perm + u.perm_off;
-    const int e_tok = tid >> 4;
-    const int e_cg = tid & 15;
     const float scale = u.scale;
+    const int tile_pieces = 16 * r8;  // 16-byte pieces in one strip's tile (128 * r8 * 2 / 16)
 
-    int jc[ITEMS];
-    bool j_ok[ITEMS];
+    // this wavefront's 16 tokens: v operands for every k step
+    const int nt = min(kTokTile, ntok_all - kTokTile * wave);  // may be <= 0: the wavefront only helps copying
+    uint4 vh[KSTEPS], vl[KSTEPS];
+    bool j_ok[KSTEPS];
 #pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-        const int j = 32 * (my_part + P * it) + 8 * kq;
-        j_ok[it] = j < r8;
-        jc[it] = j_ok[it] ? j : 0;
-    }
-
-    // this thread's y rows (one per token block) and the unit's v operands
-    uint16_t *e_y[NB];
-    bool e_ok[NB];
-    uint4 vh[NB][ITEMS], vl[NB][ITEMS];
-#pragma unroll
-    for (int ib = 0; ib < NB; ++ib) {
-        const int nt = min(kTokTile, ntok_all - kTokTile * ib);  // may be <= 0
-        e_ok[ib] = e_tok < nt;
-        e_y[ib] = y + (int64_t)toks[e_ok[ib] ? kTokTile * ib + e_tok : 0] * ldy + u.p0 + 8 * e_cg;
-#pragma unroll
-        for (int it = 0; it < ITEMS; ++it) {
-            const bool ok = (n < nt) && j_ok[it];
-            const int64_t off = u.v_off + (int64_t)(ok ? kTokTile * ib + n : 0) * r8 + jc[it];
-            uint4 ph, pl;
-            if (!VF32) {
-                ph = ld16(sy.v_hi + off);
-                pl = ld16(sy.v_lo + off);
-            } else {
-                bf16x8 h, l;
-                load_v_operand(v_in + off, ok, n_slices, slice_stride, h, l);
-                ph = __builtin_bit_cast(uint4, h);
-                pl = __builtin_bit_cast(uint4, l);
-            }
-            vh[ib][it] = ok ? ph : zero;
-            vl[ib][it] = ok ? pl : zero;
-        }
-    }
-
-    const uint16_t *bbase = arena + u.w_off + n * 8;
-    auto load_w = [&](int c0, uint4 (&w)[ITEMS][8]) {
-        const int cs = c0 + my_strip * kStrip;
-        const uint16_t *brow = bbase + (int64_t)(cs < ncols ? cs : 0) * r8;
-#pragma unroll
-        for (int it = 0; it < ITEMS; ++it)
-#pragma unroll
-            for (int b = 0; b < 8; ++b) w[it][b] = ld16(brow + b * 16 * r8 + jc[it] * 16);
-    };
-    auto load_y = [&](int c0, uint4 (&yv)[NB][S]) {
-#pragma unroll
-        for (int ib = 0; ib < NB; ++ib)
-#pragma unroll
-            for (int s = 0; s < S; ++s)
-                yv[ib][s] = (e_ok[ib] && c0 + s * kStrip < ncols)
-                                ? *reinterpret_cast<const uint4 *>(e_y[ib] + c0 + s * kStrip)
-                                : zero;
-    };
-    bool first = true;
-    auto compute = [&](int c0, const uint4 (&w)[ITEMS][8], const uint4 (&yv)[NB][S]) {
-        const bool strip_ok = c0 + my_strip * kStrip < ncols;
-#pragma unroll
-        for (int ib = 0; ib < NB; ++ib) {
-            const int nt = min(kTokTile, ntok_all - kTokTile * ib);
-            if (nt <= 0) break;  // uniform
-            if (!first) __syncthreads();  // the previous block's partial tiles have been consumed
-            first = false;
-            f32x4 acc[8];
-#pragma unroll
-            for (int b = 0; b < 8; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int it = 0; it < ITEMS; ++it)
-#pragma unroll
-                for (int b = 0; b < 8; ++b) {
-                    const bf16x8 ww = as_bf16x8(j_ok[it] ? w[it][b] : zero);
-                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vh[ib][it]), ww, acc[b], 0, 0, 0);
-                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vl[ib][it]), ww, acc[b], 0, 0, 0);
-                }
-            if (strip_ok) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int tok = 4 * kq + e;
-                    if (tok < nt) {
-                        const f32x4 lo = {acc[0][e], acc[1][e], acc[2][e], acc[3][e]};
-                        const f32x4 hi = {acc[4][e], acc[5][e], acc[6][e], acc[7][e]};
-                        *reinterpret_cast<f32x4 *>(&part[wave][tok][8 * n]) = lo;
-                        *reinterpret_cast<f32x4 *>(&part[wave][tok][8 * n + 4]) = hi;
-                    }
-                }
-            }
-            __syncthreads();
-            if (e_ok[ib]) {
-#pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    if (c0 + s * kStrip < ncols) {
-                        f32x4 d0 = *reinterpret_cast<const f32x4 *>(&part[s * P][e_tok][8 * e_cg]);
-                        f32x4 d1 = *reinterpret_cast<const f32x4 *>(&part[s * P][e_tok][8 * e_cg + 4]);
-#pragma unroll
-                        for (int p = 1; p < P; ++p) {
-                            d0 += *reinterpret_cast<const f32x4 *>(&part[s * P + p][e_tok][8 * e_cg]);
-                            d1 += *reinterpret_cast<const f32x4 *>(&part[s * P + p][e_tok][8 * e_cg + 4]);
-                        }
-                        const uint4 yy = yv[ib][s];
-                        uint4 o;
-                        o.x = pack_bf16_rne(bf16_bits_to_f32(yy.x & 0xFFFFu) + scale * d0[0],
-                                            __uint_as_float(yy.x & 0xFFFF0000u) + scale * d0[1]);
-                        o.y = pack_bf16_rne(bf16_bits_to_f32(yy.y & 0xFFFFu) + scale * d0[2],
-                                            __uint_as_float(yy.y & 0xFFFF0000u) + scale * d0[3]);
-                        o.z = pack_bf16_rne(bf16_bits_to_f32(yy.z & 0xFFFFu) + scale * d1[0],
-                                            __uint_as_float(yy.z & 0xFFFF0000u) + scale * d1[1]);
-                        o.w = pack_bf16_rne(bf16_bits_to_f32(yy.w & 0xFFFFu) + scale * d1[2],
-                                            __uint_as_float(yy.w & 0xFFFF0000u) + scale * d1[3]);
-                        *reinterpret_cast<uint4 *>(e_y[ib] + c0 + s * kStrip) = o;
-                    }
-                }
-            }
-        }
-    };
-
-    // two register sets in turn; above rank 128 (two k steps per wavefront, 64 registers of weights per
-    // pass) only y is requested a pass ahead and the weights come in at the start of their pass
-    constexpr bool WDB = ITEMS == 1;
-    uint4 wa[ITEMS][8], wb[WDB ? ITEMS : 1][8];
-    uint4 ya[NB][S], yb[NB][S];
-    load_w(0, wa);
-    load_y(0, ya);
-    for (int c0 = 0; c0 < ncols; c0 += 2 * PASS) {
-        if (c0 + PASS < ncols) {
-            if constexpr (WDB) load_w(c0 + PASS, wb);
-            load_y(c0 + PASS, yb);
-        }
-        compute(c0, wa, ya);
-        if (c0 + PASS >= ncols) break;
-        if constexpr (WDB) {
-            if (c0 + 2 * PASS < ncols) load_w(c0 + 2 * PASS, wa);
+    for (int st = 0; st < KSTEPS; ++st) {
+        const int j = 32 * st + 8 * kq;
+        j_ok[st] = j < r8;
+        const bool ok = (n < nt) && j_ok[st];
+        const int64_t off = u.v_off + (int64_t)(ok ? kTokTile * wave + n : 0) * r8 + (j_ok[st] ? j : 0);
+        uint4 ph, pl;
+        if (!VF32) {
+            ph = ld16(sy.v_hi + off);
+            pl = ld16(sy.v_lo + off);
         } else {
-            load_w(c0 + PASS, wa);
+            bf16x8 h, l;
+            load_v_operand(v_in + off, ok, n_slices, slice_stride, h, l);
+            ph = __builtin_bit_cast(uint4, h);
+            pl = __builtin_bit_cast(uint4, l);
         }
-        if (c0 + 2 * PASS < ncols) load_y(c0 + 2 * PASS, ya);
-        if constexpr (WDB)
-            compute(c0 + PASS, wb, yb);
-        else
-            compute(c0 + PASS, wa, yb);
-        if constexpr (!WDB) {
-            if (c0 + 2 * PASS < ncols) load_w(c0 + 2 * PASS, wa);
-        }
+        vh[st] = ok ? ph : zero;
+        vl[st] = ok ? pl : zero;
     }
+    // the MFMA leaves tokens 4*kq + e (e = 0..3), columns 8*n .. 8*n+7 of the strip in this lane
+    uint16_t *yrow[4];
+    bool y_ok[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        y_ok[e] = 4 * kq + e < nt;
+        yrow[e] = y + (int64_t)toks[y_ok[e] ? kTokTile * wave + 4 * kq + e : 0] * ldy + u.p0 + 8 * n;
+    }
+
+    const uint4 *gtile = reinterpret_cast<const uint4 *>(arena + u.w_off);  // strip s starts tile_pieces * s further
+    uint4 *ltile = reinterpret_cast<uint4 *>(lds);
+    const int nstrips = ncols / kStrip;
+
+    // Copy of strip S_'s tile from the pool into LDS buffer BUF_ with loads that write LDS directly
+    // (no registers in between, so the copy runs while the MFMAs of the current strip do): every
+    // wavefront moves 1 KB pieces, lane l's 16 bytes landing at the piece's LDS base + 16*l.  The
+    // tile is 16*r8 pieces of 16 bytes, a multiple of 64, so a wavefront's piece is whole or absent.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#define LORA_DMA_TILE(BUF_, S_)                                                                         \
+    _Pragma("unroll") for (int q = 0; q < WREG; ++q) {                                                  \
+        const int piece0 = 64 * wave_u + kThreads * q;                                                  \
+        if (piece0 < tile_pieces)                                                                       \
+            __builtin_amdgcn_global_load_lds(                                                           \
+                (const __attribute__((address_space(1))) void *)(gtile + (int64_t)(S_) * tile_pieces + piece0 + lane), \
+                (__attribute__((address_space(3))) void *)(ltile + (BUF_) * 2048 + piece0), 16, 0, 0);  \
+    }
+    // the copies (and everything else this wavefront has in flight) have landed
+#define LORA_DMA_WAIT()                       \
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);  \
+    __builtin_amdgcn_s_waitcnt(0x0F70);       \
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    uint4 ya[4], yb[4];
+    auto fetch_y = [&](int s, uint4 (&yv)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) yv[e] = y_ok[e] ? *reinterpret_cast<const uint4 *>(yrow[e] + s * kStrip) : zero;
+    };
+    auto compute = [&](int s, int buf, const uint4 (&yv)[4]) __attribute__((always_inline)) {
+        if (nt <= 0) return;
+        const uint4 *t = ltile + buf * 2048;
+        f32x4 acc[8];
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int st = 0; st < KSTEPS; ++st) {
+                if (32 * st < r8) {  // uniform
+                    // piece (sub-block b, rank piece 4*st + kq, column slot n)
+                    const uint4 wv = j_ok[st] ? t[(b * (r8 >> 3) + 4 * st + kq) * 16 + n] : zero;
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vh[st]), as_bf16x8(wv), acc[b], 0, 0, 0);
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vl[st]), as_bf16x8(wv), acc[b], 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (y_ok[e]) {
+                const uint4 yy = yv[e];
+                uint4 o;
+                o.x = pack_bf16_rne(bf16_bits_to_f32(yy.x & 0xFFFFu) + scale * acc[0][e],
+                                    __uint_as_float(yy.x & 0xFFFF0000u) + scale * acc[1][e]);
+                o.y = pack_bf16_rne(bf16_bits_to_f32(yy.y & 0xFFFFu) + scale * acc[2][e],
+                                    __uint_as_float(yy.y & 0xFFFF0000u) + scale * acc[3][e]);
+                o.z = pack_bf16_rne(bf16_bits_to_f32(yy.z & 0xFFFFu) + scale * acc[4][e],
+                                    __uint_as_float(yy.z & 0xFFFF0000u) + scale * acc[5][e]);
+                o.w = pack_bf16_rne(bf16_bits_to_f32(yy.w & 0xFFFFu) + scale * acc[6][e],
+                                    __uint_as_float(yy.w & 0xFFFF0000u) + scale * acc[7][e]);
+                *reinterpret_cast<uint4 *>(yrow[e] + s * kStrip) = o;
+            }
+        }
+    };
+
+    LORA_DMA_TILE(0, 0)
+    fetch_y(0, ya);
+    LORA_DMA_WAIT()
+    __syncthreads();
+    for (int s = 0; s < nstrips; s += 2) {
+        // even strips from buffer 0, odd strips from buffer 1 (a single buffer above rank 128)
+        if (s + 1 < nstrips) {
+            if (DB) { LORA_DMA_TILE(1, s + 1) }
+            fetch_y(s + 1, yb);
+        }
+        compute(s, 0, ya);
+        if (s + 1 >= nstrips) break;
+        if (!DB) {
+            __syncthreads();  // single buffer: everyone has finished reading strip s
+            LORA_DMA_TILE(0, s + 1)
+        }
+        LORA_DMA_WAIT()
+        __syncthreads();
+        if (s + 2 < nstrips) {
+            if (DB) { LORA_DMA_TILE(0, s + 2) }
+            fetch_y(s + 2, ya);
+        }
+        compute(s + 1, DB ? 1 : 0, yb);
+        if (s + 2 >= nstrips) break;
+        if (!DB) {
+            __syncthreads();
+            LORA_DMA_TILE(0, s + 2)
+        }
+        LORA_DMA_WAIT()
+        __syncthreads();
+    }
+#undef LORA_DMA_TILE
+#undef LORA_DMA_WAIT
 }
 
 template <bool BIG, bool VF32>
@@ -874,7 +856,7 @@ __global__ __launch_bounds__(kThreads, BIG ? 2 : 4) void k_expand(const Unit *__
                                                                   int64_t slice_stride, uint16_t *__restrict__ y,
                                                                   int64_t ldy, Sync sy)
 {
-    __shared__ __attribute__((aligned(16))) char lds[kExpandLds];
+    __shared__ __attribute__((aligned(16))) char lds[BIG ? kBigLds : kExpandLds];
     expand_dispatch<BIG, VF32>(units[blockIdx.x], perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
 }
 
