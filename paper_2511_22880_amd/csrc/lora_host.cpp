@@ -416,7 +416,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
         // (16 per wavefront, v kept in registers) and a quarter of the columns, at least 512
         int cols = expand_cols_per_unit(r.r8, out);
         int etile = lora::kTokTile;
-        if (token_heavy) {
+        if (token_heavy && r.r8 <= 128) {  // above rank 128 a strip's tile does not fit the kernel's LDS buffer
             etile = 64;
             cols = std::min(out, std::max(512, (out / 4 + 127) / 128 * 128));
         }
@@ -436,7 +436,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                 u.sync_idx = sync_base[si] + tok0 / lora::kTokTile;
                 u.sync_n = sync_n;
                 fill_tokens(u, r);
-                (token_heavy ? sg->expand_big_units : sg->expand_units).push_back(u);
+                (etile > lora::kTokTile ? sg->expand_big_units : sg->expand_units).push_back(u);
             }
     }
 

@@ -660,8 +660,9 @@ static __device__ __forceinline__ void expand_big_body(const Unit &u, const int3
                                                        int64_t slice_stride, uint16_t *__restrict__ y,
                                                        int64_t ldy, char *lds, const Sync &sy)
 {
-    // the tile of one strip is 128 * r8 * 2 bytes <= 32 KiB up to rank 128: two buffers; above: one
-    constexpr bool DB = KSTEPS <= 4;
+    // the tile of one strip is 128 * r8 * 2 bytes <= 32 KiB up to rank 128: two buffers of 32 KiB
+    static_assert(KSTEPS <= 4, "token-heavy expand units exist up to rank 128");
+    constexpr bool DB = true;
     constexpr int WREG = 2 * KSTEPS;  // 16-byte pieces of a tile per thread (256 threads): 128*32*KSTEPS*2 / 4096
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -818,10 +819,8 @@ static __device__ __forceinline__ void expand_dispatch(const Unit &u, const int3
             expand_big_body<1, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
         else if (r8 <= 64)
             expand_big_body<2, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
-        else if (r8 <= 128)
+        else  // the planner makes such units only up to rank 128
             expand_big_body<4, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
-        else
-            expand_big_body<8, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
     } else {
         if (r8 <= 32)
             expand_body<1, false, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
