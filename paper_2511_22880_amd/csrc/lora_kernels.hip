@@ -536,10 +536,12 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
             const bool e_ok = e_tok < bk.ntok;
             bk.e_y = y + (int64_t)toks[e_ok ? t0 + e_tok : 0] * ldy + u.p0 + 8 * e_cg;
 #pragma unroll
-            for (int s = 0; s < S; ++s)
-                bk.yv[s] = (e_ok && c0 + s * kStrip < ncols)
-                               ? *reinterpret_cast<const uint4 *>(bk.e_y + c0 + s * kStrip)
-                               : zero;
+            for (int s = 0; s < S; ++s) {
+                // no per-lane condition around the 16-byte load (it would be split into four masked
+                // 4-byte loads): threads without a token read the unit's first token's row
+                bk.yv[s] = zero;
+                if (c0 + s * kStrip < ncols) bk.yv[s] = *reinterpret_cast<const uint4 *>(bk.e_y + c0 + s * kStrip);
+            }
 #pragma unroll
             for (int it = 0; it < ITEMS; ++it) {
                 const bool ok = (n < bk.ntok) && j_ok[it];
@@ -734,7 +736,9 @@ static __device__ __forceinline__ void expand_big_body(const Unit &u, const int3
     uint4 ya[4], yb[4];
     auto fetch_y = [&](int s, uint4 (&yv)[4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) yv[e] = y_ok[e] ? *reinterpret_cast<const uint4 *>(yrow[e] + s * kStrip) : zero;
+        // unconditional: rows of absent tokens point at the unit's first token (a per-lane condition
+        // around a 16-byte load makes the compiler split it into four masked 4-byte loads)
+        for (int e = 0; e < 4; ++e) yv[e] = *reinterpret_cast<const uint4 *>(yrow[e] + s * kStrip);
     };
     auto compute = [&](int s, int buf, const uint4 (&yv)[4]) __attribute__((always_inline)) {
         if (nt <= 0) return;
