@@ -105,6 +105,9 @@ def main() -> int:
                     help="cfg1 (default, the benchmark line) | cfg2:<shape 0..2> | cfg3:<projection 0..6> | "
                          "cfg4:<shape 0..2>:<9to1|1to1|1to9>[:<0|1> only that rank class]")
     ap.add_argument("--fused", action="store_true", help="single-launch lora_apply (decode-sized batches)")
+    ap.add_argument("--padded-control", action="store_true",
+                    help="control run: every adapter stored at the largest rank of the pool, zero-padded (the "
+                         "layout whose cost the paper's motivation measures); same batch, same results")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -129,16 +132,23 @@ def main() -> int:
     T, in_f, out_f = b0.T, b0.in_features, b0.out_features
 
     # ---- pools: one arena per projection of the step (distinct memory, so nothing is served from cache)
-    nbytes = L.lora_pool_bytes(in_f, out_f, b0.ranks, b0.scales)
+    pool_ranks = np.full_like(b0.ranks, b0.ranks.max()) if args.padded_control else b0.ranks
+    nbytes = L.lora_pool_bytes(in_f, out_f, pool_ranks, b0.scales)
     arenas = [torch.zeros(nbytes, dtype=torch.uint8, device=dev) for _ in range(nl)]
-    pools = [L.lora_pool_create(in_f, out_f, b0.ranks, b0.scales, a) for a in arenas]
+    pools = [L.lora_pool_create(in_f, out_f, pool_ranks, b0.scales, a) for a in arenas]
     A = [None] * b0.n_adapters
     B = [None] * b0.n_adapters
     if seeded:
         # layer 0 from the seeded host generator, the other layers device copies of its packed arena
         for a in range(b0.n_adapters):
             A[a], B[a] = b0.adapter_bits(a)
-            L.lora_pool_load(pools[0], a, A[a], B[a], stream=stream)
+            Ap, Bp = A[a], B[a]
+            if args.padded_control:
+                Ap = np.zeros((in_f, int(pool_ranks[a])), dtype=np.uint16)
+                Bp = np.zeros((int(pool_ranks[a]), out_f), dtype=np.uint16)
+                Ap[:, :A[a].shape[1]] = A[a]
+                Bp[:B[a].shape[0]] = B[a]
+            L.lora_pool_load(pools[0], a, Ap, Bp, stream=stream)
         for l in range(1, nl):
             arenas[l].copy_(arenas[0])
         xs_bits = [wl.cfg1_decode(layer=l).x_bits() for l in range(nl)]
@@ -250,6 +260,7 @@ def main() -> int:
                    "expand_units": info["n_expand_units"], "k_slices": info["n_k_slices"],
                    "algorithmic_bytes_per_apply": shrink_bytes + expand_bytes,
                    "flops_per_apply": b0.flops(), "single_launch_apply": bool(args.fused),
+                   "padded_control": bool(args.padded_control), "weight_bytes_read_per_apply": info["weight_bytes"],
                    "parity_max_row_rel_l2": err},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

@@ -64,12 +64,19 @@ typedef struct {
     int32_t dtype; /* LORA_BF16 */
 } lora_pool_desc_t;
 
-/* Where one adapter lives inside the arena (element = one bf16).  The packed form is
- *   A^T : [rank_padded][in_features]   at a_offset   (rows rank..rank_padded-1 are zero)
- *   B^T : [out_features][rank_padded]  at b_offset   (columns rank..rank_padded-1 are zero)
- * with rank_padded = rank rounded up to a multiple of 8 (no padding for ranks 8,16,...,256).
- * Both matrices are stored with the contracted index contiguous, so a rank-r adapter costs
- * 2*r_padded*(in+out) bytes whatever the other adapters' ranks are. */
+/* Where one adapter lives inside the arena (element = one bf16): A^T (rank_padded x in_features) at
+ * a_offset, B^T (out_features x rank_padded) at b_offset, rank_padded = rank rounded up to a multiple of
+ * 8, padding rows / columns zero.  An adapter costs 2*rank_padded*(in+out) bytes whatever the other
+ * adapters' ranks are.  Inside a matrix the elements are in the order in which a 16x16x32 bf16 MFMA
+ * reads its weight operand (lane l: 8 consecutive values of the contracted index, chunk l>>4, of row
+ * l&15), so that one wavefront load of an operand is 1 KB of consecutive bytes:
+ *   A^T element (row j, k):   block jb = j/16 of h rows (h = 16, or 8 for the last block when
+ *        rank_padded mod 16 == 8), n = j mod 16, step s = k/32, kq = (k mod 32)/8, e = k mod 8:
+ *        a_offset + 16*jb*in + s*32*h + (kq*h + n)*8 + e
+ *   B^T element (column c, j): strip = c/128, within it c' = c mod 128, b = c' mod 8, n = c'/8,
+ *        kp = j/8, e = j mod 8:
+ *        b_offset + 128*strip*rank_padded + ((b*(rank_padded/8) + kp)*16 + n)*8 + e
+ * Callers never build this form themselves: lora_pool_load takes row-major A and B. */
 typedef struct {
     uint64_t a_offset;
     uint64_t b_offset;

@@ -24,17 +24,25 @@ def dev_to_bits(t: torch.Tensor) -> np.ndarray:
 class DevicePool:
     """A pool for one CoBatch with the adapters the batch uses (or all of them) loaded from host."""
 
-    def __init__(self, batch: wl.CoBatch, load="used", stream=None):
+    def __init__(self, batch: wl.CoBatch, load="used", stream=None, padded=False):
         self.batch = batch
-        n = L.lora_pool_bytes(batch.in_features, batch.out_features, batch.ranks, batch.scales)
+        # padded: the control layout, every adapter stored at the pool's largest rank with zero rows / columns
+        ranks = np.full_like(batch.ranks, batch.ranks.max()) if padded else batch.ranks
+        n = L.lora_pool_bytes(batch.in_features, batch.out_features, ranks, batch.scales)
         self.arena = torch.zeros(max(n, 256), dtype=torch.uint8, device="cuda")
-        self.pool = L.lora_pool_create(batch.in_features, batch.out_features, batch.ranks, batch.scales, self.arena)
+        self.pool = L.lora_pool_create(batch.in_features, batch.out_features, ranks, batch.scales, self.arena)
         self.A = [None] * batch.n_adapters
         self.B = [None] * batch.n_adapters
         ids = batch.used_adapters() if load == "used" else range(batch.n_adapters)
         for a in ids:
             A, B = batch.adapter_bits(int(a))
             self.A[int(a)], self.B[int(a)] = A, B
+            if padded:
+                Ap = np.zeros((batch.in_features, int(ranks[a])), dtype=np.uint16)
+                Bp = np.zeros((int(ranks[a]), batch.out_features), dtype=np.uint16)
+                Ap[:, :A.shape[1]] = A
+                Bp[:B.shape[0]] = B
+                A, B = Ap, Bp
             L.lora_pool_load(self.pool, int(a), A, B, stream=stream)
 
     def close(self):

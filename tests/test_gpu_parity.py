@@ -41,6 +41,20 @@ def test_small_mixed_ragged():
     _full_parity(wl.small_mixed(seed=3, in_features=1280, out_features=640), y0_kind="small")
 
 
+def test_padded_control_pool():
+    """The control layout (every adapter stored zero-padded at the largest rank, what a kernel sized to
+    the largest rank needs) goes through the same entry points and gives the same rows."""
+    for b in (wl.small_mixed(), wl.cfg4_skew(0, "1:1", adapters_per_class=2)):
+        print(f"[case] padded pool {b.name} T={b.T}", flush=True)
+        dp = G.DevicePool(b, padded=True)
+        x_bits, y0_bits = b.x_bits(), b.y0_bits("zero")
+        y_bits = G.apply_on_gpu(dp, x_bits, y0_bits)
+        rows = np.arange(0, b.T, 4, dtype=np.int32)
+        y_ref = G.oracle_apply(dp, x_bits, y0_bits, rows=rows)
+        G.check_parity(y_bits, y_ref, y0_bits, b.token_adapter, rows=rows)
+        dp.close()
+
+
 def test_unit_y0_rounds_once():
     """With y0 ~ N(0,1) the delta is below one bf16 ulp of most outputs: the result must be the
     oracle's value rounded to bf16, within one bf16 ulp per element."""
@@ -327,6 +341,13 @@ def test_cfg3_stack_full_size(layer, projection):
 @pytest.mark.parametrize("shape,split", [(0, "9:1"), (0, "1:1"), (0, "1:9"), (1, "1:1"), (2, "1:1")])
 def test_cfg4_skew_full_size(shape, split):
     _sampled_parity(wl.cfg4_skew(shape, split), n_rows=64)
+
+
+@pytest.mark.parametrize("split", ["9:1", "1:9"])
+def test_cfg4_two_adapter_variant_full_size(split):
+    """One rank-8 and one rank-256 adapter share the 512 tokens (the co-serving pair of the paper's
+    motivation, Fig. 1): groups of up to 461 tokens on the decode-sized units."""
+    _sampled_parity(wl.cfg4_skew(0, split, adapters_per_class=1), n_rows=64)
 
 
 def test_cfg4_isolated_class_equals_mixed_rows():
