@@ -105,6 +105,8 @@ def main() -> int:
                     help="cfg1 (default, the benchmark line) | cfg2:<shape 0..2> | cfg3:<projection 0..6> | "
                          "cfg4:<shape 0..2>:<9to1|1to1|1to9>[:<0|1> only that rank class]")
     ap.add_argument("--fused", action="store_true", help="single-launch lora_apply (decode-sized batches)")
+    ap.add_argument("--whole-k-limit", type=int, default=None,
+                    help="planning knob lora_set_whole_k_limit (default: the library's, 1024; 0 = always k-slices)")
     ap.add_argument("--padded-control", action="store_true",
                     help="control run: every adapter stored at the largest rank of the pool, zero-padded (the "
                          "layout whose cost the paper's motivation measures); same batch, same results")
@@ -126,6 +128,8 @@ def main() -> int:
     hip = Hip()
     if args.fused:
         L.lora_set_fused_apply(True)
+    if args.whole_k_limit is not None:
+        L.lora_set_whole_k_limit(args.whole_k_limit)
 
     b0, description, default_layers, seeded = pick_workload(args.workload, wl)
     nl = args.layers or default_layers

@@ -219,12 +219,21 @@ lora_status_t lora_apply_workspace_bytes(const lora_pool_t *pool, const lora_seg
 lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *seg, const void *x, int64_t ldx,
                          void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream);
 
-/* lora_apply is two launches by default (shrink units, then expand units).  In both forms the shrink
+/* Planning knob, process-wide, read by the lora_segments_plan / build / rebuild calls that follow.
+ * A batch whose decode-sized groups make between 64 and `max_units` shrink units when a unit takes
+ * the whole of k (16 rank rows x up to 16 tokens each) is planned that way: work groups of 16
+ * wavefronts, v complete when the unit ends.  Other batches cut k into up to 4 slices per unit (more,
+ * smaller units spread a small batch over the chip and fill the last round of a large one better) and
+ * add the slices up through counters.  Both plans give bitwise the same v.  Default 1024 (four rounds
+ * of one work group per compute unit); 0 = always k-slices. */
+lora_status_t lora_set_whole_k_limit(int32_t max_units);
+
+/* lora_apply is two launches by default (shrink units, then expand units).  With k-slices the shrink
  * unit that completes a token tile (found through per-tile counters in the segment object's device
  * table) adds the k-slices up and leaves the tile's v for the expand units.
- * lora_set_fused_apply(1) selects a single launch in which shrink and expand units share the grid
- * and the expand units poll, with a bounded number of polls, until their tile's v is complete.  The
- * counters' epoch is host state of the segment object, so applies that share one object must be
+ * lora_set_fused_apply(1) selects, for batches planned with k-slices and without token-heavy groups,
+ * a single launch in which shrink and expand units share the grid and the expand units poll, with a
+ * bounded number of polls, until their tile's v is complete.  The counters' epoch is host state of the segment object, so applies that share one object must be
  * issued by one thread at a time and ordered on one stream, and must not be captured into a graph
  * that is replayed.  The setting is process-wide. */
 lora_status_t lora_set_fused_apply(int enabled);

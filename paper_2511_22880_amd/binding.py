@@ -28,7 +28,7 @@ EXPORTS = (
     "lora_segments_build", "lora_segments_build_ranges", "lora_segments_rebuild", "lora_segments_info",
     "lora_segments_export", "lora_segments_export_units", "lora_segments_destroy", "lora_workspace_bytes",
     "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_profile_next_apply",
-    "lora_set_fused_apply", "lora_segments_check",
+    "lora_set_fused_apply", "lora_set_whole_k_limit", "lora_segments_check",
     "lora_status_string",
     "lora_last_error",
 )
@@ -303,6 +303,10 @@ def lora_apply(pool: Pool, seg: Segments, x, y, workspace, stream=None, ldx: Opt
 
 def lora_set_fused_apply(enabled: bool) -> None:
     _check(lib().lora_set_fused_apply(ctypes.c_int(1 if enabled else 0)))
+
+
+def lora_set_whole_k_limit(max_units: int) -> None:
+    _check(lib().lora_set_whole_k_limit(ctypes.c_int32(int(max_units))))
 
 
 def lora_segments_check(seg: Segments, stream=None) -> None:

@@ -80,6 +80,8 @@ struct lora_segments {
     size_t staging_capacity;
     size_t off_perm, off_shrink, off_prefill, off_expand, off_expand_big, off_sync, table_bytes;
     bool has_big_units;     // some unit holds more than 16 tokens (token-heavy groups)
+    bool wide;              // decode shrink units span all of k (work groups of 16 wavefronts, no partial sums)
+    int wide_slices, wide_slice_len;  // the k-slices such a work group's wavefronts divide k into
     int n_sync;             // counters: one per (group, token tile), then the time-out flag
     unsigned launches;      // fused launches since the table was uploaded (the counters' epoch)
     hipEvent_t copied;  // recorded after the upload; guards re-use of `staging`
@@ -276,6 +278,18 @@ static int expand_cols_per_unit(int r8, int out)
 // longer than a whole decode-sized launch lasts.
 static const int kPrefillMinTokens = 32;
 static const int kPrefillMinBatch = 1024;
+// Between kWholeKMin and this many whole-k shrink units (four rounds of one work group per compute
+// unit of the chip) the decode shrink runs without k-slices; measured on the rank-skew batches, 442
+// and 544 such units beat their 4 x as many k-slice units by 8 %, 32 units lose 9 % to their 128.
+static int g_whole_k_limit = 1024;
+static const int kWholeKMin = 64;  // below this, k-slices are what spreads the batch over the chip
+
+extern "C" lora_status_t lora_set_whole_k_limit(int32_t max_units)
+{
+    if (max_units < 0) return fail(LORA_ERR_INVALID_ARG, "max_units = %d", max_units);
+    g_whole_k_limit = max_units;
+    return LORA_OK;
+}
 
 static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const int32_t *ta, int32_t T)
 {
@@ -300,7 +314,24 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     sg->T = T;
     sg->n_active = n_active;
     sg->uploaded = false;
-    choose_k_slices(pool->in_features, &sg->n_k_slices, &sg->k_slice_len);
+    // Up to a few rounds of work groups, a unit takes the whole of k, so v needs no partial sums in
+    // memory.  Very few units, or very many: k-slices, which spread a small batch over more compute
+    // units and fill the last round of a large one better.
+    int64_t whole_k_units = 0;
+    for (int a = 0; a < N; ++a) {
+        if (!count[a] || (count[a] >= kPrefillMinTokens && n_active >= kPrefillMinBatch)) continue;
+        whole_k_units += (int64_t)((pool->r8[a] + lora::kRowTile - 1) / lora::kRowTile) *
+                         ((count[a] + lora::kTokTile - 1) / lora::kTokTile);
+    }
+    sg->wide = whole_k_units >= kWholeKMin && whole_k_units <= g_whole_k_limit;
+    choose_k_slices(pool->in_features, &sg->wide_slices, &sg->wide_slice_len);
+    if (sg->wide) {
+        sg->n_k_slices = 1;
+        sg->k_slice_len = pool->in_features;
+    } else {
+        sg->n_k_slices = sg->wide_slices;
+        sg->k_slice_len = sg->wide_slice_len;
+    }
 
     sg->seg_start.clear();
     sg->seg_adapter.clear();
@@ -777,7 +808,11 @@ extern "C" lora_status_t lora_shrink(const lora_pool_t *pool, const lora_segment
     if ((st = check_workspace(workspace, ws_bytes, partial_bytes(sg))) != LORA_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     const lora::LaunchCtx c = ctx_for(pool, sg, kShrink), cp = ctx_for(pool, sg, kPrefill);
-    if (sg->n_k_slices <= 1) {
+    if (sg->wide) {
+        HIP_TRY(lora::launch_shrink_wide(c, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, v, nullptr,
+                                         nullptr, s));
+        HIP_TRY(lora::launch_shrink_prefill(cp, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, s));
+    } else if (sg->n_k_slices <= 1) {
         HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, v, 1, 0, nullptr, s));
         HIP_TRY(lora::launch_shrink_prefill(cp, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, s));
     } else {
@@ -867,14 +902,19 @@ extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments
     const lora::LaunchCtx cs = ctx_for(pool, sg, kShrink), cp = ctx_for(pool, sg, kPrefill),
                           ce = ctx_for(pool, sg, kExpand);
     if (ev[0]) HIP_TRY(hipEventRecord(ev[0], s));
-    // units of more than 16 tokens span several counters: such batches always take separate launches
-    if (g_fused_apply && !sg->has_big_units) {
+    // units of more than 16 tokens span several counters, and whole-k shrink units are work groups of
+    // another size: such batches always take separate launches
+    if (g_fused_apply && !sg->has_big_units && !sg->wide) {
         HIP_TRY(lora::launch_apply_fused(cs, ce, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride,
                                          (uint16_t *)y, ldy, &sa, s));
         if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
     } else {
         HIP_TRY(lora::launch_shrink_prefill(cp, (const uint16_t *)x, ldx, sa.v_hi, sa.v_lo, nullptr, nsl, stride, s));
-        HIP_TRY(lora::launch_shrink(cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride, &sa, s));
+        if (sg->wide)
+            HIP_TRY(lora::launch_shrink_wide(cs, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, nullptr,
+                                             sa.v_hi, sa.v_lo, s));
+        else
+            HIP_TRY(lora::launch_shrink(cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride, &sa, s));
         if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
         HIP_TRY(lora::launch_expand(ce, false, parts, nsl, stride, (uint16_t *)y, ldy, &sa, s));
         HIP_TRY(lora::launch_expand(ctx_for(pool, sg, kExpandBig), true, parts, nsl, stride, (uint16_t *)y, ldy, &sa,

@@ -267,6 +267,134 @@ static __device__ __forceinline__ void shrink_body(const Unit &u, const uint16_t
 }
 
 // ------------------------------------------------------------------------------------------------
+// shrink, whole-k units: one unit = (group, <=16 tokens, 16 rank rows, all of k), one work group of
+// 16 wavefronts.  Used when the batch's units fit the chip in one round: each compute unit then
+// streams one row block of one adapter with 128 KB of loads in flight, and v leaves complete (no
+// partial sums in memory, no counters).  The work group is four k-slice units in one: wavefronts
+// 4j .. 4j+3 do exactly the arithmetic of the four wavefronts of a k-slice unit for slice j, and the
+// tiles are added in the same order (inside a slice by wavefront, then the slices), so the result
+// is bitwise the one the k-slice path gives.  Every wavefront requests its 8 weight operands and its
+// own piece of the tokens' x rows (coalesced, two tokens per load), turns the x piece into MFMA
+// operand order through a private LDS region (no work-group barrier), and runs its 8 MFMAs.
+// ------------------------------------------------------------------------------------------------
+constexpr int kWideWaves = 4 * kMaxSlices;
+constexpr int kWideThreads = 64 * kWideWaves;
+constexpr int kWideK = 32 * kShrinkSteps;  // k range of one wavefront per pass
+constexpr int kWideRow = kWideK + 8;       // LDS row length in bf16, padded by 16 bytes
+constexpr int kWideSlab = kTokTile * kWideRow * 2;
+constexpr int kWideLds = kWideWaves * kWideSlab + kWideWaves * 64 * 16;
+
+__global__ __launch_bounds__(kWideThreads) void k_shrink_wide(const Unit *__restrict__ units,
+                                                              const uint16_t *__restrict__ arena,
+                                                              const uint16_t *__restrict__ x, int64_t ldx, int in,
+                                                              int k_slice_len, int n_slices,
+                                                              float *__restrict__ v_f32,
+                                                              uint16_t *__restrict__ v_hi,
+                                                              uint16_t *__restrict__ v_lo)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kWideLds];
+    const Unit &u = units[blockIdx.x];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int slice = wave >> 2;  // the k-slice this wavefront works on
+    const int wq = wave & 3;      // its place among the slice's four wavefronts
+    const int i = lane & 15;
+    const int kq = lane >> 4;
+    uint16_t(*slab)[kWideRow] = reinterpret_cast<uint16_t(*)[kWideRow]>(lds + wave * kWideSlab);
+    f32x4(*red)[64] = reinterpret_cast<f32x4(*)[64]>(lds + kWideWaves * kWideSlab);
+
+    const int ntok = u.ntok, pn = u.pn;
+    const bool w_ok = i < pn;
+    const bool x_ok = i < ntok;
+    const uint16_t *wrow = arena + u.w_off + (kq * pn + (w_ok ? i : 0)) * 8;
+    // x staging: lane -> token 2t + half, 16-byte chunk s_chunk of the wavefront's 256 k.  The unit's
+    // token list repeats its first token beyond ntok, so every listed row is a valid row of x.
+    const int half = lane >> 5;
+    const int s_chunk = lane & 31;
+    const uint16_t *xrow[kTokTile / 2];
+#pragma unroll
+    for (int t = 0; t < kTokTile / 2; ++t) xrow[t] = x + (int64_t)(half ? u.tok[2 * t + 1] : u.tok[2 * t]) * ldx;
+
+    const int kslice_beg = slice * k_slice_len;
+    int kslice_end = kslice_beg + k_slice_len;
+    if (kslice_end > in) kslice_end = in;
+    if (slice >= n_slices) kslice_end = kslice_beg;
+
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const uint4 zero = {0u, 0u, 0u, 0u};
+    for (int kp = kslice_beg; kp < kslice_end; kp += 4 * kWideK) {
+        const int kbeg = kp + wq * kWideK;  // wavefront-uniform
+        if (kbeg >= kslice_end) break;
+        uint4 a[kShrinkSteps];
+#pragma unroll
+        for (int q = 0; q < kShrinkSteps; ++q) {
+            const int k = kbeg + 32 * q;
+            a[q] = (k < kslice_end) ? ld16(wrow + (int64_t)k * pn) : zero;
+        }
+        // in is a multiple of 64, so a 16-byte chunk is either inside the row or wholly beyond it;
+        // chunks beyond it are fetched from the row's last chunk instead and never enter an MFMA
+        int kx = kbeg + 8 * s_chunk;
+        if (kx > in - 8) kx = in - 8;
+        uint4 xs[kTokTile / 2];
+#pragma unroll
+        for (int t = 0; t < kTokTile / 2; ++t)
+            if (2 * t < ntok) xs[t] = ld16(xrow[t] + kx);
+#pragma unroll
+        for (int t = 0; t < kTokTile / 2; ++t)
+            if (2 * t < ntok) *reinterpret_cast<uint4 *>(&slab[2 * t + half][8 * s_chunk]) = xs[t];
+        // the region is private to this wavefront and LDS operations of a wavefront complete in order
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        __builtin_amdgcn_wave_barrier();
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+#pragma unroll
+        for (int q = 0; q < kShrinkSteps; ++q) {
+            const int k = kbeg + 32 * q;
+            if (k < kslice_end) {
+                const uint4 aa = w_ok ? a[q] : zero;
+                const uint4 bb = x_ok ? *reinterpret_cast<const uint4 *>(&slab[i][32 * q + 8 * kq]) : zero;
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aa), as_bf16x8(bb), acc, 0, 0, 0);
+            }
+        }
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        __builtin_amdgcn_wave_barrier();
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    }
+    red[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0) {
+        f32x4 t = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int sl = 0; sl < kMaxSlices; ++sl)
+            if (sl < n_slices) {
+                f32x4 ts = red[4 * sl][lane];
+                ts += red[4 * sl + 1][lane];
+                ts += red[4 * sl + 2][lane];
+                ts += red[4 * sl + 3][lane];
+                if (sl == 0)
+                    t = ts;
+                else
+                    t += ts;
+            }
+        // register r of lane (i, kq) is rank row 4*kq + r of the block for token i
+        if (x_ok && 4 * kq < pn) {
+            const int64_t off = u.v_off + (int64_t)i * u.r8 + 4 * kq;
+            if (v_hi) {
+                uint2 h, l;
+                h.x = pack_bf16_rne(t[0], t[1]);
+                h.y = pack_bf16_rne(t[2], t[3]);
+                l.x = pack_bf16_rne(t[0] - bf16_bits_to_f32(h.x & 0xFFFFu), t[1] - __uint_as_float(h.x & 0xFFFF0000u));
+                l.y = pack_bf16_rne(t[2] - bf16_bits_to_f32(h.y & 0xFFFFu), t[3] - __uint_as_float(h.y & 0xFFFF0000u));
+                *reinterpret_cast<uint2 *>(v_hi + off) = h;
+                *reinterpret_cast<uint2 *>(v_lo + off) = l;
+            } else {
+                *reinterpret_cast<f32x4 *>(v_f32 + off) = t;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // shrink of token-heavy groups (prefill): one unit = (group, 16*TB tokens, all rank rows, all of k).
 // The four wavefronts split k into quarters; each streams its quarter of the tokens' x rows exactly
 // once, 16 bytes per lane straight into the MFMA's token operand, XD steps ahead (x comes from
@@ -951,6 +1079,16 @@ hipError_t launch_shrink(const LaunchCtx &c, const uint16_t *x, int64_t ldx, int
     if (c.n_units <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_shrink, dim3(c.n_units), dim3(kThreads), 0, stream, c.units, c.arena, x, ldx,
                        c.in_features, k_slice_len, v_out, n_slices, slice_stride, make_sync(sync, 0));
+    return hipGetLastError();
+}
+
+hipError_t launch_shrink_wide(const LaunchCtx &c, const uint16_t *x, int64_t ldx, int k_slice_len, int n_slices,
+                              float *v_f32, uint16_t *v_hi, uint16_t *v_lo, hipStream_t stream)
+{
+    if (c.n_units <= 0) return hipSuccess;
+    if (n_slices < 1 || n_slices > kMaxSlices) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_shrink_wide, dim3(c.n_units), dim3(kWideThreads), 0, stream, c.units, c.arena, x, ldx,
+                       c.in_features, k_slice_len, n_slices, v_f32, v_hi, v_lo);
     return hipGetLastError();
 }
 

@@ -80,17 +80,50 @@ def test_cfg1_decode_full_size():
 def test_two_launch_apply_matches_fused_apply():
     """lora_apply as one launch (expand units wait on counters) and as two launches give the same
     bits: the arithmetic and its order are identical, only the hand-over of v differs."""
-    for b in (wl.small_mixed(seed=4), wl.cfg1_decode(in_features=1024, out_features=512)):
+    L.lora_set_whole_k_limit(0)     # the single launch exists for the k-slice plan only
+    try:
+        for b in (wl.small_mixed(seed=4), wl.cfg1_decode(in_features=2048, out_features=512)):
+            dp = G.DevicePool(b)
+            x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
+            y_two = G.apply_on_gpu(dp, x_bits, y0_bits)
+            try:
+                L.lora_set_fused_apply(True)
+                y_fused = G.apply_on_gpu(dp, x_bits, y0_bits)
+            finally:
+                L.lora_set_fused_apply(False)
+            assert np.array_equal(y_fused, y_two)
+            G.check_parity(y_fused, G.oracle_apply(dp, x_bits, y0_bits), y0_bits, b.token_adapter)
+            dp.close()
+    finally:
+        L.lora_set_whole_k_limit(1024)
+
+
+def test_whole_k_plan_matches_k_slice_plan_bitwise():
+    """The two plans of the decode shrink (whole-k units of 16 wavefronts; k-slice units added up
+    through counters) do the same arithmetic in the same order: same bits in y and in v."""
+    for b in (wl.small_mixed(seed=5, in_features=2048), wl.cfg1_decode(in_features=4096, out_features=256, n_tokens=96),
+              wl.cfg1_decode(in_features=3200, out_features=128, n_tokens=40)):
+        print(f"[case] plans on {b.name} T={b.T} in={b.in_features}", flush=True)
         dp = G.DevicePool(b)
         x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
-        y_two = G.apply_on_gpu(dp, x_bits, y0_bits)
-        try:
-            L.lora_set_fused_apply(True)
-            y_fused = G.apply_on_gpu(dp, x_bits, y0_bits)
-        finally:
-            L.lora_set_fused_apply(False)
-        assert np.array_equal(y_fused, y_two)
-        G.check_parity(y_fused, G.oracle_apply(dp, x_bits, y0_bits), y0_bits, b.token_adapter)
+        ys, vs = [], []
+        for limit in (1024, 0):
+            L.lora_set_whole_k_limit(limit)
+            try:
+                ys.append(G.apply_on_gpu(dp, x_bits, y0_bits))
+                seg = L.lora_segments_build(dp.pool, b.token_adapter)
+                info = L.lora_segments_info(seg)
+                assert (info["n_k_slices"] == 1) == (limit == 1024)
+                v = torch.zeros(max(info["v_floats"], 1), dtype=torch.float32, device="cuda")
+                ws = torch.empty(max(L.lora_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+                L.lora_shrink(dp.pool, seg, G.bits_to_dev(x_bits), v, ws)
+                torch.cuda.synchronize()
+                vs.append(v.cpu().numpy())
+                L.lora_segments_destroy(seg)
+            finally:
+                L.lora_set_whole_k_limit(1024)
+        assert np.array_equal(ys[0], ys[1]) and np.array_equal(vs[0].view(np.uint32), vs[1].view(np.uint32))
+        G.check_parity(ys[0], G.oracle_apply(dp, x_bits, y0_bits), y0_bits, b.token_adapter)
         dp.close()
 
 
@@ -99,10 +132,12 @@ def test_apply_repeated_on_one_table(fused):
     """The counters only grow; launch after launch on the same table must keep working (the epoch
     advances), also across a rebuild (counters and epoch start again)."""
     L.lora_set_fused_apply(fused)
+    L.lora_set_whole_k_limit(0 if fused else 1024)
     try:
         _repeated_on_one_table()
     finally:
         L.lora_set_fused_apply(False)
+        L.lora_set_whole_k_limit(1024)
 
 
 def _repeated_on_one_table():

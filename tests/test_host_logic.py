@@ -208,6 +208,29 @@ def test_planner_matches_brute_force_grouping(maker):
     L.lora_pool_destroy(pool)
 
 
+def test_whole_k_limit_switches_the_shrink_plan():
+    b = wl.cfg1_decode()
+    n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
+    pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
+    for a in range(b.n_adapters):
+        L.lora_pool_mark_resident(pool, a)
+    got = {}
+    try:
+        for limit in (1024, 216, 0):
+            L.lora_set_whole_k_limit(limit)
+            seg = L.lora_segments_plan(pool, b.token_adapter)
+            info = L.lora_segments_info(seg)
+            got[limit] = (info["n_k_slices"], info["n_shrink_units"])
+            L.lora_segments_destroy(seg)
+        with pytest.raises(L.LoraError):
+            L.lora_set_whole_k_limit(-1)
+    finally:
+        L.lora_set_whole_k_limit(1024)
+    # 217 whole-k units (16 rank rows x <= 16 tokens each) fit the default limit; below it k is cut in 4
+    assert got[1024] == (1, 217) and got[216] == (4, 868) and got[0] == (4, 868)
+    L.lora_pool_destroy(pool)
+
+
 def test_ranges_merge_requests_of_the_same_adapter():
     pool = make_pool()
     seg = L.lora_segments_plan_ranges(pool, [0, 3, 5, 9, 12], [1, -1, 0, 1])
