@@ -82,6 +82,7 @@ struct lora_segments {
     bool has_big_units;     // some unit holds more than 16 tokens (token-heavy groups)
     bool wide;              // decode shrink units span all of k (work groups of 16 wavefronts, no partial sums)
     int wide_slices, wide_slice_len;  // the k-slices such a work group's wavefronts divide k into
+    int n_prefill_hi;       // how many of prefill_units are above rank 64
     int n_sync;             // counters: one per (group, token tile), then the time-out flag
     unsigned launches;      // fused launches since the table was uploaded (the counters' epoch)
     hipEvent_t copied;  // recorded after the upload; guards re-use of `staging`
@@ -398,6 +399,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     }
     sg->n_sync = n_sync;
     sg->has_big_units = false;
+    sg->n_prefill_hi = 0;
     for (int32_t si : order) {
         const SegRec &r = sg->segs[si];
         const bool token_heavy = r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch;
@@ -420,6 +422,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                 u.v_off = r.v_off + (int64_t)tok0 * r.r8;
                 fill_tokens(u, r);
                 sg->prefill_units.push_back(u);
+                if (r.r8 > 64) ++sg->n_prefill_hi;
             }
         } else {
             for (int row0 = 0; row0 < r.r8; row0 += lora::kRowTile)
@@ -811,15 +814,15 @@ extern "C" lora_status_t lora_shrink(const lora_pool_t *pool, const lora_segment
     if (sg->wide) {
         HIP_TRY(lora::launch_shrink_wide(c, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, v, nullptr,
                                          nullptr, s));
-        HIP_TRY(lora::launch_shrink_prefill(cp, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, s));
+        HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, s));
     } else if (sg->n_k_slices <= 1) {
         HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, v, 1, 0, nullptr, s));
-        HIP_TRY(lora::launch_shrink_prefill(cp, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, s));
+        HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, s));
     } else {
         float *parts = (float *)workspace;
         HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, parts, sg->n_k_slices,
                                     sg->v_floats, nullptr, s));
-        HIP_TRY(lora::launch_shrink_prefill(cp, (const uint16_t *)x, ldx, nullptr, nullptr, parts, sg->n_k_slices,
+        HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, nullptr, nullptr, parts, sg->n_k_slices,
                                             sg->v_floats, s));
         HIP_TRY(lora::launch_reduce_slices(parts, sg->n_k_slices, sg->v_floats, v, sg->v_floats, s));
     }
@@ -909,7 +912,7 @@ extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments
                                          (uint16_t *)y, ldy, &sa, s));
         if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
     } else {
-        HIP_TRY(lora::launch_shrink_prefill(cp, (const uint16_t *)x, ldx, sa.v_hi, sa.v_lo, nullptr, nsl, stride, s));
+        HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, sa.v_hi, sa.v_lo, nullptr, nsl, stride, s));
         if (sg->wide)
             HIP_TRY(lora::launch_shrink_wide(cs, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, nullptr,
                                              sa.v_hi, sa.v_lo, s));

@@ -90,9 +90,11 @@ hipError_t launch_expand(const LaunchCtx &c, bool big, const float *v_in, int n_
                          uint16_t *y, int64_t ldy, const SyncArgs *sync, hipStream_t stream);
 
 // Shrink of token-heavy groups: one unit = (group, up to 32 tokens, all rank rows, the whole of k).
+// n_hi = how many of the units are above rank 64: with none, the launch takes the kernel that fits four
+// work groups on a compute unit, otherwise the one for any rank (two per compute unit).
 // Writes complete v: as bf16 hi + lo into v_hi / v_lo, or (v_f32 != NULL) as fp32 into v_f32 with the
 // other n_slices - 1 slices of the same rows set to zero.
-hipError_t launch_shrink_prefill(const LaunchCtx &c, const uint16_t *x, int64_t ldx, uint16_t *v_hi,
+hipError_t launch_shrink_prefill(const LaunchCtx &c, int n_hi, const uint16_t *x, int64_t ldx, uint16_t *v_hi,
                                  uint16_t *v_lo, float *v_f32, int n_slices, int64_t slice_stride,
                                  hipStream_t stream);
 

@@ -225,7 +225,9 @@ static __device__ __forceinline__ void shrink_body(const Unit &u, const uint16_t
             const int k = kbeg + 32 * q;
             if (k < kslice_end) {
                 const uint4 aa = w_ok ? a[q] : zero;
-                const uint4 bb = x_ok ? *reinterpret_cast<const uint4 *>(&slab[i][k - kp + 8 * kq]) : zero;
+                // rows of tokens beyond ntok hold whatever LDS held: they only reach accumulator columns
+                // that are never stored, and an unconditional 16-byte read stays one instruction
+                const uint4 bb = *reinterpret_cast<const uint4 *>(&slab[i][k - kp + 8 * kq]);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aa), as_bf16x8(bb), acc, 0, 0, 0);
             }
         }
@@ -352,7 +354,9 @@ __global__ __launch_bounds__(kWideThreads) void k_shrink_wide(const Unit *__rest
             const int k = kbeg + 32 * q;
             if (k < kslice_end) {
                 const uint4 aa = w_ok ? a[q] : zero;
-                const uint4 bb = x_ok ? *reinterpret_cast<const uint4 *>(&slab[i][32 * q + 8 * kq]) : zero;
+                // rows of tokens beyond ntok hold whatever LDS held: they only reach accumulator columns
+                // that are never stored, and an unconditional 16-byte read stays one instruction
+                const uint4 bb = *reinterpret_cast<const uint4 *>(&slab[i][32 * q + 8 * kq]);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aa), as_bf16x8(bb), acc, 0, 0, 0);
             }
         }
@@ -395,54 +399,87 @@ __global__ __launch_bounds__(kWideThreads) void k_shrink_wide(const Unit *__rest
 }
 
 // ------------------------------------------------------------------------------------------------
-// shrink of token-heavy groups (prefill): one unit = (group, 16*TB tokens, all rank rows, all of k).
-// The four wavefronts split k into quarters; each streams its quarter of the tokens' x rows exactly
-// once, 16 bytes per lane straight into the MFMA's token operand, XD steps ahead (x comes from
-// HBM).  The rows of A^T come from L2 (every token tile of the group re-reads them), one step
-// ahead, and are shared by the TB token blocks in registers.  The four partial tiles are summed
-// through LDS in a fixed order (3+1, 2+0, then 1+0) and v leaves complete: as bf16 hi + lo for the
-// expand, or as fp32.  JB = 16-row blocks of A^T (padded rank / 16 rounded up to 1, 2, 4, 8, 16).
+// shrink of token-heavy groups (prefill): one unit = (group, 32 tokens (16 above rank 128), all rank
+// rows, all of k).  The four wavefronts split k into quarters; each streams its quarter of the
+// tokens' x rows exactly once.  x comes from HBM with coalesced loads (a wavefront load covers 256
+// bytes of each of 4 tokens), one pass of 128 k ahead, and is turned into MFMA operand order through
+// an LDS region private to the wavefront, so no work-group barrier sits in the k loop.  (Loading the
+// token operand straight from memory, 16 rows x 64 bytes per load, costs the address path 3.7 times
+// as much per byte.)  The rows of A^T come from L2 (every token tile of the group re-reads them),
+// requested WD k steps ahead because a step of a low rank is far shorter than a round trip to L2,
+// and are shared by the TB token blocks in registers.  The four partial tiles are summed through
+// LDS (re-using the x regions) in a fixed order (3+1, 2+0, then 1+0) and v leaves complete: as bf16
+// hi + lo for the expand, or as fp32.  JB = 16-row blocks of A^T (1, 2, 4, 8, 16).
 // ------------------------------------------------------------------------------------------------
-constexpr int kPrefillLds = 2 * 16 * 64 * 16;  // two wavefronts' worth of up to 16 accumulator tiles
+constexpr int kPfTokens = 32;
+constexpr int kPfPassK = 128;                 // k per pass of a wavefront
+constexpr int kPfRow = kPfPassK + 8;          // LDS row length in bf16, padded by 16 bytes
+constexpr int kPfSlab = kPfTokens * kPfRow * 2;
+constexpr int kPrefillLds = 4 * kPfSlab;
 
-template <int JB, int TB>
-static __device__ __forceinline__ void shrink_prefill_body(const Unit &u, const int32_t *__restrict__ perm,
-                                                           const uint16_t *__restrict__ arena,
-                                                           const uint16_t *__restrict__ x, int64_t ldx, int in,
-                                                           uint16_t *__restrict__ v_hi, uint16_t *__restrict__ v_lo,
-                                                           float *__restrict__ v_f32, int n_slices,
-                                                           int64_t slice_stride, char *lds)
+// lane (n, kq) holds v[token][j .. j+3] of a tile; `at` is the element's index in v
+static __device__ __forceinline__ void store_v4(f32x4 f, int64_t at, uint16_t *__restrict__ v_hi,
+                                                uint16_t *__restrict__ v_lo, float *__restrict__ v_f32,
+                                                int n_slices, int64_t slice_stride)
 {
-    constexpr int XD = 4;
+    if (v_f32) {
+        *reinterpret_cast<f32x4 *>(v_f32 + at) = f;
+        for (int sl = 1; sl < n_slices; ++sl)
+            *reinterpret_cast<f32x4 *>(v_f32 + (int64_t)sl * slice_stride + at) = f32x4{0.f, 0.f, 0.f, 0.f};
+    } else {
+        uint2 h, l;
+        h.x = pack_bf16_rne(f[0], f[1]);
+        h.y = pack_bf16_rne(f[2], f[3]);
+        l.x = pack_bf16_rne(f[0] - bf16_bits_to_f32(h.x & 0xFFFFu), f[1] - __uint_as_float(h.x & 0xFFFF0000u));
+        l.y = pack_bf16_rne(f[2] - bf16_bits_to_f32(h.y & 0xFFFFu), f[3] - __uint_as_float(h.y & 0xFFFF0000u));
+        *reinterpret_cast<uint2 *>(v_hi + at) = h;
+        *reinterpret_cast<uint2 *>(v_lo + at) = l;
+    }
+}
+
+template <int JB, int TB, int WD>
+static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, const int32_t *__restrict__ perm,
+                                                             const uint16_t *__restrict__ arena,
+                                                             const uint16_t *__restrict__ x, int64_t ldx, int in,
+                                                             uint16_t *__restrict__ v_hi,
+                                                             uint16_t *__restrict__ v_lo, float *__restrict__ v_f32,
+                                                             int n_slices, int64_t slice_stride, char *lds)
+{
     constexpr int NT = JB * TB;
-    static_assert(NT <= 16, "accumulator tiles per wavefront");
-    f32x4(*red)[NT][64] = reinterpret_cast<f32x4(*)[NT][64]>(lds);
+    constexpr int NL = 4 * TB;  // x loads of a wavefront per pass: 4 tokens each
+    static_assert(16 * TB <= kPfTokens, "tokens of a unit");
+    static_assert(2 * NT * 64 * 16 <= kPrefillLds, "the partial tiles of two wavefronts fit the LDS");
+    static_assert(WD == 1 || WD == 2 || WD == 4, "the weight ring must divide the 4 steps of a pass");
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint16_t(*slab)[kPfRow] = reinterpret_cast<uint16_t(*)[kPfRow]>(lds + wave * kPfSlab);
+    f32x4(*red)[NT][64] = reinterpret_cast<f32x4(*)[NT][64]>(lds);  // re-uses the x regions after the k loop
     const int n = lane & 15;
     const int kq = lane >> 4;
     const int r8 = u.r8;
     const int ntok = u.ntok;
-    const uint4 zero = {0u, 0u, 0u, 0u};
 
-    const uint16_t *xrow[TB];
-    bool t_ok[TB];
+    // staging: load t of a pass takes tokens 4t .. 4t+3, this lane token 4t + kq, 16-byte chunk n
+    const uint16_t *xrow[NL];
 #pragma unroll
-    for (int tb = 0; tb < TB; ++tb) {
-        const int t = 16 * tb + n;
-        t_ok[tb] = t < ntok;
-        xrow[tb] = x + (int64_t)perm[u.perm_off + (t_ok[tb] ? t : 0)] * ldx + 8 * kq;
+    for (int t = 0; t < NL; ++t) {
+        const int tok = min(4 * t + kq, ntok - 1);
+        xrow[t] = x + (int64_t)perm[u.perm_off + tok] * ldx;
     }
+    // The caller picks JB from the rank; telling the compiler so removes the branches around the row
+    // blocks that always exist (with a branch per block the same loop ran 2.4 times slower).
+    __builtin_assume(r8 <= 16 * JB && (JB == 1 ? r8 >= 8 : r8 > 8 * JB));
     const uint16_t *wbase = arena + u.w_off;
+    const uint4 zero = {0u, 0u, 0u, 0u};
     int woff[JB];  // element offset of this lane's 16-byte piece in k step 0 of row block jb
     int wh[JB];    // rows in block jb (16, or 8 for the last block of a padded rank that is 8 mod 16)
-    bool w_ok[JB];
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) {
         const int h = min(16, r8 - 16 * jb);
         wh[jb] = h > 0 ? h : 16;
-        w_ok[jb] = n < h;
-        woff[jb] = 16 * jb * in + (kq * wh[jb] + (w_ok[jb] ? n : 0)) * 8;
+        // lanes n >= 8 of an 8-row block read the piece of row n - 8: they only reach accumulator rows
+        // beyond the padded rank, which are never stored
+        woff[jb] = 16 * jb * in + (kq * wh[jb] + (n & (wh[jb] - 1))) * 8;
     }
 
     f32x4 acc[JB][TB];
@@ -456,40 +493,63 @@ static __device__ __forceinline__ void shrink_prefill_body(const Unit &u, const 
     const int kbeg = wave * kquarter;
     const int kend = min(in, kbeg + kquarter);
 
-    uint4 xq[XD][TB], w[JB];
+    // in is a multiple of 64, so a 16-byte chunk lies inside the row or wholly beyond it; a chunk
+    // beyond the row is fetched from the row's last chunk instead and never enters an MFMA
+    auto x_pass = [&](int k0, uint4(&xs)[NL]) __attribute__((always_inline)) {
+        const int kx = min(k0 + 8 * n, in - 8);
 #pragma unroll
-    for (int d = 0; d < XD; ++d)
-#pragma unroll
-        for (int tb = 0; tb < TB; ++tb) xq[d][tb] = (kbeg + 32 * d < kend) ? ld16(xrow[tb] + kbeg + 32 * d) : zero;
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb)
-        w[jb] = (16 * jb < r8 && kbeg < kend) ? ld16(wbase + woff[jb] + (int64_t)kbeg * wh[jb]) : zero;
+        for (int t = 0; t < NL; ++t)
+            if (4 * t < ntok) xs[t] = ld16(xrow[t] + kx);
+    };
 
-    for (int k0 = kbeg; k0 < kend; k0 += 32 * XD) {
+    uint4 xs[NL], w[WD][JB];
+    if (kbeg < kend) x_pass(kbeg, xs);
 #pragma unroll
-        for (int d = 0; d < XD; ++d) {
+    for (int d = 0; d < WD; ++d)
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) {
+            w[d][jb] = zero;
+            if (16 * jb < r8 && kbeg + 32 * d < kend) w[d][jb] = ld16(wbase + woff[jb] + (int64_t)(kbeg + 32 * d) * wh[jb]);
+        }
+
+    for (int k0 = kbeg; k0 < kend; k0 += kPfPassK) {
+#pragma unroll
+        for (int t = 0; t < NL; ++t)
+            if (4 * t < ntok) *reinterpret_cast<uint4 *>(&slab[4 * t + kq][8 * n]) = xs[t];
+        if (k0 + kPfPassK < kend) x_pass(k0 + kPfPassK, xs);
+        // the region is private to this wavefront and LDS operations of a wavefront complete in order
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        __builtin_amdgcn_wave_barrier();
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+#pragma unroll
+        for (int d = 0; d < kPfPassK / 32; ++d) {
             const int k = k0 + 32 * d;
             if (k < kend) {
+                bf16x8 xo[TB];
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb)
+                    // rows of tokens beyond ntok hold a copy of the last token or whatever LDS held: they
+                    // only reach accumulator columns that are never stored
+                    xo[tb] = as_bf16x8(*reinterpret_cast<const uint4 *>(&slab[16 * tb + n][32 * d + 8 * kq]));
 #pragma unroll
                 for (int jb = 0; jb < JB; ++jb) {
                     if (16 * jb < r8) {
-                        const bf16x8 ww = as_bf16x8(w_ok[jb] ? w[jb] : zero);
+                        const bf16x8 ww = as_bf16x8(w[d % WD][jb]);
 #pragma unroll
                         for (int tb = 0; tb < TB; ++tb)
-                            acc[jb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                ww, as_bf16x8(t_ok[tb] ? xq[d][tb] : zero), acc[jb][tb], 0, 0, 0);
-                        if (k + 32 < kend) w[jb] = ld16(wbase + woff[jb] + (int64_t)(k + 32) * wh[jb]);
+                            acc[jb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ww, xo[tb], acc[jb][tb], 0, 0, 0);
+                        if (k + 32 * WD < kend) w[d % WD][jb] = ld16(wbase + woff[jb] + (int64_t)(k + 32 * WD) * wh[jb]);
                     }
-                }
-                if (k + 32 * XD < kend) {
-#pragma unroll
-                    for (int tb = 0; tb < TB; ++tb) xq[d][tb] = ld16(xrow[tb] + k + 32 * XD);
                 }
             }
         }
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        __builtin_amdgcn_wave_barrier();
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
     }
 
     // sum the four k-quarters: (wave 2 -> 0, wave 3 -> 1), then (wave 1 -> 0)
+    __syncthreads();  // every wavefront has finished with its x region
     if (wave >= 2) {
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb)
@@ -516,33 +576,20 @@ static __device__ __forceinline__ void shrink_prefill_body(const Unit &u, const 
     // lane (n, kq) holds, for token block tb and row block jb, v[token n][16*jb + 4*kq + e]
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
-        if (!t_ok[tb]) continue;
+        if (16 * tb + n >= ntok) continue;
         const int64_t row = u.v_off + (int64_t)(16 * tb + n) * r8;
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) {
             const int j = 16 * jb + 4 * kq;
-            if (j < r8) {
-                const f32x4 f = acc[jb][tb] + red[0][jb * TB + tb][lane];
-                if (v_f32) {
-                    *reinterpret_cast<f32x4 *>(v_f32 + row + j) = f;
-                    for (int sl = 1; sl < n_slices; ++sl)
-                        *reinterpret_cast<f32x4 *>(v_f32 + (int64_t)sl * slice_stride + row + j) =
-                            f32x4{0.f, 0.f, 0.f, 0.f};
-                } else {
-                    uint2 h, l;
-                    h.x = pack_bf16_rne(f[0], f[1]);
-                    h.y = pack_bf16_rne(f[2], f[3]);
-                    l.x = pack_bf16_rne(f[0] - bf16_bits_to_f32(h.x & 0xFFFFu), f[1] - __uint_as_float(h.x & 0xFFFF0000u));
-                    l.y = pack_bf16_rne(f[2] - bf16_bits_to_f32(h.y & 0xFFFFu), f[3] - __uint_as_float(h.y & 0xFFFF0000u));
-                    *reinterpret_cast<uint2 *>(v_hi + row + j) = h;
-                    *reinterpret_cast<uint2 *>(v_lo + row + j) = l;
-                }
-            }
+            if (j < r8)
+                store_v4(acc[jb][tb] + red[0][jb * TB + tb][lane], row + j, v_hi, v_lo, v_f32, n_slices,
+                         slice_stride);
         }
     }
 }
 
-__global__ __launch_bounds__(kThreads, 2) void k_shrink_prefill(const Unit *__restrict__ units,
+// Up to rank 64 the body needs at most 128 registers: four work groups per compute unit.
+__global__ __launch_bounds__(kThreads, 4) void k_shrink_prefill(const Unit *__restrict__ units,
                                                                 const int32_t *__restrict__ perm,
                                                                 const uint16_t *__restrict__ arena,
                                                                 const uint16_t *__restrict__ x, int64_t ldx, int in,
@@ -555,15 +602,39 @@ __global__ __launch_bounds__(kThreads, 2) void k_shrink_prefill(const Unit *__re
     const Unit &u = units[blockIdx.x];
     const int r8 = u.r8;
     if (r8 <= 16)
-        shrink_prefill_body<1, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+        shrink_prefill_ksplit<1, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
     else if (r8 <= 32)
-        shrink_prefill_body<2, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+        shrink_prefill_ksplit<2, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    else  // the launcher starts this kernel only for batches whose token-heavy units are all up to rank 64
+        shrink_prefill_ksplit<4, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+}
+
+// Any rank.  Above rank 64 the accumulator tiles alone take 64 registers: two work groups per compute
+// unit.  Units above rank 128 hold 16 tokens.  A batch that has such units runs all its token-heavy
+// units here, in one launch: two launches one after the other (high ranks here, the rest above)
+// measured slower, the first one leaving most of the chip idle.
+__global__ __launch_bounds__(kThreads, 2) void k_shrink_prefill_any(const Unit *__restrict__ units,
+                                                                    const int32_t *__restrict__ perm,
+                                                                    const uint16_t *__restrict__ arena,
+                                                                    const uint16_t *__restrict__ x, int64_t ldx,
+                                                                    int in, uint16_t *__restrict__ v_hi,
+                                                                    uint16_t *__restrict__ v_lo,
+                                                                    float *__restrict__ v_f32, int n_slices,
+                                                                    int64_t slice_stride)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kPrefillLds];
+    const Unit &u = units[blockIdx.x];
+    const int r8 = u.r8;
+    if (r8 <= 16)
+        shrink_prefill_ksplit<1, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    else if (r8 <= 32)
+        shrink_prefill_ksplit<2, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
     else if (r8 <= 64)
-        shrink_prefill_body<4, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+        shrink_prefill_ksplit<4, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
     else if (r8 <= 128)
-        shrink_prefill_body<8, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+        shrink_prefill_ksplit<8, 2, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
     else
-        shrink_prefill_body<16, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+        shrink_prefill_ksplit<16, 1, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -878,8 +949,10 @@ static __device__ __forceinline__ void expand_big_body(const Unit &u, const int3
 #pragma unroll
             for (int st = 0; st < KSTEPS; ++st) {
                 if (32 * st < r8) {  // uniform
-                    // piece (sub-block b, rank piece 4*st + kq, column slot n)
-                    const uint4 wv = j_ok[st] ? t[(b * (r8 >> 3) + 4 * st + kq) * 16 + n] : zero;
+                    // piece (sub-block b, rank piece 4*st + kq, column slot n).  Lanes whose rank piece
+                    // lies beyond the padded rank read piece 0 instead (their v operand is zero): an
+                    // unconditional 16-byte read stays one instruction, a conditional one becomes four
+                    const uint4 wv = t[(b * (r8 >> 3) + (j_ok[st] ? 4 * st + kq : 0)) * 16 + n];
                     acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vh[st]), as_bf16x8(wv), acc[b], 0, 0, 0);
                     acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vl[st]), as_bf16x8(wv), acc[b], 0, 0, 0);
                 }
@@ -1125,13 +1198,18 @@ hipError_t launch_apply_fused(const LaunchCtx &cs, const LaunchCtx &ce, const ui
     return hipGetLastError();
 }
 
-hipError_t launch_shrink_prefill(const LaunchCtx &c, const uint16_t *x, int64_t ldx, uint16_t *v_hi,
+hipError_t launch_shrink_prefill(const LaunchCtx &c, int n_hi, const uint16_t *x, int64_t ldx, uint16_t *v_hi,
                                  uint16_t *v_lo, float *v_f32, int n_slices, int64_t slice_stride,
                                  hipStream_t stream)
 {
     if (c.n_units <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_shrink_prefill, dim3(c.n_units), dim3(kThreads), 0, stream, c.units, c.perm, c.arena, x,
-                       ldx, c.in_features, v_hi, v_lo, v_f32, n_slices, slice_stride);
+    if (n_hi < 0 || n_hi > c.n_units) return hipErrorInvalidValue;
+    if (n_hi > 0)
+        hipLaunchKernelGGL(k_shrink_prefill_any, dim3(c.n_units), dim3(kThreads), 0, stream, c.units, c.perm, c.arena,
+                           x, ldx, c.in_features, v_hi, v_lo, v_f32, n_slices, slice_stride);
+    else
+        hipLaunchKernelGGL(k_shrink_prefill, dim3(c.n_units), dim3(kThreads), 0, stream, c.units, c.perm, c.arena, x,
+                           ldx, c.in_features, v_hi, v_lo, v_f32, n_slices, slice_stride);
     return hipGetLastError();
 }
 
