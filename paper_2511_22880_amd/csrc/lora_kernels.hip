@@ -588,6 +588,22 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
     }
 }
 
+// One wavefront copies 1 KB from memory into LDS without passing through registers: lane l's 16 bytes
+// at gptr (per lane) land at lds_piece + 16*l (lds_piece wave-uniform).  Written as an instruction the
+// compiler does not look into: for its own form of this load it waits until the copy has landed
+// before the wavefront may issue anything else that touches LDS or the registers involved, which
+// leaves nothing of the overlap the copy exists for.  The caller waits (vmcnt(0)) and synchronises
+// the work group before anyone reads the destination.
+static __device__ __forceinline__ void dma16_to_lds(const uint4 *gptr, const uint4 *lds_piece)
+{
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)lds_piece);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_addr)
+                 : "memory", "m0");
+}
+
 // Up to rank 64 the body needs at most 128 registers: four work groups per compute unit.
 __global__ __launch_bounds__(kThreads, 4) void k_shrink_prefill(const Unit *__restrict__ units,
                                                                 const int32_t *__restrict__ perm,
@@ -923,9 +939,7 @@ static __device__ __forceinline__ void expand_big_body(const Unit &u, const int3
     _Pragma("unroll") for (int q = 0; q < WREG; ++q) {                                                  \
         const int piece0 = 64 * wave_u + kThreads * q;                                                  \
         if (piece0 < tile_pieces)                                                                       \
-            __builtin_amdgcn_global_load_lds(                                                           \
-                (const __attribute__((address_space(1))) void *)(gtile + (int64_t)(S_) * tile_pieces + piece0 + lane), \
-                (__attribute__((address_space(3))) void *)(ltile + (BUF_) * 2048 + piece0), 16, 0, 0);  \
+            dma16_to_lds(gtile + (int64_t)(S_) * tile_pieces + piece0 + lane, ltile + (BUF_) * 2048 + piece0); \
     }
     // the copies (and everything else this wavefront has in flight) have landed
 #define LORA_DMA_WAIT()                       \
