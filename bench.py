@@ -115,6 +115,9 @@ def main() -> int:
     ap.add_argument("--fused", action="store_true", help="single-launch lora_apply (decode-sized batches)")
     ap.add_argument("--whole-k-limit", type=int, default=None,
                     help="planning knob lora_set_whole_k_limit (default: the library's, 1024; 0 = always k-slices)")
+    ap.add_argument("--concurrent-loads", type=int, default=0,
+                    help="adapters (ones the batch does not use) loaded into the step's pools on a second stream "
+                         "per step, while the applies run")
     ap.add_argument("--padded-control", action="store_true",
                     help="control run: every adapter stored at the largest rank of the pool, zero-padded (the "
                          "layout whose cost the paper's motivation measures); same batch, same results")
@@ -181,20 +184,40 @@ def main() -> int:
     ws = torch.empty(max(L.lora_apply_workspace_bytes(pools[0], seg), 256), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
+    # adapters that arrive while batches run: device-resident row-major sources of adapters the batch
+    # does not use, packed into the pools by lora_pool_load on a stream of their own
+    copy_stream, load_src, load_bytes, load_count = None, [], 0, [0]
+    if args.concurrent_loads > 0:
+        copy_stream = torch.cuda.Stream()
+        unused = [a for a in range(b0.n_adapters) if a not in set(int(u) for u in b0.used_adapters())]
+        assert unused, "every adapter is used by the batch"
+        for a in unused[:16]:
+            r = int(b0.ranks[a])
+            load_src.append((a, torch.empty(in_f, r, dtype=torch.bfloat16, device=dev).normal_(0.0, 0.02),
+                             torch.empty(r, out_f, dtype=torch.bfloat16, device=dev).normal_(0.0, 0.02)))
+
     def step():
+        nonlocal load_bytes
         L.lora_segments_rebuild(seg, b0.token_adapter, stream=stream)
         for l in range(nl):
             L.lora_apply(pools[l], seg, xs[l], ys[l], ws, stream=stream)
+        for _ in range(args.concurrent_loads):
+            a, As, Bs = load_src[load_count[0] % len(load_src)]
+            L.lora_pool_load(pools[load_count[0] % nl], a, As, Bs, stream=copy_stream)
+            load_count[0] += 1
+            load_bytes += 2 * int(b0.ranks[a]) * (in_f + out_f)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    load_bytes = 0
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     L.lora_segments_check(seg, stream=stream)
+    load_bytes_per_step = load_bytes / args.steps
     ms_per_step = dt / args.steps * 1e3
     n_act = int((b0.token_adapter >= 0).sum())
     value = n_act * nl / (dt / args.steps)
@@ -275,7 +298,8 @@ def main() -> int:
                    "expand_units": info["n_expand_units"], "k_slices": info["n_k_slices"],
                    "algorithmic_bytes_per_apply": shrink_bytes + expand_bytes,
                    "flops_per_apply": b0.flops(), "single_launch_apply": bool(args.fused),
-                   "padded_control": bool(args.padded_control), "weight_bytes_read_per_apply": info["weight_bytes"],
+                   "padded_control": bool(args.padded_control), "concurrent_loads_per_step": args.concurrent_loads,
+                   "adapter_bytes_loaded_per_step": load_bytes_per_step, "weight_bytes_read_per_apply": info["weight_bytes"],
                    "parity_max_row_rel_l2": err},
         "roofline": {"bound": "hbm", "kernel": dom if dom_kernel is None else f"{dom}: {dom_kernel}", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

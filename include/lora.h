@@ -45,7 +45,7 @@ typedef enum {
     LORA_ERR_SHAPE = 2,          /* feature size or rank outside what the kernels support         */
     LORA_ERR_OOM = 3,            /* arena / host / device allocation too small or failed          */
     LORA_ERR_NOT_RESIDENT = 4,   /* a token is routed to an adapter that is not loaded            */
-    LORA_ERR_STALE_SEGMENTS = 5, /* segment object built for another pool or an older generation  */
+    LORA_ERR_STALE_SEGMENTS = 5, /* an adapter the segment object uses was reloaded, moved or differs */
     LORA_ERR_WORKSPACE = 6,      /* workspace missing, misaligned or smaller than required        */
     LORA_ERR_DEVICE = 7          /* a HIP call failed (no device, launch error, copy error)       */
 } lora_status_t;
@@ -110,21 +110,52 @@ lora_status_t lora_pool_bytes(const lora_pool_desc_t *desc, size_t *arena_bytes)
 lora_status_t lora_pool_create(const lora_pool_desc_t *desc, void *dev_arena, size_t arena_bytes,
                                lora_pool_t **out);
 
+/* A live pool: the same object over an arena of any size (256-byte aligned), smaller than the sum of
+ * the adapters if wanted.  No adapter has a place until it is loaded (or reserved); lora_pool_load
+ * takes the first free piece that is large enough (adapters occupy 2*rank_padded*(in+out) bytes
+ * rounded up to 256), lora_pool_evict gives the piece back, lora_pool_compact closes the gaps.  This
+ * is one GPU's share of the adapter store that the paper keeps across servers (System Design,
+ * "Distributed Adapter Pool"): which adapters are present changes while batches run.  Host only. */
+lora_status_t lora_pool_create_live(const lora_pool_desc_t *desc, void *dev_arena, size_t arena_bytes,
+                                    lora_pool_t **out);
+
 /* Copy adapter `adapter` into the pool and mark it resident.  A is [in][rank] and B is [rank][out],
  * row-major bf16, in host memory (src_is_device = 0) or device memory (1).  The packed, transposed
  * form is written by a device kernel on `stream`.  With a host source the call allocates a device
  * staging buffer and returns after the copy has completed; with a device source it is asynchronous
- * and the source must stay valid until the stream reaches it.  Bumps the pool's generation. */
+ * and the source must stay valid until the stream reaches it.  In a live pool the adapter is given a
+ * place first: LORA_ERR_OOM if no free piece is large enough (the message says whether compaction
+ * would help).  The adapter gets a new stamp: segment objects that use it become stale, others stay
+ * valid, so adapters can be loaded on a copy stream while batches that do not use them run on
+ * another; the caller orders the load before the first launch that uses the adapter (an event). */
 lora_status_t lora_pool_load(lora_pool_t *pool, int32_t adapter, const void *A_in_by_r,
                              const void *B_r_by_out, int src_is_device, void *stream);
 
-/* Mark an adapter non-resident (its bytes stay where they are).  Bumps the generation. */
+/* Mark an adapter non-resident.  Fixed pool: its bytes stay where they are.  Live pool: its piece
+ * returns to the free list, so the caller makes sure no launch that reads it is still running.
+ * Segment objects that use the adapter are refused from now on (LORA_ERR_NOT_RESIDENT). */
 lora_status_t lora_pool_evict(lora_pool_t *pool, int32_t adapter);
+
+/* Live pool: give the adapter a place without copying anything (no-op in a fixed pool, or if it has
+ * one).  Host only.  LORA_ERR_OOM as for lora_pool_load. */
+lora_status_t lora_pool_reserve(lora_pool_t *pool, int32_t adapter);
 
 /* Declare an adapter resident without copying: for callers that wrote its packed form into the
  * arena themselves (a device-to-device copy of another pool's arena, a restored snapshot).  Host
- * only.  Bumps the generation. */
+ * only.  In a live pool the adapter must have a place (lora_pool_reserve).  New stamp as for load. */
 lora_status_t lora_pool_mark_resident(lora_pool_t *pool, int32_t adapter);
+
+/* Live pool: free bytes in total and in the largest single piece (0, 0 for a fixed pool).  Host only. */
+lora_status_t lora_pool_space(const lora_pool_t *pool, size_t *free_bytes, size_t *largest_free_bytes);
+
+/* Live pool: slide every placed adapter towards the start of the arena, in address order, with
+ * device-to-device copies on `stream` (asynchronous), leaving one free piece at the end.  A move that
+ * overlaps its own source goes through dev_scratch (device memory, may be NULL) when scratch_bytes
+ * covers the adapter, else in pieces no longer than the gap.  Moved adapters get a new stamp (segment
+ * objects that use them become stale); *n_moved (may be NULL) counts them.  The caller makes sure no
+ * launch that reads a moved adapter is still running on another stream. */
+lora_status_t lora_pool_compact(lora_pool_t *pool, void *dev_scratch, size_t scratch_bytes, void *stream,
+                                int32_t *n_moved);
 
 /* Host only: layout and residency of one adapter. */
 lora_status_t lora_pool_adapter_info(const lora_pool_t *pool, int32_t adapter, lora_adapter_info_t *info);
@@ -191,17 +222,18 @@ lora_status_t lora_segments_destroy(lora_segments_t *seg);
  * v; 0 is possible).  The workspace must be 256-byte aligned. */
 lora_status_t lora_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *seg, size_t *bytes);
 
-/* A segment object can be launched on the pool it was built for and on any other pool with the same
- * layout (equal in_features, out_features, ranks and scales, hence equal offsets) in which every
- * adapter the batch uses is resident: the layers of a model share one token->adapter map, so one
- * object serves all layers of one projection shape.  On its own pool it is refused with
- * LORA_ERR_STALE_SEGMENTS once the pool's generation has moved on. */
+/* A segment object can be launched on the pool it was built for, and on any other pool with the same
+ * feature sizes that holds every adapter the batch uses, resident, with the same rank and scale at the
+ * same place in its arena (pools created from the same description: the layers of a model share one
+ * token->adapter map, so one object serves all layers of one projection shape).  On its own pool it
+ * is refused with LORA_ERR_STALE_SEGMENTS once an adapter it uses has been loaded again or moved, and
+ * with LORA_ERR_NOT_RESIDENT once one has been evicted; changes to other adapters do not touch it. */
 
 /* Shrink: v[t, j] = sum_k x[t, k] * A_a(t)[k, j] for every active token.
  * x: device, bf16, [T][in] with row stride ldx elements (ldx >= in, ldx % 8 == 0, 16-byte aligned).
  * v: device, fp32, info.v_floats long, 16-byte aligned; token t's row starts at v_offset[t] and is
  *    rank_padded long (entries beyond the rank are written as 0).
- * LORA_ERR_STALE_SEGMENTS if the pool changed since `seg` was built, LORA_ERR_WORKSPACE if the
+ * LORA_ERR_STALE_SEGMENTS / LORA_ERR_NOT_RESIDENT as described above, LORA_ERR_WORKSPACE if the
  * workspace is too small. */
 lora_status_t lora_shrink(const lora_pool_t *pool, const lora_segments_t *seg, const void *x, int64_t ldx,
                           float *v, void *workspace, size_t ws_bytes, void *stream);

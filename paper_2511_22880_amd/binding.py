@@ -22,8 +22,8 @@ STATUS = ("LORA_OK", "LORA_ERR_INVALID_ARG", "LORA_ERR_SHAPE", "LORA_ERR_OOM", "
 
 # every symbol include/lora.h declares
 EXPORTS = (
-    "lora_pool_bytes", "lora_pool_create", "lora_pool_load", "lora_pool_evict", "lora_pool_mark_resident",
-    "lora_pool_adapter_info",
+    "lora_pool_bytes", "lora_pool_create", "lora_pool_create_live", "lora_pool_load", "lora_pool_evict",
+    "lora_pool_reserve", "lora_pool_mark_resident", "lora_pool_space", "lora_pool_compact", "lora_pool_adapter_info",
     "lora_pool_destroy", "lora_segments_plan", "lora_segments_plan_ranges", "lora_segments_upload",
     "lora_segments_build", "lora_segments_build_ranges", "lora_segments_rebuild", "lora_segments_info",
     "lora_segments_export", "lora_segments_export_units", "lora_segments_destroy", "lora_workspace_bytes",
@@ -152,6 +152,36 @@ def lora_pool_create(in_features: int, out_features: int, ranks, scales, dev_are
     h = ctypes.c_void_p(None)
     _check(lib().lora_pool_create(ctypes.byref(d), _ptr(dev_arena), ctypes.c_size_t(arena_bytes), ctypes.byref(h)))
     return Pool(h, int(in_features), int(out_features), r, s, dev_arena)
+
+
+def lora_pool_create_live(in_features: int, out_features: int, ranks, scales, dev_arena,
+                          arena_bytes: Optional[int] = None) -> Pool:
+    """A pool over an arena of any size: adapters get their place when loaded (see include/lora.h)."""
+    d, r, s = _desc(in_features, out_features, ranks, scales)
+    if arena_bytes is None:
+        arena_bytes = dev_arena.numel() * dev_arena.element_size()
+    h = ctypes.c_void_p(None)
+    _check(lib().lora_pool_create_live(ctypes.byref(d), _ptr(dev_arena), ctypes.c_size_t(arena_bytes), ctypes.byref(h)))
+    return Pool(h, int(in_features), int(out_features), r, s, dev_arena)
+
+
+def lora_pool_reserve(pool: Pool, adapter: int) -> None:
+    _check(lib().lora_pool_reserve(pool.handle, ctypes.c_int32(adapter)))
+
+
+def lora_pool_space(pool: Pool) -> dict:
+    fr, lg = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib().lora_pool_space(pool.handle, ctypes.byref(fr), ctypes.byref(lg)))
+    return {"free_bytes": int(fr.value), "largest_free_bytes": int(lg.value)}
+
+
+def lora_pool_compact(pool: Pool, scratch=None, stream=None, scratch_bytes: Optional[int] = None) -> int:
+    """Returns the number of adapters that were moved."""
+    moved = ctypes.c_int32(0)
+    nbytes = (_nbytes(scratch) if scratch is not None else 0) if scratch_bytes is None else scratch_bytes
+    _check(lib().lora_pool_compact(pool.handle, _ptr(scratch), ctypes.c_size_t(nbytes), _stream(stream),
+                                   ctypes.byref(moved)))
+    return int(moved.value)
 
 
 def lora_pool_load(pool: Pool, adapter: int, A, B, src_is_device: Optional[bool] = None, stream=None) -> None:

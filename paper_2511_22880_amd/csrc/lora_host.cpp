@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <new>
 #include <vector>
 
@@ -51,25 +52,32 @@ struct lora_pool {
     std::vector<float> scale;
     std::vector<uint64_t> a_off, b_off;  // element offsets
     std::vector<uint8_t> resident;
+    // every load, eviction, declaration of residency or move of an adapter gives it a new stamp; a
+    // segment object remembers the stamps of the adapters it uses
+    std::vector<uint64_t> epoch;
+    uint64_t next_epoch;
     uint16_t *arena;
     size_t arena_bytes;
-    uint64_t generation;
     uint64_t id;
+    // live pool: space is handed out at load time from a free list (element offset -> length, both
+    // multiples of 128 elements = 256 bytes); an adapter without space has a_off == kNoOffset
+    bool live;
+    std::map<uint64_t, uint64_t> free_blocks;
 };
+static const uint64_t kNoOffset = ~0ull;
 
 struct lora_segments {
     uint32_t magic;
     const lora_pool *pool;
-    uint64_t pool_id, pool_generation;
+    uint64_t pool_id;
+    std::vector<uint64_t> seg_epoch;  // stamp of each used adapter when the plan was made
     int32_t T, n_active;
     int n_k_slices, k_slice_len;
     int64_t v_floats, weight_bytes;
     std::vector<int32_t> perm, seg_start, seg_adapter;
     std::vector<int64_t> v_offset;
-    // layout of the pool the plan was made for (for launches on sibling pools)
+    // feature sizes of the pool the plan was made for (for launches on sibling pools)
     int layout_in, layout_out;
-    std::vector<int32_t> layout_rank;
-    std::vector<float> layout_scale;
     std::vector<SegRec> segs;
     std::vector<Unit> shrink_units, prefill_units, expand_units, expand_big_units;
     // device table: [perm | shrink units | prefill shrink units | expand units | arrival counters,
@@ -130,17 +138,23 @@ extern "C" lora_status_t lora_pool_bytes(const lora_pool_desc_t *desc, size_t *a
     return LORA_OK;
 }
 
-extern "C" lora_status_t lora_pool_create(const lora_pool_desc_t *desc, void *dev_arena, size_t arena_bytes,
-                                          lora_pool_t **out)
+static uint64_t block_elems(const lora_pool *p, int a)
+{
+    const uint64_t e = (uint64_t)p->r8[a] * ((uint64_t)p->in_features + (uint64_t)p->out_features);
+    return (e + 127) / 128 * 128;  // 256-byte granules
+}
+
+static lora_status_t create_pool(const lora_pool_desc_t *desc, void *dev_arena, size_t arena_bytes, bool live,
+                                 lora_pool_t **out)
 {
     if (!out) return fail(LORA_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
     size_t need = 0;
     lora_status_t st = lora_pool_bytes(desc, &need);
     if (st != LORA_OK) return st;
-    if (need > 0 && !dev_arena) return fail(LORA_ERR_INVALID_ARG, "dev_arena is NULL");
+    if ((need > 0 || live) && !dev_arena) return fail(LORA_ERR_INVALID_ARG, "dev_arena is NULL");
     if (((uintptr_t)dev_arena) % 256) return fail(LORA_ERR_INVALID_ARG, "dev_arena is not 256-byte aligned");
-    if (arena_bytes < need)
+    if (!live && arena_bytes < need)
         return fail(LORA_ERR_OOM, "arena of %zu bytes is smaller than the %zu bytes the pool needs", arena_bytes, need);
     lora_pool *p = new (std::nothrow) lora_pool();
     if (!p) return fail(LORA_ERR_OOM, "host allocation failed");
@@ -150,20 +164,160 @@ extern "C" lora_status_t lora_pool_create(const lora_pool_desc_t *desc, void *de
     p->n_adapters = desc->n_adapters;
     p->arena = (uint16_t *)dev_arena;
     p->arena_bytes = arena_bytes;
-    p->generation = 1;
+    p->next_epoch = 1;
     p->id = g_next_pool_id++;
+    p->live = live;
     uint64_t off = 0;
     for (int a = 0; a < desc->n_adapters; ++a) {
         const int r8 = round_up(desc->ranks[a], 8);
         p->rank.push_back(desc->ranks[a]);
         p->r8.push_back(r8);
         p->scale.push_back(desc->scales[a]);
-        p->a_off.push_back(off);
-        p->b_off.push_back(off + (uint64_t)r8 * desc->in_features);
+        p->a_off.push_back(live ? kNoOffset : off);
+        p->b_off.push_back(live ? kNoOffset : off + (uint64_t)r8 * desc->in_features);
         p->resident.push_back(0);
+        p->epoch.push_back(0);
         off += (uint64_t)adapter_elems(desc, a);
     }
+    if (live) {
+        const uint64_t elems = (uint64_t)(arena_bytes / 256) * 128;
+        if (elems) p->free_blocks[0] = elems;
+    }
     *out = p;
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_pool_create(const lora_pool_desc_t *desc, void *dev_arena, size_t arena_bytes,
+                                          lora_pool_t **out)
+{
+    return create_pool(desc, dev_arena, arena_bytes, false, out);
+}
+
+extern "C" lora_status_t lora_pool_create_live(const lora_pool_desc_t *desc, void *dev_arena, size_t arena_bytes,
+                                               lora_pool_t **out)
+{
+    return create_pool(desc, dev_arena, arena_bytes, true, out);
+}
+
+// ---- live pool: first-fit free list with coalescing -------------------------------------------------
+static void space_of(const lora_pool *p, uint64_t *free_elems, uint64_t *largest)
+{
+    *free_elems = *largest = 0;
+    for (const auto &b : p->free_blocks) {
+        *free_elems += b.second;
+        *largest = std::max(*largest, b.second);
+    }
+}
+
+static lora_status_t live_place(lora_pool *p, int a)
+{
+    if (p->a_off[a] != kNoOffset) return LORA_OK;
+    const uint64_t need = block_elems(p, a);
+    for (auto it = p->free_blocks.begin(); it != p->free_blocks.end(); ++it) {
+        if (it->second < need) continue;
+        const uint64_t off = it->first, rest = it->second - need;
+        p->free_blocks.erase(it);
+        if (rest) p->free_blocks[off + need] = rest;
+        p->a_off[a] = off;
+        p->b_off[a] = off + (uint64_t)p->r8[a] * p->in_features;
+        return LORA_OK;
+    }
+    uint64_t fr, lg;
+    space_of(p, &fr, &lg);
+    return fail(LORA_ERR_OOM,
+                "adapter %d needs %llu bytes in one piece; the arena has %llu bytes free, the largest piece %llu%s", a,
+                (unsigned long long)(need * 2), (unsigned long long)(fr * 2), (unsigned long long)(lg * 2),
+                fr >= need ? " (lora_pool_compact would make room)" : "");
+}
+
+static void live_release(lora_pool *p, int a)
+{
+    if (p->a_off[a] == kNoOffset) return;
+    uint64_t off = p->a_off[a], len = block_elems(p, a);
+    auto next = p->free_blocks.lower_bound(off);
+    if (next != p->free_blocks.end() && off + len == next->first) {
+        len += next->second;
+        next = p->free_blocks.erase(next);
+    }
+    if (next != p->free_blocks.begin()) {
+        auto prev = std::prev(next);
+        if (prev->first + prev->second == off) {
+            prev->second += len;
+            len = 0;
+        }
+    }
+    if (len) p->free_blocks[off] = len;
+    p->a_off[a] = p->b_off[a] = kNoOffset;
+}
+
+static lora_status_t check_adapter(const lora_pool *pool, int32_t adapter)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (adapter < 0 || adapter >= pool->n_adapters)
+        return fail(LORA_ERR_INVALID_ARG, "adapter %d outside 0..%d", adapter, pool->n_adapters - 1);
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_pool_reserve(lora_pool_t *pool, int32_t adapter)
+{
+    lora_status_t st = check_adapter(pool, adapter);
+    if (st != LORA_OK) return st;
+    return pool->live ? live_place(pool, adapter) : LORA_OK;
+}
+
+extern "C" lora_status_t lora_pool_space(const lora_pool_t *pool, size_t *free_bytes, size_t *largest_free_bytes)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    uint64_t fr, lg;
+    space_of(pool, &fr, &lg);
+    if (free_bytes) *free_bytes = (size_t)(fr * 2);
+    if (largest_free_bytes) *largest_free_bytes = (size_t)(lg * 2);
+    return LORA_OK;
+}
+
+// Slides the placed adapters of a live pool towards the start of the arena, in address order, with
+// device-to-device copies on `stream`.  A move whose source and destination overlap goes through
+// `dev_scratch` when that is large enough, else in pieces no longer than the gap (each piece then
+// lies wholly before its own source, and the stream runs the pieces in order).
+extern "C" lora_status_t lora_pool_compact(lora_pool_t *pool, void *dev_scratch, size_t scratch_bytes, void *stream,
+                                           int32_t *n_moved)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (n_moved) *n_moved = 0;
+    if (!pool->live) return LORA_OK;
+    hipStream_t s = (hipStream_t)stream;
+    std::vector<int> order;
+    for (int a = 0; a < pool->n_adapters; ++a)
+        if (pool->a_off[a] != kNoOffset) order.push_back(a);
+    std::sort(order.begin(), order.end(), [&](int x, int y) { return pool->a_off[x] < pool->a_off[y]; });
+    uint64_t cursor = 0;
+    int moved = 0;
+    for (int a : order) {
+        const uint64_t len = block_elems(pool, a), src = pool->a_off[a];
+        if (src != cursor) {
+            const uint64_t gap = src - cursor;
+            char *d = (char *)(pool->arena + cursor), *f = (char *)(pool->arena + src);
+            const size_t bytes = (size_t)len * 2, gap_bytes = (size_t)gap * 2;
+            if (gap_bytes >= bytes) {
+                HIP_TRY(hipMemcpyAsync(d, f, bytes, hipMemcpyDeviceToDevice, s));
+            } else if (dev_scratch && scratch_bytes >= bytes) {
+                HIP_TRY(hipMemcpyAsync(dev_scratch, f, bytes, hipMemcpyDeviceToDevice, s));
+                HIP_TRY(hipMemcpyAsync(d, dev_scratch, bytes, hipMemcpyDeviceToDevice, s));
+            } else {
+                for (size_t o = 0; o < bytes; o += gap_bytes)
+                    HIP_TRY(hipMemcpyAsync(d + o, f + o, std::min(gap_bytes, bytes - o), hipMemcpyDeviceToDevice, s));
+            }
+            pool->a_off[a] = cursor;
+            pool->b_off[a] = cursor + (uint64_t)pool->r8[a] * pool->in_features;
+            pool->epoch[a] = pool->next_epoch++;
+            ++moved;
+        }
+        cursor += len;
+    }
+    pool->free_blocks.clear();
+    const uint64_t total = (uint64_t)(pool->arena_bytes / 256) * 128;
+    if (total > cursor) pool->free_blocks[cursor] = total - cursor;
+    if (n_moved) *n_moved = moved;
     return LORA_OK;
 }
 
@@ -193,6 +347,10 @@ extern "C" lora_status_t lora_pool_load(lora_pool_t *pool, int32_t adapter, cons
     hipStream_t s = (hipStream_t)stream;
     const int r = pool->rank[adapter], r8 = pool->r8[adapter];
     const int in = pool->in_features, out = pool->out_features;
+    if (pool->live) {
+        lora_status_t st = live_place(pool, adapter);
+        if (st != LORA_OK) return st;
+    }
     uint16_t *dstA = pool->arena + pool->a_off[adapter];
     uint16_t *dstB = pool->arena + pool->b_off[adapter];
     const size_t nA = (size_t)in * r, nB = (size_t)r * out;
@@ -215,7 +373,7 @@ extern "C" lora_status_t lora_pool_load(lora_pool_t *pool, int32_t adapter, cons
         if (st != LORA_OK) return st;
     }
     pool->resident[adapter] = 1;
-    pool->generation++;
+    pool->epoch[adapter] = pool->next_epoch++;
     return LORA_OK;
 }
 
@@ -225,7 +383,8 @@ extern "C" lora_status_t lora_pool_evict(lora_pool_t *pool, int32_t adapter)
     if (adapter < 0 || adapter >= pool->n_adapters)
         return fail(LORA_ERR_INVALID_ARG, "adapter %d outside 0..%d", adapter, pool->n_adapters - 1);
     pool->resident[adapter] = 0;
-    pool->generation++;
+    pool->epoch[adapter] = pool->next_epoch++;
+    if (pool->live) live_release(pool, adapter);
     return LORA_OK;
 }
 
@@ -234,8 +393,10 @@ extern "C" lora_status_t lora_pool_mark_resident(lora_pool_t *pool, int32_t adap
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (adapter < 0 || adapter >= pool->n_adapters)
         return fail(LORA_ERR_INVALID_ARG, "adapter %d outside 0..%d", adapter, pool->n_adapters - 1);
+    if (pool->live && pool->a_off[adapter] == kNoOffset)
+        return fail(LORA_ERR_INVALID_ARG, "adapter %d has no space in the live pool: lora_pool_reserve first", adapter);
     pool->resident[adapter] = 1;
-    pool->generation++;
+    pool->epoch[adapter] = pool->next_epoch++;
     return LORA_OK;
 }
 
@@ -307,11 +468,8 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     }
     sg->pool = pool;
     sg->pool_id = pool->id;
-    sg->pool_generation = pool->generation;
     sg->layout_in = pool->in_features;
     sg->layout_out = pool->out_features;
-    sg->layout_rank = pool->rank;
-    sg->layout_scale = pool->scale;
     sg->T = T;
     sg->n_active = n_active;
     sg->uploaded = false;
@@ -336,6 +494,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
 
     sg->seg_start.clear();
     sg->seg_adapter.clear();
+    sg->seg_epoch.clear();
     sg->segs.clear();
     std::vector<int32_t> seg_of(N, -1), cursor(N, 0);
     int32_t pos = 0;
@@ -357,6 +516,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
         sg->segs.push_back(r);
         sg->seg_start.push_back(pos);
         sg->seg_adapter.push_back(a);
+        sg->seg_epoch.push_back(pool->epoch[a]);
         pos += count[a];
         voff += (int64_t)count[a] * r.r8;
         wbytes += 2LL * r.r8 * ((int64_t)pool->in_features + pool->out_features);
@@ -712,18 +872,25 @@ static lora_status_t check_launchable(const lora_pool *pool, const lora_segments
 {
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
-    if (sg->pool_id == pool->id) {
-        if (sg->pool_generation != pool->generation)
+    // The unit records carry each used adapter's place, rank and scale.  The object may be launched on
+    // the pool it was planned for as long as none of the adapters it uses has been loaded, evicted or
+    // moved since, whatever happened to other adapters, and on any pool that holds the same adapters at
+    // the same places (the layers of a model).
+    if (sg->layout_in != pool->in_features || sg->layout_out != pool->out_features)
+        return fail(LORA_ERR_STALE_SEGMENTS, "segment object was built for a pool with other feature sizes");
+    for (size_t i = 0; i < sg->seg_adapter.size(); ++i) {
+        const int32_t a = sg->seg_adapter[i];
+        const SegRec &r = sg->segs[i];
+        if (a >= pool->n_adapters)
+            return fail(LORA_ERR_STALE_SEGMENTS, "segment object uses adapter %d, which this pool does not have", a);
+        if (!pool->resident[a])
+            return fail(LORA_ERR_NOT_RESIDENT, "adapter %d is used by the batch but not loaded in this pool", a);
+        if (pool->rank[a] != r.rank || pool->scale[a] != r.scale || pool->a_off[a] != r.a_off ||
+            pool->b_off[a] != r.b_off)
+            return fail(LORA_ERR_STALE_SEGMENTS, "adapter %d has another rank, scale or place in this pool", a);
+        if (sg->pool_id == pool->id && pool->epoch[a] != sg->seg_epoch[i])
             return fail(LORA_ERR_STALE_SEGMENTS,
-                        "pool changed (generation %llu -> %llu) after the segment object was built",
-                        (unsigned long long)sg->pool_generation, (unsigned long long)pool->generation);
-    } else {
-        if (sg->layout_in != pool->in_features || sg->layout_out != pool->out_features ||
-            sg->layout_rank != pool->rank || sg->layout_scale != pool->scale)
-            return fail(LORA_ERR_STALE_SEGMENTS, "segment object was built for a pool with a different layout");
-        for (int32_t a : sg->seg_adapter)
-            if (!pool->resident[a])
-                return fail(LORA_ERR_NOT_RESIDENT, "adapter %d is used by the batch but not loaded in this pool", a);
+                        "adapter %d was loaded, evicted or moved after the segment object was built", a);
     }
     if (!sg->uploaded) return fail(LORA_ERR_INVALID_ARG, "segment object was planned but not uploaded");
     return LORA_OK;

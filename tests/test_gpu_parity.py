@@ -397,3 +397,150 @@ def test_cfg4_isolated_class_equals_mixed_rows():
     lo = iso.token_adapter >= 0
     assert lo.sum() == 256 and np.array_equal(y_mixed[lo], y_iso[lo]) and not y_iso[~lo].any()
     dp.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# Live pool: which adapters are present changes between (and during) batches.
+# ------------------------------------------------------------------------------------------------
+def _apply_live(pool, b, ta, x, y0_bits):
+    y = G.bits_to_dev(y0_bits)
+    seg = L.lora_segments_build(pool, ta)
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(pool, seg), 256), dtype=torch.uint8, device="cuda")
+    L.lora_apply(pool, seg, x, y, ws)
+    torch.cuda.synchronize()
+    L.lora_segments_check(seg)
+    return seg, G.dev_to_bits(y)
+
+
+def test_live_pool_load_evict_compact():
+    """An arena too small for all adapters: batches use what is loaded, evictions make room, a
+    fragmented arena refuses a large adapter until it is compacted, moved adapters make old segment
+    objects stale, and every batch still matches the oracle."""
+    b = wl.small_mixed(seed=11, in_features=512, out_features=384)
+    ranks = b.ranks                                   # (1, 3, 4, 8, 12, 16, 24, 32, 40, 64, 100, 128)
+    size = lambda a: 2 * int((ranks[a] + 7) // 8 * 8) * (b.in_features + b.out_features)
+    arena_bytes = size(11) + size(9) + size(7) + size(5) + size(3) + 4096
+    arena = torch.zeros(arena_bytes, dtype=torch.uint8, device="cuda")
+    pool = L.lora_pool_create_live(b.in_features, b.out_features, ranks, b.scales, arena)
+    A, B = zip(*[b.adapter_bits(a) for a in range(b.n_adapters)])
+    x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
+    x = G.bits_to_dev(x_bits)
+    rng = np.random.default_rng(0)
+
+    def batch_on(adapters):
+        ta = b.token_adapter.copy()
+        ta[ta >= 0] = rng.choice(np.asarray(adapters, dtype=np.int32), size=int((ta >= 0).sum()))
+        return ta
+
+    def check(ta, y_bits):
+        y_ref = oracle.lora_apply(x_bits, ta, ranks, b.scales, list(A), list(B), y0=wl.bf16_bits_to_f64(y0_bits))
+        G.check_parity(y_bits, y_ref, y0_bits, ta)
+
+    first = [3, 5, 7, 9, 11]
+    for a in first:
+        L.lora_pool_load(pool, a, A[a], B[a])
+    ta1 = batch_on(first)
+    seg1, y1 = _apply_live(pool, b, ta1, x, y0_bits)
+    check(ta1, y1)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_load(pool, 10, A[10], B[10])                    # rank 100: no room
+    assert e.value.status_name == "LORA_ERR_OOM"
+    # evict 3 (rank 8) and 7 (rank 32): two holes with 5 between them; rank 40 needs more than either
+    # hole and exactly as much as both
+    L.lora_pool_evict(pool, 3)
+    L.lora_pool_evict(pool, 7)
+    sp = L.lora_pool_space(pool)
+    assert sp["largest_free_bytes"] < size(8) <= sp["free_bytes"]
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_load(pool, 8, A[8], B[8])
+    assert e.value.status_name == "LORA_ERR_OOM" and "compact" in e.value.detail
+    # the old object used 3 and 7: refused; a batch on the remaining adapters still runs
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply(pool, seg1, x, G.bits_to_dev(y0_bits), ws)
+    assert e.value.status_name == "LORA_ERR_NOT_RESIDENT"
+    ta2 = batch_on([5, 9, 11])
+    seg2, y2 = _apply_live(pool, b, ta2, x, y0_bits)
+    check(ta2, y2)
+    # compaction without scratch: every move overlaps its source and goes in pieces
+    before = {a: L.lora_pool_adapter_info(pool, a)["a_offset"] for a in (5, 9, 11)}
+    moved = L.lora_pool_compact(pool)
+    torch.cuda.synchronize()
+    after = {a: L.lora_pool_adapter_info(pool, a)["a_offset"] for a in (5, 9, 11)}
+    assert moved == 3 and all(after[a] < before[a] for a in before) and after[5] == 0
+    sp = L.lora_pool_space(pool)
+    assert sp["free_bytes"] == sp["largest_free_bytes"] >= size(8)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply(pool, seg2, x, G.bits_to_dev(y0_bits), ws)     # it uses adapters that were moved
+    assert e.value.status_name == "LORA_ERR_STALE_SEGMENTS"
+    L.lora_pool_load(pool, 8, A[8], B[8])
+    ta3 = batch_on([5, 8, 9, 11])
+    seg3, y3 = _apply_live(pool, b, ta3, x, y0_bits)
+    check(ta3, y3)
+    # ... and through a scratch buffer: evict the first adapter in the arena, compact again
+    L.lora_pool_evict(pool, 5)
+    scratch = torch.empty(size(11), dtype=torch.uint8, device="cuda")
+    assert L.lora_pool_compact(pool, scratch) == 3
+    torch.cuda.synchronize()
+    ta4 = batch_on([8, 9, 11])
+    seg4, y4 = _apply_live(pool, b, ta4, x, y0_bits)
+    check(ta4, y4)
+    for s in (seg1, seg2, seg3, seg4):
+        L.lora_segments_destroy(s)
+    L.lora_pool_destroy(pool)
+
+
+def test_load_on_a_copy_stream_while_batches_run():
+    """Adapters that the running batches do not use are loaded (packed by a device kernel) on a
+    second stream meanwhile: the batches' results do not change by a bit, their segment object stays
+    valid, and once the load has been ordered before it, a batch that uses the new adapters is right."""
+    b = wl.cfg1_decode(in_features=2048, out_features=1024, n_tokens=128, n_adapters=48)
+    ranks = b.ranks
+    total = L.lora_pool_bytes(b.in_features, b.out_features, ranks, b.scales)
+    arena = torch.zeros(total, dtype=torch.uint8, device="cuda")
+    pool = L.lora_pool_create_live(b.in_features, b.out_features, ranks, b.scales, arena)
+    used = [int(a) for a in b.used_adapters()]
+    late = used[-4:]                                   # arrive while the first batches run
+    early = [a for a in used if a not in late]
+    A, B = {}, {}
+    for a in used:
+        A[a], B[a] = b.adapter_bits(a)
+    for a in early:
+        L.lora_pool_load(pool, a, A[a], B[a])
+    ta_early = b.token_adapter.copy()
+    ta_early[np.isin(ta_early, late)] = -1
+    x_bits, y0_bits = b.x_bits(), b.y0_bits("zero")
+    x = G.bits_to_dev(x_bits)
+    seg, y_base = _apply_live(pool, b, ta_early, x, y0_bits)
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(pool, seg), 256), dtype=torch.uint8, device="cuda")
+    dev_src = {a: (G.bits_to_dev(A[a]), G.bits_to_dev(B[a])) for a in late}
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    ys = []
+    for it in range(12):
+        y = G.bits_to_dev(y0_bits)
+        compute.wait_stream(torch.cuda.current_stream())
+        L.lora_apply(pool, seg, x, y, ws, stream=compute)
+        if it % 3 == 0 and it // 3 < len(late):
+            a = late[it // 3]
+            L.lora_pool_load(pool, a, dev_src[a][0], dev_src[a][1], stream=copy)
+        ys.append(y)
+    loaded = torch.cuda.Event()
+    loaded.record(copy)
+    torch.cuda.synchronize()
+    for y in ys:
+        assert np.array_equal(G.dev_to_bits(y), y_base)
+    # the late adapters' first batch: ordered after their loads
+    compute.wait_event(loaded)
+    y = G.bits_to_dev(y0_bits)
+    seg_all = L.lora_segments_build(pool, b.token_adapter, stream=compute)
+    ws2 = torch.empty(max(L.lora_apply_workspace_bytes(pool, seg_all), 256), dtype=torch.uint8, device="cuda")
+    L.lora_apply(pool, seg_all, x, y, ws2, stream=compute)
+    torch.cuda.synchronize()
+    Al = [A.get(a) for a in range(b.n_adapters)]
+    Bl = [B.get(a) for a in range(b.n_adapters)]
+    y_ref = oracle.lora_apply(x_bits, b.token_adapter, ranks, b.scales, Al, Bl)
+    G.check_parity(G.dev_to_bits(y), y_ref, y0_bits, b.token_adapter)
+    L.lora_segments_destroy(seg)
+    L.lora_segments_destroy(seg_all)
+    L.lora_pool_destroy(pool)

@@ -123,13 +123,22 @@ def test_launch_checks_happen_on_the_host():
     with pytest.raises(L.LoraError) as e:
         L.lora_apply(pool, seg, FAKE_ARENA, FAKE_ARENA, FAKE_ARENA, ldx=512, ldy=256, ws_bytes=1 << 20)
     assert e.value.status_name == "LORA_ERR_INVALID_ARG" and "upload" in e.value.detail
-    # a pool change makes the object stale
+    # evicting an adapter the batch does not use leaves the object alone (the refusal is still the missing upload)
     L.lora_pool_evict(pool, 2)
     with pytest.raises(L.LoraError) as e:
         L.lora_shrink(pool, seg, FAKE_ARENA, FAKE_ARENA, FAKE_ARENA, ldx=512, ws_bytes=1 << 20)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG" and "upload" in e.value.detail
+    # evicting one it uses: not resident; declaring it resident again: another stamp, so the object is stale
+    L.lora_pool_evict(pool, 1)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_shrink(pool, seg, FAKE_ARENA, FAKE_ARENA, FAKE_ARENA, ldx=512, ws_bytes=1 << 20)
+    assert e.value.status_name == "LORA_ERR_NOT_RESIDENT"
+    L.lora_pool_mark_resident(pool, 1)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_shrink(pool, seg, FAKE_ARENA, FAKE_ARENA, FAKE_ARENA, ldx=512, ws_bytes=1 << 20)
     assert e.value.status_name == "LORA_ERR_STALE_SEGMENTS"
-    # another layout is refused too
-    other = make_pool(ranks=(8, 16, 4, 128))
+    # a pool in which an adapter the batch uses has another rank (hence other places) is refused too
+    other = make_pool(ranks=(8, 32, 3, 128))
     with pytest.raises(L.LoraError) as e:
         L.lora_expand(other, seg, FAKE_ARENA, FAKE_ARENA, ldy=256)
     assert e.value.status_name == "LORA_ERR_STALE_SEGMENTS"
@@ -228,6 +237,72 @@ def test_whole_k_limit_switches_the_shrink_plan():
         L.lora_set_whole_k_limit(1024)
     # 217 whole-k units (16 rank rows x <= 16 tokens each) fit the default limit; below it k is cut in 4
     assert got[1024] == (1, 217) and got[216] == (4, 868) and got[0] == (4, 868)
+    L.lora_pool_destroy(pool)
+
+
+def test_live_pool_places_frees_and_coalesces():
+    """Space in a live pool: first fit, 256-byte granules, neighbours merge when freed."""
+    in_f, out_f = 256, 256
+    ranks = np.array([8, 16, 32, 8, 64, 16], dtype=np.int32)
+    scales = (2.0 / ranks).astype(np.float32)
+    size = lambda a: 2 * int((ranks[a] + 7) // 8 * 8) * (in_f + out_f)      # all multiples of 256 here
+    arena = size(0) + size(1) + size(2) + size(3)                            # room for 0..3, not for 4
+    pool = L.lora_pool_create_live(in_f, out_f, ranks, scales, FAKE_ARENA, arena)
+    assert L.lora_pool_space(pool) == {"free_bytes": arena, "largest_free_bytes": arena}
+    assert L.lora_pool_adapter_info(pool, 0)["a_offset"] == 2 ** 64 - 1     # no place yet
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_mark_resident(pool, 0)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+    for a in (0, 1, 2, 3):
+        L.lora_pool_reserve(pool, a)
+        L.lora_pool_mark_resident(pool, a)
+    offs = [L.lora_pool_adapter_info(pool, a)["a_offset"] * 2 for a in range(4)]
+    assert offs == [0, size(0), size(0) + size(1), size(0) + size(1) + size(2)]
+    info1 = L.lora_pool_adapter_info(pool, 1)
+    assert info1["b_offset"] - info1["a_offset"] == 16 * in_f and info1["resident"] == 1
+    assert L.lora_pool_space(pool) == {"free_bytes": 0, "largest_free_bytes": 0}
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_reserve(pool, 4)
+    assert e.value.status_name == "LORA_ERR_OOM"
+    # free 0 and 2: two separate pieces; 4 (rank 64) fits neither, and the message says compaction would not help
+    L.lora_pool_evict(pool, 0)
+    L.lora_pool_evict(pool, 2)
+    assert L.lora_pool_space(pool) == {"free_bytes": size(0) + size(2), "largest_free_bytes": size(2)}
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_reserve(pool, 4)
+    assert e.value.status_name == "LORA_ERR_OOM" and "compact" not in e.value.detail
+    # free 1 as well: 0, 1, 2 merge into one piece, first fit puts 5 (rank 16) at the start
+    L.lora_pool_evict(pool, 1)
+    assert L.lora_pool_space(pool)["largest_free_bytes"] == size(0) + size(1) + size(2)
+    L.lora_pool_reserve(pool, 5)
+    assert L.lora_pool_adapter_info(pool, 5)["a_offset"] == 0
+    # a segment object only depends on the adapters it uses
+    seg = L.lora_segments_plan(pool, [3, 3, -1])
+    L.lora_pool_mark_resident(pool, 5)
+    L.lora_pool_evict(pool, 5)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply(pool, seg, FAKE_ARENA, FAKE_ARENA, FAKE_ARENA, ldx=in_f, ldy=out_f, ws_bytes=1 << 20)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG" and "upload" in e.value.detail
+    with pytest.raises(L.LoraError) as e:
+        L.lora_segments_plan(pool, [5])
+    assert e.value.status_name == "LORA_ERR_NOT_RESIDENT"
+    L.lora_segments_destroy(seg)
+    L.lora_pool_destroy(pool)
+
+
+def test_live_pool_reports_when_compaction_would_help():
+    in_f, out_f = 256, 256
+    ranks = np.array([8, 8, 8, 16], dtype=np.int32)
+    scales = (2.0 / ranks).astype(np.float32)
+    one = 2 * 8 * (in_f + out_f)
+    pool = L.lora_pool_create_live(in_f, out_f, ranks, scales, FAKE_ARENA, 3 * one)
+    for a in (0, 1, 2):
+        L.lora_pool_reserve(pool, a)
+    L.lora_pool_evict(pool, 0)
+    L.lora_pool_evict(pool, 2)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_reserve(pool, 3)            # 2 * one free in total, in two pieces
+    assert e.value.status_name == "LORA_ERR_OOM" and "compact" in e.value.detail
     L.lora_pool_destroy(pool)
 
 
