@@ -102,6 +102,88 @@ def pick_workload(spec: str, wl):
     raise SystemExit(f"unknown workload {spec!r}")
 
 
+def run_projections(args, torch, L, wl, dev, stream, hip) -> int:
+    """Projections of one layer that read the same x, fused into one lora_apply_multi per layer or run
+    as separate lora_apply calls on the column blocks of the same y.  Weights and x are device-random."""
+    outs = {"qkv": (4096, 1024, 1024), "gateup": (14336, 14336), "q": (4096,)}[args.projections]
+    b0, description, default_layers, _ = pick_workload(args.workload, wl)
+    assert b0.in_features == 4096, "--projections uses the routing of cfg1 or cfg3:0 (in_features 4096)"
+    nl = args.layers or (32 if b0.T <= 1024 else 4)
+    T, in_f, P = b0.T, 4096, len(outs)
+    sizes = [L.lora_pool_bytes(in_f, o, b0.ranks, b0.scales) for o in outs]
+    starts = np.concatenate([[0], np.cumsum([(n + 4095) // 4096 * 4096 for n in sizes])])
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    arenas, pools, xs, ys = [], [], [], []
+    for l in range(nl):
+        arena = torch.empty(int(starts[-1]), dtype=torch.uint8, device=dev)
+        arena.view(torch.bfloat16).normal_(0.0, 0.02, generator=g)
+        arenas.append(arena)
+        layer_pools = []
+        for q, o in enumerate(outs):
+            pool = L.lora_pool_create(in_f, o, b0.ranks, b0.scales, arena[int(starts[q]): int(starts[q]) + sizes[q]])
+            for a in range(b0.n_adapters):
+                L.lora_pool_mark_resident(pool, a)
+            layer_pools.append(pool)
+        pools.append(layer_pools)
+        xs.append(torch.empty(T, in_f, dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0, generator=g))
+        ys.append(torch.zeros(T, sum(outs), dtype=torch.bfloat16, device=dev))
+    if args.separate:
+        segs = [L.lora_segments_build(pools[0][q], b0.token_adapter, stream=stream) for q in range(P)]
+        ws = torch.empty(max(max(L.lora_apply_workspace_bytes(pools[0][q], segs[q]) for q in range(P)), 256),
+                         dtype=torch.uint8, device=dev)
+        cols = np.concatenate([[0], np.cumsum(outs)])
+
+        def step():
+            for q in range(P):
+                L.lora_segments_rebuild(segs[q], b0.token_adapter, stream=stream)
+            for l in range(nl):
+                for q in range(P):
+                    L.lora_apply(pools[l][q], segs[q], xs[l], ys[l][:, int(cols[q]): int(cols[q + 1])], ws,
+                                 stream=stream, ldy=sum(outs))
+    else:
+        seg = L.lora_segments_build_multi(pools[0], b0.token_adapter, stream=stream)
+        ws = torch.empty(max(L.lora_apply_workspace_bytes(pools[0][0], seg), 256), dtype=torch.uint8, device=dev)
+
+        def step():
+            L.lora_segments_rebuild(seg, b0.token_adapter, stream=stream)
+            for l in range(nl):
+                L.lora_apply_multi(pools[l], seg, xs[l], ys[l], ws, stream=stream)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_act = int((b0.token_adapter >= 0).sum())
+    act = b0.token_adapter >= 0
+    rsum = int(b0.ranks[b0.token_adapter[act]].astype(np.int64).sum())
+    r8 = (b0.ranks.astype(np.int64) + 7) // 8 * 8
+    wsum = int(r8[b0.used_adapters()].sum())
+    # x once per layer when fused, once per projection otherwise; weights, y and v as ever
+    per_layer = sum(2 * wsum * (in_f + o) + 4 * n_act * o + 4 * rsum for o in outs)
+    per_layer += 2 * n_act * in_f * (P if args.separate else 1)
+    us_per_layer = dt / args.steps / nl * 1e6
+    out = {
+        "metric": "LoRA-delta tokens/s + achieved HBM GB/s (decode) / MFMA util (prefill), mixed ranks",
+        "value": n_act * P * nl / (dt / args.steps), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{description}; projections {args.projections} {outs} of {nl} layers, "
+                               + ("one lora_apply each" if args.separate else "one lora_apply_multi per layer"),
+                   "tokens": T, "active_tokens": n_act, "projections": P, "layers_per_step": nl,
+                   "us_per_layer": us_per_layer, "algorithmic_bytes_per_layer": per_layer},
+        "roofline": {"bound": "hbm", "kernel": "all launches of a layer", "achieved": per_layer / us_per_layer / 1e3,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": per_layer / us_per_layer / 1e3 / HBM_PEAK_GBS,
+                     "traffic": None},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,6 +197,10 @@ def main() -> int:
     ap.add_argument("--fused", action="store_true", help="single-launch lora_apply (decode-sized batches)")
     ap.add_argument("--whole-k-limit", type=int, default=None,
                     help="planning knob lora_set_whole_k_limit (default: the library's, 1024; 0 = always k-slices)")
+    ap.add_argument("--projections", default=None,
+                    help="several projections that share x in one pass, e.g. qkv or gateup (Llama-3-8B shapes), with "
+                         "the routing of --workload cfg1 or cfg3:0; add --separate to run them one lora_apply each")
+    ap.add_argument("--separate", action="store_true")
     ap.add_argument("--concurrent-loads", type=int, default=0,
                     help="adapters (ones the batch does not use) loaded into the step's pools on a second stream "
                          "per step, while the applies run")
@@ -141,6 +227,9 @@ def main() -> int:
         L.lora_set_fused_apply(True)
     if args.whole_k_limit is not None:
         L.lora_set_whole_k_limit(args.whole_k_limit)
+
+    if args.projections:
+        return run_projections(args, torch, L, wl, dev, stream, hip)
 
     b0, description, default_layers, seeded = pick_workload(args.workload, wl)
     nl = args.layers or default_layers

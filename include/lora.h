@@ -37,6 +37,7 @@ extern "C" {
 #endif
 
 #define LORA_MAX_RANK 256
+#define LORA_MAX_PROJECTIONS 8 /* pools per multi-projection segment object */
 #define LORA_BF16 1
 
 typedef enum {
@@ -250,6 +251,26 @@ lora_status_t lora_expand(const lora_pool_t *pool, const lora_segments_t *seg, c
 lora_status_t lora_apply_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *seg, size_t *bytes);
 lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *seg, const void *x, int64_t ldx,
                          void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream);
+
+/* Several projections that read the same x (q, k and v of a layer; gate and up) in one pass: their
+ * pools (same in_features, same ranks and scales, each with its own out_features and arena) are
+ * planned together and every launch of lora_apply_multi covers all of them, so x is fetched once per
+ * launch rather than once per projection and the fixed cost of a launch is paid once.  y is one
+ * matrix [T][out_0 + out_1 + ...], row stride ldy: projection q's columns follow those of q - 1, the
+ * layout of a fused q|k|v or gate|up output.  Each row gets bitwise what separate lora_apply calls on
+ * the column blocks would give it.  lora_segments_plan_multi is host only; build = plan + upload;
+ * lora_segments_rebuild, info, export, check and destroy work on such objects, the single-pool
+ * launch calls refuse them.  The object can be launched on other pools (the next layer's) with the
+ * same adapters at the same places whose arenas lie at the same distances from each other
+ * (LORA_ERR_STALE_SEGMENTS otherwise).  Workspace: lora_apply_workspace_bytes(pools[0], seg). */
+lora_status_t lora_segments_plan_multi(const lora_pool_t *const *pools, int32_t n_pools,
+                                       const int32_t *token_adapter_host, int32_t T, lora_segments_t **out);
+lora_status_t lora_segments_build_multi(const lora_pool_t *const *pools, int32_t n_pools,
+                                        const int32_t *token_adapter_host, int32_t T, void *stream,
+                                        lora_segments_t **out);
+lora_status_t lora_apply_multi(const lora_pool_t *const *pools, int32_t n_pools, const lora_segments_t *seg,
+                               const void *x, int64_t ldx, void *y, int64_t ldy, void *workspace,
+                               size_t ws_bytes, void *stream);
 
 /* Planning knob, process-wide, read by the lora_segments_plan / build / rebuild calls that follow.
  * A batch whose decode-sized groups make between 64 and `max_units` shrink units when a unit takes

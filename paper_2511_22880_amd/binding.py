@@ -28,6 +28,7 @@ EXPORTS = (
     "lora_segments_build", "lora_segments_build_ranges", "lora_segments_rebuild", "lora_segments_info",
     "lora_segments_export", "lora_segments_export_units", "lora_segments_destroy", "lora_workspace_bytes",
     "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_profile_next_apply",
+    "lora_segments_plan_multi", "lora_segments_build_multi", "lora_apply_multi",
     "lora_set_fused_apply", "lora_set_whole_k_limit", "lora_segments_check",
     "lora_status_string",
     "lora_last_error",
@@ -329,6 +330,36 @@ def lora_apply(pool: Pool, seg: Segments, x, y, workspace, stream=None, ldx: Opt
     _check(lib().lora_apply(pool.handle, seg.handle, _ptr(x), ctypes.c_int64(_ld(x, ldx)), _ptr(y),
                             ctypes.c_int64(_ld(y, ldy)), _ptr(workspace),
                             ctypes.c_size_t(_nbytes(workspace) if ws_bytes is None else ws_bytes), _stream(stream)))
+
+
+def _pool_array(pools):
+    arr = (ctypes.c_void_p * len(pools))(*[p.handle.value for p in pools])
+    return arr
+
+
+def lora_segments_plan_multi(pools, token_adapter) -> Segments:
+    ta = _i32(token_adapter)
+    h = ctypes.c_void_p(None)
+    _check(lib().lora_segments_plan_multi(_pool_array(pools), ctypes.c_int32(len(pools)), _ptr(ta),
+                                          ctypes.c_int32(ta.shape[0]), ctypes.byref(h)))
+    return Segments(h, pools[0])
+
+
+def lora_segments_build_multi(pools, token_adapter, stream=None) -> Segments:
+    ta = _i32(token_adapter)
+    h = ctypes.c_void_p(None)
+    _check(lib().lora_segments_build_multi(_pool_array(pools), ctypes.c_int32(len(pools)), _ptr(ta),
+                                           ctypes.c_int32(ta.shape[0]), _stream(stream), ctypes.byref(h)))
+    return Segments(h, pools[0])
+
+
+def lora_apply_multi(pools, seg: Segments, x, y, workspace, stream=None, ldx: Optional[int] = None,
+                     ldy: Optional[int] = None, ws_bytes: Optional[int] = None) -> None:
+    """y: bf16 device tensor [T][sum of the pools' out_features], updated in place."""
+    _check(lib().lora_apply_multi(_pool_array(pools), ctypes.c_int32(len(pools)), seg.handle, _ptr(x),
+                                  ctypes.c_int64(_ld(x, ldx)), _ptr(y), ctypes.c_int64(_ld(y, ldy)), _ptr(workspace),
+                                  ctypes.c_size_t(_nbytes(workspace) if ws_bytes is None else ws_bytes),
+                                  _stream(stream)))
 
 
 def lora_set_fused_apply(enabled: bool) -> None:

@@ -95,6 +95,16 @@ struct lora_segments {
     unsigned launches;      // fused launches since the table was uploaded (the counters' epoch)
     hipEvent_t copied;  // recorded after the upload; guards re-use of `staging`
     bool uploaded;
+    // Several projections in one object (they read the same x and write column blocks of one y): the
+    // unit lists of all of them, one after the other.  Unit offsets are relative to `mbase`, the lowest
+    // of the pools' arenas; projection q's v rows, counters and output columns follow those of q - 1.
+    std::vector<const lora_pool *> mpools;
+    std::vector<uint64_t> mpool_ids;
+    std::vector<std::vector<SegRec>> msegs;
+    std::vector<std::vector<uint64_t>> mepochs;
+    std::vector<int> mouts;          // out_features of each projection
+    std::vector<uint64_t> mdelta;    // element distance of each pool's arena from the lowest one
+    int out_total;
 };
 
 static const uint32_t kPoolMagic = 0x4C505231u, kSegMagic = 0x4C534731u;
@@ -727,6 +737,122 @@ extern "C" lora_status_t lora_segments_plan_ranges(const lora_pool_t *pool, cons
     return lora_segments_plan(pool, ta.data(), (int32_t)ta.size(), out);
 }
 
+// Plans every projection on its own, then strings the unit lists together.
+static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const lora_pool *> &pools,
+                                     const int32_t *ta, int32_t T)
+{
+    const lora_pool *p0 = pools[0];
+    const uint16_t *base = p0->arena;
+    for (const lora_pool *q : pools) {
+        if (q->in_features != p0->in_features || q->rank != p0->rank || q->scale != p0->scale)
+            return fail(LORA_ERR_SHAPE, "the pools of one multi-projection object must agree in in_features, ranks and scales");
+        if (((uintptr_t)q->arena - (uintptr_t)p0->arena) % 2) return fail(LORA_ERR_INVALID_ARG, "arena alignment");
+        base = std::min(base, (const uint16_t *)q->arena);
+    }
+    lora_status_t st = plan_into(sg, p0, ta, T);
+    if (st != LORA_OK) return st;
+    sg->mpools = pools;
+    sg->mpool_ids.clear();
+    sg->msegs.clear();
+    sg->mepochs.clear();
+    sg->mouts.clear();
+    sg->mdelta.clear();
+    const int64_t v_one = sg->v_floats;
+    const int sync_one = sg->n_sync;
+    auto shift = [](std::vector<Unit> &units, size_t from, uint64_t delta, int64_t vbase, int sync, int col) {
+        for (size_t i = from; i < units.size(); ++i) {
+            units[i].w_off += delta;
+            units[i].v_off += vbase;
+            units[i].sync_idx += sync;
+            units[i].p0 += col;  // only the expand lists get a column base
+        }
+    };
+    const uint64_t delta0 = (uint64_t)(((uintptr_t)p0->arena - (uintptr_t)base) / 2);
+    shift(sg->shrink_units, 0, delta0, 0, 0, 0);
+    shift(sg->prefill_units, 0, delta0, 0, 0, 0);
+    shift(sg->expand_units, 0, delta0, 0, 0, 0);
+    shift(sg->expand_big_units, 0, delta0, 0, 0, 0);
+    sg->mpool_ids.push_back(p0->id);
+    sg->msegs.push_back(sg->segs);
+    sg->mepochs.push_back(sg->seg_epoch);
+    sg->mouts.push_back(p0->out_features);
+    sg->mdelta.push_back(delta0);
+    int col = p0->out_features;
+    int64_t weight_bytes = sg->weight_bytes;
+    lora_segments *tmp = new (std::nothrow) lora_segments();
+    if (!tmp) return fail(LORA_ERR_OOM, "host allocation failed");
+    for (size_t q = 1; q < pools.size(); ++q) {
+        st = plan_into(tmp, pools[q], ta, T);
+        if (st != LORA_OK) break;
+        const uint64_t delta = (uint64_t)(((uintptr_t)pools[q]->arena - (uintptr_t)base) / 2);
+        const size_t n0 = sg->shrink_units.size(), n1 = sg->prefill_units.size(), n2 = sg->expand_units.size(),
+                     n3 = sg->expand_big_units.size();
+        sg->shrink_units.insert(sg->shrink_units.end(), tmp->shrink_units.begin(), tmp->shrink_units.end());
+        sg->prefill_units.insert(sg->prefill_units.end(), tmp->prefill_units.begin(), tmp->prefill_units.end());
+        sg->expand_units.insert(sg->expand_units.end(), tmp->expand_units.begin(), tmp->expand_units.end());
+        sg->expand_big_units.insert(sg->expand_big_units.end(), tmp->expand_big_units.begin(),
+                                    tmp->expand_big_units.end());
+        shift(sg->shrink_units, n0, delta, (int64_t)q * v_one, (int)q * sync_one, 0);
+        shift(sg->prefill_units, n1, delta, (int64_t)q * v_one, (int)q * sync_one, 0);
+        shift(sg->expand_units, n2, delta, (int64_t)q * v_one, (int)q * sync_one, col);
+        shift(sg->expand_big_units, n3, delta, (int64_t)q * v_one, (int)q * sync_one, col);
+        sg->n_prefill_hi += tmp->n_prefill_hi;
+        sg->mpool_ids.push_back(pools[q]->id);
+        sg->msegs.push_back(tmp->segs);
+        sg->mepochs.push_back(tmp->seg_epoch);
+        sg->mouts.push_back(pools[q]->out_features);
+        sg->mdelta.push_back(delta);
+        col += pools[q]->out_features;
+        weight_bytes += tmp->weight_bytes;
+    }
+    delete tmp;
+    if (st != LORA_OK) return st;
+    sg->out_total = col;
+    sg->v_floats = v_one * (int64_t)pools.size();
+    sg->n_sync = sync_one * (int)pools.size();
+    sg->weight_bytes = weight_bytes;
+    sg->off_perm = 0;
+    sg->off_shrink = round_up_sz(sg->perm.size() * sizeof(int32_t), 256);
+    sg->off_prefill = round_up_sz(sg->off_shrink + sg->shrink_units.size() * sizeof(Unit), 256);
+    sg->off_expand = round_up_sz(sg->off_prefill + sg->prefill_units.size() * sizeof(Unit), 256);
+    sg->off_expand_big = round_up_sz(sg->off_expand + sg->expand_units.size() * sizeof(Unit), 256);
+    sg->off_sync = round_up_sz(sg->off_expand_big + sg->expand_big_units.size() * sizeof(Unit), 256);
+    sg->table_bytes = round_up_sz(sg->off_sync + (size_t)(2 * sg->n_sync + 1) * sizeof(unsigned), 256);
+    return LORA_OK;
+}
+
+static lora_status_t check_pool_list(const lora_pool_t *const *pools, int32_t n, std::vector<const lora_pool *> *out)
+{
+    if (!pools || n < 1 || n > LORA_MAX_PROJECTIONS)
+        return fail(LORA_ERR_INVALID_ARG, "pools is NULL or n_pools = %d outside 1..%d", n, LORA_MAX_PROJECTIONS);
+    for (int32_t q = 0; q < n; ++q) {
+        if (!pool_ok(pools[q])) return fail(LORA_ERR_INVALID_ARG, "pools[%d] is NULL or not a pool", q);
+        out->push_back(pools[q]);
+    }
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_segments_plan_multi(const lora_pool_t *const *pools, int32_t n_pools,
+                                                  const int32_t *ta, int32_t T, lora_segments_t **out)
+{
+    if (!out) return fail(LORA_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    std::vector<const lora_pool *> list;
+    lora_status_t st = check_pool_list(pools, n_pools, &list);
+    if (st != LORA_OK) return st;
+    if (T < 0) return fail(LORA_ERR_INVALID_ARG, "T = %d", T);
+    if (T > 0 && !ta) return fail(LORA_ERR_INVALID_ARG, "token_adapter_host is NULL");
+    lora_segments *sg = new_segments();
+    if (!sg) return fail(LORA_ERR_OOM, "host allocation failed");
+    st = plan_multi_into(sg, list, ta, T);
+    if (st != LORA_OK) {
+        lora_segments_destroy(sg);
+        return st;
+    }
+    *out = sg;
+    return LORA_OK;
+}
+
 extern "C" lora_status_t lora_segments_upload(lora_segments_t *sg, void *stream)
 {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
@@ -768,6 +894,20 @@ extern "C" lora_status_t lora_segments_upload(lora_segments_t *sg, void *stream)
     return LORA_OK;
 }
 
+extern "C" lora_status_t lora_segments_build_multi(const lora_pool_t *const *pools, int32_t n_pools,
+                                                   const int32_t *ta, int32_t T, void *stream,
+                                                   lora_segments_t **out)
+{
+    lora_status_t st = lora_segments_plan_multi(pools, n_pools, ta, T, out);
+    if (st != LORA_OK) return st;
+    st = lora_segments_upload(*out, stream);
+    if (st != LORA_OK) {
+        lora_segments_destroy(*out);
+        *out = nullptr;
+    }
+    return st;
+}
+
 extern "C" lora_status_t lora_segments_build(const lora_pool_t *pool, const int32_t *ta, int32_t T, void *stream,
                                              lora_segments_t **out)
 {
@@ -802,7 +942,16 @@ extern "C" lora_status_t lora_segments_rebuild(lora_segments_t *sg, const int32_
         return fail(LORA_ERR_STALE_SEGMENTS, "the pool this segment object was built for no longer exists");
     if (T < 0) return fail(LORA_ERR_INVALID_ARG, "T = %d", T);
     if (T > 0 && !ta) return fail(LORA_ERR_INVALID_ARG, "token_adapter_host is NULL");
-    lora_status_t st = plan_into(sg, sg->pool, ta, T);
+    lora_status_t st;
+    if (sg->mpools.empty()) {
+        st = plan_into(sg, sg->pool, ta, T);
+    } else {
+        const std::vector<const lora_pool *> pools = sg->mpools;
+        for (size_t q = 0; q < pools.size(); ++q)
+            if (!pool_ok(pools[q]) || pools[q]->id != sg->mpool_ids[q])
+                return fail(LORA_ERR_STALE_SEGMENTS, "a pool this segment object was built for no longer exists");
+        st = plan_multi_into(sg, pools, ta, T);
+    }
     if (st != LORA_OK) {
         sg->uploaded = false;
         return st;
@@ -868,19 +1017,18 @@ extern "C" lora_status_t lora_segments_export_units(const lora_segments_t *sg, i
 // layout (same feature sizes and ranks, hence the same offsets): the layers of a model that share a
 // projection shape and an adapter set.  On such a sibling pool every adapter the batch uses must be
 // resident.
-static lora_status_t check_launchable(const lora_pool *pool, const lora_segments *sg)
+// The unit records carry each used adapter's place, rank and scale.  An object may be launched on the
+// pool it was planned for as long as none of the adapters it uses has been loaded, evicted or moved
+// since, whatever happened to other adapters, and on any pool that holds the same adapters at the same
+// places (the layers of a model).
+static lora_status_t check_adapters(const lora_pool *pool, const lora_segments *sg, const std::vector<SegRec> &segs,
+                                    const std::vector<uint64_t> &epochs, uint64_t planned_pool_id)
 {
-    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
-    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
-    // The unit records carry each used adapter's place, rank and scale.  The object may be launched on
-    // the pool it was planned for as long as none of the adapters it uses has been loaded, evicted or
-    // moved since, whatever happened to other adapters, and on any pool that holds the same adapters at
-    // the same places (the layers of a model).
-    if (sg->layout_in != pool->in_features || sg->layout_out != pool->out_features)
+    if (sg->layout_in != pool->in_features)
         return fail(LORA_ERR_STALE_SEGMENTS, "segment object was built for a pool with other feature sizes");
     for (size_t i = 0; i < sg->seg_adapter.size(); ++i) {
         const int32_t a = sg->seg_adapter[i];
-        const SegRec &r = sg->segs[i];
+        const SegRec &r = segs[i];
         if (a >= pool->n_adapters)
             return fail(LORA_ERR_STALE_SEGMENTS, "segment object uses adapter %d, which this pool does not have", a);
         if (!pool->resident[a])
@@ -888,10 +1036,23 @@ static lora_status_t check_launchable(const lora_pool *pool, const lora_segments
         if (pool->rank[a] != r.rank || pool->scale[a] != r.scale || pool->a_off[a] != r.a_off ||
             pool->b_off[a] != r.b_off)
             return fail(LORA_ERR_STALE_SEGMENTS, "adapter %d has another rank, scale or place in this pool", a);
-        if (sg->pool_id == pool->id && pool->epoch[a] != sg->seg_epoch[i])
+        if (planned_pool_id == pool->id && pool->epoch[a] != epochs[i])
             return fail(LORA_ERR_STALE_SEGMENTS,
                         "adapter %d was loaded, evicted or moved after the segment object was built", a);
     }
+    return LORA_OK;
+}
+
+static lora_status_t check_launchable(const lora_pool *pool, const lora_segments *sg)
+{
+    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (!sg->mpools.empty())
+        return fail(LORA_ERR_INVALID_ARG, "segment object was built for several pools: use lora_apply_multi");
+    if (sg->layout_out != pool->out_features)
+        return fail(LORA_ERR_STALE_SEGMENTS, "segment object was built for a pool with other feature sizes");
+    lora_status_t st = check_adapters(pool, sg, sg->segs, sg->seg_epoch, sg->pool_id);
+    if (st != LORA_OK) return st;
     if (!sg->uploaded) return fail(LORA_ERR_INVALID_ARG, "segment object was planned but not uploaded");
     return LORA_OK;
 }
@@ -920,7 +1081,8 @@ static size_t apply_packed_bytes(const lora_segments *sg) { return round_up_sz((
 
 enum UnitKind { kShrink, kPrefill, kExpand, kExpandBig };
 
-static lora::LaunchCtx ctx_for(const lora_pool *pool, const lora_segments *sg, UnitKind kind)
+static lora::LaunchCtx ctx_for(const uint16_t *arena, int in_features, int out_features, const lora_segments *sg,
+                                UnitKind kind)
 {
     lora::LaunchCtx c;
     const size_t off = kind == kShrink    ? sg->off_shrink
@@ -933,11 +1095,16 @@ static lora::LaunchCtx ctx_for(const lora_pool *pool, const lora_segments *sg, U
                                                        : sg->expand_big_units;
     c.units = (const Unit *)(sg->dev + off);
     c.perm = (const int32_t *)(sg->dev + sg->off_perm);
-    c.arena = pool->arena;
+    c.arena = arena;
     c.n_units = (int)list.size();
-    c.in_features = pool->in_features;
-    c.out_features = pool->out_features;
+    c.in_features = in_features;
+    c.out_features = out_features;
     return c;
+}
+
+static lora::LaunchCtx ctx_for(const lora_pool *pool, const lora_segments *sg, UnitKind kind)
+{
+    return ctx_for(pool->arena, pool->in_features, pool->out_features, sg, kind);
 }
 
 extern "C" lora_status_t lora_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *sg, size_t *bytes)
@@ -1041,16 +1208,15 @@ extern "C" lora_status_t lora_profile_next_apply(void *before, void *between, vo
     return LORA_OK;
 }
 
-extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *sg, const void *x, int64_t ldx,
-                                    void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream)
+// The launches of one apply: `arena` is the base the units' weight offsets count from, `out` the
+// width of y that the units' columns lie in.
+static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lora_segments *sg, const void *x,
+                               int64_t ldx, void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream)
 {
-    lora_status_t st = check_launchable(pool, sg);
-    if (st != LORA_OK) return st;
-    if (sg->n_active == 0) return LORA_OK;
-    if ((st = check_matrix(x, ldx, pool->in_features, "x")) != LORA_OK) return st;
-    if ((st = check_matrix(y, ldy, pool->out_features, "y")) != LORA_OK) return st;
-    size_t need = 0;
-    lora_apply_workspace_bytes(pool, sg, &need);
+    lora_status_t st;
+    if ((st = check_matrix(x, ldx, in, "x")) != LORA_OK) return st;
+    if ((st = check_matrix(y, ldy, out, "y")) != LORA_OK) return st;
+    const size_t need = apply_parts_bytes(sg) + 2 * apply_packed_bytes(sg);
     if ((st = check_workspace(workspace, ws_bytes, need)) != LORA_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     float *parts = (float *)workspace;
@@ -1069,8 +1235,8 @@ extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments
     sa.v_lo = (uint16_t *)((char *)workspace + apply_parts_bytes(sg) + apply_packed_bytes(sg));
     sa.epoch = ++msg->launches;
     sa.spin_limit = kSpinLimit;
-    const lora::LaunchCtx cs = ctx_for(pool, sg, kShrink), cp = ctx_for(pool, sg, kPrefill),
-                          ce = ctx_for(pool, sg, kExpand);
+    const lora::LaunchCtx cs = ctx_for(arena, in, out, sg, kShrink), cp = ctx_for(arena, in, out, sg, kPrefill),
+                          ce = ctx_for(arena, in, out, sg, kExpand), cb = ctx_for(arena, in, out, sg, kExpandBig);
     if (ev[0]) HIP_TRY(hipEventRecord(ev[0], s));
     // units of more than 16 tokens span several counters, and whole-k shrink units are work groups of
     // another size: such batches always take separate launches
@@ -1079,7 +1245,8 @@ extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments
                                          (uint16_t *)y, ldy, &sa, s));
         if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
     } else {
-        HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, sa.v_hi, sa.v_lo, nullptr, nsl, stride, s));
+        HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, sa.v_hi, sa.v_lo, nullptr,
+                                            nsl, stride, s));
         if (sg->wide)
             HIP_TRY(lora::launch_shrink_wide(cs, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, nullptr,
                                              sa.v_hi, sa.v_lo, s));
@@ -1087,11 +1254,46 @@ extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments
             HIP_TRY(lora::launch_shrink(cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride, &sa, s));
         if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
         HIP_TRY(lora::launch_expand(ce, false, parts, nsl, stride, (uint16_t *)y, ldy, &sa, s));
-        HIP_TRY(lora::launch_expand(ctx_for(pool, sg, kExpandBig), true, parts, nsl, stride, (uint16_t *)y, ldy, &sa,
-                                    s));
+        HIP_TRY(lora::launch_expand(cb, true, parts, nsl, stride, (uint16_t *)y, ldy, &sa, s));
     }
     if (ev[2]) HIP_TRY(hipEventRecord(ev[2], s));
     return LORA_OK;
+}
+
+extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *sg, const void *x, int64_t ldx,
+                                    void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream)
+{
+    lora_status_t st = check_launchable(pool, sg);
+    if (st != LORA_OK) return st;
+    if (sg->n_active == 0) return LORA_OK;
+    return run_apply(pool->arena, pool->in_features, pool->out_features, sg, x, ldx, y, ldy, workspace, ws_bytes,
+                     stream);
+}
+
+extern "C" lora_status_t lora_apply_multi(const lora_pool_t *const *pools, int32_t n_pools,
+                                          const lora_segments_t *sg, const void *x, int64_t ldx, void *y,
+                                          int64_t ldy, void *workspace, size_t ws_bytes, void *stream)
+{
+    std::vector<const lora_pool *> list;
+    lora_status_t st = check_pool_list(pools, n_pools, &list);
+    if (st != LORA_OK) return st;
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (sg->mpools.size() != list.size())
+        return fail(LORA_ERR_INVALID_ARG, "segment object was built for %zu pools, %zu given", sg->mpools.size(),
+                    list.size());
+    const uint16_t *base = list[0]->arena;
+    for (const lora_pool *q : list) base = std::min(base, (const uint16_t *)q->arena);
+    for (size_t q = 0; q < list.size(); ++q) {
+        if (list[q]->out_features != sg->mouts[q])
+            return fail(LORA_ERR_STALE_SEGMENTS, "pools[%zu] has another out_features than the pool planned for", q);
+        if ((uint64_t)(((uintptr_t)list[q]->arena - (uintptr_t)base) / 2) != sg->mdelta[q])
+            return fail(LORA_ERR_STALE_SEGMENTS,
+                        "the arenas of the given pools are not spaced as those the object was planned for");
+        if ((st = check_adapters(list[q], sg, sg->msegs[q], sg->mepochs[q], sg->mpool_ids[q])) != LORA_OK) return st;
+    }
+    if (!sg->uploaded) return fail(LORA_ERR_INVALID_ARG, "segment object was planned but not uploaded");
+    if (sg->n_active == 0) return LORA_OK;
+    return run_apply(base, list[0]->in_features, sg->out_total, sg, x, ldx, y, ldy, workspace, ws_bytes, stream);
 }
 
 extern "C" const char *lora_status_string(lora_status_t status)

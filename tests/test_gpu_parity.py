@@ -544,3 +544,75 @@ def test_load_on_a_copy_stream_while_batches_run():
     L.lora_segments_destroy(seg)
     L.lora_segments_destroy(seg_all)
     L.lora_pool_destroy(pool)
+
+
+# ------------------------------------------------------------------------------------------------
+# Several projections that share x (q|k|v, gate|up) in one pass.
+# ------------------------------------------------------------------------------------------------
+def _multi_case(batch, outs, y0_kind="small"):
+    """Pools of the same adapters (ranks, routing) with different out_features; weights per projection
+    from the generator's projection key."""
+    print(f"[case] multi {batch.name} T={batch.T} in={batch.in_features} outs={outs}", flush=True)
+    batches = []
+    for q, o in enumerate(outs):
+        bq = wl.CoBatch(batch.name, batch.in_features, o, batch.ranks, batch.scales, batch.token_adapter,
+                        seed=batch.seed, config=batch.config, layer=batch.layer, projection=q)
+        batches.append(bq)
+    sizes = [L.lora_pool_bytes(batch.in_features, o, batch.ranks, batch.scales) for o in outs]
+    starts = np.concatenate([[0], np.cumsum([(n + 4095) // 4096 * 4096 for n in sizes])])
+    arena = torch.zeros(int(starts[-1]), dtype=torch.uint8, device="cuda")
+    pools, A, B = [], [], []
+    used = [int(a) for a in batch.used_adapters()]
+    for q, (bq, o) in enumerate(zip(batches, outs)):
+        pool = L.lora_pool_create(batch.in_features, o, batch.ranks, batch.scales,
+                                  arena[int(starts[q]): int(starts[q]) + sizes[q]])
+        Aq, Bq = [None] * batch.n_adapters, [None] * batch.n_adapters
+        for a in used:
+            Aq[a], Bq[a] = bq.adapter_bits(a)
+            L.lora_pool_load(pool, a, Aq[a], Bq[a])
+        pools.append(pool)
+        A.append(Aq)
+        B.append(Bq)
+    x_bits = batch.x_bits()
+    x = G.bits_to_dev(x_bits)
+    y0_bits = np.concatenate([bq.y0_bits(y0_kind) for bq in batches], axis=1)
+    # all projections in one pass
+    y = G.bits_to_dev(y0_bits)
+    seg = L.lora_segments_build_multi(pools, batch.token_adapter)
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(pools[0], seg), 256), dtype=torch.uint8, device="cuda")
+    L.lora_apply_multi(pools, seg, x, y, ws)
+    torch.cuda.synchronize()
+    L.lora_segments_check(seg)
+    y_multi = G.dev_to_bits(y)
+    # a second pass on the same object after a rebuild must give the same bits
+    L.lora_segments_rebuild(seg, batch.token_adapter)
+    y2 = G.bits_to_dev(y0_bits)
+    L.lora_apply_multi(pools, seg, x, y2, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(G.dev_to_bits(y2), y_multi)
+    L.lora_segments_destroy(seg)
+    # one projection at a time on the column blocks of the same matrix: the same bits; and the oracle
+    y_sep = G.bits_to_dev(y0_bits)
+    col = 0
+    for q, o in enumerate(outs):
+        s1 = L.lora_segments_build(pools[q], batch.token_adapter)
+        w1 = torch.empty(max(L.lora_apply_workspace_bytes(pools[q], s1), 256), dtype=torch.uint8, device="cuda")
+        L.lora_apply(pools[q], s1, x, y_sep[:, col: col + o], w1, ldy=y_sep.shape[1])
+        torch.cuda.synchronize()
+        L.lora_segments_destroy(s1)
+        y_ref = oracle.lora_apply(x_bits, batch.token_adapter, batch.ranks, batch.scales, A[q], B[q],
+                                  y0=wl.bf16_bits_to_f64(y0_bits[:, col: col + o]))
+        G.check_parity(y_multi[:, col: col + o], y_ref, y0_bits[:, col: col + o], batch.token_adapter)
+        col += o
+    assert np.array_equal(G.dev_to_bits(y_sep), y_multi)
+    for p in pools:
+        L.lora_pool_destroy(p)
+
+
+def test_multi_projection_apply_decode_and_prefill():
+    _multi_case(wl.small_mixed(seed=12, in_features=1024), (512, 128, 256))
+    _multi_case(wl.cfg1_decode(in_features=2048, out_features=128, n_tokens=160, n_adapters=64), (256, 256), "zero")
+    heavy = wl.cfg2_prefill(0, length_scale=0.08)
+    heavy.in_features = 1024
+    assert heavy.T >= 1024
+    _multi_case(heavy, (640, 128, 128), "zero")

@@ -1,6 +1,7 @@
 """Host side of the C-ABI library, no GPU: the library loads and exports every symbol the header
 declares, argument errors are reported before the device is touched, pool offsets follow the ragged
 layout, and the planner's grouping and work units match a brute-force grouping."""
+import ctypes
 import os
 import re
 
@@ -304,6 +305,59 @@ def test_live_pool_reports_when_compaction_would_help():
         L.lora_pool_reserve(pool, 3)            # 2 * one free in total, in two pieces
     assert e.value.status_name == "LORA_ERR_OOM" and "compact" in e.value.detail
     L.lora_pool_destroy(pool)
+
+
+def test_multi_projection_plan_is_the_projections_plans_one_after_the_other():
+    """q|k|v in one object: the unit lists of the three plans, expand columns shifted by the column base
+    of each projection, v rows and counters of projection q after those of q - 1."""
+    ranks = np.array([8, 16, 3, 128, 64], dtype=np.int32)
+    scales = (2.0 / ranks).astype(np.float32)
+    outs = (512, 128, 256)
+    pools, addr = [], FAKE_ARENA
+    for o in outs:
+        n = L.lora_pool_bytes(512, o, ranks, scales)
+        pools.append(L.lora_pool_create(512, o, ranks, scales, addr, n))
+        addr += (n + 4095) // 4096 * 4096
+        for a in range(len(ranks)):
+            L.lora_pool_mark_resident(pools[-1], a)
+    ta = np.array([0, 3, 3, -1, 4, 1, 3, 0, 2, 4, 4, 3] * 5, dtype=np.int32)
+    multi = L.lora_segments_plan_multi(pools, ta)
+    mi, mu = L.lora_segments_info(multi), L.lora_segments_export_units(multi)
+    singles = [L.lora_segments_plan(p, ta) for p in pools]
+    si = [L.lora_segments_info(s_) for s_ in singles]
+    su = [L.lora_segments_export_units(s_) for s_ in singles]
+    assert mi["v_floats"] == sum(i["v_floats"] for i in si) and mi["weight_bytes"] == sum(i["weight_bytes"] for i in si)
+    assert mi["n_shrink_units"] == sum(i["n_shrink_units"] for i in si)
+    assert mi["n_expand_units"] == sum(i["n_expand_units"] for i in si)
+    assert np.array_equal(mu["shrink"], np.concatenate([u["shrink"] for u in su]))
+    want, col = [], 0
+    for u, o in zip(su, outs):
+        e = u["expand"].copy()
+        e[:, 3] += col              # first output column
+        want.append(e)
+        col += o
+    assert np.array_equal(mu["expand"], np.concatenate(want))
+    # the single-pool launch calls refuse such an object; pools that disagree in ranks cannot share one
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply(pools[0], multi, FAKE_ARENA, FAKE_ARENA, FAKE_ARENA, ldx=512, ldy=512, ws_bytes=1 << 20)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG" and "lora_apply_multi" in e.value.detail
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply_multi(pools, multi, FAKE_ARENA, FAKE_ARENA, FAKE_ARENA, ldx=512, ldy=sum(outs), ws_bytes=1 << 24)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG" and "upload" in e.value.detail
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply_multi(pools[:2], multi, FAKE_ARENA, FAKE_ARENA, FAKE_ARENA, ldx=512, ldy=sum(outs), ws_bytes=1 << 24)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply_multi(pools[::-1], multi, FAKE_ARENA, FAKE_ARENA, FAKE_ARENA, ldx=512, ldy=sum(outs), ws_bytes=1 << 24)
+    assert e.value.status_name == "LORA_ERR_STALE_SEGMENTS"
+    other = make_pool(in_f=512, out_f=256, ranks=(8, 16, 3, 128, 32))
+    with pytest.raises(L.LoraError) as e:
+        L.lora_segments_plan_multi([pools[0], other], ta)
+    assert e.value.status_name == "LORA_ERR_SHAPE"
+    for s_ in singles + [multi]:
+        L.lora_segments_destroy(s_)
+    for p_ in pools + [other]:
+        L.lora_pool_destroy(p_)
 
 
 def test_ranges_merge_requests_of_the_same_adapter():
