@@ -32,6 +32,7 @@ EXPORTS = (
     "lora_set_fused_apply", "lora_set_whole_k_limit", "lora_segments_check",
     "lora_status_string",
     "lora_last_error",
+    "lora_place_extrapolate", "lora_place_assign",
 )
 
 
@@ -385,3 +386,40 @@ def lora_status_string(status: int) -> str:
 
 def lora_last_error() -> str:
     return lib().lora_last_error().decode("utf-8", "replace")
+
+
+# ---- adapter placement and routing (include/lora_placement.h; host only) ----------------------------
+class _PlaceProblem(ctypes.Structure):
+    _fields_ = [("n_servers", ctypes.c_int32), ("n_adapters", ctypes.c_int32), ("ranks", ctypes.c_void_p),
+                ("demand_tps", ctypes.c_void_p), ("n_ops", ctypes.c_int32), ("op_ranks", ctypes.c_void_p),
+                ("op_tps", ctypes.c_void_p), ("prev_phi", ctypes.c_void_p)]
+
+
+def lora_place_extrapolate(history, current: float) -> float:
+    h = np.ascontiguousarray(history, dtype=np.float64)
+    out = ctypes.c_double(0.0)
+    _check(lib().lora_place_extrapolate(_ptr(h) if h.size else ctypes.c_void_p(None), ctypes.c_int32(h.size),
+                                        ctypes.c_double(float(current)), ctypes.byref(out)))
+    return float(out.value)
+
+
+def lora_place_assign(n_servers: int, ranks, demand_tps, operating_points: dict, prev_phi=None) -> dict:
+    """operating_points: {rank: tokens/s}.  Returns phi [n_adapters][n_servers], server_util,
+    server_max_rank, budget {rank: servers} and target."""
+    ranks = _i32(ranks)
+    demand = np.ascontiguousarray(demand_tps, dtype=np.float64)
+    op_r = _i32(sorted(operating_points))
+    op_t = np.ascontiguousarray([operating_points[int(r)] for r in op_r], dtype=np.float64)
+    prev = None if prev_phi is None else np.ascontiguousarray(prev_phi, dtype=np.float64)
+    n = int(ranks.shape[0])
+    phi = np.zeros((n, n_servers), dtype=np.float64)
+    util = np.zeros(n_servers, dtype=np.float64)
+    maxr = np.zeros(n_servers, dtype=np.int32)
+    budget = np.zeros(op_r.shape[0], dtype=np.int32)
+    target = ctypes.c_double(0.0)
+    pr = _PlaceProblem(int(n_servers), n, ranks.ctypes.data, demand.ctypes.data, int(op_r.shape[0]), op_r.ctypes.data,
+                       op_t.ctypes.data, None if prev is None else prev.ctypes.data)
+    _check(lib().lora_place_assign(ctypes.byref(pr), _ptr(phi), _ptr(util), _ptr(maxr), _ptr(budget),
+                                   ctypes.byref(target)))
+    return {"phi": phi, "server_util": util, "server_max_rank": maxr,
+            "budget": {int(r): int(b) for r, b in zip(op_r, budget)}, "target": float(target.value)}

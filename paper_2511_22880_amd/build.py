@@ -9,8 +9,10 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblora_gfx950.so")
-SOURCES = [os.path.join(CSRC, "lora_host.cpp"), os.path.join(CSRC, "lora_kernels.hip")]
-HEADERS = [os.path.join(CSRC, "lora_internal.h"), os.path.join(ROOT, "include", "lora.h")]
+SOURCES = [os.path.join(CSRC, "lora_host.cpp"), os.path.join(CSRC, "lora_place.cpp"),
+           os.path.join(CSRC, "lora_kernels.hip")]
+HEADERS = [os.path.join(CSRC, "lora_internal.h"), os.path.join(ROOT, "include", "lora.h"),
+           os.path.join(ROOT, "include", "lora_placement.h")]
 
 
 def build(verbose: bool = False) -> str:

@@ -598,10 +598,14 @@ static __device__ __forceinline__ void dma16_to_lds(const uint4 *gptr, const uin
 {
     const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
         (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)lds_piece);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :
+    // M0 carries the LDS address of the piece; its old value is put back, so the register the
+    // compiler reserves for itself is unchanged after the statement
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
+                 "s_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
                  : "v"(gptr), "s"(lds_addr)
-                 : "memory", "m0");
+                 : "memory");
 }
 
 // Up to rank 64 the body needs at most 128 registers: four work groups per compute unit.

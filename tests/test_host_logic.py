@@ -27,7 +27,8 @@ def make_pool(in_f=512, out_f=256, ranks=(8, 16, 3, 128), resident=True):
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "lora.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include")))
+                     if h.endswith(".h"))
     declared = set(re.findall(r"\b(lora_[a-z_]+)\s*\(", header))
     assert declared == set(L.EXPORTS), declared ^ set(L.EXPORTS)
     lib = L.lib()
