@@ -616,3 +616,32 @@ def test_multi_projection_apply_decode_and_prefill():
     heavy.in_features = 1024
     assert heavy.T >= 1024
     _multi_case(heavy, (640, 128, 128), "zero")
+
+
+# ------------------------------------------------------------------------------------------------
+# Edges of the shape space and of the tiles.
+# ------------------------------------------------------------------------------------------------
+def _custom(name, in_f, out_f, ranks, ta, seed=0):
+    ranks = np.asarray(ranks, dtype=np.int32)
+    return wl.CoBatch(name, in_f, out_f, ranks, (2.0 / ranks).astype(np.float32), np.asarray(ta, dtype=np.int32),
+                      seed=seed, config=8)
+
+
+def test_smallest_shapes_and_single_tokens():
+    """in = 64 and out = 128 (the smallest the library takes), rank 1 and rank 256, one token."""
+    _full_parity(_custom("min_shape", 64, 128, [1, 256, 8], [1]))
+    _full_parity(_custom("min_shape", 64, 128, [1, 256, 8], [0, 1, 2, -1, 1, 0]), y0_kind="small")
+    _full_parity(_custom("one_token_wide", 4096, 4096, [128], [0]))
+    _full_parity(_custom("ragged_in", 64 * 37, 128 * 3, [5, 72, 136, 256], [3, 2, 1, 0] * 9))
+
+
+@pytest.mark.parametrize("ntok", [15, 16, 17, 31, 32, 33, 63, 64, 65, 129])
+def test_group_sizes_around_the_token_tiles(ntok):
+    """One group of exactly ntok tokens beside scattered others: the 16-token units of a small batch,
+    and (in a batch of 1024+ tokens) the 32-token shrink and 64-token expand units."""
+    ranks = [8, 24, 64, 128, 200]
+    small = [a for a in (0, 1, 2, 3, 4) for _ in range(3)] + [2] * ntok + [-1, 4, 0]
+    _full_parity(_custom(f"tiles_small_{ntok}", 576, 384, ranks, small, seed=ntok))
+    for big_rank in (1, 3):
+        heavy = [big_rank] * ntok + [0] * 700 + [4] * 40 + [2] * 300 + [-1] * 3 + [3, 1, 4]
+        _full_parity(_custom(f"tiles_heavy_{ntok}_{big_rank}", 320, 256, ranks, heavy, seed=ntok + 100 * big_rank))
