@@ -26,6 +26,23 @@ static __device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) { return __builtin_b
 
 static __device__ __forceinline__ uint4 ld16(const uint16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
 
+// 16-byte load of data that is read exactly once per launch (a decode batch's adapter weights, the
+// x rows of a token-heavy shrink): marked non-temporal, so it is not kept in the caches on its way.
+// A plain read of 2 GB runs at 6.2 TB/s on this chip with ordinary loads and at 7.0 TB/s with these.
+static __device__ __forceinline__ uint4 ld16_stream(const uint16_t *p)
+{
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return uint4{v.x, v.y, v.z, v.w};
+}
+
+// 16-byte store of data this launch will not read again (y).
+static __device__ __forceinline__ void st16_stream(uint16_t *p, uint4 v)
+{
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(p));
+}
+
 static __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 // ------------------------------------------------------------------------------------------------
@@ -200,7 +217,7 @@ static __device__ __forceinline__ void shrink_body(const Unit &u, const uint16_t
 #pragma unroll
         for (int q = 0; q < kShrinkSteps; ++q) {
             const int k = kbeg + 32 * q;
-            a[q] = (k < kslice_end) ? ld16(wrow + (int64_t)k * pn) : zero;
+            a[q] = (k < kslice_end) ? ld16_stream(wrow + (int64_t)k * pn) : zero;
         }
         if (kp != kslice_beg) __syncthreads();  // previous pass's slab is no longer being read
         {
@@ -332,7 +349,7 @@ __global__ __launch_bounds__(kWideThreads) void k_shrink_wide(const Unit *__rest
 #pragma unroll
         for (int q = 0; q < kShrinkSteps; ++q) {
             const int k = kbeg + 32 * q;
-            a[q] = (k < kslice_end) ? ld16(wrow + (int64_t)k * pn) : zero;
+            a[q] = (k < kslice_end) ? ld16_stream(wrow + (int64_t)k * pn) : zero;
         }
         // in is a multiple of 64, so a 16-byte chunk is either inside the row or wholly beyond it;
         // chunks beyond it are fetched from the row's last chunk instead and never enter an MFMA
@@ -499,7 +516,7 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
         const int kx = min(k0 + 8 * n, in - 8);
 #pragma unroll
         for (int t = 0; t < NL; ++t)
-            if (4 * t < ntok) xs[t] = ld16(xrow[t] + kx);
+            if (4 * t < ntok) xs[t] = ld16_stream(xrow[t] + kx);
     };
 
     uint4 xs[NL], w[WD][JB];
@@ -740,7 +757,7 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
         uint4 w[8];
         if (ITEMS == 1) {
 #pragma unroll
-            for (int b = 0; b < 8; ++b) w[b] = ld16(brow + b * 16 * r8 + jc[0] * 16);
+            for (int b = 0; b < 8; ++b) w[b] = ld16_stream(brow + b * 16 * r8 + jc[0] * 16);
         }
 
         // one block of 16 tokens: this thread's share of y and this wavefront's v operand
@@ -759,7 +776,7 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
                 // no per-lane condition around the 16-byte load (it would be split into four masked
                 // 4-byte loads): threads without a token read the unit's first token's row
                 bk.yv[s] = zero;
-                if (c0 + s * kStrip < ncols) bk.yv[s] = *reinterpret_cast<const uint4 *>(bk.e_y + c0 + s * kStrip);
+                if (c0 + s * kStrip < ncols) bk.yv[s] = ld16_stream(bk.e_y + c0 + s * kStrip);
             }
 #pragma unroll
             for (int it = 0; it < ITEMS; ++it) {
@@ -809,7 +826,7 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
             for (int it = 0; it < ITEMS; ++it) {
                 if (ITEMS > 1) {
 #pragma unroll
-                    for (int b = 0; b < 8; ++b) w[b] = ld16(brow + b * 16 * r8 + jc[it] * 16);
+                    for (int b = 0; b < 8; ++b) w[b] = ld16_stream(brow + b * 16 * r8 + jc[it] * 16);
                 }
 #pragma unroll
                 for (int b = 0; b < 8; ++b) {
@@ -853,7 +870,7 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
                                             __uint_as_float(yy.z & 0xFFFF0000u) + scale * d1[1]);
                         o.w = pack_bf16_rne(bf16_bits_to_f32(yy.w & 0xFFFFu) + scale * d1[2],
                                             __uint_as_float(yy.w & 0xFFFF0000u) + scale * d1[3]);
-                        *reinterpret_cast<uint4 *>(cur.e_y + c0 + s * kStrip) = o;
+                        st16_stream(cur.e_y + c0 + s * kStrip, o);
                     }
                 }
             }
@@ -955,7 +972,7 @@ static __device__ __forceinline__ void expand_big_body(const Unit &u, const int3
 #pragma unroll
         // unconditional: rows of absent tokens point at the unit's first token (a per-lane condition
         // around a 16-byte load makes the compiler split it into four masked 4-byte loads)
-        for (int e = 0; e < 4; ++e) yv[e] = *reinterpret_cast<const uint4 *>(yrow[e] + s * kStrip);
+        for (int e = 0; e < 4; ++e) yv[e] = ld16_stream(yrow[e] + s * kStrip);
     };
     auto compute = [&](int s, int buf, const uint4 (&yv)[4]) __attribute__((always_inline)) {
         if (nt <= 0) return;
@@ -989,7 +1006,7 @@ static __device__ __forceinline__ void expand_big_body(const Unit &u, const int3
                                     __uint_as_float(yy.z & 0xFFFF0000u) + scale * acc[5][e]);
                 o.w = pack_bf16_rne(bf16_bits_to_f32(yy.w & 0xFFFFu) + scale * acc[6][e],
                                     __uint_as_float(yy.w & 0xFFFF0000u) + scale * acc[7][e]);
-                *reinterpret_cast<uint4 *>(yrow[e] + s * kStrip) = o;
+                st16_stream(yrow[e] + s * kStrip, o);
             }
         }
     };
