@@ -211,7 +211,9 @@ lora_status_t lora_segments_export(const lora_segments_t *seg, int32_t *perm, in
  * k-slice (shrink) or 0}.  Groups of fewer than 32 tokens are cut into shrink units of <= 16 tokens x
  * 16 rank rows x one k-slice; token-heavy groups into shrink units of up to 32 tokens x all rank
  * rows x all of k (listed after the others, k-slice 0) and into expand units of up to 64 tokens.
- * Either output may be NULL. */
+ * The order is the launch order: the decode shrink units of one group take places of one residue
+ * mod 8 where the counts allow it (the launch's work groups go to the chip's 8 XCDs in turn, and the
+ * group's rows of x then stay in one XCD's L2).  Either output may be NULL. */
 lora_status_t lora_segments_export_units(const lora_segments_t *seg, int32_t *shrink_units,
                                          int32_t *expand_units);
 

@@ -463,6 +463,61 @@ extern "C" lora_status_t lora_set_whole_k_limit(int32_t max_units)
     return LORA_OK;
 }
 
+// Order of the decode shrink units in their launch.  The work groups of a launch go to the chip's
+// eight XCDs in turn (work group b to XCD b mod 8) and each XCD has an L2 of its own, so the units of
+// one group of tokens (one per 16 rank rows, k-slice and token tile, all reading the group's rows of
+// x) are given places of one residue mod 8: the rows of x then come from memory once per group instead
+// of once per XCD that holds one of its units.  Groups are dealt to the eight lists heaviest first,
+// each to the list with the fewest bytes that still has room (every list takes its share of the
+// units, so a launch of up to one work group per compute unit stays a single round; a group that does
+// not fit is cut); inside a list the heaviest units come first, and the lists are interleaved.
+static void order_units_by_xcd(std::vector<Unit> &units)
+{
+    const int X = 8;
+    const size_t n = units.size();
+    if (n < 2 * (size_t)X) return;
+    const size_t cap = (n + X - 1) / X;
+    auto weight = [](const Unit &u) { return (int64_t)(u.pn + u.ntok); };
+    // units of a group are adjacent in the list as planned
+    std::vector<std::pair<size_t, size_t>> groups;  // [first, last)
+    for (size_t i = 0; i < n;) {
+        size_t j = i + 1;
+        while (j < n && units[j].seg == units[i].seg) ++j;
+        groups.push_back({i, j});
+        i = j;
+    }
+    std::vector<int64_t> gw(groups.size(), 0);
+    for (size_t g = 0; g < groups.size(); ++g)
+        for (size_t i = groups[g].first; i < groups[g].second; ++i) gw[g] += weight(units[i]);
+    std::vector<size_t> gorder(groups.size());
+    for (size_t g = 0; g < gorder.size(); ++g) gorder[g] = g;
+    std::stable_sort(gorder.begin(), gorder.end(), [&](size_t a, size_t b) { return gw[a] > gw[b]; });
+    std::vector<std::vector<size_t>> list(X);
+    std::vector<int64_t> load(X, 0);
+    for (size_t g : gorder) {
+        size_t i = groups[g].first;
+        while (i < groups[g].second) {
+            int best = -1;
+            for (int q = 0; q < X; ++q)
+                if (list[q].size() < cap && (best < 0 || load[q] < load[best])) best = q;
+            while (i < groups[g].second && list[best].size() < cap) {
+                list[best].push_back(i);
+                load[best] += weight(units[i]);
+                ++i;
+            }
+        }
+    }
+    for (int q = 0; q < X; ++q)
+        std::stable_sort(list[q].begin(), list[q].end(),
+                         [&](size_t a, size_t b) { return weight(units[a]) > weight(units[b]); });
+    std::vector<Unit> out;
+    out.reserve(n);
+    for (size_t j = 0; j < cap; ++j)
+        for (int q = 0; q < X; ++q)
+            if (j < list[q].size()) out.push_back(units[list[q][j]]);
+    units.swap(out);
+}
+
 static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const int32_t *ta, int32_t T)
 {
     const int N = pool->n_adapters;
@@ -643,6 +698,8 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                 (etile > lora::kTokTile ? sg->expand_big_units : sg->expand_units).push_back(u);
             }
     }
+
+    order_units_by_xcd(sg->shrink_units);
 
     sg->off_perm = 0;
     sg->off_shrink = round_up_sz(sg->perm.size() * sizeof(int32_t), 256);

@@ -381,3 +381,27 @@ def test_empty_batches_plan():
         assert info["n_shrink_units"] == 0 and info["n_expand_units"] == 0
         L.lora_segments_destroy(seg)
     L.lora_pool_destroy(pool)
+
+
+def test_decode_shrink_units_of_a_group_share_an_xcd():
+    """Launch order of the decode shrink units: work group b runs on XCD b mod 8, so a group's units
+    (which all read the group's rows of x) are given places of one residue mod 8, the eight residues
+    get the same number of units (a one-round launch stays one round) and about the same bytes."""
+    b = wl.cfg1_decode()
+    n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
+    pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
+    for a in range(b.n_adapters):
+        L.lora_pool_mark_resident(pool, a)
+    seg = L.lora_segments_plan(pool, b.token_adapter)
+    su = L.lora_segments_export_units(seg)["shrink"]
+    res = np.arange(len(su)) % 8
+    counts = np.bincount(res, minlength=8)
+    assert counts.max() - counts.min() <= 1
+    groups = np.unique(su[:, 0])
+    together = sum(len(np.unique(res[su[:, 0] == g])) == 1 for g in groups)
+    assert together >= 0.85 * len(groups)
+    weight = (su[:, 2] + su[:, 4]).astype(np.int64)          # tokens + rank rows: bytes of x and A^T per k
+    per_xcd = np.array([weight[res == q].sum() for q in range(8)])
+    assert per_xcd.max() <= 1.15 * per_xcd.mean()
+    L.lora_segments_destroy(seg)
+    L.lora_pool_destroy(pool)
