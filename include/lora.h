@@ -293,6 +293,16 @@ lora_status_t lora_set_whole_k_limit(int32_t max_units);
  * that is replayed.  The setting is process-wide. */
 lora_status_t lora_set_fused_apply(int enabled);
 
+/* A mixed batch (token-heavy groups and at least 32 decode-sized shrink units) is four launches: the
+ * token-heavy groups' shrink and expand, the decode-sized groups' shrink and expand.  The two pairs
+ * touch different tokens (other rows of v and y), and the decode-sized pair is short and bound by
+ * latency, so by default lora_apply / lora_apply_multi issue it onto a stream that belongs to the
+ * segment object (created at the first such apply, default priority, non-blocking), between an event
+ * recorded on `stream` at the start of the apply and one that `stream` waits for at its end: the pairs
+ * run side by side and everything later on `stream` is ordered behind both.  y is bitwise the same
+ * either way.  lora_set_side_stream(0) keeps all four launches on `stream`.  Process-wide. */
+lora_status_t lora_set_side_stream(int enabled);
+
 /* Synchronises `stream` and reports LORA_ERR_DEVICE if an expand unit of an earlier fused lora_apply
  * on this object ran into its (bounded) wait limit, in which case that apply's y is not valid. */
 lora_status_t lora_segments_check(const lora_segments_t *seg, void *stream);
@@ -300,7 +310,8 @@ lora_status_t lora_segments_check(const lora_segments_t *seg, void *stream);
 /* Measurement hook.  The next lora_apply on the calling thread records the given hipEvent_t handles
  * (passed as void*, any may be NULL) on its stream: `before` ahead of the shrink launch, `between`
  * after it, `after` behind the expand launch (a fused apply records `between` and `after` together,
- * behind its single launch).  The hook clears itself after that call. */
+ * behind its single launch; in a mixed batch with the side stream on, `between` follows the token-heavy
+ * groups' shrink launch and `after` the join of both streams).  The hook clears itself after that call. */
 lora_status_t lora_profile_next_apply(void *before, void *between, void *after);
 
 const char *lora_status_string(lora_status_t status);

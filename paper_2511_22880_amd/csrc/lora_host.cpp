@@ -94,6 +94,10 @@ struct lora_segments {
     int n_sync;             // counters: one per (group, token tile), then the time-out flag
     unsigned launches;      // fused launches since the table was uploaded (the counters' epoch)
     hipEvent_t copied;  // recorded after the upload; guards re-use of `staging`
+    // mixed batches: the decode-sized groups' launches go to a stream of the object's own, between a
+    // fork and a join event, and run beside the token-heavy groups' launches on the caller's stream
+    hipStream_t side;
+    hipEvent_t fork, join;
     bool uploaded;
     // Several projections in one object (they read the same x and write column blocks of one y): the
     // unit lists of all of them, one after the other.  Unit offsets are relative to `mbase`, the lowest
@@ -721,6 +725,8 @@ static lora_segments *new_segments()
     sg->staging = nullptr;
     sg->staging_capacity = 0;
     sg->copied = nullptr;
+    sg->side = nullptr;
+    sg->fork = sg->join = nullptr;
     sg->uploaded = false;
     sg->n_sync = 0;
     sg->launches = 0;
@@ -736,6 +742,12 @@ extern "C" lora_status_t lora_segments_destroy(lora_segments_t *seg)
         (void)hipEventSynchronize(seg->copied);
         (void)hipEventDestroy(seg->copied);
     }
+    if (seg->side) {
+        (void)hipStreamSynchronize(seg->side);
+        (void)hipStreamDestroy(seg->side);
+    }
+    if (seg->fork) (void)hipEventDestroy(seg->fork);
+    if (seg->join) (void)hipEventDestroy(seg->join);
     if (seg->dev) {
         hipError_t e = hipFree(seg->dev);
         if (e != hipSuccess) st = hip_fail(e, "hipFree(segment table)");
@@ -1236,12 +1248,20 @@ extern "C" lora_status_t lora_expand(const lora_pool_t *pool, const lora_segment
 }
 
 static thread_local hipEvent_t g_prof[3] = {nullptr, nullptr, nullptr};
+static int g_side_stream = 1;
+static const int kSideStreamMinUnits = 32;  // decode shrink units below which a second stream is not worth its events
 static int g_fused_apply = 0;
 static const unsigned kSpinLimit = 1u << 18;  // polls of a waiting expand unit before it gives up
 
 extern "C" lora_status_t lora_set_fused_apply(int enabled)
 {
     g_fused_apply = enabled ? 1 : 0;
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_set_side_stream(int enabled)
+{
+    g_side_stream = enabled ? 1 : 0;
     return LORA_OK;
 }
 
@@ -1302,16 +1322,33 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
                                          (uint16_t *)y, ldy, &sa, s));
         if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
     } else {
+        // A mixed batch: the decode-sized groups' two launches are short, latency-bound and touch
+        // other tokens (rows of v and y) than the token-heavy groups' two, so they go to a stream of
+        // the segment object's own and run beside them; the caller's stream waits for them at the end.
+        hipStream_t sd = s;
+        const bool split = g_side_stream && sg->has_big_units && cs.n_units >= kSideStreamMinUnits;
+        if (split) {
+            if (!msg->side) HIP_TRY(hipStreamCreateWithFlags(&msg->side, hipStreamNonBlocking));
+            if (!msg->fork) HIP_TRY(hipEventCreateWithFlags(&msg->fork, hipEventDisableTiming));
+            if (!msg->join) HIP_TRY(hipEventCreateWithFlags(&msg->join, hipEventDisableTiming));
+            sd = msg->side;
+            HIP_TRY(hipEventRecord(msg->fork, s));
+            HIP_TRY(hipStreamWaitEvent(sd, msg->fork, 0));
+        }
         HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, sa.v_hi, sa.v_lo, nullptr,
                                             nsl, stride, s));
         if (sg->wide)
             HIP_TRY(lora::launch_shrink_wide(cs, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, nullptr,
-                                             sa.v_hi, sa.v_lo, s));
+                                             sa.v_hi, sa.v_lo, sd));
         else
-            HIP_TRY(lora::launch_shrink(cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride, &sa, s));
+            HIP_TRY(lora::launch_shrink(cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride, &sa, sd));
         if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
-        HIP_TRY(lora::launch_expand(ce, false, parts, nsl, stride, (uint16_t *)y, ldy, &sa, s));
+        HIP_TRY(lora::launch_expand(ce, false, parts, nsl, stride, (uint16_t *)y, ldy, &sa, sd));
         HIP_TRY(lora::launch_expand(cb, true, parts, nsl, stride, (uint16_t *)y, ldy, &sa, s));
+        if (split) {
+            HIP_TRY(hipEventRecord(msg->join, sd));
+            HIP_TRY(hipStreamWaitEvent(s, msg->join, 0));
+        }
     }
     if (ev[2]) HIP_TRY(hipEventRecord(ev[2], s));
     return LORA_OK;

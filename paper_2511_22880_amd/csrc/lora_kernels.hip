@@ -735,6 +735,12 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
     const int e_tok = tid >> 4;
     const int e_cg = tid & 15;
     const float scale = u.scale;
+    // The row of y this thread updates in the first block of tokens, fetched before anything else: a
+    // wavefront's loads return in request order, so requested behind the weights it would come back
+    // with the last of them, and the loads of y (which need it) would only start then, a second trip
+    // to memory on the unit's critical path.
+    const int64_t first_row = toks[e_tok < min(kTokTile, ntok_all) ? e_tok : 0];
+    __builtin_amdgcn_sched_barrier(0);
 
     int jc[ITEMS];
     bool j_ok[ITEMS];
@@ -758,6 +764,8 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
         if (ITEMS == 1) {
 #pragma unroll
             for (int b = 0; b < 8; ++b) w[b] = ld16_stream(brow + b * 16 * r8 + jc[0] * 16);
+            // nothing that needs the row index (a wait for its load) moves up in front of these requests
+            __builtin_amdgcn_sched_barrier(0);
         }
 
         // one block of 16 tokens: this thread's share of y and this wavefront's v operand
@@ -770,7 +778,8 @@ static __device__ __forceinline__ void expand_body(const Unit &u, const int32_t 
         auto load_blk = [&](int t0, Blk &bk) __attribute__((always_inline)) {
             bk.ntok = min(kTokTile, ntok_all - t0);
             const bool e_ok = e_tok < bk.ntok;
-            bk.e_y = y + (int64_t)toks[e_ok ? t0 + e_tok : 0] * ldy + u.p0 + 8 * e_cg;
+            const int64_t row = t0 == 0 ? first_row : (int64_t)toks[e_ok ? t0 + e_tok : 0];
+            bk.e_y = y + row * ldy + u.p0 + 8 * e_cg;
 #pragma unroll
             for (int s = 0; s < S; ++s) {
                 // no per-lane condition around the 16-byte load (it would be split into four masked

@@ -373,6 +373,38 @@ def test_cfg3_stack_full_size(layer, projection):
     _sampled_parity(wl.cfg3_stack(layer=layer, projection=projection), seed=layer)
 
 
+def test_mixed_batch_side_stream_matches_single_stream():
+    """A mixed batch issues its decode-sized launches onto the segment object's own stream, between a
+    fork and a join event.  Same bits as with all four launches on one stream, on a non-default
+    stream, apply after apply on one object (each reading the y the one before it wrote), with a
+    dependent operation queued right behind the last apply."""
+    b = wl.cfg3_stack(layer=3, projection=1)      # k_proj 4096 -> 1024: the quickest mixed batch
+    dp = G.DevicePool(b)
+    x = G.bits_to_dev(b.x_bits())
+    results = []
+    for side in (True, False):
+        L.lora_set_side_stream(side)
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                seg = L.lora_segments_build(dp.pool, b.token_adapter, stream=stream)
+                info = L.lora_segments_info(seg)
+                assert info["n_shrink_units"] > 32
+                ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+                y = G.bits_to_dev(b.y0_bits("small"))
+                for _ in range(6):
+                    L.lora_apply(dp.pool, seg, x, y, ws, stream=stream)
+                y_after = y.clone()           # ordered behind the join of the last apply
+            stream.synchronize()
+            L.lora_segments_check(seg, stream=stream)
+            L.lora_segments_destroy(seg)
+            results.append(G.dev_to_bits(y_after))
+        finally:
+            L.lora_set_side_stream(True)
+    assert np.array_equal(results[0], results[1])
+    dp.close()
+
+
 @pytest.mark.parametrize("shape,split", [(0, "9:1"), (0, "1:1"), (0, "1:9"), (1, "1:1"), (2, "1:1")])
 def test_cfg4_skew_full_size(shape, split):
     _sampled_parity(wl.cfg4_skew(shape, split), n_rows=64)
