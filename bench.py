@@ -184,6 +184,92 @@ def run_projections(args, torch, L, wl, dev, stream, hip) -> int:
     return 0
 
 
+def run_layer(args, torch, L, wl, dev, stream) -> int:
+    """All seven adapted projections of Llama-3-8B layers on one routing (cfg1's or cfg3's): per layer
+    q|k|v in one lora_apply_multi (they share x), o, gate|up in one lora_apply_multi, down.  Each
+    projection has its own x and y (no base model here, so nothing flows from one to the next).
+    Weights and x are device-random; `value` counts a token once per layer it has passed."""
+    b0, description, _, _ = pick_workload(args.workload, wl)
+    assert b0.in_features == 4096, "--projections layer uses the routing of cfg1 or cfg3:0"
+    groups = [(4096, (4096, 1024, 1024)), (4096, (4096,)), (4096, (14336, 14336)), (14336, (4096,))]
+    nl = args.layers or 8      # the routing is planned once per step, as in a model of 32 layers
+    T = b0.T
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    layers = []
+    for l in range(nl):
+        applies = []
+        for in_f, outs in groups:
+            sizes = [L.lora_pool_bytes(in_f, o, b0.ranks, b0.scales) for o in outs]
+            starts = np.concatenate([[0], np.cumsum([(n + 4095) // 4096 * 4096 for n in sizes])])
+            arena = torch.empty(int(starts[-1]), dtype=torch.uint8, device=dev)
+            arena.view(torch.bfloat16).normal_(0.0, 0.02, generator=g)
+            pools = []
+            for q, o in enumerate(outs):
+                pool = L.lora_pool_create(in_f, o, b0.ranks, b0.scales, arena[int(starts[q]): int(starts[q]) + sizes[q]])
+                for a in range(b0.n_adapters):
+                    L.lora_pool_mark_resident(pool, a)
+                pools.append(pool)
+            x = torch.empty(T, in_f, dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0, generator=g)
+            y = torch.zeros(T, sum(outs), dtype=torch.bfloat16, device=dev)
+            applies.append((arena, pools, x, y))
+        layers.append(applies)
+    # one segment object per apply of a layer; every layer's pools are spaced alike, so they serve all layers
+    segs, wss = [], []
+    for arena, pools, x, y in layers[0]:
+        seg = (L.lora_segments_build_multi(pools, b0.token_adapter, stream=stream) if len(pools) > 1
+               else L.lora_segments_build(pools[0], b0.token_adapter, stream=stream))
+        segs.append(seg)
+        wss.append(torch.empty(max(L.lora_apply_workspace_bytes(pools[0], seg), 256), dtype=torch.uint8, device=dev))
+
+    def step():
+        for seg in segs:
+            L.lora_segments_rebuild(seg, b0.token_adapter, stream=stream)
+        for applies in layers:
+            for (arena, pools, x, y), seg, ws in zip(applies, segs, wss):
+                if len(pools) > 1:
+                    L.lora_apply_multi(pools, seg, x, y, ws, stream=stream)
+                else:
+                    L.lora_apply(pools[0], seg, x, y, ws, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    for seg in segs:
+        L.lora_segments_check(seg, stream=stream)
+    act = b0.token_adapter >= 0
+    n_act = int(act.sum())
+    rsum = int(b0.ranks[b0.token_adapter[act]].astype(np.int64).sum())
+    r8 = (b0.ranks.astype(np.int64) + 7) // 8 * 8
+    wsum = int(r8[b0.used_adapters()].sum())
+    per_layer = 0
+    for in_f, outs in groups:
+        per_layer += 2 * n_act * in_f + sum(2 * wsum * (in_f + o) + 4 * n_act * o + 4 * rsum for o in outs)
+    us_per_layer = dt / args.steps / nl * 1e6
+    out = {
+        "metric": "LoRA-delta tokens/s + achieved HBM GB/s (decode) / MFMA util (prefill), mixed ranks",
+        "value": n_act * nl / (dt / args.steps), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{description}; all seven projections of {nl} Llama-3-8B layers per step "
+                               "(q|k|v and gate|up as lora_apply_multi, o and down as lora_apply)",
+                   "tokens": T, "active_tokens": n_act, "layers_per_step": nl, "us_per_layer": us_per_layer,
+                   "algorithmic_bytes_per_layer": per_layer,
+                   "tokens_per_s_through_32_layers": n_act / (32 * us_per_layer * 1e-6)},
+        "roofline": {"bound": "hbm", "kernel": "all launches of a layer", "achieved": per_layer / us_per_layer / 1e3,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": per_layer / us_per_layer / 1e3 / HBM_PEAK_GBS,
+                     "traffic": None},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -199,7 +285,8 @@ def main() -> int:
                     help="planning knob lora_set_whole_k_limit (default: the library's, 1024; 0 = always k-slices)")
     ap.add_argument("--projections", default=None,
                     help="several projections that share x in one pass, e.g. qkv or gateup (Llama-3-8B shapes), with "
-                         "the routing of --workload cfg1 or cfg3:0; add --separate to run them one lora_apply each")
+                         "the routing of --workload cfg1 or cfg3:0; add --separate to run them one lora_apply each; "
+                         "`layer`: all seven projections of a layer (q|k|v, o, gate|up, down)")
     ap.add_argument("--separate", action="store_true")
     ap.add_argument("--concurrent-loads", type=int, default=0,
                     help="adapters (ones the batch does not use) loaded into the step's pools on a second stream "
@@ -228,6 +315,8 @@ def main() -> int:
     if args.whole_k_limit is not None:
         L.lora_set_whole_k_limit(args.whole_k_limit)
 
+    if args.projections == "layer":
+        return run_layer(args, torch, L, wl, dev, stream)
     if args.projections:
         return run_projections(args, torch, L, wl, dev, stream, hip)
 
