@@ -25,6 +25,11 @@
  *     status; nothing throws, aborts or exits.  lora_last_error() gives a thread-local detail line
  *     for the last non-OK status returned on this thread.
  *   - in_features must be a multiple of 64 and out_features of 128; ranks are 1..LORA_MAX_RANK.
+ *   - Threads: the objects are not locked.  Calls that touch one pool, or a segment object and the
+ *     pools it was planned for, must come from one thread at a time; unrelated objects may be used
+ *     from different threads at once.  The lora_set_* knobs are process-wide and are meant to be
+ *     set before any planning.  A failed host allocation comes back as LORA_ERR_OOM like any other
+ *     status (no C++ exception leaves the library).
  */
 #ifndef LORA_GFX950_H
 #define LORA_GFX950_H

@@ -4,6 +4,7 @@
 #include "lora_internal.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -38,6 +39,12 @@ static lora_status_t hip_fail(hipError_t e, const char *what)
         hipError_t e_ = (call);                               \
         if (e_ != hipSuccess) return hip_fail(e_, #call);     \
     } while (0)
+
+// No exception crosses the C boundary: every entry point is a function-try-block that ends in this
+// (the containers of the host objects can throw std::bad_alloc).
+#define API_CATCH                                                                               \
+    catch (const std::bad_alloc &) { return fail(LORA_ERR_OOM, "host allocation failed"); }     \
+    catch (...) { return fail(LORA_ERR_INVALID_ARG, "unexpected C++ exception in the library"); }
 
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 static inline size_t round_up_sz(size_t v, size_t m) { return (v + m - 1) / m * m; }
@@ -112,7 +119,7 @@ struct lora_segments {
 };
 
 static const uint32_t kPoolMagic = 0x4C505231u, kSegMagic = 0x4C534731u;
-static uint64_t g_next_pool_id = 1;
+static std::atomic<uint64_t> g_next_pool_id{1};
 
 static bool pool_ok(const lora_pool *p) { return p && p->magic == kPoolMagic; }
 static bool seg_ok(const lora_segments *s) { return s && s->magic == kSegMagic; }
@@ -142,7 +149,7 @@ static size_t adapter_elems(const lora_pool_desc_t *d, int a)
 }
 
 extern "C" lora_status_t lora_pool_bytes(const lora_pool_desc_t *desc, size_t *arena_bytes)
-{
+try {
     lora_status_t st = check_desc(desc);
     if (st != LORA_OK) return st;
     if (!arena_bytes) return fail(LORA_ERR_INVALID_ARG, "arena_bytes is NULL");
@@ -151,6 +158,7 @@ extern "C" lora_status_t lora_pool_bytes(const lora_pool_desc_t *desc, size_t *a
     *arena_bytes = round_up_sz(elems * 2, 256);
     return LORA_OK;
 }
+API_CATCH
 
 static uint64_t block_elems(const lora_pool *p, int a)
 {
@@ -203,15 +211,17 @@ static lora_status_t create_pool(const lora_pool_desc_t *desc, void *dev_arena, 
 
 extern "C" lora_status_t lora_pool_create(const lora_pool_desc_t *desc, void *dev_arena, size_t arena_bytes,
                                           lora_pool_t **out)
-{
+try {
     return create_pool(desc, dev_arena, arena_bytes, false, out);
 }
+API_CATCH
 
 extern "C" lora_status_t lora_pool_create_live(const lora_pool_desc_t *desc, void *dev_arena, size_t arena_bytes,
                                                lora_pool_t **out)
-{
+try {
     return create_pool(desc, dev_arena, arena_bytes, true, out);
 }
+API_CATCH
 
 // ---- live pool: first-fit free list with coalescing -------------------------------------------------
 static void space_of(const lora_pool *p, uint64_t *free_elems, uint64_t *largest)
@@ -273,14 +283,15 @@ static lora_status_t check_adapter(const lora_pool *pool, int32_t adapter)
 }
 
 extern "C" lora_status_t lora_pool_reserve(lora_pool_t *pool, int32_t adapter)
-{
+try {
     lora_status_t st = check_adapter(pool, adapter);
     if (st != LORA_OK) return st;
     return pool->live ? live_place(pool, adapter) : LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_pool_space(const lora_pool_t *pool, size_t *free_bytes, size_t *largest_free_bytes)
-{
+try {
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     uint64_t fr, lg;
     space_of(pool, &fr, &lg);
@@ -288,6 +299,7 @@ extern "C" lora_status_t lora_pool_space(const lora_pool_t *pool, size_t *free_b
     if (largest_free_bytes) *largest_free_bytes = (size_t)(lg * 2);
     return LORA_OK;
 }
+API_CATCH
 
 // Slides the placed adapters of a live pool towards the start of the arena, in address order, with
 // device-to-device copies on `stream`.  A move whose source and destination overlap goes through
@@ -295,7 +307,7 @@ extern "C" lora_status_t lora_pool_space(const lora_pool_t *pool, size_t *free_b
 // lies wholly before its own source, and the stream runs the pieces in order).
 extern "C" lora_status_t lora_pool_compact(lora_pool_t *pool, void *dev_scratch, size_t scratch_bytes, void *stream,
                                            int32_t *n_moved)
-{
+try {
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (n_moved) *n_moved = 0;
     if (!pool->live) return LORA_OK;
@@ -334,9 +346,10 @@ extern "C" lora_status_t lora_pool_compact(lora_pool_t *pool, void *dev_scratch,
     if (n_moved) *n_moved = moved;
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_pool_adapter_info(const lora_pool_t *pool, int32_t adapter, lora_adapter_info_t *info)
-{
+try {
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (!info) return fail(LORA_ERR_INVALID_ARG, "info is NULL");
     if (adapter < 0 || adapter >= pool->n_adapters)
@@ -349,10 +362,11 @@ extern "C" lora_status_t lora_pool_adapter_info(const lora_pool_t *pool, int32_t
     info->resident = pool->resident[adapter];
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_pool_load(lora_pool_t *pool, int32_t adapter, const void *A, const void *B,
                                         int src_is_device, void *stream)
-{
+try {
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (adapter < 0 || adapter >= pool->n_adapters)
         return fail(LORA_ERR_INVALID_ARG, "adapter %d outside 0..%d", adapter, pool->n_adapters - 1);
@@ -390,9 +404,10 @@ extern "C" lora_status_t lora_pool_load(lora_pool_t *pool, int32_t adapter, cons
     pool->epoch[adapter] = pool->next_epoch++;
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_pool_evict(lora_pool_t *pool, int32_t adapter)
-{
+try {
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (adapter < 0 || adapter >= pool->n_adapters)
         return fail(LORA_ERR_INVALID_ARG, "adapter %d outside 0..%d", adapter, pool->n_adapters - 1);
@@ -401,9 +416,10 @@ extern "C" lora_status_t lora_pool_evict(lora_pool_t *pool, int32_t adapter)
     if (pool->live) live_release(pool, adapter);
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_pool_mark_resident(lora_pool_t *pool, int32_t adapter)
-{
+try {
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (adapter < 0 || adapter >= pool->n_adapters)
         return fail(LORA_ERR_INVALID_ARG, "adapter %d outside 0..%d", adapter, pool->n_adapters - 1);
@@ -413,15 +429,17 @@ extern "C" lora_status_t lora_pool_mark_resident(lora_pool_t *pool, int32_t adap
     pool->epoch[adapter] = pool->next_epoch++;
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_pool_destroy(lora_pool_t *pool)
-{
+try {
     if (!pool) return LORA_OK;
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "not a pool");
     pool->magic = 0;
     delete pool;
     return LORA_OK;
 }
+API_CATCH
 
 // ------------------------------------------------------------------------------------------------
 // planner
@@ -468,11 +486,12 @@ static int g_whole_k_limit = 1024;
 static const int kWholeKMin = 64;  // below this, k-slices are what spreads the batch over the chip
 
 extern "C" lora_status_t lora_set_whole_k_limit(int32_t max_units)
-{
+try {
     if (max_units < 0) return fail(LORA_ERR_INVALID_ARG, "max_units = %d", max_units);
     g_whole_k_limit = max_units;
     return LORA_OK;
 }
+API_CATCH
 
 // Order of the decode shrink units in their launch.  The work groups of a launch go to the chip's
 // eight XCDs in turn (work group b to XCD b mod 8) and each XCD has an L2 of its own, so the units of
@@ -749,7 +768,7 @@ static lora_segments *new_segments()
 }
 
 extern "C" lora_status_t lora_segments_destroy(lora_segments_t *seg)
-{
+try {
     if (!seg) return LORA_OK;
     if (!seg_ok(seg)) return fail(LORA_ERR_INVALID_ARG, "not a segment object");
     lora_status_t st = LORA_OK;
@@ -775,10 +794,11 @@ extern "C" lora_status_t lora_segments_destroy(lora_segments_t *seg)
     delete seg;
     return st;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_segments_plan(const lora_pool_t *pool, const int32_t *ta, int32_t T,
                                             lora_segments_t **out)
-{
+try {
     if (!out) return fail(LORA_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
@@ -794,6 +814,7 @@ extern "C" lora_status_t lora_segments_plan(const lora_pool_t *pool, const int32
     *out = sg;
     return LORA_OK;
 }
+API_CATCH
 
 static lora_status_t ranges_to_tokens(const lora_pool_t *pool, const int32_t *start, const int32_t *adapter,
                                       int32_t S, std::vector<int32_t> *ta)
@@ -812,7 +833,7 @@ static lora_status_t ranges_to_tokens(const lora_pool_t *pool, const int32_t *st
 
 extern "C" lora_status_t lora_segments_plan_ranges(const lora_pool_t *pool, const int32_t *start,
                                                    const int32_t *adapter, int32_t S, lora_segments_t **out)
-{
+try {
     if (!out) return fail(LORA_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
     std::vector<int32_t> ta;
@@ -820,6 +841,7 @@ extern "C" lora_status_t lora_segments_plan_ranges(const lora_pool_t *pool, cons
     if (st != LORA_OK) return st;
     return lora_segments_plan(pool, ta.data(), (int32_t)ta.size(), out);
 }
+API_CATCH
 
 // Plans every projection on its own, then strings the unit lists together.
 static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const lora_pool *> &pools,
@@ -918,7 +940,7 @@ static lora_status_t check_pool_list(const lora_pool_t *const *pools, int32_t n,
 
 extern "C" lora_status_t lora_segments_plan_multi(const lora_pool_t *const *pools, int32_t n_pools,
                                                   const int32_t *ta, int32_t T, lora_segments_t **out)
-{
+try {
     if (!out) return fail(LORA_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
     std::vector<const lora_pool *> list;
@@ -936,9 +958,10 @@ extern "C" lora_status_t lora_segments_plan_multi(const lora_pool_t *const *pool
     *out = sg;
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_segments_upload(lora_segments_t *sg, void *stream)
-{
+try {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     hipStream_t s = (hipStream_t)stream;
     if (!sg->copied) HIP_TRY(hipEventCreateWithFlags(&sg->copied, hipEventDisableTiming));
@@ -977,11 +1000,12 @@ extern "C" lora_status_t lora_segments_upload(lora_segments_t *sg, void *stream)
     sg->uploaded = true;
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_segments_build_multi(const lora_pool_t *const *pools, int32_t n_pools,
                                                    const int32_t *ta, int32_t T, void *stream,
                                                    lora_segments_t **out)
-{
+try {
     lora_status_t st = lora_segments_plan_multi(pools, n_pools, ta, T, out);
     if (st != LORA_OK) return st;
     st = lora_segments_upload(*out, stream);
@@ -991,10 +1015,11 @@ extern "C" lora_status_t lora_segments_build_multi(const lora_pool_t *const *poo
     }
     return st;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_segments_build(const lora_pool_t *pool, const int32_t *ta, int32_t T, void *stream,
                                              lora_segments_t **out)
-{
+try {
     lora_status_t st = lora_segments_plan(pool, ta, T, out);
     if (st != LORA_OK) return st;
     st = lora_segments_upload(*out, stream);
@@ -1004,11 +1029,12 @@ extern "C" lora_status_t lora_segments_build(const lora_pool_t *pool, const int3
     }
     return st;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_segments_build_ranges(const lora_pool_t *pool, const int32_t *start,
                                                     const int32_t *adapter, int32_t S, void *stream,
                                                     lora_segments_t **out)
-{
+try {
     lora_status_t st = lora_segments_plan_ranges(pool, start, adapter, S, out);
     if (st != LORA_OK) return st;
     st = lora_segments_upload(*out, stream);
@@ -1018,9 +1044,10 @@ extern "C" lora_status_t lora_segments_build_ranges(const lora_pool_t *pool, con
     }
     return st;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_segments_rebuild(lora_segments_t *sg, const int32_t *ta, int32_t T, void *stream)
-{
+try {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     if (!pool_ok(sg->pool) || sg->pool->id != sg->pool_id)
         return fail(LORA_ERR_STALE_SEGMENTS, "the pool this segment object was built for no longer exists");
@@ -1042,9 +1069,10 @@ extern "C" lora_status_t lora_segments_rebuild(lora_segments_t *sg, const int32_
     }
     return lora_segments_upload(sg, stream);
 }
+API_CATCH
 
 extern "C" lora_status_t lora_segments_info(const lora_segments_t *sg, lora_segments_info_t *info)
-{
+try {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     if (!info) return fail(LORA_ERR_INVALID_ARG, "info is NULL");
     info->n_tokens = sg->T;
@@ -1057,10 +1085,11 @@ extern "C" lora_status_t lora_segments_info(const lora_segments_t *sg, lora_segm
     info->weight_bytes = sg->weight_bytes;
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_segments_export(const lora_segments_t *sg, int32_t *perm, int32_t *seg_start,
                                               int32_t *seg_adapter, int64_t *v_offset)
-{
+try {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     if (perm && !sg->perm.empty()) memcpy(perm, sg->perm.data(), sg->perm.size() * sizeof(int32_t));
     if (seg_start) memcpy(seg_start, sg->seg_start.data(), sg->seg_start.size() * sizeof(int32_t));
@@ -1069,6 +1098,7 @@ extern "C" lora_status_t lora_segments_export(const lora_segments_t *sg, int32_t
     if (v_offset && !sg->v_offset.empty()) memcpy(v_offset, sg->v_offset.data(), sg->v_offset.size() * sizeof(int64_t));
     return LORA_OK;
 }
+API_CATCH
 
 static void export_units(const std::vector<Unit> &units, int32_t *dst)
 {
@@ -1081,7 +1111,7 @@ static void export_units(const std::vector<Unit> &units, int32_t *dst)
 
 extern "C" lora_status_t lora_segments_export_units(const lora_segments_t *sg, int32_t *shrink_units,
                                                     int32_t *expand_units)
-{
+try {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     if (shrink_units) {
         export_units(sg->shrink_units, shrink_units);
@@ -1093,6 +1123,7 @@ extern "C" lora_status_t lora_segments_export_units(const lora_segments_t *sg, i
     }
     return LORA_OK;
 }
+API_CATCH
 
 // ------------------------------------------------------------------------------------------------
 // hot path
@@ -1192,22 +1223,24 @@ static lora::LaunchCtx ctx_for(const lora_pool *pool, const lora_segments *sg, U
 }
 
 extern "C" lora_status_t lora_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *sg, size_t *bytes)
-{
+try {
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     if (!bytes) return fail(LORA_ERR_INVALID_ARG, "bytes is NULL");
     *bytes = partial_bytes(sg);
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_apply_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *sg, size_t *bytes)
-{
+try {
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     if (!bytes) return fail(LORA_ERR_INVALID_ARG, "bytes is NULL");
     *bytes = apply_parts_bytes(sg) + 2 * apply_packed_bytes(sg);
     return LORA_OK;
 }
+API_CATCH
 
 static lora_status_t check_workspace(const void *ws, size_t have, size_t need)
 {
@@ -1220,7 +1253,7 @@ static lora_status_t check_workspace(const void *ws, size_t have, size_t need)
 
 extern "C" lora_status_t lora_shrink(const lora_pool_t *pool, const lora_segments_t *sg, const void *x, int64_t ldx,
                                      float *v, void *workspace, size_t ws_bytes, void *stream)
-{
+try {
     lora_status_t st = check_launchable(pool, sg);
     if (st != LORA_OK) return st;
     if (sg->n_active == 0) return LORA_OK;
@@ -1246,10 +1279,11 @@ extern "C" lora_status_t lora_shrink(const lora_pool_t *pool, const lora_segment
     }
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_expand(const lora_pool_t *pool, const lora_segments_t *sg, const float *v, void *y,
                                      int64_t ldy, void *stream)
-{
+try {
     lora_status_t st = check_launchable(pool, sg);
     if (st != LORA_OK) return st;
     if (sg->n_active == 0) return LORA_OK;
@@ -1261,6 +1295,7 @@ extern "C" lora_status_t lora_expand(const lora_pool_t *pool, const lora_segment
                                 (hipStream_t)stream));
     return LORA_OK;
 }
+API_CATCH
 
 static thread_local hipEvent_t g_prof[3] = {nullptr, nullptr, nullptr};
 static int g_side_stream = 1;
@@ -1269,19 +1304,21 @@ static int g_fused_apply = 0;
 static const unsigned kSpinLimit = 1u << 18;  // polls of a waiting expand unit before it gives up
 
 extern "C" lora_status_t lora_set_fused_apply(int enabled)
-{
+try {
     g_fused_apply = enabled ? 1 : 0;
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_set_side_stream(int enabled)
-{
+try {
     g_side_stream = enabled ? 1 : 0;
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_segments_check(const lora_segments_t *sg, void *stream)
-{
+try {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     if (!sg->uploaded || !sg->dev) return LORA_OK;
     unsigned flag = 0;
@@ -1291,14 +1328,16 @@ extern "C" lora_status_t lora_segments_check(const lora_segments_t *sg, void *st
     if (flag) return fail(LORA_ERR_DEVICE, "an expand unit of a fused lora_apply gave up waiting for its shrink units");
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_profile_next_apply(void *before, void *between, void *after)
-{
+try {
     g_prof[0] = (hipEvent_t)before;
     g_prof[1] = (hipEvent_t)between;
     g_prof[2] = (hipEvent_t)after;
     return LORA_OK;
 }
+API_CATCH
 
 // The launches of one apply: `arena` is the base the units' weight offsets count from, `out` the
 // width of y that the units' columns lie in.
@@ -1371,18 +1410,19 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
 
 extern "C" lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *sg, const void *x, int64_t ldx,
                                     void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream)
-{
+try {
     lora_status_t st = check_launchable(pool, sg);
     if (st != LORA_OK) return st;
     if (sg->n_active == 0) return LORA_OK;
     return run_apply(pool->arena, pool->in_features, pool->out_features, sg, x, ldx, y, ldy, workspace, ws_bytes,
                      stream);
 }
+API_CATCH
 
 extern "C" lora_status_t lora_apply_multi(const lora_pool_t *const *pools, int32_t n_pools,
                                           const lora_segments_t *sg, const void *x, int64_t ldx, void *y,
                                           int64_t ldy, void *workspace, size_t ws_bytes, void *stream)
-{
+try {
     std::vector<const lora_pool *> list;
     lora_status_t st = check_pool_list(pools, n_pools, &list);
     if (st != LORA_OK) return st;
@@ -1404,6 +1444,7 @@ extern "C" lora_status_t lora_apply_multi(const lora_pool_t *const *pools, int32
     if (sg->n_active == 0) return LORA_OK;
     return run_apply(base, list[0]->in_features, sg->out_total, sg, x, ldx, y, ldy, workspace, ws_bytes, stream);
 }
+API_CATCH
 
 extern "C" const char *lora_status_string(lora_status_t status)
 {

@@ -6,7 +6,13 @@
 #include <cmath>
 #include <limits>
 #include <map>
+#include <new>
 #include <vector>
+
+// No exception crosses the C boundary: every entry point is a function-try-block that ends in this.
+#define API_CATCH                                        \
+    catch (const std::bad_alloc &) { return LORA_ERR_OOM; } \
+    catch (...) { return LORA_ERR_INVALID_ARG; }
 
 namespace {
 
@@ -66,16 +72,17 @@ std::vector<int> max_weight_assignment(const std::vector<std::vector<double>> &w
 }  // namespace
 
 extern "C" lora_status_t lora_place_extrapolate(const double *history, int32_t n, double current, double *demand)
-{
+try {
     if (!demand || n < 0 || (n > 0 && !history)) return LORA_ERR_INVALID_ARG;
     const double d = n == 0 ? current : current + (current - history[n - 1]);
     *demand = d > 0.0 ? d : 0.0;
     return LORA_OK;
 }
+API_CATCH
 
 extern "C" lora_status_t lora_place_assign(const lora_place_problem_t *pr, double *phi, double *server_util,
                                            int32_t *server_max_rank, int32_t *rank_budget, double *target_util)
-{
+try {
     if (!pr || pr->n_servers < 1 || pr->n_adapters < 0 || pr->n_ops < 0) return LORA_ERR_INVALID_ARG;
     const int S = pr->n_servers, N = pr->n_adapters;
     if (N > 0 && (!pr->ranks || !pr->demand_tps || !phi)) return LORA_ERR_INVALID_ARG;
@@ -200,3 +207,4 @@ extern "C" lora_status_t lora_place_assign(const lora_place_problem_t *pr, doubl
     if (target_util) *target_util = target;
     return LORA_OK;
 }
+API_CATCH
