@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <memory>
 #include <new>
 #include <vector>
 
@@ -796,6 +797,25 @@ try {
 }
 API_CATCH
 
+// Owns a segment object until it is handed to the caller, so that an early return or an exception
+// on the way does not leak it (or its device table).
+struct SegmentsGuard {
+    lora_segments *sg;
+    explicit SegmentsGuard(lora_segments *s) : sg(s) {}
+    ~SegmentsGuard()
+    {
+        if (sg) (void)lora_segments_destroy(sg);
+    }
+    lora_segments *release()
+    {
+        lora_segments *s = sg;
+        sg = nullptr;
+        return s;
+    }
+    SegmentsGuard(const SegmentsGuard &) = delete;
+    SegmentsGuard &operator=(const SegmentsGuard &) = delete;
+};
+
 extern "C" lora_status_t lora_segments_plan(const lora_pool_t *pool, const int32_t *ta, int32_t T,
                                             lora_segments_t **out)
 try {
@@ -804,14 +824,11 @@ try {
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (T < 0) return fail(LORA_ERR_INVALID_ARG, "T = %d", T);
     if (T > 0 && !ta) return fail(LORA_ERR_INVALID_ARG, "token_adapter_host is NULL");
-    lora_segments *sg = new_segments();
-    if (!sg) return fail(LORA_ERR_OOM, "host allocation failed");
-    lora_status_t st = plan_into(sg, pool, ta, T);
-    if (st != LORA_OK) {
-        lora_segments_destroy(sg);
-        return st;
-    }
-    *out = sg;
+    SegmentsGuard g(new_segments());
+    if (!g.sg) return fail(LORA_ERR_OOM, "host allocation failed");
+    lora_status_t st = plan_into(g.sg, pool, ta, T);
+    if (st != LORA_OK) return st;
+    *out = g.release();
     return LORA_OK;
 }
 API_CATCH
@@ -885,7 +902,8 @@ static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const 
     sg->mdelta.push_back(delta0);
     int col = p0->out_features;
     int64_t weight_bytes = sg->weight_bytes;
-    lora_segments *tmp = new (std::nothrow) lora_segments();
+    std::unique_ptr<lora_segments> tmp_owner(new (std::nothrow) lora_segments());  // host lists only
+    lora_segments *tmp = tmp_owner.get();
     if (!tmp) return fail(LORA_ERR_OOM, "host allocation failed");
     for (size_t q = 1; q < pools.size(); ++q) {
         st = plan_into(tmp, pools[q], ta, T, (int)pools.size());
@@ -911,7 +929,6 @@ static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const 
         col += pools[q]->out_features;
         weight_bytes += tmp->weight_bytes;
     }
-    delete tmp;
     if (st != LORA_OK) return st;
     sg->out_total = col;
     sg->v_floats = v_one * (int64_t)pools.size();
@@ -948,14 +965,11 @@ try {
     if (st != LORA_OK) return st;
     if (T < 0) return fail(LORA_ERR_INVALID_ARG, "T = %d", T);
     if (T > 0 && !ta) return fail(LORA_ERR_INVALID_ARG, "token_adapter_host is NULL");
-    lora_segments *sg = new_segments();
-    if (!sg) return fail(LORA_ERR_OOM, "host allocation failed");
-    st = plan_multi_into(sg, list, ta, T);
-    if (st != LORA_OK) {
-        lora_segments_destroy(sg);
-        return st;
-    }
-    *out = sg;
+    SegmentsGuard g(new_segments());
+    if (!g.sg) return fail(LORA_ERR_OOM, "host allocation failed");
+    st = plan_multi_into(g.sg, list, ta, T);
+    if (st != LORA_OK) return st;
+    *out = g.release();
     return LORA_OK;
 }
 API_CATCH
