@@ -473,13 +473,6 @@ static int expand_cols_per_unit(int r8, int out)
 // longer than a whole decode-sized launch lasts.
 static const int kPrefillMinTokens = 32;
 static const int kPrefillMinBatch = 1024;
-// A launch of at most this many token-heavy shrink units (two per compute unit of the chip, what the
-// any-rank kernel holds at once) leaves places empty and lasts as long as its longest unit, a rank-128
-// one: those units are then cut into two runs of 64 rank rows, which read the same rows of x and write
-// separate columns of v, and every unit fits the kernel that holds four per compute unit.  Measured on
-// the mixed batch of cfg3 (≈290 such units): q_proj 44 -> 38.5 us, down_proj 129 -> 107 us; on cfg2's
-// 718 units the cut loses 7-14 %, so fuller launches keep whole units.
-static const int kRowSplitMaxUnits = 512;
 // Between kWholeKMin and this many whole-k shrink units (four rounds of one work group per compute
 // unit of the chip) the decode shrink runs without k-slices; measured on the rank-skew batches, 442
 // and 544 such units beat their 4 x as many k-slice units by 8 %, 32 units lose 9 % to their 128.
@@ -549,8 +542,7 @@ static void order_units_by_xcd(std::vector<Unit> &units)
     units.swap(out);
 }
 
-static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const int32_t *ta, int32_t T,
-                               int n_projections = 1)
+static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const int32_t *ta, int32_t T)
 {
     const int N = pool->n_adapters;
     std::vector<int32_t> count(N, 0);
@@ -657,37 +649,30 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     sg->n_sync = n_sync;
     sg->has_big_units = false;
     sg->n_prefill_hi = 0;
-    int64_t heavy_units = 0;  // token-heavy shrink units of the launch if none is cut
-    for (const SegRec &r : sg->segs)
-        if (r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch)
-            heavy_units += (r.ntok + (r.r8 <= 128 ? 32 : 16) - 1) / (r.r8 <= 128 ? 32 : 16);
-    const bool row_split = heavy_units * n_projections <= kRowSplitMaxUnits;
     for (int32_t si : order) {
         const SegRec &r = sg->segs[si];
         const bool token_heavy = r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch;
         const int sync_n = ((r.r8 + lora::kRowTile - 1) / lora::kRowTile) * sg->n_k_slices;
         if (token_heavy) {
-            // shrink: tiles of 32 tokens (16 above rank 128), all rank rows (or runs of 64), all of k
+            // shrink: tiles of 32 tokens (16 above rank 128), all rank rows, all of k
             sg->has_big_units = true;
             const int tile = r.r8 <= 128 ? 32 : 16;
-            const int rows = (row_split && r.r8 > 64 && r.r8 <= 128) ? 64 : r.r8;
-            for (int tok0 = 0; tok0 < r.ntok; tok0 += tile)
-                for (int row0 = 0; row0 < r.r8; row0 += rows) {
-                    Unit u;
-                    memset(&u, 0, sizeof u);
-                    u.seg = si;
-                    u.tok0 = tok0;
-                    u.ntok = std::min(tile, r.ntok - tok0);
-                    u.p0 = row0;
-                    u.pn = std::min(rows, r.r8 - row0);
-                    u.r8 = r.r8;
-                    u.scale = r.scale;
-                    u.w_off = r.a_off + (uint64_t)row0 * pool->in_features;
-                    u.v_off = r.v_off + (int64_t)tok0 * r.r8 + row0;
-                    fill_tokens(u, r);
-                    sg->prefill_units.push_back(u);
-                    if (u.pn > 64) ++sg->n_prefill_hi;
-                }
+            for (int tok0 = 0; tok0 < r.ntok; tok0 += tile) {
+                Unit u;
+                memset(&u, 0, sizeof u);
+                u.seg = si;
+                u.tok0 = tok0;
+                u.ntok = std::min(tile, r.ntok - tok0);
+                u.p0 = 0;
+                u.pn = r.r8;
+                u.r8 = r.r8;
+                u.scale = r.scale;
+                u.w_off = r.a_off;
+                u.v_off = r.v_off + (int64_t)tok0 * r.r8;
+                fill_tokens(u, r);
+                sg->prefill_units.push_back(u);
+                if (r.r8 > 64) ++sg->n_prefill_hi;
+            }
         } else {
             for (int row0 = 0; row0 < r.r8; row0 += lora::kRowTile)
                 for (int ks = 0; ks < sg->n_k_slices; ++ks)
@@ -872,7 +857,7 @@ static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const 
         if (((uintptr_t)q->arena - (uintptr_t)p0->arena) % 2) return fail(LORA_ERR_INVALID_ARG, "arena alignment");
         base = std::min(base, (const uint16_t *)q->arena);
     }
-    lora_status_t st = plan_into(sg, p0, ta, T, (int)pools.size());
+    lora_status_t st = plan_into(sg, p0, ta, T);
     if (st != LORA_OK) return st;
     sg->mpools = pools;
     sg->mpool_ids.clear();
@@ -906,7 +891,7 @@ static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const 
     lora_segments *tmp = tmp_owner.get();
     if (!tmp) return fail(LORA_ERR_OOM, "host allocation failed");
     for (size_t q = 1; q < pools.size(); ++q) {
-        st = plan_into(tmp, pools[q], ta, T, (int)pools.size());
+        st = plan_into(tmp, pools[q], ta, T);
         if (st != LORA_OK) break;
         const uint64_t delta = (uint64_t)(((uintptr_t)pools[q]->arena - (uintptr_t)base) / 2);
         const size_t n0 = sg->shrink_units.size(), n1 = sg->prefill_units.size(), n2 = sg->expand_units.size(),

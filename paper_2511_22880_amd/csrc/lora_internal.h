@@ -31,8 +31,7 @@ struct Unit {
     int32_t r8;       // padded rank = row length of v and of B^T
     int32_t ntok;     // tokens in this unit: 1..16 (decode units), up to 64 (expand) or 32 (prefill shrink)
     int32_t p0;       // shrink: first rank row; expand: first output column
-    int32_t pn;       // shrink: valid rank rows (1..16, multiple of 8 except the tail; token-heavy units:
-                      // all r8 rows or a run of 64); expand: columns
+    int32_t pn;       // shrink: valid rank rows (1..16, multiple of 8 except the tail); expand: columns
     int32_t ks;       // shrink: k-slice index
     float scale;
     int32_t seg;
@@ -90,8 +89,8 @@ hipError_t launch_shrink_wide(const LaunchCtx &c, const uint16_t *x, int64_t ldx
 hipError_t launch_expand(const LaunchCtx &c, bool big, const float *v_in, int n_slices, int64_t slice_stride,
                          uint16_t *y, int64_t ldy, const SyncArgs *sync, hipStream_t stream);
 
-// Shrink of token-heavy groups: one unit = (group, up to 32 tokens, rank rows p0 .. p0+pn-1 (all of them,
-// or a run of 64), the whole of k).  n_hi = how many of the units hold more than 64 rank rows: with none, the launch takes the kernel that fits four
+// Shrink of token-heavy groups: one unit = (group, up to 32 tokens, all rank rows, the whole of k).
+// n_hi = how many of the units are above rank 64: with none, the launch takes the kernel that fits four
 // work groups on a compute unit, otherwise the one for any rank (two per compute unit).
 // Writes complete v: as bf16 hi + lo into v_hi / v_lo, or (v_f32 != NULL) as fp32 into v_f32 with the
 // other n_slices - 1 slices of the same rows set to zero.

@@ -417,7 +417,7 @@ __global__ __launch_bounds__(kWideThreads) void k_shrink_wide(const Unit *__rest
 
 // ------------------------------------------------------------------------------------------------
 // shrink of token-heavy groups (prefill): one unit = (group, 32 tokens (16 above rank 128), all rank
-// rows or a run of 64 of them, all of k).  The four wavefronts split k into quarters; each streams its quarter of the
+// rows, all of k).  The four wavefronts split k into quarters; each streams its quarter of the
 // tokens' x rows exactly once.  x comes from HBM with coalesced loads (a wavefront load covers 256
 // bytes of each of 4 tokens), one pass of 128 k ahead, and is turned into MFMA operand order through
 // an LDS region private to the wavefront, so no work-group barrier sits in the k loop.  (Loading the
@@ -473,7 +473,7 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
     f32x4(*red)[NT][64] = reinterpret_cast<f32x4(*)[NT][64]>(lds);  // re-uses the x regions after the k loop
     const int n = lane & 15;
     const int kq = lane >> 4;
-    const int r8 = u.pn;  // rank rows of this unit (all of the group's, or a run of 64 of them)
+    const int r8 = u.r8;
     const int ntok = u.ntok;
 
     // staging: load t of a pass takes tokens 4t .. 4t+3, this lane token 4t + kq, 16-byte chunk n
@@ -594,7 +594,7 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
         if (16 * tb + n >= ntok) continue;
-        const int64_t row = u.v_off + (int64_t)(16 * tb + n) * u.r8;
+        const int64_t row = u.v_off + (int64_t)(16 * tb + n) * r8;
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) {
             const int j = 16 * jb + 4 * kq;
@@ -637,7 +637,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_shrink_prefill(const Unit *__re
 {
     __shared__ __attribute__((aligned(16))) char lds[kPrefillLds];
     const Unit &u = units[blockIdx.x];
-    const int r8 = u.pn;
+    const int r8 = u.r8;
     if (r8 <= 16)
         shrink_prefill_ksplit<1, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
     else if (r8 <= 32)
@@ -661,7 +661,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_shrink_prefill_any(const Unit *
 {
     __shared__ __attribute__((aligned(16))) char lds[kPrefillLds];
     const Unit &u = units[blockIdx.x];
-    const int r8 = u.pn;
+    const int r8 = u.r8;
     if (r8 <= 16)
         shrink_prefill_ksplit<1, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
     else if (r8 <= 32)

@@ -196,9 +196,9 @@ def test_planner_matches_brute_force_grouping(maker):
         cover = np.zeros((ntok, rr, nsl), dtype=np.int32)
         token_heavy = ntok >= 32 and info["n_active"] >= 1024
         for seg_i, tok0, nt, p0, pn, ks in units["shrink"][units["shrink"][:, 0] == s]:
-            if token_heavy:       # token tiles: all rank rows or a run of 64 of them, all of k
-                assert 1 <= nt <= 32 and ks == 0 and ((p0, pn) == (0, rr) or (p0 % 64 == 0 and pn == min(64, rr - p0)))
-                cover[tok0:tok0 + nt, p0:p0 + pn, :] += 1
+            if token_heavy:       # token tiles: all rank rows, all of k
+                assert 1 <= nt <= 32 and (p0, pn, ks) == (0, rr, 0)
+                cover[tok0:tok0 + nt, :, :] += 1
             else:
                 assert 1 <= nt <= 16 and 1 <= pn <= 16
                 cover[tok0:tok0 + nt, p0:p0 + pn, ks] += 1
@@ -217,31 +217,6 @@ def test_planner_matches_brute_force_grouping(maker):
     assert ub[~heavy].max(initial=0) <= 64 * 1024 and ub[heavy].max(initial=0) <= 256 * 1024
     L.lora_segments_destroy(seg)
     L.lora_pool_destroy(pool)
-
-
-def test_token_heavy_units_are_cut_by_rank_rows_only_in_underfilled_launches():
-    """Up to 512 token-heavy shrink units (two per compute unit) the rank-72..128 groups' units are cut
-    into runs of 64 rank rows, so no unit holds more than 64; fuller launches keep whole units."""
-    for b, cut in ((wl.cfg3_stack(), True), (wl.cfg2_prefill(0), False)):
-        n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
-        pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
-        for a in range(b.n_adapters):
-            L.lora_pool_mark_resident(pool, a)
-        seg = L.lora_segments_plan(pool, b.token_adapter)
-        ex, units = L.lora_segments_export(seg), L.lora_segments_export_units(seg)
-        sh = units["shrink"]
-        ntok_of = np.diff(ex["seg_start"])[sh[:, 0]]
-        heavy = sh[ntok_of >= 32]
-        r8 = ((b.ranks + 7) // 8 * 8)[ex["seg_adapter"][heavy[:, 0]]]
-        assert (r8 > 64).any()
-        whole = len(set(map(tuple, heavy[:, :3])))      # (group, first token, tokens): units if none is cut
-        assert (whole <= 512) == cut
-        if cut:
-            assert heavy[:, 4].max() <= 64 and len(heavy) > whole
-        else:
-            assert np.array_equal(heavy[:, 4], r8) and len(heavy) == whole
-        L.lora_segments_destroy(seg)
-        L.lora_pool_destroy(pool)
 
 
 def test_whole_k_limit_switches_the_shrink_plan():
