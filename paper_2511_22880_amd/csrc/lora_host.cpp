@@ -1382,8 +1382,12 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
         const bool split = g_side_stream && sg->has_big_units && cs.n_units >= kSideStreamMinUnits;
         if (split) {
             if (!msg->side) HIP_TRY(hipStreamCreateWithFlags(&msg->side, hipStreamNonBlocking));
-            if (!msg->fork) HIP_TRY(hipEventCreateWithFlags(&msg->fork, hipEventDisableTiming));
-            if (!msg->join) HIP_TRY(hipEventCreateWithFlags(&msg->join, hipEventDisableTiming));
+            // the two events order launches of this device among themselves and nothing reads them on
+            // the host: created without the system-scope fence an event otherwise carries (whole layer
+            // of the mixed batch 865 -> 803 us)
+            const unsigned ev_flags = hipEventDisableTiming | hipEventDisableSystemFence;
+            if (!msg->fork) HIP_TRY(hipEventCreateWithFlags(&msg->fork, ev_flags));
+            if (!msg->join) HIP_TRY(hipEventCreateWithFlags(&msg->join, ev_flags));
             sd = msg->side;
             HIP_TRY(hipEventRecord(msg->fork, s));
             HIP_TRY(hipStreamWaitEvent(sd, msg->fork, 0));
