@@ -298,14 +298,23 @@ lora_status_t lora_set_whole_k_limit(int32_t max_units);
  * that is replayed.  The setting is process-wide. */
 lora_status_t lora_set_fused_apply(int enabled);
 
-/* A mixed batch (token-heavy groups and at least 32 decode-sized shrink units) is four launches: the
- * token-heavy groups' shrink and expand, the decode-sized groups' shrink and expand.  The two pairs
- * touch different tokens (other rows of v and y), and the decode-sized pair is short and bound by
- * latency, so by default lora_apply / lora_apply_multi issue it onto a stream that belongs to the
- * segment object (created at the first such apply, default priority, non-blocking), between an event
- * recorded on `stream` at the start of the apply and one that `stream` waits for at its end: the pairs
- * run side by side and everything later on `stream` is ordered behind both.  y is bitwise the same
- * either way.  lora_set_side_stream(0) keeps all four launches on `stream`.  Process-wide. */
+/* A mixed batch holds token-heavy groups and decode-sized groups, whose units are of different kinds.
+ * By default (lora_set_merged_launches(1)) such a batch is planned with the decode-sized groups in
+ * k-slices, whose work groups have the size of the token-heavy ones', and lora_apply /
+ * lora_apply_multi run it as two launches on `stream`: one shrink launch and one expand launch that
+ * each hold both kinds of unit, the token-heavy ones first.  The setting is read when a batch is
+ * planned (build / rebuild) and when it is applied; change it only between a plan and nothing.
+ * Process-wide.
+ *
+ * With lora_set_merged_launches(0) a mixed batch is four launches: the token-heavy groups' shrink
+ * and expand, the decode-sized groups' shrink and expand.  The two pairs touch different tokens
+ * (other rows of v and y), and the decode-sized pair is short and bound by latency, so with
+ * lora_set_side_stream(1) (the default) it is issued onto a stream that belongs to the segment object
+ * (created at the first such apply, default priority, non-blocking), between an event recorded on
+ * `stream` at the start of the apply and one that `stream` waits for at its end: the pairs run side
+ * by side and everything later on `stream` is ordered behind both.  lora_set_side_stream(0) keeps all
+ * four launches on `stream`.  y is bitwise the same in all three forms.  Process-wide. */
+lora_status_t lora_set_merged_launches(int enabled);
 lora_status_t lora_set_side_stream(int enabled);
 
 /* Synchronises `stream` and reports LORA_ERR_DEVICE if an expand unit of an earlier fused lora_apply

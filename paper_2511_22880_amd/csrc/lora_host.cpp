@@ -477,6 +477,10 @@ static const int kPrefillMinBatch = 1024;
 // unit of the chip) the decode shrink runs without k-slices; measured on the rank-skew batches, 442
 // and 544 such units beat their 4 x as many k-slice units by 8 %, 32 units lose 9 % to their 128.
 static int g_whole_k_limit = 1024;
+// Mixed batches (token-heavy groups beside decode-sized ones) in two launches that hold both kinds of
+// unit: the decode-sized groups are then planned in k-slices, whose work groups have the size of the
+// token-heavy ones'.
+static int g_merged_mixed = 1;
 static const int kWholeKMin = 64;  // below this, k-slices are what spreads the batch over the chip
 
 extern "C" lora_status_t lora_set_whole_k_limit(int32_t max_units)
@@ -571,7 +575,9 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
         whole_k_units += (int64_t)((pool->r8[a] + lora::kRowTile - 1) / lora::kRowTile) *
                          ((count[a] + lora::kTokTile - 1) / lora::kTokTile);
     }
-    sg->wide = whole_k_units >= kWholeKMin && whole_k_units <= g_whole_k_limit;
+    bool heavy_groups = false;
+    for (int a = 0; a < N; ++a) heavy_groups |= count[a] >= kPrefillMinTokens && n_active >= kPrefillMinBatch;
+    sg->wide = whole_k_units >= kWholeKMin && whole_k_units <= g_whole_k_limit && !(g_merged_mixed && heavy_groups);
     choose_k_slices(pool->in_features, &sg->wide_slices, &sg->wide_slice_len);
     if (sg->wide) {
         sg->n_k_slices = 1;
@@ -1309,6 +1315,13 @@ try {
 }
 API_CATCH
 
+extern "C" lora_status_t lora_set_merged_launches(int enabled)
+try {
+    g_merged_mixed = enabled ? 1 : 0;
+    return LORA_OK;
+}
+API_CATCH
+
 extern "C" lora_status_t lora_set_side_stream(int enabled)
 try {
     g_side_stream = enabled ? 1 : 0;
@@ -1378,6 +1391,14 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
         // A mixed batch: the decode-sized groups' two launches are short, latency-bound and touch
         // other tokens (rows of v and y) than the token-heavy groups' two, so they go to a stream of
         // the segment object's own and run beside them; the caller's stream waits for them at the end.
+        if (g_merged_mixed && sg->has_big_units && !sg->wide && cs.n_units > 0) {
+            HIP_TRY(lora::launch_shrink_mixed(cp, sg->n_prefill_hi, cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts,
+                                              nsl, stride, &sa, s));
+            if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
+            HIP_TRY(lora::launch_expand_mixed(cb, ce, parts, nsl, stride, (uint16_t *)y, ldy, &sa, s));
+            if (ev[2]) HIP_TRY(hipEventRecord(ev[2], s));
+            return LORA_OK;
+        }
         hipStream_t sd = s;
         const bool split = g_side_stream && sg->has_big_units && cs.n_units >= kSideStreamMinUnits;
         if (split) {

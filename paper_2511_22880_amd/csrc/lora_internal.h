@@ -98,6 +98,17 @@ hipError_t launch_shrink_prefill(const LaunchCtx &c, int n_hi, const uint16_t *x
                                  uint16_t *v_lo, float *v_f32, int n_slices, int64_t slice_stride,
                                  hipStream_t stream);
 
+// A mixed batch's shrink in one launch: the token-heavy units of `heavy` (n_hi of them above rank 64),
+// then the k-slice units of `c`, which leave partial sums in `parts` and complete v through `sync` as
+// launch_shrink does.  Likewise the expand: the 64-token units of `big`, then the units of `c`; both
+// read v from sync->v_hi / v_lo.
+hipError_t launch_shrink_mixed(const LaunchCtx &heavy, int n_hi, const LaunchCtx &c, const uint16_t *x, int64_t ldx,
+                               int k_slice_len, float *parts, int n_slices, int64_t slice_stride,
+                               const SyncArgs *sync, hipStream_t stream);
+hipError_t launch_expand_mixed(const LaunchCtx &big, const LaunchCtx &c, const float *parts, int n_slices,
+                               int64_t slice_stride, uint16_t *y, int64_t ldy, const SyncArgs *sync,
+                               hipStream_t stream);
+
 // Both halves in one launch (shrink units first); the expand units poll `ready` of their token tile,
 // at most spin_limit times each.
 hipError_t launch_apply_fused(const LaunchCtx &shrink, const LaunchCtx &expand, const uint16_t *x, int64_t ldx,

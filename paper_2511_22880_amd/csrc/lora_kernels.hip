@@ -625,7 +625,33 @@ static __device__ __forceinline__ void dma16_to_lds(const uint4 *gptr, const uin
                  : "memory");
 }
 
-// Up to rank 64 the body needs at most 128 registers: four work groups per compute unit.
+// Picks the body by the unit's rank rows.  ANY = false: the launch holds no unit above rank 64 and the
+// bodies fit 128 registers (four work groups per compute unit).  ANY = true: any rank; above rank 64
+// the accumulator tiles alone take 64 registers (two work groups per compute unit), units above rank
+// 128 hold 16 tokens.
+template <bool ANY>
+static __device__ __forceinline__ void prefill_dispatch(const Unit &u, const int32_t *__restrict__ perm,
+                                                        const uint16_t *__restrict__ arena,
+                                                        const uint16_t *__restrict__ x, int64_t ldx, int in,
+                                                        uint16_t *__restrict__ v_hi, uint16_t *__restrict__ v_lo,
+                                                        float *__restrict__ v_f32, int n_slices,
+                                                        int64_t slice_stride, char *lds)
+{
+    const int r8 = u.r8;
+    if (r8 <= 16)
+        shrink_prefill_ksplit<1, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    else if (r8 <= 32)
+        shrink_prefill_ksplit<2, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    else if (!ANY)  // the launcher takes this form only for batches whose token-heavy units are all up to rank 64
+        shrink_prefill_ksplit<4, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    else if (r8 <= 64)
+        shrink_prefill_ksplit<4, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    else if (r8 <= 128)
+        shrink_prefill_ksplit<8, 2, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    else
+        shrink_prefill_ksplit<16, 1, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+}
+
 __global__ __launch_bounds__(kThreads, 4) void k_shrink_prefill(const Unit *__restrict__ units,
                                                                 const int32_t *__restrict__ perm,
                                                                 const uint16_t *__restrict__ arena,
@@ -636,20 +662,13 @@ __global__ __launch_bounds__(kThreads, 4) void k_shrink_prefill(const Unit *__re
                                                                 int64_t slice_stride)
 {
     __shared__ __attribute__((aligned(16))) char lds[kPrefillLds];
-    const Unit &u = units[blockIdx.x];
-    const int r8 = u.r8;
-    if (r8 <= 16)
-        shrink_prefill_ksplit<1, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
-    else if (r8 <= 32)
-        shrink_prefill_ksplit<2, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
-    else  // the launcher starts this kernel only for batches whose token-heavy units are all up to rank 64
-        shrink_prefill_ksplit<4, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    prefill_dispatch<false>(units[blockIdx.x], perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride,
+                            lds);
 }
 
-// Any rank.  Above rank 64 the accumulator tiles alone take 64 registers: two work groups per compute
-// unit.  Units above rank 128 hold 16 tokens.  A batch that has such units runs all its token-heavy
-// units here, in one launch: two launches one after the other (high ranks here, the rest above)
-// measured slower, the first one leaving most of the chip idle.
+// A batch that has units above rank 64 runs all its token-heavy units here, in one launch: two
+// launches one after the other (high ranks here, the rest above) measured slower, the first one
+// leaving most of the chip idle.
 __global__ __launch_bounds__(kThreads, 2) void k_shrink_prefill_any(const Unit *__restrict__ units,
                                                                     const int32_t *__restrict__ perm,
                                                                     const uint16_t *__restrict__ arena,
@@ -660,18 +679,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_shrink_prefill_any(const Unit *
                                                                     int64_t slice_stride)
 {
     __shared__ __attribute__((aligned(16))) char lds[kPrefillLds];
-    const Unit &u = units[blockIdx.x];
-    const int r8 = u.r8;
-    if (r8 <= 16)
-        shrink_prefill_ksplit<1, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
-    else if (r8 <= 32)
-        shrink_prefill_ksplit<2, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
-    else if (r8 <= 64)
-        shrink_prefill_ksplit<4, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
-    else if (r8 <= 128)
-        shrink_prefill_ksplit<8, 2, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
-    else
-        shrink_prefill_ksplit<16, 1, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+    prefill_dispatch<true>(units[blockIdx.x], perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride,
+                           lds);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1128,6 +1137,45 @@ __global__ __launch_bounds__(kThreads, 4) void k_apply_fused(const Unit *__restr
                                       lds, sy);
 }
 
+// A mixed batch in two launches on one queue: the token-heavy groups' units first in the grid (they
+// last longest), the decode-sized groups' k-slice units behind them, which fill the places the long
+// units leave.  Every unit does what it does in a launch of its own kind: the token-heavy shrink
+// units write v complete as bf16 hi + lo, the k-slice units leave partial sums and the one that
+// completes a token tile writes its hi + lo; both kinds of expand unit read v from there.
+constexpr int kMixedShrinkLds = kPrefillLds > kShrinkLds ? kPrefillLds : kShrinkLds;
+constexpr int kMixedExpandLds = kBigLds > kExpandLds ? kBigLds : kExpandLds;
+
+template <bool ANY>
+__global__ __launch_bounds__(kThreads, ANY ? 2 : 4) void k_shrink_mixed(
+    const Unit *__restrict__ heavy_units, int n_heavy, const Unit *__restrict__ units,
+    const int32_t *__restrict__ perm, const uint16_t *__restrict__ arena, const uint16_t *__restrict__ x, int64_t ldx,
+    int in, int k_slice_len, float *__restrict__ parts, int n_slices, int64_t slice_stride, Sync sy)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kMixedShrinkLds];
+    const int b = blockIdx.x;
+    if (b < n_heavy)
+        prefill_dispatch<ANY>(heavy_units[b], perm, arena, x, ldx, in, sy.v_hi, sy.v_lo, nullptr, n_slices,
+                              slice_stride, lds);
+    else
+        shrink_body(units[b - n_heavy], arena, x, ldx, in, k_slice_len, parts, n_slices, slice_stride, lds, sy);
+}
+
+__global__ __launch_bounds__(kThreads, 2) void k_expand_mixed(const Unit *__restrict__ big_units, int n_big,
+                                                              const Unit *__restrict__ units,
+                                                              const int32_t *__restrict__ perm,
+                                                              const uint16_t *__restrict__ arena,
+                                                              const float *__restrict__ parts, int n_slices,
+                                                              int64_t slice_stride, uint16_t *__restrict__ y,
+                                                              int64_t ldy, Sync sy)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kMixedExpandLds];
+    const int b = blockIdx.x;
+    if (b < n_big)
+        expand_dispatch<true, false>(big_units[b], perm, arena, parts, n_slices, slice_stride, y, ldy, lds, sy);
+    else
+        expand_dispatch<false, false>(units[b - n_big], perm, arena, parts, n_slices, slice_stride, y, ldy, lds, sy);
+}
+
 __global__ __launch_bounds__(256) void k_reduce_slices(const float *__restrict__ parts, int n_slices,
                                                        int64_t slice_stride, float *__restrict__ v, int64_t n)
 {
@@ -1254,6 +1302,37 @@ hipError_t launch_shrink_prefill(const LaunchCtx &c, int n_hi, const uint16_t *x
     else
         hipLaunchKernelGGL(k_shrink_prefill, dim3(c.n_units), dim3(kThreads), 0, stream, c.units, c.perm, c.arena, x,
                            ldx, c.in_features, v_hi, v_lo, v_f32, n_slices, slice_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_shrink_mixed(const LaunchCtx &heavy, int n_hi, const LaunchCtx &c, const uint16_t *x, int64_t ldx,
+                               int k_slice_len, float *parts, int n_slices, int64_t slice_stride,
+                               const SyncArgs *sync, hipStream_t stream)
+{
+    const int total = heavy.n_units + c.n_units;
+    if (total <= 0) return hipSuccess;
+    if (!sync || n_hi < 0 || n_hi > heavy.n_units) return hipErrorInvalidValue;
+    const Sync sy = make_sync(sync, 0);
+    if (n_hi > 0)
+        hipLaunchKernelGGL(k_shrink_mixed<true>, dim3(total), dim3(kThreads), 0, stream, heavy.units, heavy.n_units,
+                           c.units, c.perm, c.arena, x, ldx, c.in_features, k_slice_len, parts, n_slices,
+                           slice_stride, sy);
+    else
+        hipLaunchKernelGGL(k_shrink_mixed<false>, dim3(total), dim3(kThreads), 0, stream, heavy.units, heavy.n_units,
+                           c.units, c.perm, c.arena, x, ldx, c.in_features, k_slice_len, parts, n_slices,
+                           slice_stride, sy);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand_mixed(const LaunchCtx &big, const LaunchCtx &c, const float *parts, int n_slices,
+                               int64_t slice_stride, uint16_t *y, int64_t ldy, const SyncArgs *sync,
+                               hipStream_t stream)
+{
+    const int total = big.n_units + c.n_units;
+    if (total <= 0) return hipSuccess;
+    if (!sync) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_expand_mixed, dim3(total), dim3(kThreads), 0, stream, big.units, big.n_units, c.units,
+                       c.perm, c.arena, parts, n_slices, slice_stride, y, ldy, make_sync(sync, 0));
     return hipGetLastError();
 }
 

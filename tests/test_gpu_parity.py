@@ -389,16 +389,18 @@ def test_cfg3_stack_full_size(layer, projection):
     _sampled_parity(wl.cfg3_stack(layer=layer, projection=projection), seed=layer)
 
 
-def test_mixed_batch_side_stream_matches_single_stream():
-    """A mixed batch issues its decode-sized launches onto the segment object's own stream, between a
-    fork and a join event.  Same bits as with all four launches on one stream, on a non-default
-    stream, apply after apply on one object (each reading the y the one before it wrote), with a
-    dependent operation queued right behind the last apply."""
+def test_mixed_batch_forms_give_the_same_bits():
+    """A mixed batch runs as two launches that hold both kinds of unit (the default), or as four
+    launches with the decode-sized pair on the segment object's own stream between a fork and a join
+    event, or as four launches on one stream.  Same bits in all three forms, on a non-default stream,
+    apply after apply on one object (each reading the y the one before it wrote), with a dependent
+    operation queued right behind the last apply."""
     b = wl.cfg3_stack(layer=3, projection=1)      # k_proj 4096 -> 1024: the quickest mixed batch
     dp = G.DevicePool(b)
     x = G.bits_to_dev(b.x_bits())
     results = []
-    for side in (True, False):
+    for merged, side in ((True, True), (False, True), (False, False)):
+        L.lora_set_merged_launches(merged)
         L.lora_set_side_stream(side)
         try:
             stream = torch.cuda.Stream()
@@ -406,18 +408,30 @@ def test_mixed_batch_side_stream_matches_single_stream():
                 seg = L.lora_segments_build(dp.pool, b.token_adapter, stream=stream)
                 info = L.lora_segments_info(seg)
                 assert info["n_shrink_units"] > 32
+                assert (info["n_k_slices"] > 1) == merged      # decode-sized groups in k-slices only when merged
                 ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
                 y = G.bits_to_dev(b.y0_bits("small"))
                 for _ in range(6):
                     L.lora_apply(dp.pool, seg, x, y, ws, stream=stream)
-                y_after = y.clone()           # ordered behind the join of the last apply
+                y_after = y.clone()           # ordered behind the last apply (and its join)
             stream.synchronize()
             L.lora_segments_check(seg, stream=stream)
             L.lora_segments_destroy(seg)
             results.append(G.dev_to_bits(y_after))
         finally:
+            L.lora_set_merged_launches(True)
             L.lora_set_side_stream(True)
-    assert np.array_equal(results[0], results[1])
+    assert np.array_equal(results[0], results[1]) and np.array_equal(results[1], results[2])
+    # and the default form against the oracle, after one apply on y0
+    y = G.bits_to_dev(b.y0_bits("small"))
+    seg = L.lora_segments_build(dp.pool, b.token_adapter)
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+    L.lora_apply(dp.pool, seg, x, y, ws)
+    torch.cuda.synchronize()
+    rows = np.arange(0, b.T, 16, dtype=np.int32)
+    y_ref = G.oracle_apply(dp, b.x_bits(), b.y0_bits("small"), rows=rows)
+    G.check_parity(G.dev_to_bits(y), y_ref, b.y0_bits("small"), b.token_adapter, rows=rows)
+    L.lora_segments_destroy(seg)
     dp.close()
 
 
