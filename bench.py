@@ -192,7 +192,9 @@ def run_layer(args, torch, L, wl, dev, stream) -> int:
     b0, description, _, _ = pick_workload(args.workload, wl)
     assert b0.in_features == 4096, "--projections layer uses the routing of cfg1 or cfg3:0"
     groups = [(4096, (4096, 1024, 1024)), (4096, (4096,)), (4096, (14336, 14336)), (14336, (4096,))]
-    nl = args.layers or 8      # the routing is planned once per step, as in a model of 32 layers
+    # the routing is planned once per step, as in a model of 32 layers; the mixed batch's pools of 32
+    # layers would not leave room for x and y, so it runs 8 layers per step
+    nl = args.layers or (32 if args.workload == "cfg1" else 8)
     T = b0.T
     g = torch.Generator(device=dev)
     g.manual_seed(0)
@@ -281,6 +283,10 @@ def main() -> int:
                     help="cfg1 (default, the benchmark line) | cfg2:<shape 0..2> | cfg3:<projection 0..6> | "
                          "cfg4:<shape 0..2>:<9to1|1to1|1to9>[:<0|1> only that rank class]")
     ap.add_argument("--fused", action="store_true", help="single-launch lora_apply (decode-sized batches)")
+    ap.add_argument("--mixed-form", choices=("merged", "two-streams", "one-stream"), default="merged",
+                    help="how a mixed batch (token-heavy and decode-sized groups) is launched: two launches that "
+                         "hold both kinds of unit (default), four launches with the decode-sized pair on a side "
+                         "stream, or four launches on one stream")
     ap.add_argument("--whole-k-limit", type=int, default=None,
                     help="planning knob lora_set_whole_k_limit (default: the library's, 1024; 0 = always k-slices)")
     ap.add_argument("--projections", default=None,
@@ -314,6 +320,8 @@ def main() -> int:
         L.lora_set_fused_apply(True)
     if args.whole_k_limit is not None:
         L.lora_set_whole_k_limit(args.whole_k_limit)
+    L.lora_set_merged_launches(args.mixed_form == "merged")
+    L.lora_set_side_stream(args.mixed_form != "one-stream")
 
     if args.projections == "layer":
         return run_layer(args, torch, L, wl, dev, stream)
@@ -475,7 +483,7 @@ def main() -> int:
                    "distinct_adapters": info["n_segments"], "shrink_units": info["n_shrink_units"],
                    "expand_units": info["n_expand_units"], "k_slices": info["n_k_slices"],
                    "algorithmic_bytes_per_apply": shrink_bytes + expand_bytes,
-                   "flops_per_apply": b0.flops(), "single_launch_apply": bool(args.fused),
+                   "flops_per_apply": b0.flops(), "single_launch_apply": bool(args.fused), "mixed_form": args.mixed_form,
                    "padded_control": bool(args.padded_control), "concurrent_loads_per_step": args.concurrent_loads,
                    "adapter_bytes_loaded_per_step": load_bytes_per_step, "weight_bytes_read_per_apply": info["weight_bytes"],
                    "parity_max_row_rel_l2": err},
