@@ -218,7 +218,10 @@ lora_status_t lora_segments_export(const lora_segments_t *seg, int32_t *perm, in
  * rows x all of k (listed after the others, k-slice 0) and into expand units of up to 64 tokens.
  * The order is the launch order: the decode shrink units of one group take places of one residue
  * mod 8 where the counts allow it (the launch's work groups go to the chip's 8 XCDs in turn, and the
- * group's rows of x then stay in one XCD's L2).  Either output may be NULL. */
+ * group's rows of x then stay in one XCD's L2); the 64-token expand units (listed after the others)
+ * of one group come in rows of 8, each column run with 8 / (column runs) consecutive token tiles, so
+ * that a column run's part of B^T is fetched by that many XCDs instead of all 8.  Either output may
+ * be NULL. */
 lora_status_t lora_segments_export_units(const lora_segments_t *seg, int32_t *shrink_units,
                                          int32_t *expand_units);
 

@@ -709,24 +709,38 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
             etile = 64;
             cols = std::min(out, std::max(512, (out / 4 + 127) / 128 * 128));
         }
-        for (int c0 = 0; c0 < out; c0 += cols)
-            for (int tok0 = 0; tok0 < r.ntok; tok0 += etile) {
-                Unit u;
-                memset(&u, 0, sizeof u);
-                u.seg = si;
-                u.tok0 = tok0;
-                u.ntok = std::min(etile, r.ntok - tok0);
-                u.p0 = c0;
-                u.pn = std::min(cols, out - c0);
-                u.r8 = r.r8;
-                u.scale = r.scale;
-                u.w_off = r.b_off + (uint64_t)c0 * r.r8;
-                u.v_off = r.v_off + (int64_t)tok0 * r.r8;
-                u.sync_idx = sync_base[si] + tok0 / lora::kTokTile;
-                u.sync_n = sync_n;
-                fill_tokens(u, r);
-                (etile > lora::kTokTile ? sg->expand_big_units : sg->expand_units).push_back(u);
-            }
+        auto emit = [&](int c0, int tok0) {
+            Unit u;
+            memset(&u, 0, sizeof u);
+            u.seg = si;
+            u.tok0 = tok0;
+            u.ntok = std::min(etile, r.ntok - tok0);
+            u.p0 = c0;
+            u.pn = std::min(cols, out - c0);
+            u.r8 = r.r8;
+            u.scale = r.scale;
+            u.w_off = r.b_off + (uint64_t)c0 * r.r8;
+            u.v_off = r.v_off + (int64_t)tok0 * r.r8;
+            u.sync_idx = sync_base[si] + tok0 / lora::kTokTile;
+            u.sync_n = sync_n;
+            fill_tokens(u, r);
+            (etile > lora::kTokTile ? sg->expand_big_units : sg->expand_units).push_back(u);
+        };
+        const int ncb = (out + cols - 1) / cols;
+        if (etile > lora::kTokTile && (ncb == 2 || ncb == 4)) {
+            // Work group b of a launch runs on XCD b mod 8, each XCD with an L2 of its own.  With the
+            // units of a group in rows of 8 (each column run with 8 / ncb consecutive token tiles) a
+            // column run's rows of B^T are fetched by 8 / ncb XCDs instead of all eight (cfg2 4096->4096:
+            // 276 -> 231 MB fetched per launch for 185 MB of y, 78.5 -> 75.3 us).
+            const int tiles_per_row = 8 / ncb;
+            const int ntiles = (r.ntok + etile - 1) / etile;
+            for (int t0 = 0; t0 < ntiles; t0 += tiles_per_row)
+                for (int cb = 0; cb < ncb; ++cb)
+                    for (int t = t0; t < std::min(ntiles, t0 + tiles_per_row); ++t) emit(cb * cols, t * etile);
+        } else {
+            for (int c0 = 0; c0 < out; c0 += cols)
+                for (int tok0 = 0; tok0 < r.ntok; tok0 += etile) emit(c0, tok0);
+        }
     }
 
     order_units_by_xcd(sg->shrink_units);

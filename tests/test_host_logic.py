@@ -219,6 +219,34 @@ def test_planner_matches_brute_force_grouping(maker):
     L.lora_pool_destroy(pool)
 
 
+def test_column_runs_of_64_token_expand_units_meet_few_xcds():
+    """Work group b of a launch runs on XCD b mod 8.  The 64-token expand units of a group are listed
+    in rows of 8 (each of the 4 column runs with 2 consecutive token tiles), so a column run of a
+    group takes 2 of the 8 residues, whatever place the group starts at (a last row of 4 units, when
+    the group has an odd number of token tiles, aside)."""
+    b = wl.cfg2_prefill(0)
+    n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
+    pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
+    for a in range(b.n_adapters):
+        L.lora_pool_mark_resident(pool, a)
+    seg = L.lora_segments_plan(pool, b.token_adapter)
+    ex, units = L.lora_segments_export(seg), L.lora_segments_export_units(seg)
+    eu = units["expand"]
+    ntok_of = np.diff(ex["seg_start"])[eu[:, 0]]
+    big = eu[ntok_of >= 32]                  # every group of cfg2 is token-heavy and up to rank 128
+    assert len(big) == len(eu) and big[:, 2].max() == 64
+    ntiles = {int(s): (int(n) + 63) // 64 for s, n in enumerate(np.diff(ex["seg_start"]))}
+    runs = {}
+    for pos, (s, tok0, nt, p0, pn, ks) in enumerate(big):
+        if ntiles[int(s)] % 2 and tok0 // 64 == ntiles[int(s)] - 1:
+            continue                         # an odd tile count leaves a last row of 4 units
+        runs.setdefault((int(s), int(p0)), set()).add(pos % 8)
+    assert len({p0 for _, p0 in runs}) == 4
+    assert max(len(r) for r in runs.values()) <= 2
+    L.lora_segments_destroy(seg)
+    L.lora_pool_destroy(pool)
+
+
 def test_whole_k_limit_switches_the_shrink_plan():
     b = wl.cfg1_decode()
     n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
