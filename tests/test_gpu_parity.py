@@ -435,6 +435,28 @@ def test_mixed_batch_forms_give_the_same_bits():
     dp.close()
 
 
+def test_mixed_batch_with_token_heavy_groups_up_to_rank_64():
+    """A mixed batch whose token-heavy groups all have rank <= 64 takes the forms of the merged
+    launches that fit four work groups per compute unit; the decode-sized groups beside them have
+    any rank (1 .. 256, ranks that are no multiple of 8 or 16).  All rows checked."""
+    ranks = (8, 16, 32, 64, 24, 40, 128, 100, 256, 3, 200, 12)
+    lens = (300, 210, 170, 129, 95, 64)          # adapters 0..5 get token-heavy groups (ranks <= 64)
+    b0 = wl.small_mixed(seed=21, in_features=1024, out_features=512, n_adapters=len(ranks), ranks=ranks,
+                        decode_tokens=260, prefill_lens=())
+    dec = b0.token_adapter.copy()
+    dec[(dec >= 0) & (dec < 6)] += 6             # decode tokens only on adapters 6..11 (and -1)
+    ta = np.concatenate([np.full(n, a, dtype=np.int32) for a, n in enumerate(lens)] + [dec])
+    b = wl.CoBatch("mixed_low_rank_heavy", 1024, 512, b0.ranks, b0.scales, ta, seed=21, config=9)
+    assert int((b.token_adapter >= 0).sum()) >= 1024
+    dp = G.DevicePool(b)
+    seg = L.lora_segments_build(dp.pool, b.token_adapter)
+    info = L.lora_segments_info(seg)
+    assert info["n_k_slices"] >= 1 and info["n_shrink_units"] > len(lens)
+    L.lora_segments_destroy(seg)
+    dp.close()
+    _full_parity(b, y0_kind="small")
+
+
 @pytest.mark.parametrize("shape,split", [(0, "9:1"), (0, "1:1"), (0, "1:9"), (1, "1:1"), (2, "1:1")])
 def test_cfg4_skew_full_size(shape, split):
     _sampled_parity(wl.cfg4_skew(shape, split), n_rows=64)
