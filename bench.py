@@ -58,10 +58,14 @@ class Hip:
     def __init__(self):
         self.rt = ctypes.CDLL("libamdhip64.so")
 
+    # hipEventDisableSystemFence: a timing event without the system-scope release (cache write-back
+    # and invalidate) it otherwise performs between the two kernels it separates
+    EVENT_FLAGS = 0x20000000
+
     def event(self) -> ctypes.c_void_p:
         e = ctypes.c_void_p()
-        rc = self.rt.hipEventCreate(ctypes.byref(e))
-        assert rc == 0, f"hipEventCreate -> {rc}"
+        rc = self.rt.hipEventCreateWithFlags(ctypes.byref(e), ctypes.c_uint(self.EVENT_FLAGS))
+        assert rc == 0, f"hipEventCreateWithFlags -> {rc}"
         return e
 
     def elapsed_ms(self, a, b) -> float:
@@ -410,7 +414,7 @@ def main() -> int:
 
     # ---- per-phase durations, live, with HIP events on the launch stream around the launches of the
     # same steps (shrink launches | expand launches; a fused apply is one launch).  The events sit
-    # between back-to-back launches, so they also see the dispatch gap that a kernel trace leaves out.
+    # between back-to-back launches, so they also see the dispatch of a launch, which a kernel trace leaves out.
     n_prof_steps = max(1, min(args.steps, 10))
     evs = [[(hip.event(), hip.event(), hip.event()) for _ in range(nl)] for _ in range(n_prof_steps)]
     for s in range(n_prof_steps):
