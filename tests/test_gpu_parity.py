@@ -675,6 +675,22 @@ def _multi_case(batch, outs, y0_kind="small"):
     torch.cuda.synchronize()
     assert np.array_equal(G.dev_to_bits(y2), y_multi)
     L.lora_segments_destroy(seg)
+    # the other forms of a mixed batch (four launches, with and without the side stream): same bits
+    for side in (True, False):
+        L.lora_set_merged_launches(False)
+        L.lora_set_side_stream(side)
+        try:
+            seg = L.lora_segments_build_multi(pools, batch.token_adapter)
+            ws2 = torch.empty(max(L.lora_apply_workspace_bytes(pools[0], seg), 256), dtype=torch.uint8, device="cuda")
+            y3 = G.bits_to_dev(y0_bits)
+            L.lora_apply_multi(pools, seg, x, y3, ws2)
+            torch.cuda.synchronize()
+            L.lora_segments_check(seg)
+            L.lora_segments_destroy(seg)
+        finally:
+            L.lora_set_merged_launches(True)
+            L.lora_set_side_stream(True)
+        assert np.array_equal(G.dev_to_bits(y3), y_multi)
     # one projection at a time on the column blocks of the same matrix: the same bits; and the oracle
     y_sep = G.bits_to_dev(y0_bits)
     col = 0
