@@ -306,8 +306,8 @@ lora_status_t lora_set_fused_apply(int enabled);
  * k-slices, whose work groups have the size of the token-heavy ones', and lora_apply /
  * lora_apply_multi run it as two launches on `stream`: one shrink launch and one expand launch that
  * each hold both kinds of unit, the token-heavy ones first.  The setting is read when a batch is
- * planned (build / rebuild) and when it is applied; change it only between a plan and nothing.
- * Process-wide.
+ * planned (build / rebuild) and again when it is applied; a batch planned under one setting and
+ * applied under the other still gives the same y, through the four launches below.  Process-wide.
  *
  * With lora_set_merged_launches(0) a mixed batch is four launches: the token-heavy groups' shrink
  * and expand, the decode-sized groups' shrink and expand.  The two pairs touch different tokens
