@@ -422,6 +422,22 @@ def test_mixed_batch_forms_give_the_same_bits():
             L.lora_set_merged_launches(True)
             L.lora_set_side_stream(True)
     assert np.array_equal(results[0], results[1]) and np.array_equal(results[1], results[2])
+    # planned under one setting, applied under the other: still the same bits
+    for planned in (True, False):
+        try:
+            L.lora_set_merged_launches(planned)
+            seg = L.lora_segments_build(dp.pool, b.token_adapter)
+            L.lora_set_merged_launches(not planned)
+            ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+            y = G.bits_to_dev(b.y0_bits("small"))
+            for _ in range(6):
+                L.lora_apply(dp.pool, seg, x, y, ws)
+            torch.cuda.synchronize()
+            L.lora_segments_check(seg)
+            L.lora_segments_destroy(seg)
+        finally:
+            L.lora_set_merged_launches(True)
+        assert np.array_equal(G.dev_to_bits(y), results[0])
     # and the default form against the oracle, after one apply on y0
     y = G.bits_to_dev(b.y0_bits("small"))
     seg = L.lora_segments_build(dp.pool, b.token_adapter)
