@@ -44,6 +44,8 @@ MEASURED_TRAFFIC = {
 }
 # The kernels behind a launch phase, for the workloads whose plan is one kernel per phase (names as a
 # kernel trace shows them).
+MEASURED_READ_CEILING_GBS = 6100.0
+
 PHASE_KERNELS = {
     ("cfg1", "shrink launch"): "lora::k_shrink_wide",
     ("cfg1", "expand launch"): "lora::k_expand<false, false>",
@@ -493,6 +495,10 @@ def main() -> int:
                    "parity_max_row_rel_l2": err},
         "roofline": {"bound": "hbm", "kernel": dom if dom_kernel is None else f"{dom}: {dom_kernel}", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     # context: what a kernel that only reads gets from HBM on this chip (1 GB read once by 256 to
+                     # 1024 work groups, 8 x 16-byte loads per lane in flight: 6.1 TB/s, measured)
+                     "measured_read_ceiling_GBps": MEASURED_READ_CEILING_GBS,
+                     "frac_of_measured_read_ceiling": achieved / MEASURED_READ_CEILING_GBS,
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": dom_us,
                      "shrink_launch_us": float(shrink_us.mean()), "expand_launch_us": float(expand_us.mean()),
                      "apply_GBps": (shrink_bytes + expand_bytes) / (apply_us * 1e-6) / 1e9,
