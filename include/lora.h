@@ -284,7 +284,8 @@ lora_status_t lora_apply_multi(const lora_pool_t *const *pools, int32_t n_pools,
 
 /* Planning knob, process-wide, read by the lora_segments_plan / build / rebuild calls that follow.
  * A batch whose decode-sized groups make between 64 and `max_units` shrink units when a unit takes
- * the whole of k (16 rank rows x up to 16 tokens each) is planned that way: work groups of 16
+ * the whole of k (16 rank rows x up to 16 tokens each) is planned that way, if in_features is at most
+ * 8192 and the batch is not a mixed one run as merged launches (below): work groups of 16
  * wavefronts, v complete when the unit ends.  Other batches cut k into up to 4 slices per unit (more,
  * smaller units spread a small batch over the chip and fill the last round of a large one better) and
  * add the slices up through counters.  Both plans give bitwise the same v.  Default 1024 (four rounds

@@ -482,6 +482,10 @@ static int g_whole_k_limit = 1024;
 // token-heavy ones'.
 static int g_merged_mixed = 1;
 static const int kWholeKMin = 64;  // below this, k-slices are what spreads the batch over the chip
+// A wavefront of a whole-k unit walks in_features / 16 of k in passes of 256, one trip to memory each:
+// beyond this many input features the k-slice units win (cfg1's routing, shrink launch: 14.4 vs 15.5 us
+// at 8192, 23.5 vs 22.4 us at 14336, 41.8 vs 38.8 us at 28672; the rank-skew batch at 28672: 96 vs 86 us).
+static const int kWholeKMaxIn = 8192;
 
 extern "C" lora_status_t lora_set_whole_k_limit(int32_t max_units)
 try {
@@ -577,7 +581,8 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     }
     bool heavy_groups = false;
     for (int a = 0; a < N; ++a) heavy_groups |= count[a] >= kPrefillMinTokens && n_active >= kPrefillMinBatch;
-    sg->wide = whole_k_units >= kWholeKMin && whole_k_units <= g_whole_k_limit && !(g_merged_mixed && heavy_groups);
+    sg->wide = whole_k_units >= kWholeKMin && whole_k_units <= g_whole_k_limit &&
+               pool->in_features <= kWholeKMaxIn && !(g_merged_mixed && heavy_groups);
     choose_k_slices(pool->in_features, &sg->wide_slices, &sg->wide_slice_len);
     if (sg->wide) {
         sg->n_k_slices = 1;
