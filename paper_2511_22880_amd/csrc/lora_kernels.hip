@@ -383,20 +383,22 @@ __global__ __launch_bounds__(kWideThreads) void k_shrink_wide(const Unit *__rest
     }
     red[wave][lane] = acc;
     __syncthreads();
+    // the first wavefront of every slice adds the slice's four tiles (in wavefront order), then
+    // wavefront 0 adds the slices (in slice order): the order of the k-slice plan, two short steps
+    // instead of sixteen reads by one wavefront
+    if (wq == 0 && slice < n_slices) {
+        f32x4 ts = red[wave][lane];
+        ts += red[wave + 1][lane];
+        ts += red[wave + 2][lane];
+        ts += red[wave + 3][lane];
+        red[wave][lane] = ts;
+    }
+    __syncthreads();
     if (wave == 0) {
-        f32x4 t = {0.f, 0.f, 0.f, 0.f};
+        f32x4 t = red[0][lane];
 #pragma unroll
-        for (int sl = 0; sl < kMaxSlices; ++sl)
-            if (sl < n_slices) {
-                f32x4 ts = red[4 * sl][lane];
-                ts += red[4 * sl + 1][lane];
-                ts += red[4 * sl + 2][lane];
-                ts += red[4 * sl + 3][lane];
-                if (sl == 0)
-                    t = ts;
-                else
-                    t += ts;
-            }
+        for (int sl = 1; sl < kMaxSlices; ++sl)
+            if (sl < n_slices) t += red[4 * sl][lane];
         // register r of lane (i, kq) is rank row 4*kq + r of the block for token i
         if (x_ok && 4 * kq < pn) {
             const int64_t off = u.v_off + (int64_t)i * u.r8 + 4 * kq;
