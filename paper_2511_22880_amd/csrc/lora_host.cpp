@@ -486,6 +486,13 @@ static const int kWholeKMin = 64;  // below this, k-slices are what spreads the 
 // beyond this many input features the k-slice units win (cfg1's routing, shrink launch: 14.4 vs 15.5 us
 // at 8192, 23.5 vs 22.4 us at 14336, 41.8 vs 38.8 us at 28672; the rank-skew batch at 28672: 96 vs 86 us).
 static const int kWholeKMaxIn = 8192;
+// Likewise a token-heavy shrink unit: a wavefront takes a quarter of k in passes of 128.  Beyond
+// kWholeKMaxIn input features, and when the launch has at most this many such units (two work groups
+// per compute unit, so they all run at once and the launch lasts as long as one unit), the units of a
+// batch planned in k-slices are cut in two along k: the mixed batch of cfg3 on down_proj (14336 ->
+// 4096, 291 units) 115 -> 102 us, +9 % per apply; at 4096 the cut loses 2-5 %, and cfg2's 718 units
+// at 14336 neither gain nor lose.
+static const int kHeavyKCutMaxUnits = 512;
 
 extern "C" lora_status_t lora_set_whole_k_limit(int32_t max_units)
 try {
@@ -550,7 +557,8 @@ static void order_units_by_xcd(std::vector<Unit> &units)
     units.swap(out);
 }
 
-static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const int32_t *ta, int32_t T)
+static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const int32_t *ta, int32_t T,
+                               int n_projections = 1)  // projections whose units share the launches
 {
     const int N = pool->n_adapters;
     std::vector<int32_t> count(N, 0);
@@ -660,30 +668,45 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     sg->n_sync = n_sync;
     sg->has_big_units = false;
     sg->n_prefill_hi = 0;
+    // A launch of few token-heavy shrink units lasts as long as one unit's walk through k (a wavefront
+    // takes a quarter of k in passes of 128, one trip to memory each); such units are cut into k-slices.
+    int64_t heavy_units = 0;
+    for (const SegRec &r : sg->segs)
+        if (r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch)
+            heavy_units += (r.ntok + (r.r8 <= 128 ? 32 : 16) - 1) / (r.r8 <= 128 ? 32 : 16);
+    const int heavy_k_slices = (sg->n_k_slices >= 2 && heavy_units > 0 && pool->in_features > kWholeKMaxIn &&
+                                heavy_units * n_projections <= kHeavyKCutMaxUnits)
+                                   ? 2
+                                   : 1;
     for (int32_t si : order) {
         const SegRec &r = sg->segs[si];
         const bool token_heavy = r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch;
         const int sync_n = ((r.r8 + lora::kRowTile - 1) / lora::kRowTile) * sg->n_k_slices;
         if (token_heavy) {
-            // shrink: tiles of 32 tokens (16 above rank 128), all rank rows, all of k
+            // shrink: tiles of 32 tokens (16 above rank 128), all rank rows, all of k or (heavy_k_slices
+            // > 1) a slice of it, the slices' sums meeting at the counter of the tile's first 16 tokens
             sg->has_big_units = true;
             const int tile = r.r8 <= 128 ? 32 : 16;
-            for (int tok0 = 0; tok0 < r.ntok; tok0 += tile) {
-                Unit u;
-                memset(&u, 0, sizeof u);
-                u.seg = si;
-                u.tok0 = tok0;
-                u.ntok = std::min(tile, r.ntok - tok0);
-                u.p0 = 0;
-                u.pn = r.r8;
-                u.r8 = r.r8;
-                u.scale = r.scale;
-                u.w_off = r.a_off;
-                u.v_off = r.v_off + (int64_t)tok0 * r.r8;
-                fill_tokens(u, r);
-                sg->prefill_units.push_back(u);
-                if (r.r8 > 64) ++sg->n_prefill_hi;
-            }
+            for (int tok0 = 0; tok0 < r.ntok; tok0 += tile)
+                for (int ks = 0; ks < heavy_k_slices; ++ks) {
+                    Unit u;
+                    memset(&u, 0, sizeof u);
+                    u.seg = si;
+                    u.tok0 = tok0;
+                    u.ntok = std::min(tile, r.ntok - tok0);
+                    u.p0 = 0;
+                    u.pn = r.r8;
+                    u.ks = ks;
+                    u.r8 = r.r8;
+                    u.scale = r.scale;
+                    u.w_off = r.a_off;
+                    u.v_off = r.v_off + (int64_t)tok0 * r.r8;
+                    u.sync_idx = sync_base[si] + tok0 / lora::kTokTile;
+                    u.sync_n = heavy_k_slices;
+                    fill_tokens(u, r);
+                    sg->prefill_units.push_back(u);
+                    if (r.r8 > 64) ++sg->n_prefill_hi;
+                }
         } else {
             for (int row0 = 0; row0 < r.r8; row0 += lora::kRowTile)
                 for (int ks = 0; ks < sg->n_k_slices; ++ks)
@@ -882,7 +905,7 @@ static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const 
         if (((uintptr_t)q->arena - (uintptr_t)p0->arena) % 2) return fail(LORA_ERR_INVALID_ARG, "arena alignment");
         base = std::min(base, (const uint16_t *)q->arena);
     }
-    lora_status_t st = plan_into(sg, p0, ta, T);
+    lora_status_t st = plan_into(sg, p0, ta, T, (int)pools.size());
     if (st != LORA_OK) return st;
     sg->mpools = pools;
     sg->mpool_ids.clear();
@@ -916,7 +939,7 @@ static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const 
     lora_segments *tmp = tmp_owner.get();
     if (!tmp) return fail(LORA_ERR_OOM, "host allocation failed");
     for (size_t q = 1; q < pools.size(); ++q) {
-        st = plan_into(tmp, pools[q], ta, T);
+        st = plan_into(tmp, pools[q], ta, T, (int)pools.size());
         if (st != LORA_OK) break;
         const uint64_t delta = (uint64_t)(((uintptr_t)pools[q]->arena - (uintptr_t)base) / 2);
         const size_t n0 = sg->shrink_units.size(), n1 = sg->prefill_units.size(), n2 = sg->expand_units.size(),
@@ -1289,16 +1312,18 @@ try {
     if (sg->wide) {
         HIP_TRY(lora::launch_shrink_wide(c, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, v, nullptr,
                                          nullptr, s));
-        HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, s));
+        HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, nullptr,
+                                            nullptr, s));
     } else if (sg->n_k_slices <= 1) {
         HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, v, 1, 0, nullptr, s));
-        HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, s));
+        HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, nullptr,
+                                            nullptr, s));
     } else {
         float *parts = (float *)workspace;
         HIP_TRY(lora::launch_shrink(c, (const uint16_t *)x, ldx, sg->k_slice_len, parts, sg->n_k_slices,
                                     sg->v_floats, nullptr, s));
         HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, nullptr, nullptr, parts, sg->n_k_slices,
-                                            sg->v_floats, s));
+                                            sg->v_floats, nullptr, nullptr, s));
         HIP_TRY(lora::launch_reduce_slices(parts, sg->n_k_slices, sg->v_floats, v, sg->v_floats, s));
     }
     return LORA_OK;
@@ -1433,7 +1458,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
             HIP_TRY(hipStreamWaitEvent(sd, msg->fork, 0));
         }
         HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, sa.v_hi, sa.v_lo, nullptr,
-                                            nsl, stride, s));
+                                            nsl, stride, parts, &sa, s));
         if (sg->wide)
             HIP_TRY(lora::launch_shrink_wide(cs, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, nullptr,
                                              sa.v_hi, sa.v_lo, sd));

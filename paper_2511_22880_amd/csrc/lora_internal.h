@@ -93,10 +93,12 @@ hipError_t launch_expand(const LaunchCtx &c, bool big, const float *v_in, int n_
 // n_hi = how many of the units are above rank 64: with none, the launch takes the kernel that fits four
 // work groups on a compute unit, otherwise the one for any rank (two per compute unit).
 // Writes complete v: as bf16 hi + lo into v_hi / v_lo, or (v_f32 != NULL) as fp32 into v_f32 with the
-// other n_slices - 1 slices of the same rows set to zero.
+// other n_slices - 1 slices of the same rows set to zero.  Units cut by k (sync_n = slices of the unit's
+// tokens, ks = which) put their sums into slices of `parts` and complete v through `sync`'s counters
+// (apply), or into slices of v_f32 for the caller to add up (stand-alone shrink, sync = NULL).
 hipError_t launch_shrink_prefill(const LaunchCtx &c, int n_hi, const uint16_t *x, int64_t ldx, uint16_t *v_hi,
-                                 uint16_t *v_lo, float *v_f32, int n_slices, int64_t slice_stride,
-                                 hipStream_t stream);
+                                 uint16_t *v_lo, float *v_f32, int n_slices, int64_t slice_stride, float *parts,
+                                 const SyncArgs *sync, hipStream_t stream);
 
 // A mixed batch's shrink in one launch: the token-heavy units of `heavy` (n_hi of them above rank 64),
 // then the k-slice units of `c`, which leave partial sums in `parts` and complete v through `sync` as

@@ -462,7 +462,8 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
                                                              const uint16_t *__restrict__ x, int64_t ldx, int in,
                                                              uint16_t *__restrict__ v_hi,
                                                              uint16_t *__restrict__ v_lo, float *__restrict__ v_f32,
-                                                             int n_slices, int64_t slice_stride, char *lds)
+                                                             int n_slices, int64_t slice_stride, char *lds,
+                                                             float *__restrict__ parts, const Sync &sy)
 {
     constexpr int NT = JB * TB;
     constexpr int NL = 4 * TB;  // x loads of a wavefront per pass: 4 tokens each
@@ -507,10 +508,15 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) acc[jb][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // this wavefront's quarter of k
-    const int kquarter = ((in + 3) / 4 + 31) & ~31;
-    const int kbeg = wave * kquarter;
-    const int kend = min(in, kbeg + kquarter);
+    // this wavefront's quarter of the unit's k range: all of k, or (in launches of few units, which
+    // last as long as a unit's walk through k) k-slice u.ks of u.sync_n, multiples of 128 long
+    const int n_ks = u.sync_n > 1 ? u.sync_n : 1;
+    const int ks_len = n_ks > 1 ? ((in / n_ks + 127) / 128) * 128 : in;
+    const int ks_beg = min(in, u.ks * ks_len);
+    const int ks_end = min(in, ks_beg + ks_len);
+    const int kquarter = ((ks_end - ks_beg + 3) / 4 + 31) & ~31;
+    const int kbeg = ks_beg + wave * kquarter;
+    const int kend = min(ks_end, kbeg + kquarter);
 
     // in is a multiple of 64, so a 16-byte chunk lies inside the row or wholly beyond it; a chunk
     // beyond the row is fetched from the row's last chunk instead and never enters an MFMA
@@ -593,6 +599,26 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
     if (wave != 0) return;
 
     // lane (n, kq) holds, for token block tb and row block jb, v[token n][16*jb + 4*kq + e]
+    if (n_ks == 1) {
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            if (16 * tb + n >= ntok) continue;
+            const int64_t row = u.v_off + (int64_t)(16 * tb + n) * r8;
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) {
+                const int j = 16 * jb + 4 * kq;
+                if (j < r8)
+                    store_v4(acc[jb][tb] + red[0][jb * TB + tb][lane], row + j, v_hi, v_lo, v_f32, n_slices,
+                             slice_stride);
+            }
+        }
+        return;
+    }
+    // A k-slice of the unit's tokens: the sums go to slice u.ks of the fp32 partial sums.  Stand-alone
+    // shrink (v_f32): the caller adds the slices up afterwards, so slice 0's unit clears the slices
+    // this group does not use.  Apply: stores that go through to memory, then the tile's counter; the
+    // unit that completes the tile adds the slices in slice order and leaves v as bf16 hi + lo.
+    float *dst = v_f32 ? v_f32 : parts;
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
         if (16 * tb + n >= ntok) continue;
@@ -600,9 +626,33 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) {
             const int j = 16 * jb + 4 * kq;
-            if (j < r8)
-                store_v4(acc[jb][tb] + red[0][jb * TB + tb][lane], row + j, v_hi, v_lo, v_f32, n_slices,
-                         slice_stride);
+            if (j >= r8) continue;
+            const f32x4 f = acc[jb][tb] + red[0][jb * TB + tb][lane];
+            if (v_f32) {
+                *reinterpret_cast<f32x4 *>(dst + (int64_t)u.ks * slice_stride + row + j) = f;
+                if (u.ks == 0)
+                    for (int sl = n_ks; sl < n_slices; ++sl)
+                        *reinterpret_cast<f32x4 *>(dst + (int64_t)sl * slice_stride + row + j) =
+                            f32x4{0.f, 0.f, 0.f, 0.f};
+            } else {
+                st_through_f32x4(dst + (int64_t)u.ks * slice_stride + row + j, f);
+            }
+        }
+    }
+    if (v_f32) return;
+    stores_done();
+    unsigned old = 0;
+    if (lane == 0) old = atomicAdd(sy.counters + u.sync_idx, 1u);
+    old = __builtin_amdgcn_readfirstlane(old);
+    if (old + 1u == sy.epoch * (unsigned)n_ks) {
+        const int tasks = ntok * (u.r8 >> 3);
+        for (int task = lane; task < tasks; task += 64) {
+            f32x4 f0, f1;
+            sum_slices(parts + u.v_off + 8 * task, n_ks, slice_stride, f0, f1);
+            uint4 ph, pl;
+            split_bf16(f0, f1, ph, pl);
+            st_through_u16x8(v_hi + u.v_off + 8 * task, ph);
+            st_through_u16x8(v_lo + u.v_off + 8 * task, pl);
         }
     }
 }
@@ -637,21 +687,22 @@ static __device__ __forceinline__ void prefill_dispatch(const Unit &u, const int
                                                         const uint16_t *__restrict__ x, int64_t ldx, int in,
                                                         uint16_t *__restrict__ v_hi, uint16_t *__restrict__ v_lo,
                                                         float *__restrict__ v_f32, int n_slices,
-                                                        int64_t slice_stride, char *lds)
+                                                        int64_t slice_stride, char *lds,
+                                                        float *__restrict__ parts, const Sync &sy)
 {
     const int r8 = u.r8;
     if (r8 <= 16)
-        shrink_prefill_ksplit<1, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+        shrink_prefill_ksplit<1, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
     else if (r8 <= 32)
-        shrink_prefill_ksplit<2, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+        shrink_prefill_ksplit<2, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
     else if (!ANY)  // the launcher takes this form only for batches whose token-heavy units are all up to rank 64
-        shrink_prefill_ksplit<4, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+        shrink_prefill_ksplit<4, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
     else if (r8 <= 64)
-        shrink_prefill_ksplit<4, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+        shrink_prefill_ksplit<4, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
     else if (r8 <= 128)
-        shrink_prefill_ksplit<8, 2, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+        shrink_prefill_ksplit<8, 2, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
     else
-        shrink_prefill_ksplit<16, 1, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds);
+        shrink_prefill_ksplit<16, 1, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
 }
 
 __global__ __launch_bounds__(kThreads, 4) void k_shrink_prefill(const Unit *__restrict__ units,
@@ -661,11 +712,11 @@ __global__ __launch_bounds__(kThreads, 4) void k_shrink_prefill(const Unit *__re
                                                                 uint16_t *__restrict__ v_hi,
                                                                 uint16_t *__restrict__ v_lo,
                                                                 float *__restrict__ v_f32, int n_slices,
-                                                                int64_t slice_stride)
+                                                                int64_t slice_stride, float *__restrict__ parts, Sync sy)
 {
     __shared__ __attribute__((aligned(16))) char lds[kPrefillLds];
     prefill_dispatch<false>(units[blockIdx.x], perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride,
-                            lds);
+                            lds, parts, sy);
 }
 
 // A batch that has units above rank 64 runs all its token-heavy units here, in one launch: two
@@ -678,11 +729,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_shrink_prefill_any(const Unit *
                                                                     int in, uint16_t *__restrict__ v_hi,
                                                                     uint16_t *__restrict__ v_lo,
                                                                     float *__restrict__ v_f32, int n_slices,
-                                                                    int64_t slice_stride)
+                                                                    int64_t slice_stride, float *__restrict__ parts, Sync sy)
 {
     __shared__ __attribute__((aligned(16))) char lds[kPrefillLds];
     prefill_dispatch<true>(units[blockIdx.x], perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride,
-                           lds);
+                           lds, parts, sy);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1157,7 +1208,7 @@ __global__ __launch_bounds__(kThreads, ANY ? 2 : 4) void k_shrink_mixed(
     const int b = blockIdx.x;
     if (b < n_heavy)
         prefill_dispatch<ANY>(heavy_units[b], perm, arena, x, ldx, in, sy.v_hi, sy.v_lo, nullptr, n_slices,
-                              slice_stride, lds);
+                              slice_stride, lds, parts, sy);
     else
         shrink_body(units[b - n_heavy], arena, x, ldx, in, k_slice_len, parts, n_slices, slice_stride, lds, sy);
 }
@@ -1293,17 +1344,18 @@ hipError_t launch_apply_fused(const LaunchCtx &cs, const LaunchCtx &ce, const ui
 }
 
 hipError_t launch_shrink_prefill(const LaunchCtx &c, int n_hi, const uint16_t *x, int64_t ldx, uint16_t *v_hi,
-                                 uint16_t *v_lo, float *v_f32, int n_slices, int64_t slice_stride,
-                                 hipStream_t stream)
+                                 uint16_t *v_lo, float *v_f32, int n_slices, int64_t slice_stride, float *parts,
+                                 const SyncArgs *sync, hipStream_t stream)
 {
     if (c.n_units <= 0) return hipSuccess;
     if (n_hi < 0 || n_hi > c.n_units) return hipErrorInvalidValue;
+    const Sync sy = make_sync(sync, 0);
     if (n_hi > 0)
         hipLaunchKernelGGL(k_shrink_prefill_any, dim3(c.n_units), dim3(kThreads), 0, stream, c.units, c.perm, c.arena,
-                           x, ldx, c.in_features, v_hi, v_lo, v_f32, n_slices, slice_stride);
+                           x, ldx, c.in_features, v_hi, v_lo, v_f32, n_slices, slice_stride, parts, sy);
     else
         hipLaunchKernelGGL(k_shrink_prefill, dim3(c.n_units), dim3(kThreads), 0, stream, c.units, c.perm, c.arena, x,
-                           ldx, c.in_features, v_hi, v_lo, v_f32, n_slices, slice_stride);
+                           ldx, c.in_features, v_hi, v_lo, v_f32, n_slices, slice_stride, parts, sy);
     return hipGetLastError();
 }
 

@@ -203,9 +203,52 @@ def test_token_heavy_groups_of_every_rank_bucket(in_features):
     _full_parity(b, y0_kind="small" if in_features == 3072 else "zero")
 
 
-@pytest.mark.parametrize("big", [False, True])
+def _long_k_mixed():
+    """A mixed batch at 9216 input features: its token-heavy shrink units are cut in two along k."""
+    ranks = (8, 40, 64, 128, 24, 100, 16, 3)
+    lens = (200, 300, 150, 100)
+    b0 = wl.small_mixed(seed=33, in_features=9216, out_features=256, n_adapters=len(ranks), ranks=ranks,
+                        decode_tokens=330, prefill_lens=())
+    ta = np.concatenate([np.full(n, a, dtype=np.int32) for a, n in enumerate(lens)] + [b0.token_adapter])
+    b = wl.CoBatch("long_k_mixed", 9216, 256, b0.ranks, b0.scales, ta, seed=33, config=9)
+    assert int((b.token_adapter >= 0).sum()) >= 1024
+    return b
+
+
+def test_token_heavy_units_cut_by_k():
+    """More than 8192 input features, few token-heavy units: they are cut in two along k, the halves'
+    sums meet through the tile's counter (apply after apply on one object: the counters only grow)."""
+    b = _long_k_mixed()
+    dp = G.DevicePool(b)
+    seg = L.lora_segments_build(dp.pool, b.token_adapter)
+    units, ex = L.lora_segments_export_units(seg), L.lora_segments_export(seg)
+    sh = units["shrink"]
+    heavy = sh[np.diff(ex["seg_start"])[sh[:, 0]] >= 32]
+    assert set(heavy[:, 5]) == {0, 1}
+    x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
+    x = G.bits_to_dev(x_bits)
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+    first = None
+    for _ in range(4):
+        y = G.bits_to_dev(y0_bits)
+        L.lora_apply(dp.pool, seg, x, y, ws)
+        torch.cuda.synchronize()
+        bits = G.dev_to_bits(y)
+        if first is None:
+            first = bits
+        assert np.array_equal(bits, first)
+    L.lora_segments_check(seg)
+    L.lora_segments_destroy(seg)
+    y_ref = G.oracle_apply(dp, x_bits, y0_bits)
+    G.check_parity(first, y_ref, y0_bits, b.token_adapter)
+    dp.close()
+
+
+@pytest.mark.parametrize("big", [False, True, "long_k"])
 def test_shrink_and_expand_separately(big):
-    if big:
+    if big == "long_k":
+        b = _long_k_mixed()
+    elif big:
         b = wl.small_mixed(seed=9, in_features=576, out_features=384, decode_tokens=40,
                            prefill_lens=(200, 470, 33, 350, 17))
         assert b.T >= 1024

@@ -247,6 +247,29 @@ def test_column_runs_of_64_token_expand_units_meet_few_xcds():
     L.lora_pool_destroy(pool)
 
 
+def test_token_heavy_units_are_cut_by_k_beyond_8192_input_features():
+    """A mixed batch planned in k-slices, more than 8192 input features, at most 512 token-heavy shrink
+    units: every 32-token tile of a token-heavy group gets two units, k-slices 0 and 1 of the same
+    rows.  At 4096 input features, and in a fuller launch, one unit per tile."""
+    for b, cut in ((wl.cfg3_stack(projection=6), True), (wl.cfg3_stack(projection=0), False), (wl.cfg2_prefill(2), False)):
+        n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
+        pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
+        for a in range(b.n_adapters):
+            L.lora_pool_mark_resident(pool, a)
+        seg = L.lora_segments_plan(pool, b.token_adapter)
+        ex, units = L.lora_segments_export(seg), L.lora_segments_export_units(seg)
+        sh = units["shrink"]
+        heavy = sh[np.diff(ex["seg_start"])[sh[:, 0]] >= 32]
+        tiles = {}
+        for s_, tok0, nt, p0, pn, ks in heavy:
+            tiles.setdefault((int(s_), int(tok0), int(nt), int(p0), int(pn)), []).append(int(ks))
+        assert len(tiles) > 0
+        for ks_list in tiles.values():
+            assert sorted(ks_list) == ([0, 1] if cut else [0])
+        L.lora_segments_destroy(seg)
+        L.lora_pool_destroy(pool)
+
+
 def test_whole_k_limit_switches_the_shrink_plan():
     b = wl.cfg1_decode()
     n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
