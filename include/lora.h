@@ -215,8 +215,7 @@ lora_status_t lora_segments_export(const lora_segments_t *seg, int32_t *perm, in
  * group), token count, first row (shrink) or first column (expand), row or column count,
  * k-slice (shrink) or 0}.  Groups of fewer than 32 tokens are cut into shrink units of <= 16 tokens x
  * 16 rank rows x one k-slice; token-heavy groups into shrink units of up to 32 tokens x all rank
- * rows x all of k (listed after the others, k-slice 0; two k-slices each in a mixed batch of more than
- * 8192 input features and few such units) and into expand units of up to 64 tokens.
+ * rows x all of k (listed after the others, k-slice 0; two or four k-slices each in a mixed batch with few such units) and into expand units of up to 64 tokens.
  * The order is the launch order: the decode shrink units of one group take places of one residue
  * mod 8 where the counts allow it (the launch's work groups go to the chip's 8 XCDs in turn, and the
  * group's rows of x then stay in one XCD's L2); the 64-token expand units (listed after the others)
@@ -319,8 +318,9 @@ lora_status_t lora_set_fused_apply(int enabled);
  * `stream` at the start of the apply and one that `stream` waits for at its end: the pairs run side
  * by side and everything later on `stream` is ordered behind both.  lora_set_side_stream(0) keeps all
  * four launches on `stream`.  y is bitwise the same in all three forms, except where the merged
- * form's plan also cuts the token-heavy shrink units along k (more than 8192 input features and at
- * most 512 such units: then the sums of v are grouped differently, within the same tolerance).
+ * form's plan also cuts the token-heavy shrink units along k (launches of few such units: at most
+ * 160 of them, 300 beyond 8192 input features; the sums of v are then grouped differently, within
+ * the same tolerance).
  * Process-wide. */
 lora_status_t lora_set_merged_launches(int enabled);
 lora_status_t lora_set_side_stream(int enabled);

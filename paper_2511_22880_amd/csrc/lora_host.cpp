@@ -486,13 +486,15 @@ static const int kWholeKMin = 64;  // below this, k-slices are what spreads the 
 // beyond this many input features the k-slice units win (cfg1's routing, shrink launch: 14.4 vs 15.5 us
 // at 8192, 23.5 vs 22.4 us at 14336, 41.8 vs 38.8 us at 28672; the rank-skew batch at 28672: 96 vs 86 us).
 static const int kWholeKMaxIn = 8192;
-// Likewise a token-heavy shrink unit: a wavefront takes a quarter of k in passes of 128.  Beyond
-// kWholeKMaxIn input features, and when the launch has at most this many such units (two work groups
-// per compute unit, so they all run at once and the launch lasts as long as one unit), the units of a
-// batch planned in k-slices are cut in two along k: the mixed batch of cfg3 on down_proj (14336 ->
-// 4096, 291 units) 115 -> 102 us, +9 % per apply; at 4096 the cut loses 2-5 %, and cfg2's 718 units
-// at 14336 neither gain nor lose.
-static const int kHeavyKCutMaxUnits = 512;
+// Likewise a token-heavy shrink unit: a wavefront takes a quarter of k in passes of 128, and a launch of
+// few such units lasts as long as one unit's walk (cfg3's routing scaled to 1.5 k .. 9.5 k tokens: 32-37
+// us at 4096 input features, 99-116 us at 14336, whatever the number of tokens).  In a batch planned
+// in k-slices such units are cut into 4 or 2 slices along k while the cut units stay below these counts
+// (measured, shrink launch in us uncut / 2 / 4 slices; 4096: 41 units 32 / 28 / 23, 79 units 33 / 28 /
+// 25, 148 units 33 / 30 / 33, 291 units 37 / 40 / 45; 14336: 41 units 99 / 67 / 52, 79 units 102 / 67 /
+// 59, 148 units 102 / 75 / 77, 291 units 116 / 102 / 109; cfg2's 718 units at 14336: 155 / 155 / 162).
+static const int kHeavyKCutMaxUnits = 320;
+static const int kHeavyKCutMaxUnitsLongK = 600;
 
 extern "C" lora_status_t lora_set_whole_k_limit(int32_t max_units)
 try {
@@ -674,10 +676,12 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     for (const SegRec &r : sg->segs)
         if (r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch)
             heavy_units += (r.ntok + (r.r8 <= 128 ? 32 : 16) - 1) / (r.r8 <= 128 ? 32 : 16);
-    const int heavy_k_slices = (sg->n_k_slices >= 2 && heavy_units > 0 && pool->in_features > kWholeKMaxIn &&
-                                heavy_units * n_projections <= kHeavyKCutMaxUnits)
-                                   ? 2
-                                   : 1;
+    int heavy_k_slices = 1;
+    if (sg->n_k_slices >= 2 && heavy_units > 0) {
+        const int64_t limit = pool->in_features > kWholeKMaxIn ? kHeavyKCutMaxUnitsLongK : kHeavyKCutMaxUnits;
+        for (int c = std::min(4, sg->n_k_slices); c >= 2 && heavy_k_slices == 1; c /= 2)
+            if (heavy_units * n_projections * c <= limit) heavy_k_slices = c;
+    }
     for (int32_t si : order) {
         const SegRec &r = sg->segs[si];
         const bool token_heavy = r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch;

@@ -193,12 +193,16 @@ def test_planner_matches_brute_force_grouping(maker):
     nsl = info["n_k_slices"]
     for s, a in enumerate(ex["seg_adapter"]):
         ntok, rr = len(groups[int(a)]), int(r8[a])
-        cover = np.zeros((ntok, rr, nsl), dtype=np.int32)
         token_heavy = ntok >= 32 and info["n_active"] >= 1024
-        for seg_i, tok0, nt, p0, pn, ks in units["shrink"][units["shrink"][:, 0] == s]:
-            if token_heavy:       # token tiles: all rank rows, all of k
-                assert 1 <= nt <= 32 and (p0, pn, ks) == (0, rr, 0)
-                cover[tok0:tok0 + nt, :, :] += 1
+        mine = units["shrink"][units["shrink"][:, 0] == s]
+        # token tiles: all rank rows, and all of k or (launches of few such units) 2 or 4 slices of it
+        cuts = int(mine[:, 5].max()) + 1 if token_heavy else nsl
+        assert cuts in (1, 2, 4) and cuts <= max(nsl, 1)
+        cover = np.zeros((ntok, rr, cuts), dtype=np.int32)
+        for seg_i, tok0, nt, p0, pn, ks in mine:
+            if token_heavy:
+                assert 1 <= nt <= 32 and (p0, pn) == (0, rr) and 0 <= ks < cuts
+                cover[tok0:tok0 + nt, :, ks] += 1
             else:
                 assert 1 <= nt <= 16 and 1 <= pn <= 16
                 cover[tok0:tok0 + nt, p0:p0 + pn, ks] += 1
@@ -247,11 +251,14 @@ def test_column_runs_of_64_token_expand_units_meet_few_xcds():
     L.lora_pool_destroy(pool)
 
 
-def test_token_heavy_units_are_cut_by_k_beyond_8192_input_features():
-    """A mixed batch planned in k-slices, more than 8192 input features, at most 512 token-heavy shrink
-    units: every 32-token tile of a token-heavy group gets two units, k-slices 0 and 1 of the same
-    rows.  At 4096 input features, and in a fuller launch, one unit per tile."""
-    for b, cut in ((wl.cfg3_stack(projection=6), True), (wl.cfg3_stack(projection=0), False), (wl.cfg2_prefill(2), False)):
+def test_token_heavy_units_are_cut_by_k_in_launches_of_few_units():
+    """A mixed batch planned in k-slices: every 32-token tile of a token-heavy group gets 4 or 2 units
+    (k-slices of the same rows) while the cut units stay at or below 320 (600 beyond 8192 input
+    features), else one."""
+    cases = ((wl.cfg3_stack(projection=6), 2), (wl.cfg3_stack(projection=0), 1), (wl.cfg2_prefill(2), 1),
+             (wl.cfg3_stack(projection=0, length_scale=0.5), 2), (wl.cfg3_stack(projection=0, length_scale=0.25), 4),
+             (wl.cfg3_stack(projection=6, length_scale=0.5), 4))
+    for b, cuts in cases:
         n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
         pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
         for a in range(b.n_adapters):
@@ -264,8 +271,11 @@ def test_token_heavy_units_are_cut_by_k_beyond_8192_input_features():
         for s_, tok0, nt, p0, pn, ks in heavy:
             tiles.setdefault((int(s_), int(tok0), int(nt), int(p0), int(pn)), []).append(int(ks))
         assert len(tiles) > 0
+        limit = 600 if b.in_features > 8192 else 320
+        assert len(tiles) * cuts <= limit or cuts == 1
+        assert cuts == 4 or len(tiles) * cuts * 2 > limit
         for ks_list in tiles.values():
-            assert sorted(ks_list) == ([0, 1] if cut else [0])
+            assert sorted(ks_list) == list(range(cuts))
         L.lora_segments_destroy(seg)
         L.lora_pool_destroy(pool)
 
