@@ -219,7 +219,8 @@ lora_status_t lora_segments_export(const lora_segments_t *seg, int32_t *perm, in
  * The order is the launch order: the decode shrink units of one group take places of one residue
  * mod 8 where the counts allow it (the launch's work groups go to the chip's 8 XCDs in turn, and the
  * group's rows of x then stay in one XCD's L2); the 64-token expand units (listed after the others)
- * of one group come in rows of 8, each column run with 8 / (column runs) consecutive token tiles, so
+ * of one group (its columns in 4 runs, 8 in a launch of few such units) come in rows of 8, each
+ * column run with 8 / (column runs) consecutive token tiles, so
  * that a column run's part of B^T is fetched by that many XCDs instead of all 8.  Either output may
  * be NULL. */
 lora_status_t lora_segments_export_units(const lora_segments_t *seg, int32_t *shrink_units,

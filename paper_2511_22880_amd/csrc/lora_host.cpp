@@ -495,6 +495,7 @@ static const int kWholeKMaxIn = 8192;
 // 59, 148 units 102 / 75 / 77, 291 units 116 / 102 / 109; cfg2's 718 units at 14336: 155 / 155 / 162).
 static const int kHeavyKCutMaxUnits = 320;
 static const int kHeavyKCutMaxUnitsLongK = 600;
+static const int kBigRunsMaxUnits = 400;  // 64-token expand units of a launch whose groups' columns go in 8 runs
 
 extern "C" lora_status_t lora_set_whole_k_limit(int32_t max_units)
 try {
@@ -682,6 +683,14 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
         for (int c = std::min(4, sg->n_k_slices); c >= 2 && heavy_k_slices == 1; c /= 2)
             if (heavy_units * n_projections * c <= limit) heavy_k_slices = c;
     }
+    // The 64-token expand units: a group's columns in 4 runs, or in 8 shorter ones while that keeps the
+    // launch at few such units (it then lasts as long as one of them; cfg3's routing at 1.5 k / 2.7 k
+    // tokens: expand launch 25.7 -> 19.5 / 26.6 -> 23.1 us at 4096 columns, 78.6 -> 60.8 / 80.5 -> 72.8
+    // us at 14336; at 4.9 k tokens and beyond 8 runs are level or lose).
+    int64_t big_tiles = 0;
+    for (const SegRec &r : sg->segs)
+        if (r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch && r.r8 <= 128) big_tiles += (r.ntok + 63) / 64;
+    const int big_runs = big_tiles * 8 * n_projections <= kBigRunsMaxUnits ? 8 : 4;
     for (int32_t si : order) {
         const SegRec &r = sg->segs[si];
         const bool token_heavy = r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch;
@@ -734,12 +743,12 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                     }
         }
         // expand: small groups one column pass and <= 16 tokens per unit; token-heavy groups 64 tokens
-        // (16 per wavefront, v kept in registers) and a quarter of the columns, at least 512
+        // (16 per wavefront, v kept in registers) and a quarter (or an eighth) of the columns, at least 512
         int cols = expand_cols_per_unit(r.r8, out);
         int etile = lora::kTokTile;
         if (token_heavy && r.r8 <= 128) {  // above rank 128 a strip's tile does not fit the kernel's LDS buffer
             etile = 64;
-            cols = std::min(out, std::max(512, (out / 4 + 127) / 128 * 128));
+            cols = std::min(out, std::max(512, (out / big_runs + 127) / 128 * 128));
         }
         auto emit = [&](int c0, int tok0) {
             Unit u;
@@ -759,7 +768,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
             (etile > lora::kTokTile ? sg->expand_big_units : sg->expand_units).push_back(u);
         };
         const int ncb = (out + cols - 1) / cols;
-        if (etile > lora::kTokTile && (ncb == 2 || ncb == 4)) {
+        if (etile > lora::kTokTile && (ncb == 2 || ncb == 4 || ncb == 8)) {
             // Work group b of a launch runs on XCD b mod 8, each XCD with an L2 of its own.  With the
             // units of a group in rows of 8 (each column run with 8 / ncb consecutive token tiles) a
             // column run's rows of B^T are fetched by 8 / ncb XCDs instead of all eight (cfg2 4096->4096:
