@@ -94,9 +94,11 @@ def pick_workload(spec: str, wl):
                 "{8,16,32,64,128}", 4, False)
     if kind == "cfg3":
         proj = int(parts[1]) if len(parts) > 1 else 0
-        b = wl.cfg3_stack(layer=0, projection=proj)
+        scale = float(parts[2]) if len(parts) > 2 else 1.0       # prompt lengths times this (smaller chunks)
+        b = wl.cfg3_stack(layer=0, projection=proj, length_scale=scale)
+        tag = "" if scale == 1.0 else f" (prompt lengths x {scale:g})"
         return (b, f"cfg3 mixed batch, {wl.CFG3_PROJECTIONS[proj][0]}_proj {b.in_features}->{b.out_features}, "
-                f"8 prefills + 384 decode tokens, T={b.T}, 256 adapters", 8, False)
+                f"8 prefills{tag} + 384 decode tokens, T={b.T}, 256 adapters", 8, False)
     if kind == "cfg4":
         shape = int(parts[1]) if len(parts) > 1 else 0
         split = (parts[2] if len(parts) > 2 else "1to1").replace("to", ":")
@@ -286,7 +288,7 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=None,
                     help="projections per step (default: 32 for cfg1, fewer for the larger workloads)")
     ap.add_argument("--workload", default="cfg1",
-                    help="cfg1 (default, the benchmark line) | cfg2:<shape 0..2> | cfg3:<projection 0..6> | "
+                    help="cfg1 (default, the benchmark line) | cfg2:<shape 0..2> | cfg3:<projection 0..6>[:<prompt length scale>] | "
                          "cfg4:<shape 0..2>:<9to1|1to1|1to9>[:<0|1> only that rank class]")
     ap.add_argument("--fused", action="store_true", help="single-launch lora_apply (decode-sized batches)")
     ap.add_argument("--mixed-form", choices=("merged", "two-streams", "one-stream"), default="merged",
