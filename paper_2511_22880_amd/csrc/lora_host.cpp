@@ -681,7 +681,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     if (sg->n_k_slices >= 2 && heavy_units > 0) {
         const int64_t limit = pool->in_features > kWholeKMaxIn ? kHeavyKCutMaxUnitsLongK : kHeavyKCutMaxUnits;
         for (int c = std::min(4, sg->n_k_slices); c >= 2 && heavy_k_slices == 1; c /= 2)
-            if (heavy_units * n_projections * c <= limit) heavy_k_slices = c;
+            if (heavy_units * c <= limit) heavy_k_slices = c;  // per projection: lora_apply_multi gives the bits of separate applies
     }
     // The 64-token expand units: a group's columns in 4 runs, or in 8 shorter ones while that keeps the
     // launch at few such units (it then lasts as long as one of them; cfg3's routing at 1.5 k / 2.7 k

@@ -722,6 +722,8 @@ def _multi_case(batch, outs, y0_kind="small"):
     # all projections in one pass
     y = G.bits_to_dev(y0_bits)
     seg = L.lora_segments_build_multi(pools, batch.token_adapter)
+    su, sx = L.lora_segments_export_units(seg)["shrink"], L.lora_segments_export(seg)
+    heavy_cut = bool((su[np.diff(sx["seg_start"])[su[:, 0] % len(sx["seg_adapter"])] >= 32][:, 5] > 0).any())
     ws = torch.empty(max(L.lora_apply_workspace_bytes(pools[0], seg), 256), dtype=torch.uint8, device="cuda")
     L.lora_apply_multi(pools, seg, x, y, ws)
     torch.cuda.synchronize()
@@ -749,7 +751,13 @@ def _multi_case(batch, outs, y0_kind="small"):
         finally:
             L.lora_set_merged_launches(True)
             L.lora_set_side_stream(True)
-        assert np.array_equal(G.dev_to_bits(y3), y_multi)
+        if heavy_cut:       # the merged plan also cut token-heavy units along k: other grouping of the sums
+            d = wl.bf16_bits_to_f64(G.dev_to_bits(y3)) - wl.bf16_bits_to_f64(y_multi)
+            ref = wl.bf16_bits_to_f64(y_multi)
+            act = batch.token_adapter >= 0
+            assert (np.linalg.norm(d[act], axis=1) / np.linalg.norm(ref[act], axis=1)).max() < G.TOL
+        else:
+            assert np.array_equal(G.dev_to_bits(y3), y_multi)
     # one projection at a time on the column blocks of the same matrix: the same bits; and the oracle
     y_sep = G.bits_to_dev(y0_bits)
     col = 0
@@ -775,6 +783,9 @@ def test_multi_projection_apply_decode_and_prefill():
     heavy.in_features = 1024
     assert heavy.T >= 1024
     _multi_case(heavy, (640, 128, 128), "zero")
+    heavy2 = wl.cfg2_prefill(0, length_scale=0.08)      # 2048 input features: k-slices, token-heavy units cut along k
+    heavy2.in_features = 2048
+    _multi_case(heavy2, (256, 128), "zero")
 
 
 # ------------------------------------------------------------------------------------------------
