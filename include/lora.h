@@ -289,7 +289,8 @@ lora_status_t lora_apply_multi(const lora_pool_t *const *pools, int32_t n_pools,
  * 8192 and the batch is not a mixed one run as merged launches (below): work groups of 16
  * wavefronts, v complete when the unit ends.  Other batches cut k into up to 4 slices per unit (more,
  * smaller units spread a small batch over the chip and fill the last round of a large one better) and
- * add the slices up through counters.  Both plans give bitwise the same v.  Default 1024 (four rounds
+ * add the slices up through counters.  Both plans give bitwise the same v for these groups (token-heavy
+ * groups, whose units a k-slice plan may also cut along k, get another grouping of their sums).  Default 1024 (four rounds
  * of one work group per compute unit); 0 = always k-slices. */
 lora_status_t lora_set_whole_k_limit(int32_t max_units);
 
