@@ -215,14 +215,14 @@ lora_status_t lora_segments_export(const lora_segments_t *seg, int32_t *perm, in
  * group), token count, first row (shrink) or first column (expand), row or column count,
  * k-slice (shrink) or 0}.  Groups of fewer than 32 tokens are cut into shrink units of <= 16 tokens x
  * 16 rank rows x one k-slice; token-heavy groups into shrink units of up to 32 tokens x all rank
- * rows x all of k (listed after the others, k-slice 0; two or four k-slices each in a mixed batch with few such units) and into expand units of up to 64 tokens.
+ * rows x all of k (listed after the others, k-slice 0; in a batch planned in k-slices with few such
+ * units, two or four k-slices each) and into expand units of up to 64 tokens.
  * The order is the launch order: the decode shrink units of one group take places of one residue
  * mod 8 where the counts allow it (the launch's work groups go to the chip's 8 XCDs in turn, and the
  * group's rows of x then stay in one XCD's L2); the 64-token expand units (listed after the others)
  * of one group (its columns in 4 runs, 8 in a launch of few such units) come in rows of 8, each
- * column run with 8 / (column runs) consecutive token tiles, so
- * that a column run's part of B^T is fetched by that many XCDs instead of all 8.  Either output may
- * be NULL. */
+ * column run with 8 / (column runs) consecutive token tiles, so that a column run's part of B^T is
+ * fetched by that many XCDs instead of all 8.  Either output may be NULL. */
 lora_status_t lora_segments_export_units(const lora_segments_t *seg, int32_t *shrink_units,
                                          int32_t *expand_units);
 
@@ -289,9 +289,9 @@ lora_status_t lora_apply_multi(const lora_pool_t *const *pools, int32_t n_pools,
  * 8192 and the batch is not a mixed one run as merged launches (below): work groups of 16
  * wavefronts, v complete when the unit ends.  Other batches cut k into up to 4 slices per unit (more,
  * smaller units spread a small batch over the chip and fill the last round of a large one better) and
- * add the slices up through counters.  Both plans give bitwise the same v for these groups (token-heavy
- * groups, whose units a k-slice plan may also cut along k, get another grouping of their sums).  Default 1024 (four rounds
- * of one work group per compute unit); 0 = always k-slices. */
+ * add the slices up through counters.  Both plans give bitwise the same v for these groups
+ * (token-heavy groups, whose units a k-slice plan may also cut along k, get another grouping of
+ * their sums).  Default 1024 (four rounds of one work group per compute unit); 0 = always k-slices. */
 lora_status_t lora_set_whole_k_limit(int32_t max_units);
 
 /* lora_apply is two launches by default (shrink units, then expand units).  With k-slices the shrink
