@@ -299,10 +299,12 @@ lora_status_t lora_set_whole_k_limit(int32_t max_units);
  * table) adds the k-slices up and leaves the tile's v for the expand units.
  * lora_set_fused_apply(1) selects, for batches planned with k-slices and without token-heavy groups,
  * a single launch in which shrink and expand units share the grid and the expand units poll, with a
- * bounded number of polls, until their tile's v is complete.  The counters' epoch is host state of
- * the segment object, so applies that share one object must be
- * issued by one thread at a time and ordered on one stream, and must not be captured into a graph
- * that is replayed.  The setting is process-wide. */
+ * bounded number of polls, until their tile's v is complete.  Applies that share one segment object
+ * share its counters, so they must be issued by one thread at a time and ordered on one stream.
+ * In the two-launch forms every counter is back at zero when the launch that used it ends, so such
+ * an apply may be captured into a graph and replayed.  The single-launch form takes an epoch from
+ * host state of the segment object at launch: it must not be captured, and not be used on an object
+ * that a captured graph replays.  The setting is process-wide. */
 lora_status_t lora_set_fused_apply(int enabled);
 
 /* A mixed batch holds token-heavy groups and decode-sized groups, whose units are of different kinds.

@@ -1424,8 +1424,9 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
     const int64_t stride = nsl > 1 ? sg->v_floats : 0;
     hipEvent_t ev[3] = {g_prof[0], g_prof[1], g_prof[2]};
     g_prof[0] = g_prof[1] = g_prof[2] = nullptr;
-    // The counters' epoch lives in the segment object, so applies that share an object must be issued
-    // by one thread at a time and ordered on one stream.
+    // The arrival counters live in the segment object's device table (and the single-launch form's
+    // epoch in the object), so applies that share an object must be issued by one thread at a time and
+    // ordered on one stream.
     lora_segments *msg = const_cast<lora_segments *>(sg);
     lora::SyncArgs sa;
     sa.counters = (unsigned *)(sg->dev + sg->off_sync);
@@ -1433,7 +1434,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
     sa.timeout_flag = sa.counters + 2 * sg->n_sync;
     sa.v_hi = (uint16_t *)((char *)workspace + apply_parts_bytes(sg));
     sa.v_lo = (uint16_t *)((char *)workspace + apply_parts_bytes(sg) + apply_packed_bytes(sg));
-    sa.epoch = ++msg->launches;
+    sa.epoch = msg->launches + 1;  // read by the single-launch form only, which also advances it
     sa.spin_limit = kSpinLimit;
     const lora::LaunchCtx cs = ctx_for(arena, in, out, sg, kShrink), cp = ctx_for(arena, in, out, sg, kPrefill),
                           ce = ctx_for(arena, in, out, sg, kExpand), cb = ctx_for(arena, in, out, sg, kExpandBig);
@@ -1441,6 +1442,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
     // units of more than 16 tokens span several counters, and whole-k shrink units are work groups of
     // another size: such batches always take separate launches
     if (g_fused_apply && !sg->has_big_units && !sg->wide) {
+        ++msg->launches;
         HIP_TRY(lora::launch_apply_fused(cs, ce, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride,
                                          (uint16_t *)y, ldy, &sa, s));
         if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));

@@ -50,17 +50,20 @@ static __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __
 // are not coherent with each other, and a device-scope fence (write back / invalidate a whole L2)
 // costs far more than the data is worth.  So the partial sums of v never live in a cache: they are
 // stored and loaded with device-scope relaxed atomics (64 bits at a time), which go through to
-// memory.  A shrink work group waits until its stores have completed, then bumps the counter of its
-// (group, token tile); an expand work group polls that counter until it has reached
-// epoch * (shrink units of the tile).  Counters only grow: epoch is the number of fused launches
-// the table has seen, so nothing is cleared between launches.  The wait is bounded: at the limit
+// memory.  A shrink work group waits until its stores have completed, then bumps the arrival counter
+// of its (group, token tile); the one whose bump completes the tile's count for this launch adds the
+// slices up, sets the arrival counter back to zero (a launch leaves the table as it found it, so a
+// launch replayed from a captured graph finds what the first one found) and bumps the tile's ready
+// counter.  Only the single-launch form reads the ready counters: an expand work group polls its
+// tile's until it has reached epoch, the number of such launches the table has seen (they only
+// grow, so nothing is cleared between launches).  The wait is bounded: at the limit
 // the work group records it in *timeout_flag and goes on, so every wavefront reaches its end.
 // Shrink units come first in the grid and never wait, and work groups are dispatched in grid order,
 // so a waiting expand unit never keeps a shrink unit from running.
 // ------------------------------------------------------------------------------------------------
 struct Sync {
     unsigned *counters;       // arrivals, one per (group, token tile); NULL = no hand-over through counters
-    unsigned *ready;          // one per tile: bumped once per launch when the tile's v is complete
+    unsigned *ready;          // one per tile: bumped once per single-launch apply when the tile's v is complete
     unsigned *timeout_flag;
     uint16_t *v_hi;           // complete v as two bf16 terms, same indexing as the fp32 partial sums
     uint16_t *v_lo;
@@ -267,7 +270,10 @@ static __device__ __forceinline__ void shrink_body(const Unit &u, const uint16_t
             unsigned old = 0;
             if (lane == 0) old = atomicAdd(sy.counters + u.sync_idx, 1u);
             old = __builtin_amdgcn_readfirstlane(old);
-            if (old + 1u == sy.epoch * (unsigned)u.sync_n) {
+            if (old + 1u == (unsigned)u.sync_n) {
+                // the last of this launch's arrivals at the tile: the counter goes back to zero for the
+                // next launch (nothing else touches it before this launch ends)
+                if (lane == 0) atomicExch(sy.counters + u.sync_idx, 0u);
                 const int64_t tile_off = u.v_off - u.p0;
                 const int tasks = ntok * (u.r8 >> 3);
                 for (int task = lane; task < tasks; task += 64) {
@@ -279,7 +285,7 @@ static __device__ __forceinline__ void shrink_body(const Unit &u, const uint16_t
                     st_through_u16x8(sy.v_lo + tile_off + 8 * task, pl);
                 }
                 stores_done();
-                if (lane == 0) atomicAdd(sy.ready + u.sync_idx, 1u);
+                if (sy.wait && lane == 0) atomicAdd(sy.ready + u.sync_idx, 1u);  // polled by the single-launch form only
             }
         }
     }
@@ -644,7 +650,8 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
     unsigned old = 0;
     if (lane == 0) old = atomicAdd(sy.counters + u.sync_idx, 1u);
     old = __builtin_amdgcn_readfirstlane(old);
-    if (old + 1u == sy.epoch * (unsigned)n_ks) {
+    if (old + 1u == (unsigned)n_ks) {
+        if (lane == 0) atomicExch(sy.counters + u.sync_idx, 0u);  // back to zero for the next launch
         const int tasks = ntok * (u.r8 >> 3);
         for (int task = lane; task < tasks; task += 64) {
             f32x4 f0, f1;

@@ -788,6 +788,59 @@ def test_multi_projection_apply_decode_and_prefill():
     _multi_case(heavy2, (256, 128), "zero")
 
 
+def test_apply_replayed_from_a_captured_graph():
+    """The two-launch applies leave the segment object's device table as they found it (the arrival
+    counters of k-slice units go back to zero), so an apply captured into a graph can be replayed:
+    y after n replays is bitwise y after n eager applies.  Decode batch on the whole-k plan, the same
+    on the k-slice plan, and a mixed batch whose token-heavy units are cut along k; other work runs
+    between the replays."""
+    cases = [("whole-k", wl.cfg1_decode(in_features=1024, out_features=512, n_tokens=200, n_adapters=40), None),
+             ("k-slices", wl.cfg1_decode(in_features=2048, out_features=512, n_tokens=200, n_adapters=40), 0),
+             ("mixed", _long_k_mixed(), None)]
+    for name, b, limit in cases:
+        print(f"[case] graph replay {name} T={b.T}", flush=True)
+        if limit is not None:
+            L.lora_set_whole_k_limit(limit)
+        try:
+            dp = G.DevicePool(b)
+            seg = L.lora_segments_build(dp.pool, b.token_adapter)
+        finally:
+            L.lora_set_whole_k_limit(1024)
+        info = L.lora_segments_info(seg)
+        assert (info["n_k_slices"] > 1) == (name != "whole-k")
+        x = G.bits_to_dev(b.x_bits())
+        ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+        y0 = b.y0_bits("small")
+        n_rep = 4
+        y_eager = G.bits_to_dev(y0)
+        for _ in range(n_rep):
+            L.lora_apply(dp.pool, seg, x, y_eager, ws)
+        torch.cuda.synchronize()
+        want = G.dev_to_bits(y_eager)
+        y_graph = G.bits_to_dev(y0)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            L.lora_apply(dp.pool, seg, x, y_graph, ws, stream=torch.cuda.current_stream())
+        y_graph.copy_(G.bits_to_dev(y0))          # whatever the capture did or did not execute
+        scratch = torch.zeros(1 << 20, device="cuda")
+        for _ in range(n_rep):
+            graph.replay()
+            scratch.add_(1.0)                     # eager work between the replays
+            torch.cuda.synchronize()
+        assert np.array_equal(G.dev_to_bits(y_graph), want), name
+        # and an eager apply after the replays still finds the table in order
+        y_after = G.bits_to_dev(y0)
+        L.lora_apply(dp.pool, seg, x, y_after, ws)
+        y_once = G.bits_to_dev(y0)
+        L.lora_apply(dp.pool, seg, x, y_once, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(G.dev_to_bits(y_after), G.dev_to_bits(y_once))
+        L.lora_segments_check(seg)
+        del graph
+        L.lora_segments_destroy(seg)
+        dp.close()
+
+
 # ------------------------------------------------------------------------------------------------
 # Edges of the shape space and of the tiles.
 # ------------------------------------------------------------------------------------------------
