@@ -96,6 +96,7 @@ struct lora_segments {
     size_t staging_capacity;
     size_t off_perm, off_shrink, off_prefill, off_expand, off_expand_big, off_sync, table_bytes;
     bool has_big_units;     // some unit holds more than 16 tokens (token-heavy groups)
+    bool heavy_small_expand;  // a token-heavy group above rank 128: shrunk by token-heavy units, expanded by 16-token units
     bool wide;              // decode shrink units span all of k (work groups of 16 wavefronts, no partial sums)
     int wide_slices, wide_slice_len;  // the k-slices such a work group's wavefronts divide k into
     int n_prefill_hi;       // how many of prefill_units are above rank 64
@@ -670,6 +671,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     }
     sg->n_sync = n_sync;
     sg->has_big_units = false;
+    sg->heavy_small_expand = false;
     sg->n_prefill_hi = 0;
     // A launch of few token-heavy shrink units lasts as long as one unit's walk through k (a wavefront
     // takes a quarter of k in passes of 128, one trip to memory each); such units are cut into k-slices.
@@ -699,6 +701,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
             // shrink: tiles of 32 tokens (16 above rank 128), all rank rows, all of k or (heavy_k_slices
             // > 1) a slice of it, the slices' sums meeting at the counter of the tile's first 16 tokens
             sg->has_big_units = true;
+            if (r.r8 > 128) sg->heavy_small_expand = true;
             const int tile = r.r8 <= 128 ? 32 : 16;
             for (int tok0 = 0; tok0 < r.ntok; tok0 += tile)
                 for (int ks = 0; ks < heavy_k_slices; ++ks) {
@@ -967,6 +970,7 @@ static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const 
         shift(sg->expand_units, n2, delta, (int64_t)q * v_one, (int)q * sync_one, col);
         shift(sg->expand_big_units, n3, delta, (int64_t)q * v_one, (int)q * sync_one, col);
         sg->n_prefill_hi += tmp->n_prefill_hi;
+        sg->heavy_small_expand = sg->heavy_small_expand || tmp->heavy_small_expand;
         sg->mpool_ids.push_back(pools[q]->id);
         sg->msegs.push_back(tmp->segs);
         sg->mepochs.push_back(tmp->seg_epoch);
@@ -1459,7 +1463,10 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
             return LORA_OK;
         }
         hipStream_t sd = s;
-        const bool split = g_side_stream && sg->has_big_units && cs.n_units >= kSideStreamMinUnits;
+        // not when a token-heavy group's v is read by 16-token expand units (groups above rank 128):
+        // those would sit on the side stream, which does not wait for the token-heavy shrink launch
+        const bool split = g_side_stream && sg->has_big_units && !sg->heavy_small_expand &&
+                           cs.n_units >= kSideStreamMinUnits;
         if (split) {
             if (!msg->side) HIP_TRY(hipStreamCreateWithFlags(&msg->side, hipStreamNonBlocking));
             // the two events order launches of this device among themselves and nothing reads them on

@@ -868,3 +868,56 @@ def test_group_sizes_around_the_token_tiles(ntok):
     for big_rank in (1, 3):
         heavy = [big_rank] * ntok + [0] * 700 + [4] * 40 + [2] * 300 + [-1] * 3 + [3, 1, 4]
         _full_parity(_custom(f"tiles_heavy_{ntok}_{big_rank}", 320, 256, ranks, heavy, seed=ntok + 100 * big_rank))
+
+
+def _random_cobatch(seed):
+    """A seeded co-batch of arbitrary structure: feature sizes anywhere on the library's grid, ranks
+    anywhere in 1..256, groups from single tokens to more than a thousand, tokens without adapter,
+    in contiguous runs or scattered."""
+    rng = np.random.default_rng(10_000 + seed)
+    in_f = 64 * int(rng.integers(1, 49))
+    out_f = 128 * int(rng.integers(1, 25))
+    n_adapters = int(rng.integers(1, 13))
+    ranks = np.where(rng.random(n_adapters) < 0.5, rng.choice([8, 16, 32, 64, 128], n_adapters),
+                     rng.integers(1, 257, n_adapters))
+    sizes = []
+    for a in range(n_adapters):
+        kind = rng.random()
+        if kind < 0.15:
+            continue                                    # resident but unused
+        hi = 20 if kind < 0.55 else 70 if kind < 0.75 else 400 if kind < 0.93 else 1500
+        sizes.append((a, int(rng.integers(1, hi + 1))))
+    if seed % 2 and sizes:                              # odd seeds: a batch large enough for token-heavy units
+        a, n = sizes[int(rng.integers(0, len(sizes)))]
+        sizes.append((a, int(rng.integers(600, 1500))))
+    ta = np.concatenate([np.full(n, a, dtype=np.int32) for a, n in sizes]
+                        + [np.full(int(rng.integers(0, 6)), -1, dtype=np.int32)])
+    if rng.random() < 0.5:
+        rng.shuffle(ta)
+    return _custom(f"random_{seed}", in_f, out_f, ranks, ta, seed=seed)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_cobatches_under_random_plan_settings(seed):
+    """Seeded random co-batches, each under a seeded choice of the process-wide plan settings (whole-k
+    limit, single-launch apply, merged launches of mixed batches, side stream): every combination has
+    to meet the oracle."""
+    rng = np.random.default_rng(20_000 + seed)
+    b = _random_cobatch(seed)
+    if b.T == 0:
+        pytest.skip("the draw left no token")
+    limit = int(rng.choice([0, 64, 1024]))
+    fused, merged, side = (bool(rng.integers(0, 2)) for _ in range(3))
+    print(f"[settings] whole_k_limit={limit} fused={fused} merged={merged} side_stream={side} ranks={b.ranks.tolist()}",
+          flush=True)
+    L.lora_set_whole_k_limit(limit)
+    L.lora_set_fused_apply(fused)
+    L.lora_set_merged_launches(merged)
+    L.lora_set_side_stream(side)
+    try:
+        _full_parity(b, y0_kind="small" if seed % 2 else "zero")
+    finally:
+        L.lora_set_whole_k_limit(1024)
+        L.lora_set_fused_apply(False)
+        L.lora_set_merged_launches(True)
+        L.lora_set_side_stream(True)
