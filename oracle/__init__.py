@@ -131,7 +131,11 @@ def lora_apply(x_bits, token_adapter, ranks, scales, A: Sequence[Optional[np.nda
     scales = np.ascontiguousarray(scales, dtype=np.float32)
     A = [None if m is None else _u16(m) for m in A]
     B = [None if m is None else _u16(m) for m in B]
-    out_f = next(m.shape[1] for m in B if m is not None)
+    out_f = next((m.shape[1] for m in B if m is not None), None)
+    if out_f is None:  # no adapter given at all (no token uses one): the width of y comes from y0
+        if y0 is None:
+            raise ValueError("no adapter and no y0: the width of y is not defined")
+        out_f = int(np.shape(y0)[1])
     _check_adapters(A, ranks, ta, lambda r: (in_f, r))
     _check_adapters(B, ranks, ta, lambda r: (r, out_f))
     y0p = None

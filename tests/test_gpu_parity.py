@@ -921,3 +921,96 @@ def test_random_cobatches_under_random_plan_settings(seed):
         L.lora_set_fused_apply(False)
         L.lora_set_merged_launches(True)
         L.lora_set_side_stream(True)
+
+
+@pytest.mark.parametrize("seed", range(100, 112))
+def test_random_cobatches_through_every_entry_point(seed):
+    """Seeded random co-batches under seeded plan settings, through the calls a server makes on one
+    segment object: apply on a non-default stream with x and y inside wider buffers (row strides above
+    the feature sizes, guard columns that must stay as they are), a second apply on top of the first,
+    shrink and expand on their own, then the same object rebuilt for another token->adapter map."""
+    rng = np.random.default_rng(30_000 + seed)
+    b = _random_cobatch(seed)
+    if b.T == 0:
+        pytest.skip("the draw left no token")
+    limit = int(rng.choice([0, 64, 1024]))
+    fused, merged, side = (bool(rng.integers(0, 2)) for _ in range(3))
+    padx, pady = 8 * int(rng.integers(0, 5)), 8 * int(rng.integers(1, 5))
+    print(f"[case] {b.name} T={b.T} in={b.in_features} out={b.out_features} ranks={b.ranks.tolist()} "
+          f"whole_k_limit={limit} fused={fused} merged={merged} side_stream={side} padx={padx} pady={pady}", flush=True)
+    L.lora_set_whole_k_limit(limit)
+    L.lora_set_fused_apply(fused)
+    L.lora_set_merged_launches(merged)
+    L.lora_set_side_stream(side)
+    try:
+        dp = G.DevicePool(b)
+        x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
+        guard = np.uint16(0x7FC1)                     # a NaN pattern: any use of a guard column would show
+        xw = np.full((b.T, b.in_features + padx), guard, dtype=np.uint16)
+        xw[:, :b.in_features] = x_bits
+        yw = np.full((b.T, b.out_features + 2 * pady), guard, dtype=np.uint16)
+        yw[:, pady:pady + b.out_features] = y0_bits
+        x_dev = G.bits_to_dev(xw)
+        y_dev = G.bits_to_dev(yw)
+        x_view, y_view = x_dev[:, :b.in_features], y_dev[:, pady:pady + b.out_features]
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            seg = L.lora_segments_build(dp.pool, b.token_adapter, stream=stream)
+            ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+            L.lora_apply(dp.pool, seg, x_view, y_view, ws, stream=stream)
+            y1 = y_dev.clone()
+            L.lora_apply(dp.pool, seg, x_view, y_view, ws, stream=stream)
+            y2 = y_dev.clone()
+        stream.synchronize()
+        L.lora_segments_check(seg, stream=stream)
+        y1w, y2w = G.dev_to_bits(y1), G.dev_to_bits(y2)
+        for yw_after in (y1w, y2w):
+            assert (yw_after[:, :pady] == guard).all() and (yw_after[:, pady + b.out_features:] == guard).all()
+        y1_bits = np.ascontiguousarray(y1w[:, pady:pady + b.out_features])
+        y2_bits = np.ascontiguousarray(y2w[:, pady:pady + b.out_features])
+        G.check_parity(y1_bits, G.oracle_apply(dp, x_bits, y0_bits), y0_bits, b.token_adapter)
+        G.check_parity(y2_bits, G.oracle_apply(dp, x_bits, y1_bits), y1_bits, b.token_adapter)
+
+        # shrink and expand on their own, same object, default stream
+        info = L.lora_segments_info(seg)
+        v = torch.full((max(info["v_floats"], 1),), float("nan"), dtype=torch.float32, device="cuda")
+        ws2 = torch.empty(max(L.lora_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+        y_sep = G.bits_to_dev(y0_bits)
+        L.lora_shrink(dp.pool, seg, x_view, v, ws2)
+        L.lora_expand(dp.pool, seg, v, y_sep)
+        torch.cuda.synchronize()
+        assert not torch.isnan(v[:info["v_floats"]]).any(), "an entry of v was not written"
+        G.check_parity(G.dev_to_bits(y_sep), G.oracle_apply(dp, x_bits, y0_bits), y0_bits, b.token_adapter)
+
+        # the same object for another map over the same adapters (some tokens lose theirs)
+        ta2 = b.token_adapter.copy()
+        rng.shuffle(ta2)
+        ta2[rng.random(b.T) < 0.1] = -1
+        L.lora_segments_rebuild(seg, ta2)
+        ws3 = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+        y3 = G.bits_to_dev(y0_bits)
+        for _ in range(2):                       # twice from the same y0: the second must not see the first's counters
+            y3.copy_(G.bits_to_dev(y0_bits))
+            L.lora_apply(dp.pool, seg, x_view, y3, ws3)
+        torch.cuda.synchronize()
+        L.lora_segments_check(seg)
+        G.check_parity(G.dev_to_bits(y3), G.oracle_apply(dp, x_bits, y0_bits, token_adapter=ta2), y0_bits, ta2)
+        L.lora_segments_destroy(seg)
+        dp.close()
+    finally:
+        L.lora_set_whole_k_limit(1024)
+        L.lora_set_fused_apply(False)
+        L.lora_set_merged_launches(True)
+        L.lora_set_side_stream(True)
+
+
+@pytest.mark.parametrize("seed", range(200, 208))
+def test_random_cobatches_over_several_projections(seed):
+    """Seeded random co-batches through lora_apply_multi over two or three projections of seeded widths:
+    the same bits as one apply per projection, in every form of a mixed batch, and the oracle's values."""
+    rng = np.random.default_rng(40_000 + seed)
+    b = _random_cobatch(seed)
+    if not (b.token_adapter >= 0).any():
+        pytest.skip("the draw left no token with an adapter")
+    outs = [128 * int(rng.integers(1, 13)) for _ in range(int(rng.integers(2, 4)))]
+    _multi_case(b, outs, y0_kind="small" if seed % 2 else "zero")
