@@ -301,8 +301,10 @@ lora_status_t lora_set_whole_k_limit(int32_t max_units);
  * a single launch in which shrink and expand units share the grid and the expand units poll, with a
  * bounded number of polls, until their tile's v is complete.  Applies that share one segment object
  * share its counters, so they must be issued by one thread at a time and ordered on one stream.
- * In the two-launch forms every counter is back at zero when the launch that used it ends, so such
- * an apply may be captured into a graph and replayed.  The single-launch form takes an epoch from
+ * In the forms of separate shrink and expand launches every counter is back at zero when the launch
+ * that used it ends, so such an apply may be captured into a graph and replayed (the form of a mixed
+ * batch that uses the object's own stream makes that stream and its two events at the object's
+ * first such apply, which has to come before the capture).  The single-launch form takes an epoch from
  * host state of the segment object at launch: it must not be captured, and not be used on an object
  * that a captured graph replays.  The setting is process-wide. */
 lora_status_t lora_set_fused_apply(int enabled);

@@ -796,7 +796,8 @@ def test_apply_replayed_from_a_captured_graph():
     between the replays."""
     cases = [("whole-k", wl.cfg1_decode(in_features=1024, out_features=512, n_tokens=200, n_adapters=40), None),
              ("k-slices", wl.cfg1_decode(in_features=2048, out_features=512, n_tokens=200, n_adapters=40), 0),
-             ("mixed", _long_k_mixed(), None)]
+             ("mixed", _long_k_mixed(), None),
+             ("mixed, own stream", wl.cfg3_stack(layer=3, projection=1), None)]
     for name, b, limit in cases:
         print(f"[case] graph replay {name} T={b.T}", flush=True)
         if limit is not None:
@@ -806,39 +807,48 @@ def test_apply_replayed_from_a_captured_graph():
             seg = L.lora_segments_build(dp.pool, b.token_adapter)
         finally:
             L.lora_set_whole_k_limit(1024)
-        info = L.lora_segments_info(seg)
-        assert (info["n_k_slices"] > 1) == (name != "whole-k")
-        x = G.bits_to_dev(b.x_bits())
-        ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
-        y0 = b.y0_bits("small")
-        n_rep = 4
-        y_eager = G.bits_to_dev(y0)
-        for _ in range(n_rep):
-            L.lora_apply(dp.pool, seg, x, y_eager, ws)
-        torch.cuda.synchronize()
-        want = G.dev_to_bits(y_eager)
-        y_graph = G.bits_to_dev(y0)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            L.lora_apply(dp.pool, seg, x, y_graph, ws, stream=torch.cuda.current_stream())
-        y_graph.copy_(G.bits_to_dev(y0))          # whatever the capture did or did not execute
-        scratch = torch.zeros(1 << 20, device="cuda")
-        for _ in range(n_rep):
-            graph.replay()
-            scratch.add_(1.0)                     # eager work between the replays
-            torch.cuda.synchronize()
-        assert np.array_equal(G.dev_to_bits(y_graph), want), name
-        # and an eager apply after the replays still finds the table in order
-        y_after = G.bits_to_dev(y0)
-        L.lora_apply(dp.pool, seg, x, y_after, ws)
-        y_once = G.bits_to_dev(y0)
-        L.lora_apply(dp.pool, seg, x, y_once, ws)
-        torch.cuda.synchronize()
-        assert np.array_equal(G.dev_to_bits(y_after), G.dev_to_bits(y_once))
-        L.lora_segments_check(seg)
-        del graph
+        assert (L.lora_segments_info(seg)["n_k_slices"] > 1) == (name != "whole-k")
+        # the four-launch form of a mixed batch (decode-sized pair on the object's own stream, made at
+        # the first apply: the eager applies below come before the capture) is chosen at apply time
+        L.lora_set_merged_launches(name != "mixed, own stream")
+        try:
+            _graph_replay_case(name, b, dp, seg)
+        finally:
+            L.lora_set_merged_launches(True)
         L.lora_segments_destroy(seg)
         dp.close()
+
+
+def _graph_replay_case(name, b, dp, seg):
+    x = G.bits_to_dev(b.x_bits())
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+    y0 = b.y0_bits("small")
+    n_rep = 4
+    y_eager = G.bits_to_dev(y0)
+    for _ in range(n_rep):
+        L.lora_apply(dp.pool, seg, x, y_eager, ws)
+    torch.cuda.synchronize()
+    want = G.dev_to_bits(y_eager)
+    y_graph = G.bits_to_dev(y0)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        L.lora_apply(dp.pool, seg, x, y_graph, ws, stream=torch.cuda.current_stream())
+    y_graph.copy_(G.bits_to_dev(y0))          # whatever the capture did or did not execute
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for _ in range(n_rep):
+        graph.replay()
+        scratch.add_(1.0)                     # eager work between the replays
+        torch.cuda.synchronize()
+    assert np.array_equal(G.dev_to_bits(y_graph), want), name
+    # and an eager apply after the replays still finds the table in order
+    y_after = G.bits_to_dev(y0)
+    L.lora_apply(dp.pool, seg, x, y_after, ws)
+    y_once = G.bits_to_dev(y0)
+    L.lora_apply(dp.pool, seg, x, y_once, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(G.dev_to_bits(y_after), G.dev_to_bits(y_once))
+    L.lora_segments_check(seg)
+    del graph
 
 
 # ------------------------------------------------------------------------------------------------
