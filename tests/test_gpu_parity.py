@@ -1024,3 +1024,12 @@ def test_random_cobatches_over_several_projections(seed):
         pytest.skip("the draw left no token with an adapter")
     outs = [128 * int(rng.integers(1, 13)) for _ in range(int(rng.integers(2, 4)))]
     _multi_case(b, outs, y0_kind="small" if seed % 2 else "zero")
+
+
+def test_two_hundred_thousand_tokens():
+    """A batch far beyond the configurations' sizes (200,003 tokens, two token-heavy groups and a few
+    scattered tokens): thousands of units per launch, token offsets beyond 2^16 tiles, v beyond 2^24 floats."""
+    ta = np.concatenate([np.full(150_000, 0), np.full(50_000, 1), [2, 3, -1]]).astype(np.int32)
+    np.random.default_rng(7).shuffle(ta)
+    b = _custom("many_tokens", 256, 256, [16, 128, 40, 200], ta, seed=7)
+    _full_parity(b, y0_kind="small")
