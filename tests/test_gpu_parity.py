@@ -1033,3 +1033,33 @@ def test_two_hundred_thousand_tokens():
     np.random.default_rng(7).shuffle(ta)
     b = _custom("many_tokens", 256, 256, [16, 128, 40, 200], ta, seed=7)
     _full_parity(b, y0_kind="small")
+
+
+def test_adapters_placed_beyond_four_gigabytes():
+    """A live pool over a 4.6 GB arena whose first 4.3 GB are reserved for other adapters: the adapters
+    a batch uses lie beyond byte 2^32 (element offsets beyond 2^31).  A mixed batch (token-heavy units,
+    64-token expand units, k-slice units) and a decode batch (whole-k units) against the oracle."""
+    import types
+    n_fill, in_f, out_f = 1040, 4096, 4096
+    ranks = np.array([256] * n_fill + [128, 256, 64, 8], dtype=np.int32)
+    a0 = n_fill
+    heavy = [a0] * 1100 + [a0 + 1] * 40 + [a0 + 2] * 300 + [a0 + 3, a0 + 1, -1, a0 + 3] * 5
+    for name, ta in (("mixed", heavy), ("decode", [a0, a0 + 1, a0 + 3, a0 + 2, a0 + 1, -1] * 5)):
+        b = _custom(f"beyond_4g_{name}", in_f, out_f, ranks, ta, seed=11)
+        arena = torch.empty(4_600_000_000, dtype=torch.uint8, device="cuda")
+        pool = L.lora_pool_create_live(in_f, out_f, b.ranks, b.scales, arena)
+        for a in range(n_fill):
+            L.lora_pool_reserve(pool, a)
+        A, B = [None] * b.n_adapters, [None] * b.n_adapters
+        for a in range(a0, a0 + 4):
+            A[a], B[a] = b.adapter_bits(a)
+            L.lora_pool_load(pool, a, A[a], B[a])
+            info = L.lora_pool_adapter_info(pool, a)
+            assert 2 * min(info["a_offset"], info["b_offset"]) >= 1 << 32, info     # offsets count bf16 elements
+        dp = types.SimpleNamespace(batch=b, pool=pool, A=A, B=B)
+        x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
+        print(f"[case] {b.name} T={b.T}", flush=True)
+        y_bits = G.apply_on_gpu(dp, x_bits, y0_bits)
+        G.check_parity(y_bits, G.oracle_apply(dp, x_bits, y0_bits), y0_bits, b.token_adapter)
+        L.lora_pool_destroy(pool)
+        del arena
