@@ -256,7 +256,9 @@ lora_status_t lora_shrink(const lora_pool_t *pool, const lora_segments_t *seg, c
 lora_status_t lora_expand(const lora_pool_t *pool, const lora_segments_t *seg, const float *v, void *y,
                           int64_t ldy, void *stream);
 
-/* Shrink then expand on one stream.  v never leaves the workspace, whose size
+/* Shrink then expand on one stream.  x, y, the workspace and the pool's arena must not overlap one
+ * another (the launches read x and the arena while they write the workspace and y; nothing checks
+ * this).  v never leaves the workspace, whose size
  * lora_apply_workspace_bytes gives (the k-slices' partial sums of v; the expand adds them up, in
  * slice order, while it loads them). */
 lora_status_t lora_apply_workspace_bytes(const lora_pool_t *pool, const lora_segments_t *seg, size_t *bytes);
@@ -304,7 +306,9 @@ lora_status_t lora_set_whole_k_limit(int32_t max_units);
  * In the forms of separate shrink and expand launches every counter is back at zero when the launch
  * that used it ends, so such an apply may be captured into a graph and replayed (the form of a mixed
  * batch that uses the object's own stream makes that stream and its two events at the object's
- * first such apply, which has to come before the capture).  The single-launch form takes an epoch from
+ * first such apply, which has to come before the capture).  A captured apply holds the launch sizes
+ * and the table address of the plan it was captured with: after lora_segments_rebuild on the
+ * object, capture again.  The single-launch form takes an epoch from
  * host state of the segment object at launch: it must not be captured, and not be used on an object
  * that a captured graph replays.  The setting is process-wide. */
 lora_status_t lora_set_fused_apply(int enabled);
