@@ -80,8 +80,21 @@ class Hip:
         self.rt.hipEventDestroy(e)
 
 
-def pick_workload(spec: str, wl):
+def pick_workload(spec: str, wl, tp: str = None):
     """-> (batch, description, default projections per step, seeded host weights?)"""
+    if tp:
+        # one GPU's shard of a tensor-parallel layer: a column-parallel layer keeps A_a and holds
+        # out/N columns of B_a, a row-parallel layer holds in/N rows of A_a and all of B_a (its v is
+        # what the ranks would sum before the expand; that exchange needs other GPUs and is not run)
+        import dataclasses
+        n, kind = tp.split(":")
+        n = int(n)
+        b, description, layers, seeded = pick_workload(spec, wl)
+        in_f, out_f = (b.in_features, b.out_features // n) if kind == "col" else (b.in_features // n, b.out_features)
+        if kind not in ("col", "row") or in_f % 64 or out_f % 128 or n < 1:
+            raise SystemExit(f"--tp {tp}: want <N>:col or <N>:row with in/N a multiple of 64, out/N of 128")
+        b = dataclasses.replace(b, name=f"{b.name}_tp{n}{kind}", in_features=in_f, out_features=out_f)
+        return b, f"{description}; tensor-parallel shard 1/{n} ({kind}): {in_f}->{out_f}", layers, seeded
     parts = spec.split(":")
     kind = parts[0]
     if kind == "cfg1":
@@ -290,6 +303,10 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg1",
                     help="cfg1 (default, the benchmark line) | cfg2:<shape 0..2> | cfg3:<projection 0..6>[:<prompt length scale>] | "
                          "cfg4:<shape 0..2>:<9to1|1to1|1to9>[:<0|1> only that rank class]")
+    ap.add_argument("--tp", default=None, metavar="N:col|N:row",
+                    help="time one GPU's shard of the workload's projection under N-way tensor parallelism: "
+                         "col = out_features/N columns of B (column-parallel layer), row = in_features/N rows of A "
+                         "(row-parallel layer; the sum of v over the ranks is not part of the run)")
     ap.add_argument("--fused", action="store_true", help="single-launch lora_apply (decode-sized batches)")
     ap.add_argument("--mixed-form", choices=("merged", "two-streams", "one-stream"), default="merged",
                     help="how a mixed batch (token-heavy and decode-sized groups) is launched: two launches that "
@@ -336,7 +353,7 @@ def main() -> int:
     if args.projections:
         return run_projections(args, torch, L, wl, dev, stream, hip)
 
-    b0, description, default_layers, seeded = pick_workload(args.workload, wl)
+    b0, description, default_layers, seeded = pick_workload(args.workload, wl, args.tp)
     nl = args.layers or default_layers
     T, in_f, out_f = b0.T, b0.in_features, b0.out_features
 

@@ -1063,3 +1063,15 @@ def test_adapters_placed_beyond_four_gigabytes():
         G.check_parity(y_bits, G.oracle_apply(dp, x_bits, y0_bits), y0_bits, b.token_adapter)
         L.lora_pool_destroy(pool)
         del arena
+
+
+@pytest.mark.parametrize("kind", ["col", "row"])
+def test_tensor_parallel_shard_shapes(kind):
+    """One GPU's shard of the 70B shapes under 8-way tensor parallelism: 8192 -> 28672/8 (a column-parallel
+    layer's columns of B) and 28672/8 -> 8192 (a row-parallel layer's rows of A), rank-skew routing."""
+    import dataclasses
+    if kind == "col":
+        b = dataclasses.replace(wl.cfg4_skew(1, "1:1"), name="cfg4_tp8col", out_features=28672 // 8)
+    else:
+        b = dataclasses.replace(wl.cfg4_skew(2, "1:1"), name="cfg4_tp8row", in_features=28672 // 8)
+    _full_parity(b, y0_kind="small")
