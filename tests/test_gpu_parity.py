@@ -1075,3 +1075,75 @@ def test_tensor_parallel_shard_shapes(kind):
     else:
         b = dataclasses.replace(wl.cfg4_skew(2, "1:1"), name="cfg4_tp8row", in_features=28672 // 8)
     _full_parity(b, y0_kind="small")
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_live_pool_under_random_operations(seed):
+    """A seeded sequence of loads, evictions, reloads with other weights, compactions (with and without
+    a scratch buffer) and batches on an arena that holds about half of the adapters: every batch over
+    the adapters resident at that moment matches the oracle on the weights loaded last, a load that
+    does not fit says so, and the pool's free bytes follow the model."""
+    rng = np.random.default_rng(60_000 + seed)
+    in_f, out_f = 64 * int(rng.integers(2, 17)), 128 * int(rng.integers(1, 9))
+    n = 14
+    ranks = rng.integers(1, 257, n).astype(np.int32)
+    size = lambda a: 2 * int((ranks[a] + 7) // 8 * 8) * (in_f + out_f)
+    total = sum(size(a) for a in range(n))
+    arena_bytes = (total // 2 + 4096) // 256 * 256
+    ta0 = rng.integers(0, n, size=int(rng.integers(20, 200))).astype(np.int32)
+    b = _custom(f"live_random_{seed}", in_f, out_f, ranks, ta0, seed=seed)
+    arena = torch.zeros(arena_bytes, dtype=torch.uint8, device="cuda")
+    pool = L.lora_pool_create_live(in_f, out_f, ranks, b.scales, arena)
+    x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
+    x = G.bits_to_dev(x_bits)
+    A, B = [None] * n, [None] * n              # what each resident adapter holds now
+    version = [0] * n
+    resident = set()
+    scratch = torch.empty(max(size(a) for a in range(n)), dtype=torch.uint8, device="cuda")
+    segs, batches = [], 0
+    print(f"[case] {b.name} in={in_f} out={out_f} ranks={ranks.tolist()} arena={arena_bytes}", flush=True)
+    for step in range(60):
+        op = rng.random()
+        if op < 0.40:                                        # load (or reload with other weights)
+            a = int(rng.integers(0, n))
+            version[a] += 1
+            src = _with_seed(b, 1000 * version[a] + seed)
+            Aa, Ba = src.adapter_bits(a)
+            free = L.lora_pool_space(pool)
+            try:
+                L.lora_pool_load(pool, a, Aa, Ba)
+                A[a], B[a] = Aa, Ba
+                resident.add(a)
+            except L.LoraError as e:
+                assert e.status_name == "LORA_ERR_OOM", e
+                assert a not in resident and free["largest_free_bytes"] < size(a)
+        elif op < 0.60 and resident:                         # evict
+            a = int(rng.choice(sorted(resident)))
+            L.lora_pool_evict(pool, a)
+            resident.discard(a)
+            A[a] = B[a] = None
+        elif op < 0.70:                                      # compact
+            L.lora_pool_compact(pool, scratch if rng.random() < 0.5 else None)
+            sp = L.lora_pool_space(pool)
+            assert sp["free_bytes"] == sp["largest_free_bytes"]
+        elif resident:                                       # a batch over what is resident now
+            ta = b.token_adapter.copy()
+            ta[:] = rng.choice(np.asarray(sorted(resident), dtype=np.int32), size=b.T)
+            ta[rng.random(b.T) < 0.05] = -1
+            seg, y = _apply_live(pool, b, ta, x, y0_bits)
+            segs.append(seg)
+            y_ref = oracle.lora_apply(x_bits, ta, ranks, b.scales, A, B, y0=wl.bf16_bits_to_f64(y0_bits))
+            G.check_parity(y, y_ref, y0_bits, ta)
+            batches += 1
+        used = sum(size(a) for a in resident)
+        assert L.lora_pool_space(pool)["free_bytes"] <= arena_bytes - used
+        assert L.lora_pool_space(pool)["free_bytes"] >= arena_bytes - used - 256 * (len(resident) + 1)
+    assert batches >= 3
+    for s in segs:
+        L.lora_segments_destroy(s)
+    L.lora_pool_destroy(pool)
+
+
+def _with_seed(b, seed):
+    import dataclasses
+    return dataclasses.replace(b, seed=seed)
