@@ -1147,3 +1147,46 @@ def test_live_pool_under_random_operations(seed):
 def _with_seed(b, seed):
     import dataclasses
     return dataclasses.replace(b, seed=seed)
+
+
+def test_plan_then_upload_and_the_measurement_hook():
+    """lora_segments_plan + lora_segments_upload give the object lora_segments_build gives (same bits
+    from an apply); a planned object that was never uploaded is refused; the measurement hook records
+    its three events around the next apply's launches, in order, without changing the result."""
+    import ctypes
+    b = wl.cfg1_decode(in_features=2048, out_features=1024, n_tokens=100, n_adapters=30)
+    dp = G.DevicePool(b)
+    x, y0_bits = G.bits_to_dev(b.x_bits()), b.y0_bits("small")
+    built = L.lora_segments_build(dp.pool, b.token_adapter)
+    planned = L.lora_segments_plan(dp.pool, b.token_adapter)
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, built), 256), dtype=torch.uint8, device="cuda")
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply(dp.pool, planned, x, G.bits_to_dev(y0_bits), ws)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG" and "upload" in e.value.detail
+    stream = torch.cuda.Stream()
+    L.lora_segments_upload(planned, stream=stream)
+    ys = []
+    rt = ctypes.CDLL("libamdhip64.so")
+    events = [ctypes.c_void_p() for _ in range(3)]
+    for ev in events:
+        assert rt.hipEventCreate(ctypes.byref(ev)) == 0
+    with torch.cuda.stream(stream):
+        for seg, hook in ((built, False), (planned, False), (planned, True), (planned, False)):
+            y = G.bits_to_dev(y0_bits)
+            if hook:
+                L.lora_profile_next_apply(*events)
+            L.lora_apply(dp.pool, seg, x, y, ws, stream=stream)
+            ys.append(y)
+    stream.synchronize()
+    bits = [G.dev_to_bits(y) for y in ys]
+    assert all(np.array_equal(bits[0], other) for other in bits[1:])
+    G.check_parity(bits[0], G.oracle_apply(dp, b.x_bits(), y0_bits), y0_bits, b.token_adapter)
+    ms = ctypes.c_float()
+    for first, second in ((0, 1), (1, 2)):
+        assert rt.hipEventElapsedTime(ctypes.byref(ms), events[first], events[second]) == 0
+        assert 0.0 < ms.value < 50.0, ms.value         # one launch each: microseconds, not the whole loop
+    for ev in events:
+        rt.hipEventDestroy(ev)
+    L.lora_segments_destroy(built)
+    L.lora_segments_destroy(planned)
+    dp.close()
