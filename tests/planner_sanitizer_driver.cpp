@@ -1,12 +1,16 @@
 // Host-only sanitizer run of the planner (AddressSanitizer + UndefinedBehaviorSanitizer): random pools and
 // batches through lora_segments_plan, lora_segments_plan_multi and the export calls.  The launch entry
-// points of the kernels are stubbed: nothing here touches a GPU.  Built and run by test_host_sanitizers.py.
+// points of the kernels are stubbed: nothing here touches a GPU.  With the argument "threads" (and built
+// with ThreadSanitizer instead) four threads plan on pools of their own at once.  Built and run by
+// test_host_sanitizers.py.
 #include "lora.h"
 #include "lora_placement.h"
 #include "lora_internal.h"
 #include <cstdio>
 #include <cstdlib>
 #include <random>
+#include <string>
+#include <thread>
 #include <vector>
 namespace lora {
 hipError_t launch_shrink(const LaunchCtx &, const uint16_t *, int64_t, int, float *, int, int64_t, const SyncArgs *, hipStream_t) { return hipSuccess; }
@@ -20,21 +24,22 @@ hipError_t launch_reduce_slices(const float *, int, int64_t, float *, int64_t, h
 hipError_t launch_pack_adapter(const uint16_t *, const uint16_t *, int, int, int, int, uint16_t *, uint16_t *, hipStream_t) { return hipSuccess; }
 }
 #define LK(x) do{lora_status_t s_=(x); if(s_!=LORA_OK){printf("ERR %s: %s %s\n",#x,lora_status_string(s_),lora_last_error()); return 1;} }while(0)
-int main(){
-  std::mt19937 g(1);
-  for (int iter = 0; iter < 300; ++iter) {
+// One round on objects of its own: a pool, a plan, its exports, now and then a second pool and a plan
+// over both.  `knobs`: also flip a process-wide setting (only where a single thread runs).
+static int pool_round(std::mt19937 &g, int iter, bool knobs, uintptr_t arena_base){
+  {
     const int in = 64 * (1 + g() % 128), out = 128 * (1 + g() % 64), N = 1 + g() % 200;
     std::vector<int32_t> ranks(N); std::vector<float> scales(N);
     for (int a = 0; a < N; ++a) { ranks[a] = (g() % 4 == 0) ? 1 + g() % 256 : (8 << (g() % 6)); scales[a] = 2.f / ranks[a]; }
     lora_pool_desc_t d{in, out, N, ranks.data(), scales.data(), LORA_BF16};
     size_t ab; LK(lora_pool_bytes(&d, &ab));
-    lora_pool_t *pool; LK(lora_pool_create(&d, (void *)0x10000000, ab, &pool));
+    lora_pool_t *pool; LK(lora_pool_create(&d, (void *)arena_base, ab, &pool));
     for (int a = 0; a < N; ++a) LK(lora_pool_mark_resident(pool, a));
     const int T = g() % 3 == 0 ? 1 + g() % 4000 : 1 + g() % 600;
     std::vector<int32_t> ta(T);
     const int hot = g() % N;
     for (auto &t : ta) { unsigned r = g() % 10; t = r == 0 ? -1 : (r < 4 ? hot : (int)(g() % N)); }
-    if (iter % 7 == 0) lora_set_whole_k_limit(0); else lora_set_whole_k_limit(1024);
+    if (knobs) { if (iter % 7 == 0) lora_set_whole_k_limit(0); else lora_set_whole_k_limit(1024); }
     lora_segments_t *seg; LK(lora_segments_plan(pool, ta.data(), T, &seg));
     lora_segments_info_t info; LK(lora_segments_info(seg, &info));
     std::vector<int32_t> su(6 * (size_t)info.n_shrink_units), eu(6 * (size_t)info.n_expand_units), perm(info.n_active), ss(info.n_segments + 1), sa(info.n_segments);
@@ -49,7 +54,7 @@ int main(){
     if (iter % 5 == 0) {
       lora_pool_desc_t d2{in, 128 * (1 + (int)(g() % 16)), N, ranks.data(), scales.data(), LORA_BF16};
       size_t ab2; LK(lora_pool_bytes(&d2, &ab2));
-      lora_pool_t *p2; LK(lora_pool_create(&d2, (void *)(0x10000000 + ((ab + 4095) & ~4095ull)), ab2, &p2));
+      lora_pool_t *p2; LK(lora_pool_create(&d2, (void *)(arena_base + ((ab + 4095) & ~4095ull)), ab2, &p2));
       for (int a = 0; a < N; ++a) LK(lora_pool_mark_resident(p2, a));
       const lora_pool_t *pl[2] = {pool, p2};
       lora_segments_t *m; LK(lora_segments_plan_multi(pl, 2, ta.data(), T, &m));
@@ -60,6 +65,27 @@ int main(){
     }
     LK(lora_pool_destroy(pool));
   }
+  return 0;
+}
+int main(int argc, char **argv){
+  if (argc > 1 && std::string(argv[1]) == "threads") {
+    // the header's rule: objects that have nothing to do with each other may be used from different
+    // threads at once (built with -fsanitize=thread)
+    std::vector<std::thread> th;
+    std::vector<int> rc(4, 0);
+    for (int t = 0; t < 4; ++t)
+      th.emplace_back([t, &rc]{
+        std::mt19937 g(100 + t);
+        for (int iter = 0; iter < 60 && !rc[t]; ++iter) rc[t] = pool_round(g, iter, false, (uintptr_t)0x10000000 + ((uintptr_t)t << 32));
+      });
+    for (auto &x : th) x.join();
+    for (int r : rc) if (r) return 1;
+    printf("planner thread run ok\n");
+    return 0;
+  }
+  std::mt19937 g(1);
+  for (int iter = 0; iter < 300; ++iter)
+    if (pool_round(g, iter, true, 0x10000000)) return 1;
   // the placement routine (host only): random demands, with and without a previous table
   for (int iter = 0; iter < 200; ++iter) {
     const int S = 1 + g() % 12, N = g() % 120;
