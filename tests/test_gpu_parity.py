@@ -937,8 +937,8 @@ def test_random_cobatches_under_random_plan_settings(seed):
 def test_random_cobatches_through_every_entry_point(seed):
     """Seeded random co-batches under seeded plan settings, through the calls a server makes on one
     segment object: apply on a non-default stream with x and y inside wider buffers (row strides above
-    the feature sizes, guard columns that must stay as they are), a second apply on top of the first,
-    shrink and expand on their own, then the same object rebuilt for another token->adapter map."""
+    the feature sizes, guard columns that must stay as they are), a second apply on top of the first
+    under other apply-time settings, shrink and expand on their own, then the same object rebuilt for another token->adapter map."""
     rng = np.random.default_rng(30_000 + seed)
     b = _random_cobatch(seed)
     if b.T == 0:
@@ -969,6 +969,10 @@ def test_random_cobatches_through_every_entry_point(seed):
             ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
             L.lora_apply(dp.pool, seg, x_view, y_view, ws, stream=stream)
             y1 = y_dev.clone()
+            # the settings that act when an apply is issued, drawn again: the object's plan stays
+            L.lora_set_fused_apply(bool(rng.integers(0, 2)))
+            L.lora_set_merged_launches(bool(rng.integers(0, 2)))
+            L.lora_set_side_stream(bool(rng.integers(0, 2)))
             L.lora_apply(dp.pool, seg, x_view, y_view, ws, stream=stream)
             y2 = y_dev.clone()
         stream.synchronize()
