@@ -336,8 +336,15 @@ lora_status_t lora_set_fused_apply(int enabled);
 lora_status_t lora_set_merged_launches(int enabled);
 lora_status_t lora_set_side_stream(int enabled);
 
+/* Polls an expand unit of the single-launch apply makes before it gives up waiting, flags the object
+ * and goes on with whatever v holds (default 2^18; 0 restores the default).  Process-wide.  A small
+ * value makes the give-up path reachable on a healthy machine, which is what it is for: every
+ * wavefront still ends, lora_segments_check then reports the apply as failed. */
+lora_status_t lora_set_fused_wait_limit(uint32_t polls);
+
 /* Synchronises `stream` and reports LORA_ERR_DEVICE if an expand unit of an earlier fused lora_apply
- * on this object ran into its (bounded) wait limit, in which case that apply's y is not valid. */
+ * on this object ran into its (bounded) wait limit, in which case that apply's y is not valid.  The
+ * flag stays until the object's table is uploaded again (lora_segments_rebuild / _upload). */
 lora_status_t lora_segments_check(const lora_segments_t *seg, void *stream);
 
 /* Measurement hook.  The next lora_apply on the calling thread records the given hipEvent_t handles

@@ -29,7 +29,7 @@ EXPORTS = (
     "lora_segments_export", "lora_segments_export_units", "lora_segments_destroy", "lora_workspace_bytes",
     "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_profile_next_apply",
     "lora_segments_plan_multi", "lora_segments_build_multi", "lora_apply_multi",
-    "lora_set_fused_apply", "lora_set_whole_k_limit", "lora_segments_check", "lora_set_side_stream", "lora_set_merged_launches",
+    "lora_set_fused_apply", "lora_set_whole_k_limit", "lora_segments_check", "lora_set_side_stream", "lora_set_merged_launches", "lora_set_fused_wait_limit",
     "lora_status_string",
     "lora_last_error",
     "lora_place_extrapolate", "lora_place_assign",
@@ -373,6 +373,10 @@ def lora_set_side_stream(enabled: bool) -> None:
 
 def lora_set_merged_launches(enabled: bool) -> None:
     _check(lib().lora_set_merged_launches(ctypes.c_int(1 if enabled else 0)))
+
+
+def lora_set_fused_wait_limit(polls: int) -> None:
+    _check(lib().lora_set_fused_wait_limit(ctypes.c_uint32(polls)))
 
 
 def lora_set_whole_k_limit(max_units: int) -> None:

@@ -1368,6 +1368,7 @@ static int g_side_stream = 1;
 static const int kSideStreamMinUnits = 32;  // decode shrink units below which a second stream is not worth its events
 static int g_fused_apply = 0;
 static const unsigned kSpinLimit = 1u << 18;  // polls of a waiting expand unit before it gives up
+static unsigned g_spin_limit = kSpinLimit;
 
 extern "C" lora_status_t lora_set_fused_apply(int enabled)
 try {
@@ -1389,6 +1390,12 @@ try {
     return LORA_OK;
 }
 API_CATCH
+
+extern "C" lora_status_t lora_set_fused_wait_limit(uint32_t polls)
+{
+    g_spin_limit = polls ? polls : kSpinLimit;
+    return LORA_OK;
+}
 
 extern "C" lora_status_t lora_segments_check(const lora_segments_t *sg, void *stream)
 try {
@@ -1439,7 +1446,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
     sa.v_hi = (uint16_t *)((char *)workspace + apply_parts_bytes(sg));
     sa.v_lo = (uint16_t *)((char *)workspace + apply_parts_bytes(sg) + apply_packed_bytes(sg));
     sa.epoch = msg->launches + 1;  // read by the single-launch form only, which also advances it
-    sa.spin_limit = kSpinLimit;
+    sa.spin_limit = g_spin_limit;
     const lora::LaunchCtx cs = ctx_for(arena, in, out, sg, kShrink), cp = ctx_for(arena, in, out, sg, kPrefill),
                           ce = ctx_for(arena, in, out, sg, kExpand), cb = ctx_for(arena, in, out, sg, kExpandBig);
     if (ev[0]) HIP_TRY(hipEventRecord(ev[0], s));

@@ -1194,3 +1194,38 @@ def test_plan_then_upload_and_the_measurement_hook():
     L.lora_segments_destroy(built)
     L.lora_segments_destroy(planned)
     dp.close()
+
+
+def test_single_launch_apply_gives_up_waiting_and_says_so():
+    """The failure path of the single-launch apply, reached from the host: with a wait limit of one poll
+    the expand units give up before their shrink units are done, every wavefront still ends,
+    lora_segments_check reports the apply as failed (and keeps reporting it), and after the object's
+    table is uploaded again with the default limit the same object gives the right result."""
+    b = wl.cfg1_decode(in_features=2048, out_features=512)
+    dp = G.DevicePool(b)
+    x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
+    x = G.bits_to_dev(x_bits)
+    L.lora_set_whole_k_limit(0)
+    L.lora_set_fused_apply(True)
+    try:
+        seg = L.lora_segments_build(dp.pool, b.token_adapter)
+        assert L.lora_segments_info(seg)["n_k_slices"] > 1
+        ws = torch.zeros(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+        L.lora_set_fused_wait_limit(1)
+        L.lora_apply(dp.pool, seg, x, G.bits_to_dev(y0_bits), ws)
+        for _ in range(2):
+            with pytest.raises(L.LoraError) as e:
+                L.lora_segments_check(seg)
+            assert e.value.status_name == "LORA_ERR_DEVICE" and "waiting" in e.value.detail
+        L.lora_set_fused_wait_limit(0)
+        L.lora_segments_rebuild(seg, b.token_adapter)
+        y = G.bits_to_dev(y0_bits)
+        L.lora_apply(dp.pool, seg, x, y, ws)
+        L.lora_segments_check(seg)
+        G.check_parity(G.dev_to_bits(y), G.oracle_apply(dp, x_bits, y0_bits), y0_bits, b.token_adapter)
+        L.lora_segments_destroy(seg)
+    finally:
+        L.lora_set_fused_wait_limit(0)
+        L.lora_set_fused_apply(False)
+        L.lora_set_whole_k_limit(1024)
+    dp.close()
