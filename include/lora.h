@@ -214,7 +214,8 @@ lora_status_t lora_segments_export(const lora_segments_t *seg, int32_t *perm, in
 /* Host copies of the work-unit lists, 6 int32 per unit: {segment, first token (relative to the
  * group), token count, first row (shrink) or first column (expand), row or column count,
  * k-slice (shrink) or 0}.  Groups of fewer than 32 tokens are cut into shrink units of <= 16 tokens x
- * 16 rank rows x one k-slice; token-heavy groups into shrink units of up to 32 tokens x all rank
+ * 16 rank rows x one k-slice (in a whole-k plan of at most 256 units, the units of the most tokens
+ * come as two units of 8 rank rows each, as many token counts as fit 256 units); token-heavy groups into shrink units of up to 32 tokens x all rank
  * rows x all of k (listed after the others, k-slice 0; in a batch planned in k-slices with few such
  * units, two or four k-slices each) and into expand units of up to 64 tokens.
  * The order is the launch order: the decode shrink units of one group take places of one residue

@@ -482,6 +482,8 @@ static int g_whole_k_limit = 1024;
 // unit: the decode-sized groups are then planned in k-slices, whose work groups have the size of the
 // token-heavy ones'.
 static int g_merged_mixed = 1;
+static const int kComputeUnits = 256;   // of the chip: a whole-k launch within this many units is one round
+static const int kSplitRowsFloor = 1;   // fewest tokens of a whole-k unit that may be cut into 8-row halves
 static const int kWholeKMin = 64;  // below this, k-slices are what spreads the batch over the chip
 // A wavefront of a whole-k unit walks in_features / 16 of k in passes of 256, one trip to memory each:
 // beyond this many input features the k-slice units win (cfg1's routing, shrink launch: 14.4 vs 15.5 us
@@ -596,6 +598,25 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     sg->wide = whole_k_units >= kWholeKMin && whole_k_units <= g_whole_k_limit &&
                pool->in_features <= kWholeKMaxIn && !(g_merged_mixed && heavy_groups);
     choose_k_slices(pool->in_features, &sg->wide_slices, &sg->wide_slice_len);
+    // Whole-k units of many tokens pass up to twice the bytes of the others through their compute unit
+    // (x beside A^T) and end the launch.  While the launch stays at one work group per compute unit,
+    // the 16 rank rows of the units with the most tokens are cut into two units of 8, which share x
+    // through the XCD's L2 as they already share A^T (cfg1: 217 -> 249 units, shrink launch 9.3 -> 8.9
+    // us): split_min_tokens is the smallest token count whose units can all be cut within that budget.
+    int split_min_tokens = 0;
+    if (sg->wide) {
+        int64_t per_tokens[lora::kTokTile + 1] = {0};  // full 16-row units by their token count
+        for (int a = 0; a < N; ++a) {
+            if (!count[a] || (count[a] >= kPrefillMinTokens && n_active >= kPrefillMinBatch)) continue;
+            for (int tok0 = 0; tok0 < count[a]; tok0 += lora::kTokTile)
+                per_tokens[std::min(lora::kTokTile, count[a] - tok0)] += pool->r8[a] / lora::kRowTile;
+        }
+        int64_t extra = 0;
+        for (int m = lora::kTokTile; m >= kSplitRowsFloor && whole_k_units + extra + per_tokens[m] <= kComputeUnits; --m) {
+            extra += per_tokens[m];
+            if (per_tokens[m]) split_min_tokens = m;
+        }
+    }
     if (sg->wide) {
         sg->n_k_slices = 1;
         sg->k_slice_len = pool->in_features;
@@ -727,22 +748,28 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
             for (int row0 = 0; row0 < r.r8; row0 += lora::kRowTile)
                 for (int ks = 0; ks < sg->n_k_slices; ++ks)
                     for (int tok0 = 0; tok0 < r.ntok; tok0 += lora::kTokTile) {
-                        Unit u;
-                        memset(&u, 0, sizeof u);
-                        u.seg = si;
-                        u.tok0 = tok0;
-                        u.ntok = std::min(lora::kTokTile, r.ntok - tok0);
-                        u.p0 = row0;
-                        u.pn = std::min(lora::kRowTile, r.r8 - row0);
-                        u.ks = ks;
-                        u.r8 = r.r8;
-                        u.scale = r.scale;
-                        u.w_off = r.a_off + (uint64_t)row0 * pool->in_features;
-                        u.v_off = r.v_off + (int64_t)tok0 * r.r8 + row0;
-                        u.sync_idx = sync_base[si] + tok0 / lora::kTokTile;
-                        u.sync_n = sync_n;
-                        fill_tokens(u, r);
-                        sg->shrink_units.push_back(u);
+                        const int ntok = std::min(lora::kTokTile, r.ntok - tok0);
+                        const int rows = std::min(lora::kRowTile, r.r8 - row0);
+                        // w_off stays the start of the 16-row block of A^T the unit's rows lie in
+                        const int halves = split_min_tokens && rows == lora::kRowTile && ntok >= split_min_tokens ? 2 : 1;
+                        for (int hf = 0; hf < halves; ++hf) {
+                            Unit u;
+                            memset(&u, 0, sizeof u);
+                            u.seg = si;
+                            u.tok0 = tok0;
+                            u.ntok = ntok;
+                            u.p0 = row0 + hf * (rows / halves);
+                            u.pn = rows / halves;
+                            u.ks = ks;
+                            u.r8 = r.r8;
+                            u.scale = r.scale;
+                            u.w_off = r.a_off + (uint64_t)row0 * pool->in_features;
+                            u.v_off = r.v_off + (int64_t)tok0 * r.r8 + u.p0;
+                            u.sync_idx = sync_base[si] + tok0 / lora::kTokTile;
+                            u.sync_n = sync_n;
+                            fill_tokens(u, r);
+                            sg->shrink_units.push_back(u);
+                        }
                     }
         }
         // expand: small groups one column pass and <= 16 tokens per unit; token-heavy groups 64 tokens

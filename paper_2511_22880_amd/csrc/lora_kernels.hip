@@ -292,7 +292,7 @@ static __device__ __forceinline__ void shrink_body(const Unit &u, const uint16_t
 }
 
 // ------------------------------------------------------------------------------------------------
-// shrink, whole-k units: one unit = (group, <=16 tokens, 16 rank rows, all of k), one work group of
+// shrink, whole-k units: one unit = (group, <=16 tokens, 16 rank rows or one half of them, all of k), one work group of
 // 16 wavefronts.  Used when the batch's units fit the chip in one round: each compute unit then
 // streams one row block of one adapter with 128 KB of loads in flight, and v leaves complete (no
 // partial sums in memory, no counters).  The work group is four k-slice units in one: wavefronts
@@ -332,7 +332,11 @@ __global__ __launch_bounds__(kWideThreads) void k_shrink_wide(const Unit *__rest
     const int ntok = u.ntok, pn = u.pn;
     const bool w_ok = i < pn;
     const bool x_ok = i < ntok;
-    const uint16_t *wrow = arena + u.w_off + (kq * pn + (w_ok ? i : 0)) * 8;
+    // the unit's rows are rows row0 .. row0 + pn - 1 of a block of blk_rows rows of A^T (all of the
+    // block, or one half of a 16-row block), which starts at w_off
+    const int blk_rows = min(kRowTile, u.r8 - (u.p0 & ~(kRowTile - 1)));
+    const int row0 = u.p0 & (kRowTile - 1);
+    const uint16_t *wrow = arena + u.w_off + (kq * blk_rows + row0 + (w_ok ? i : 0)) * 8;
     // x staging: lane -> token 2t + half, 16-byte chunk s_chunk of the wavefront's 256 k.  The unit's
     // token list repeats its first token beyond ntok, so every listed row is a valid row of x.
     const int half = lane >> 5;
@@ -355,7 +359,7 @@ __global__ __launch_bounds__(kWideThreads) void k_shrink_wide(const Unit *__rest
 #pragma unroll
         for (int q = 0; q < kShrinkSteps; ++q) {
             const int k = kbeg + 32 * q;
-            a[q] = (k < kslice_end) ? ld16_stream(wrow + (int64_t)k * pn) : zero;
+            a[q] = (k < kslice_end) ? ld16_stream(wrow + (int64_t)k * blk_rows) : zero;
         }
         // in is a multiple of 64, so a 16-byte chunk is either inside the row or wholly beyond it;
         // chunks beyond it are fetched from the row's last chunk instead and never enter an MFMA

@@ -298,9 +298,53 @@ def test_whole_k_limit_switches_the_shrink_plan():
             L.lora_set_whole_k_limit(-1)
     finally:
         L.lora_set_whole_k_limit(1024)
-    # 217 whole-k units (16 rank rows x <= 16 tokens each) fit the default limit; below it k is cut in 4
-    assert got[1024] == (1, 217) and got[216] == (4, 868) and got[0] == (4, 868)
+    # 217 whole-k units (16 rank rows x <= 16 tokens each) fit the default limit (32 of them, those of
+    # 5 tokens and more, cut into two units of 8 rows: 249, within the 256 of one round); below it k is
+    # cut in 4
+    assert got[1024] == (1, 249) and got[216] == (4, 868) and got[0] == (4, 868)
     L.lora_pool_destroy(pool)
+
+
+def test_whole_k_units_of_most_tokens_are_cut_into_row_halves():
+    """In a whole-k plan of at most 256 units the 16-row units with the most tokens come as two units of
+    8 rows on the same tokens (the same start of the row block in the pool, v offsets 8 apart), heaviest
+    first, as many token counts as fit 256 units; the units still tile (token tile x rank rows) exactly."""
+    for T in (256, 128, 64, 24):
+        b = wl.cfg1_decode(n_tokens=T)
+        n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
+        pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
+        for a in range(b.n_adapters):
+            L.lora_pool_mark_resident(pool, a)
+        seg = L.lora_segments_plan(pool, b.token_adapter)
+        info = L.lora_segments_info(seg)
+        if info["n_k_slices"] != 1:
+            L.lora_segments_destroy(seg)
+            L.lora_pool_destroy(pool)
+            continue
+        u = L.lora_segments_export_units(seg)["shrink"]
+        ex = L.lora_segments_export(seg)
+        r8 = (b.ranks[ex["seg_adapter"]] + 7) // 8 * 8
+        assert len(u) <= 256
+        # exact tiling of every group's (tokens x padded rank rows)
+        for si in range(info["n_segments"]):
+            ntok = int(ex["seg_start"][si + 1] - ex["seg_start"][si])
+            cover = np.zeros((ntok, int(r8[si])), dtype=np.int32)
+            for seg_i, tok0, nt, p0, pn, ks in u[u[:, 0] == si]:
+                cover[tok0:tok0 + nt, p0:p0 + pn] += 1
+            assert (cover == 1).all()
+        # halves: 8 rows inside a full 16-row block; the cut follows the token count
+        in_full_block = (u[:, 4] == 8) & ((u[:, 3] % 16 == 8) | (r8[u[:, 0]] - u[:, 3] >= 16))
+        whole = (u[:, 4] == 16)
+        assert in_full_block.sum() % 2 == 0
+        if in_full_block.any() and whole.any():
+            assert u[in_full_block, 2].min() > u[whole, 2].max() - 1     # every cut unit has at least as many tokens as any whole one
+            assert u[in_full_block, 2].min() >= u[whole, 2].max()
+        uncut = len(u) - in_full_block.sum() // 2
+        if whole.any():      # the next token count down would not have fitted
+            m = int(u[whole, 2].max())
+            assert len(u) + int((whole & (u[:, 2] == m)).sum()) > 256 or not in_full_block.any() and uncut > 256
+        L.lora_segments_destroy(seg)
+        L.lora_pool_destroy(pool)
 
 
 def test_live_pool_places_frees_and_coalesces():
