@@ -266,6 +266,23 @@ lora_status_t lora_apply_workspace_bytes(const lora_pool_t *pool, const lora_seg
 lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *seg, const void *x, int64_t ldx,
                          void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  lora_apply with a workspace of the library's own, a file-scope
+ * device array of LORA_STATIC_WORKSPACE_BYTES that every GPU the library runs on holds until the
+ * process ends (its address is looked up once per device, at the first call there).  The call makes
+ * no device allocation, no stream and no event; x, y, the pool's arena and the segment object's table
+ * are still the caller's / the object's, made beforehand.  LORA_ERR_WORKSPACE, with both sizes in the
+ * message, if lora_apply_workspace_bytes(pool, seg) exceeds LORA_STATIC_WORKSPACE_BYTES (cfg1's 256
+ * decode tokens need 0.1 MB, 9.5 k mixed tokens 9.5 MB).  Same launches and bitwise the same y as
+ * lora_apply.  Nothing in the workspace has to start at zero (every element read by a launch was
+ * written earlier in the same apply).  All such calls on one GPU share the one array: calls whose
+ * launches may overlap there (different streams, different threads) race; order them on one stream.
+ * A mixed batch planned for four launches keeps them on `stream` unless an earlier lora_apply on the
+ * object has already made its side stream. */
+#define LORA_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+lora_status_t lora_apply_static(const lora_pool_t *pool, const lora_segments_t *seg, const void *x, int64_t ldx,
+                                void *y, int64_t ldy, void *stream);
+
 /* Several projections that read the same x (q, k and v of a layer; gate and up) in one pass: their
  * pools (same in_features, same ranks and scales, each with its own out_features and arena) are
  * planned together and every launch of lora_apply_multi covers all of them, so x is fetched once per

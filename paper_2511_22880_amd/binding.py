@@ -27,7 +27,8 @@ EXPORTS = (
     "lora_pool_destroy", "lora_segments_plan", "lora_segments_plan_ranges", "lora_segments_upload",
     "lora_segments_build", "lora_segments_build_ranges", "lora_segments_rebuild", "lora_segments_info",
     "lora_segments_export", "lora_segments_export_units", "lora_segments_destroy", "lora_workspace_bytes",
-    "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_profile_next_apply",
+    "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_apply_static",
+    "lora_profile_next_apply",
     "lora_segments_plan_multi", "lora_segments_build_multi", "lora_apply_multi",
     "lora_set_fused_apply", "lora_set_whole_k_limit", "lora_segments_check", "lora_set_side_stream", "lora_set_merged_launches", "lora_set_fused_wait_limit",
     "lora_status_string",
@@ -331,6 +332,16 @@ def lora_apply(pool: Pool, seg: Segments, x, y, workspace, stream=None, ldx: Opt
     _check(lib().lora_apply(pool.handle, seg.handle, _ptr(x), ctypes.c_int64(_ld(x, ldx)), _ptr(y),
                             ctypes.c_int64(_ld(y, ldy)), _ptr(workspace),
                             ctypes.c_size_t(_nbytes(workspace) if ws_bytes is None else ws_bytes), _stream(stream)))
+
+
+LORA_STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def lora_apply_static(pool: Pool, seg: Segments, x, y, stream=None, ldx: Optional[int] = None,
+                      ldy: Optional[int] = None) -> None:
+    """lora_apply on the library's own static workspace: allocates nothing."""
+    _check(lib().lora_apply_static(pool.handle, seg.handle, _ptr(x), ctypes.c_int64(_ld(x, ldx)), _ptr(y),
+                                   ctypes.c_int64(_ld(y, ldy)), _stream(stream)))
 
 
 def _pool_array(pools):

@@ -1448,8 +1448,10 @@ API_CATCH
 
 // The launches of one apply: `arena` is the base the units' weight offsets count from, `out` the
 // width of y that the units' columns lie in.
+// may_create: the apply may make the segment object's side stream and events at its first use.
 static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lora_segments *sg, const void *x,
-                               int64_t ldx, void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream)
+                               int64_t ldx, void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream,
+                               bool may_create = true)
 {
     lora_status_t st;
     if ((st = check_matrix(x, ldx, in, "x")) != LORA_OK) return st;
@@ -1500,7 +1502,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
         // not when a token-heavy group's v is read by 16-token expand units (groups above rank 128):
         // those would sit on the side stream, which does not wait for the token-heavy shrink launch
         const bool split = g_side_stream && sg->has_big_units && !sg->heavy_small_expand &&
-                           cs.n_units >= kSideStreamMinUnits;
+                           cs.n_units >= kSideStreamMinUnits && (may_create || (sg->side && sg->fork && sg->join));
         if (split) {
             if (!msg->side) HIP_TRY(hipStreamCreateWithFlags(&msg->side, hipStreamNonBlocking));
             // the two events order launches of this device among themselves and nothing reads them on
@@ -1540,6 +1542,28 @@ try {
     if (sg->n_active == 0) return LORA_OK;
     return run_apply(pool->arena, pool->in_features, pool->out_features, sg, x, ldx, y, ldy, workspace, ws_bytes,
                      stream);
+}
+API_CATCH
+
+// lora_apply with the library's own workspace: nothing is allocated here, neither device memory nor a
+// stream or an event (a mixed batch planned for four launches keeps them on `stream` unless the
+// object's side stream already exists).
+extern "C" lora_status_t lora_apply_static(const lora_pool_t *pool, const lora_segments_t *sg, const void *x,
+                                           int64_t ldx, void *y, int64_t ldy, void *stream)
+try {
+    lora_status_t st = check_launchable(pool, sg);
+    if (st != LORA_OK) return st;
+    if (sg->n_active == 0) return LORA_OK;
+    const size_t need = apply_parts_bytes(sg) + 2 * apply_packed_bytes(sg);
+    if (need > lora::kStaticScratchBytes)
+        return fail(LORA_ERR_WORKSPACE,
+                    "this batch needs a workspace of %zu bytes, the library's own holds LORA_STATIC_WORKSPACE_BYTES = "
+                    "%zu: use lora_apply with a workspace of the caller's",
+                    need, (size_t)lora::kStaticScratchBytes);
+    void *ws = nullptr;
+    HIP_TRY(lora::static_scratch(&ws));
+    return run_apply(pool->arena, pool->in_features, pool->out_features, sg, x, ldx, y, ldy, ws,
+                     lora::kStaticScratchBytes, stream, false);
 }
 API_CATCH
 

@@ -126,4 +126,11 @@ hipError_t launch_reduce_slices(const float *parts, int n_slices, int64_t slice_
 hipError_t launch_pack_adapter(const uint16_t *A, const uint16_t *B, int in, int out, int r, int r8,
                                uint16_t *dst_a, uint16_t *dst_b, hipStream_t stream);
 
+// The library's own workspace for callers that cannot allocate: a file-scope device array of
+// kStaticScratchBytes in the kernels' source file.  Gives that array's address on the current device
+// (looked up once per device, then kept); the host must use this address, never the array's name.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+constexpr int kMaxDevices = 64;
+hipError_t static_scratch(void **ptr);
+
 }  // namespace lora

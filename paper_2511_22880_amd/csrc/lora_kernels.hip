@@ -17,6 +17,8 @@
 // takes one unit.  No unit ever depends on another adapter's rank.
 #include "lora_internal.h"
 
+#include <atomic>
+
 namespace lora {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -1409,6 +1411,33 @@ hipError_t launch_reduce_slices(const float *parts, int n_slices, int64_t slice_
     hipLaunchKernelGGL(k_reduce_slices, dim3((unsigned)blocks), dim3(256), 0, stream, parts, n_slices,
                        slice_stride, v, n);
     return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Workspace of the entry point that allocates nothing (lora_apply_static): each GPU the library runs
+// on holds one copy of this array, at its own address, until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; every use of its memory goes through the
+// address looked up here, once per device, with that device current.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t static_scratch(void **ptr)
+{
+    static std::atomic<void *> addr[kMaxDevices];
+    *ptr = nullptr;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        addr[dev].store(p, std::memory_order_release);  // two threads racing here store the same address
+    }
+    *ptr = p;
+    return hipSuccess;
 }
 
 hipError_t launch_pack_adapter(const uint16_t *A, const uint16_t *B, int in, int out, int r, int r8,
