@@ -102,6 +102,8 @@ typedef struct {
     int32_t n_k_slices;      /* split-K partial sums per v element (1 = none)           */
     int64_t v_floats;        /* length of v in floats: sum over active tokens of rank_padded */
     int64_t weight_bytes;    /* packed bytes of the distinct adapters the batch touches */
+    int32_t single_launch;   /* 1: planned for the one-launch decode form (see lora_set_decode_single_launch) */
+    int32_t launch_work_groups; /* work groups of that launch (a multiple of 8, at most 256), else 0 */
 } lora_segments_info_t;
 
 /* ---- pool: the ragged, rank-packed adapter arena (set-up time, not on the per-step path) ---- */
@@ -226,6 +228,14 @@ lora_status_t lora_segments_export(const lora_segments_t *seg, int32_t *perm, in
  * fetched by that many XCDs instead of all 8.  Either output may be NULL. */
 lora_status_t lora_segments_export_units(const lora_segments_t *seg, int32_t *shrink_units,
                                          int32_t *expand_units);
+
+/* Host copies of the one-launch decode form's lists (info.single_launch == 1), by place in the launch:
+ * shrink_units holds launch_work_groups records, expand_units four times as many (work group b runs
+ * shrink unit b, then expand units 4b .. 4b+3), 7 int32 each: the six of lora_segments_export_units
+ * and the index of the (group, token tile) whose v the unit writes or reads.  Empty places have a
+ * token count of 0.  Either output may be NULL. */
+lora_status_t lora_segments_export_launch_units(const lora_segments_t *seg, int32_t *shrink_units,
+                                                int32_t *expand_units);
 
 lora_status_t lora_segments_destroy(lora_segments_t *seg);
 
@@ -352,6 +362,26 @@ lora_status_t lora_set_fused_apply(int enabled);
  * the same tolerance).
  * Process-wide. */
 lora_status_t lora_set_merged_launches(int enabled);
+
+/* A decode-sized batch on the whole-k plan (no token-heavy groups, one pool) whose units fit one round of
+ * the chip (at most 256 shrink units, 1024 expand units) is planned for, and run as, ONE launch of at
+ * most one work group per compute unit: work group b does one shrink unit and then four expand
+ * units, and the expand units' loads of B^T follow the shrink units' loads of A^T without the tail,
+ * the pause and the ramp of a launch boundary.  v goes from the shrink units to the expand units of a
+ * (group, token tile) through the L2 of one XCD: the planner puts all of a tile's units at places of
+ * one residue mod 8, which the hardware's dispatch order (work group b to the XCD of b mod 8) turns
+ * into one XCD.  The library checks that order with one probe launch per device (at the first
+ * lora_segments_upload there; on a device where it does not hold, batches keep their two launches)
+ * and every work group of the launch checks its own XCD: a mismatch, like a wait that ran out, is
+ * reported by lora_segments_check.  y is bitwise what the two launches give.
+ * The launch takes an epoch from host state of the segment object, so under stream capture lora_apply
+ * issues the two launches instead (same bits), and applies that share an object must be ordered on
+ * one stream, as ever.  Two such launches that run at the same time on one GPU (different objects on
+ * different streams) can hold each other's compute units while they wait: their waits are bounded and
+ * reported, but callers that overlap applies should select two launches.
+ * lora_set_decode_single_launch(0): always two launches.  Read when a batch is planned and again when it
+ * is applied.  Process-wide; default 1. */
+lora_status_t lora_set_decode_single_launch(int enabled);
 lora_status_t lora_set_side_stream(int enabled);
 
 /* Polls an expand unit of the single-launch apply makes before it gives up waiting, flags the object

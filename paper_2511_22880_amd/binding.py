@@ -13,7 +13,8 @@ from typing import Optional, Sequence
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "liblora_gfx950.so")
+# LORA_GFX950_LIB selects another build of the same library (the measurement build with device clocks)
+LIB_PATH = os.environ.get("LORA_GFX950_LIB") or os.path.join(_PKG, "liblora_gfx950.so")
 
 LORA_MAX_RANK = 256
 LORA_BF16 = 1
@@ -26,11 +27,11 @@ EXPORTS = (
     "lora_pool_reserve", "lora_pool_mark_resident", "lora_pool_space", "lora_pool_compact", "lora_pool_adapter_info",
     "lora_pool_destroy", "lora_segments_plan", "lora_segments_plan_ranges", "lora_segments_upload",
     "lora_segments_build", "lora_segments_build_ranges", "lora_segments_rebuild", "lora_segments_info",
-    "lora_segments_export", "lora_segments_export_units", "lora_segments_destroy", "lora_workspace_bytes",
+    "lora_segments_export", "lora_segments_export_units", "lora_segments_export_launch_units", "lora_segments_destroy", "lora_workspace_bytes",
     "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_apply_static",
     "lora_profile_next_apply",
     "lora_segments_plan_multi", "lora_segments_build_multi", "lora_apply_multi",
-    "lora_set_fused_apply", "lora_set_whole_k_limit", "lora_segments_check", "lora_set_side_stream", "lora_set_merged_launches", "lora_set_fused_wait_limit",
+    "lora_set_fused_apply", "lora_set_decode_single_launch", "lora_set_whole_k_limit", "lora_segments_check", "lora_set_side_stream", "lora_set_merged_launches", "lora_set_fused_wait_limit",
     "lora_status_string",
     "lora_last_error",
     "lora_place_extrapolate", "lora_place_assign",
@@ -58,7 +59,8 @@ class _AdapterInfo(ctypes.Structure):
 class _SegInfo(ctypes.Structure):
     _fields_ = [("n_tokens", ctypes.c_int32), ("n_active", ctypes.c_int32), ("n_segments", ctypes.c_int32),
                 ("n_shrink_units", ctypes.c_int32), ("n_expand_units", ctypes.c_int32),
-                ("n_k_slices", ctypes.c_int32), ("v_floats", ctypes.c_int64), ("weight_bytes", ctypes.c_int64)]
+                ("n_k_slices", ctypes.c_int32), ("v_floats", ctypes.c_int64), ("weight_bytes", ctypes.c_int64),
+                ("single_launch", ctypes.c_int32), ("launch_work_groups", ctypes.c_int32)]
 
 
 _lib = None
@@ -287,6 +289,15 @@ def lora_segments_export_units(seg: Segments) -> dict:
     return {"shrink": su, "expand": eu}
 
 
+def lora_segments_export_launch_units(seg: Segments) -> dict:
+    """The one-launch decode form's lists by place in the launch, 7 int32 per place."""
+    g = lora_segments_info(seg)["launch_work_groups"]
+    su = np.zeros((g, 7), dtype=np.int32)
+    eu = np.zeros((4 * g, 7), dtype=np.int32)
+    _check(lib().lora_segments_export_launch_units(seg.handle, _ptr(su), _ptr(eu)))
+    return {"shrink": su, "expand": eu}
+
+
 def lora_segments_destroy(seg: Segments) -> None:
     if seg.handle:
         _check(lib().lora_segments_destroy(seg.handle))
@@ -378,6 +389,10 @@ def lora_set_fused_apply(enabled: bool) -> None:
     _check(lib().lora_set_fused_apply(ctypes.c_int(1 if enabled else 0)))
 
 
+def lora_set_decode_single_launch(enabled: bool) -> None:
+    _check(lib().lora_set_decode_single_launch(ctypes.c_int(1 if enabled else 0)))
+
+
 def lora_set_side_stream(enabled: bool) -> None:
     _check(lib().lora_set_side_stream(ctypes.c_int(1 if enabled else 0)))
 
@@ -401,6 +416,17 @@ def lora_segments_check(seg: Segments, stream=None) -> None:
 def lora_profile_next_apply(before=None, between=None, after=None) -> None:
     """hipEvent_t handles (integers) recorded around the two launches of the next lora_apply."""
     _check(lib().lora_profile_next_apply(_ptr(before), _ptr(between), _ptr(after)))
+
+
+def lora_debug_clock_buffer(dev_buf, n_work_groups: int) -> None:
+    """Measurement build only: 8 uint64 clock values (100 MHz) per work group of the launches that follow."""
+    fn = getattr(lib(), "lora_debug_clock_buffer", None)
+    if fn is None:
+        raise RuntimeError("this build of the library has no device clocks: build with `python -m "
+                           "paper_2511_22880_amd.build --clocks` and set LORA_GFX950_LIB to it")
+    rc = fn(_ptr(dev_buf), ctypes.c_uint(int(n_work_groups)))
+    if rc != 0:
+        raise RuntimeError(f"lora_debug_clock_buffer: hip error {rc}")
 
 
 def lora_status_string(status: int) -> str:

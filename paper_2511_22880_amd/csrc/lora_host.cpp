@@ -88,18 +88,23 @@ struct lora_segments {
     int layout_in, layout_out;
     std::vector<SegRec> segs;
     std::vector<Unit> shrink_units, prefill_units, expand_units, expand_big_units;
+    // the one-launch decode form's own lists, by place in the launch (empty places have ntok == 0)
+    std::vector<Unit> fused_shrink, fused_expand;
     // device table: [perm | shrink units | prefill shrink units | expand units | arrival counters,
     // ready counters, time-out flag]
     char *dev;
     size_t dev_capacity;
     char *staging;  // pinned host copy of the table
     size_t staging_capacity;
-    size_t off_perm, off_shrink, off_prefill, off_expand, off_expand_big, off_sync, table_bytes;
+    size_t off_perm, off_shrink, off_prefill, off_expand, off_expand_big, off_fused_shrink, off_fused_expand, off_sync,
+        table_bytes;
     bool has_big_units;     // some unit holds more than 16 tokens (token-heavy groups)
     bool heavy_small_expand;  // a token-heavy group above rank 128: shrunk by token-heavy units, expanded by 16-token units
     bool wide;              // decode shrink units span all of k (work groups of 16 wavefronts, no partial sums)
     int wide_slices, wide_slice_len;  // the k-slices such a work group's wavefronts divide k into
     int n_prefill_hi;       // how many of prefill_units are above rank 64
+    bool decode_fused;      // whole-k decode batch that can run as one launch (see finish_decode_fused)
+    int fused_grid;         // work groups of that launch
     int n_sync;             // counters: one per (group, token tile), then the time-out flag
     unsigned launches;      // fused launches since the table was uploaded (the counters' epoch)
     hipEvent_t copied;  // recorded after the upload; guards re-use of `staging`
@@ -482,7 +487,6 @@ static int g_whole_k_limit = 1024;
 // unit: the decode-sized groups are then planned in k-slices, whose work groups have the size of the
 // token-heavy ones'.
 static int g_merged_mixed = 1;
-static const int kComputeUnits = 256;   // of the chip: a whole-k launch within this many units is one round
 static const int kSplitRowsFloor = 1;   // fewest tokens of a whole-k unit that may be cut into 8-row halves
 static const int kWholeKMin = 64;  // below this, k-slices are what spreads the batch over the chip
 // A wavefront of a whole-k unit walks in_features / 16 of k in passes of 256, one trip to memory each:
@@ -563,6 +567,153 @@ static void order_units_by_xcd(std::vector<Unit> &units)
     units.swap(out);
 }
 
+static int g_compute_units = 256;  // of the chip: a whole-k launch within this many units is one round
+static const int kXcds = 8;         // XCDs of the chip, each with an L2 of its own; work group b of a launch runs on XCD b mod 8
+static int g_decode_single_launch = 1;
+
+// Offsets of the lists inside the device table.
+static void layout_table(lora_segments *sg)
+{
+    sg->off_perm = 0;
+    sg->off_shrink = round_up_sz(sg->perm.size() * sizeof(int32_t), 256);
+    sg->off_prefill = round_up_sz(sg->off_shrink + sg->shrink_units.size() * sizeof(Unit), 256);
+    sg->off_expand = round_up_sz(sg->off_prefill + sg->prefill_units.size() * sizeof(Unit), 256);
+    sg->off_expand_big = round_up_sz(sg->off_expand + sg->expand_units.size() * sizeof(Unit), 256);
+    sg->off_fused_shrink = round_up_sz(sg->off_expand_big + sg->expand_big_units.size() * sizeof(Unit), 256);
+    sg->off_fused_expand = round_up_sz(sg->off_fused_shrink + sg->fused_shrink.size() * sizeof(Unit), 256);
+    sg->off_sync = round_up_sz(sg->off_fused_expand + sg->fused_expand.size() * sizeof(Unit), 256);
+    sg->table_bytes = round_up_sz(sg->off_sync + (size_t)(2 * sg->n_sync + 4 + 2 * 256) * sizeof(unsigned), 256);
+}
+
+// The one-launch form of a whole-k decode batch (k_decode_fused): at most one work group per compute
+// unit, work group b running one shrink unit and then four expand units, v handed over through the L2
+// of the XCD the work group runs on (b mod 8).  So every unit of one (group, token tile), the shrink
+// units that write its part of v and the expand units that read it, must sit at places of one residue
+// mod 8, and the launch must be a single round: at most compute units / 8 shrink units and four
+// times as many expand units per XCD.  The tiles are dealt to the eight XCDs heaviest group first,
+// each to the XCD with the fewest bytes that still has room (a group's tiles together where they fit:
+// they read the same A^T and B^T, which that L2 then serves); if some tile finds no room the batch
+// keeps its two launches.  Then, per XCD, while places are left, the 16 rank rows of the shrink units
+// with the most tokens are cut into two units of 8 (they pass the most bytes, x beside A^T, through
+// their compute unit and would end the launch).  Inside an XCD the heaviest shrink units share a work
+// group with the lightest expand units.
+static void finish_decode_fused(lora_segments *sg, int in_features)
+{
+    sg->fused_shrink.clear();
+    sg->fused_expand.clear();
+    sg->fused_grid = 0;
+    const int cap_s = g_compute_units / kXcds, cap_e = 4 * cap_s;
+    sg->decode_fused = g_decode_single_launch && sg->wide && sg->prefill_units.empty() && sg->expand_big_units.empty() &&
+                       !sg->shrink_units.empty() && !sg->expand_units.empty() && sg->n_sync > 0 &&
+                       sg->shrink_units.size() <= (size_t)g_compute_units &&
+                       sg->expand_units.size() <= (size_t)(4 * g_compute_units) && g_compute_units % kXcds == 0;
+    if (!sg->decode_fused) return;
+    struct Tile {
+        std::vector<int> s, e;
+        int seg = -1;
+        int64_t bytes = 0;
+    };
+    std::vector<Tile> tiles(sg->n_sync);
+    auto s_bytes = [&](const Unit &u) { return 2 * (int64_t)in_features * (u.pn + u.ntok); };
+    auto e_bytes = [&](const Unit &u) { return 2 * (int64_t)u.pn * (u.r8 + 2 * u.ntok); };
+    for (size_t k = 0; k < sg->shrink_units.size(); ++k) {
+        const Unit &u = sg->shrink_units[k];
+        tiles[u.sync_idx].s.push_back((int)k);
+        tiles[u.sync_idx].seg = u.seg;
+        tiles[u.sync_idx].bytes += s_bytes(u);
+    }
+    for (size_t k = 0; k < sg->expand_units.size(); ++k) {
+        const Unit &u = sg->expand_units[k];
+        const int pass = u.r8 <= 32 ? 512 : (u.r8 <= 64 ? 256 : 128);
+        if (u.pn > pass || u.ntok > lora::kTokTile) sg->decode_fused = false;  // not a single column pass
+        tiles[u.sync_idx].e.push_back((int)k);
+        tiles[u.sync_idx].bytes += e_bytes(u);
+    }
+    for (const Tile &t : tiles)
+        if (t.s.empty() || t.e.empty() || (int)t.s.size() > cap_s || (int)t.e.size() > cap_e) sg->decode_fused = false;
+    if (!sg->decode_fused) return;
+    // groups (a group's tiles have consecutive counters), heaviest first
+    std::vector<std::vector<int>> groups;
+    for (int t = 0; t < sg->n_sync; ++t) {
+        if (groups.empty() || tiles[groups.back().back()].seg != tiles[t].seg) groups.emplace_back();
+        groups.back().push_back(t);
+    }
+    std::vector<int64_t> gbytes(groups.size(), 0);
+    for (size_t g = 0; g < groups.size(); ++g)
+        for (int t : groups[g]) gbytes[g] += tiles[t].bytes;
+    std::vector<size_t> gorder(groups.size());
+    for (size_t g = 0; g < gorder.size(); ++g) gorder[g] = g;
+    std::stable_sort(gorder.begin(), gorder.end(), [&](size_t a, size_t b) { return gbytes[a] > gbytes[b]; });
+    std::vector<std::vector<int>> on_xcd(kXcds);  // tiles of each XCD
+    std::vector<int64_t> load(kXcds, 0);
+    std::vector<int> ns(kXcds, 0), ne(kXcds, 0);
+    auto place = [&](const std::vector<int> &ts) {
+        int need_s = 0, need_e = 0;
+        int64_t bytes = 0;
+        for (int t : ts) {
+            need_s += (int)tiles[t].s.size();
+            need_e += (int)tiles[t].e.size();
+            bytes += tiles[t].bytes;
+        }
+        int best = -1;
+        for (int q = 0; q < kXcds; ++q)
+            if (ns[q] + need_s <= cap_s && ne[q] + need_e <= cap_e && (best < 0 || load[q] < load[best])) best = q;
+        if (best < 0) return false;
+        for (int t : ts) on_xcd[best].push_back(t);
+        ns[best] += need_s;
+        ne[best] += need_e;
+        load[best] += bytes;
+        return true;
+    };
+    for (size_t g : gorder) {
+        if (place(groups[g])) continue;
+        for (int t : groups[g])
+            if (!place(std::vector<int>{t})) {
+                sg->decode_fused = false;
+                return;
+            }
+    }
+    // per XCD: the lists, the cut of the heaviest shrink units into row halves, the order
+    std::vector<std::vector<Unit>> xs(kXcds), xe(kXcds);
+    int rounds = 0;
+    for (int q = 0; q < kXcds; ++q) {
+        for (int t : on_xcd[q]) {
+            for (int k : tiles[t].s) xs[q].push_back(sg->shrink_units[k]);
+            for (int k : tiles[t].e) xe[q].push_back(sg->expand_units[k]);
+        }
+        std::stable_sort(xs[q].begin(), xs[q].end(), [&](const Unit &a, const Unit &b) { return s_bytes(a) > s_bytes(b); });
+        const size_t n0 = xs[q].size();
+        for (size_t k = 0; k < n0 && (int)xs[q].size() < cap_s; ++k) {
+            if (xs[q][k].pn != lora::kRowTile) continue;
+            Unit lo = xs[q][k], hi = xs[q][k];
+            lo.pn = hi.pn = lora::kRowTile / 2;
+            hi.p0 += lora::kRowTile / 2;
+            hi.v_off += lora::kRowTile / 2;
+            xs[q][k] = lo;
+            xs[q].push_back(hi);
+        }
+        std::stable_sort(xs[q].begin(), xs[q].end(), [&](const Unit &a, const Unit &b) { return s_bytes(a) > s_bytes(b); });
+        std::stable_sort(xe[q].begin(), xe[q].end(), [&](const Unit &a, const Unit &b) { return e_bytes(a) < e_bytes(b); });
+        rounds = std::max(rounds, std::max((int)xs[q].size(), ((int)xe[q].size() + 3) / 4));
+    }
+    std::vector<int32_t> feeders(sg->n_sync, 0);
+    for (int q = 0; q < kXcds; ++q)
+        for (const Unit &u : xs[q]) ++feeders[u.sync_idx];
+    sg->fused_grid = rounds * kXcds;
+    Unit empty;
+    memset(&empty, 0, sizeof empty);
+    sg->fused_shrink.assign((size_t)sg->fused_grid, empty);
+    sg->fused_expand.assign((size_t)sg->fused_grid * 4, empty);
+    for (int q = 0; q < kXcds; ++q) {
+        for (size_t j = 0; j < xs[q].size(); ++j) sg->fused_shrink[j * kXcds + q] = xs[q][j];
+        for (size_t j = 0; j < xe[q].size(); ++j) {
+            Unit u = xe[q][j];
+            u.sync_n = feeders[u.sync_idx];
+            sg->fused_expand[((j / 4) * kXcds + q) * 4 + j % 4] = u;
+        }
+    }
+}
+
 static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const int32_t *ta, int32_t T,
                                int n_projections = 1)  // projections whose units share the launches
 {
@@ -604,7 +755,10 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     // through the XCD's L2 as they already share A^T (cfg1: 217 -> 249 units, shrink launch 9.3 -> 8.9
     // us): split_min_tokens is the smallest token count whose units can all be cut within that budget.
     int split_min_tokens = 0;
-    if (sg->wide) {
+    // (a batch that may run as one launch gets its row halves per XCD, in finish_decode_fused)
+    const bool want_fused = g_decode_single_launch && sg->wide && !heavy_groups && n_projections == 1 &&
+                            whole_k_units <= g_compute_units;
+    if (sg->wide && !want_fused) {
         int64_t per_tokens[lora::kTokTile + 1] = {0};  // full 16-row units by their token count
         for (int a = 0; a < N; ++a) {
             if (!count[a] || (count[a] >= kPrefillMinTokens && n_active >= kPrefillMinBatch)) continue;
@@ -612,7 +766,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
                 per_tokens[std::min(lora::kTokTile, count[a] - tok0)] += pool->r8[a] / lora::kRowTile;
         }
         int64_t extra = 0;
-        for (int m = lora::kTokTile; m >= kSplitRowsFloor && whole_k_units + extra + per_tokens[m] <= kComputeUnits; --m) {
+        for (int m = lora::kTokTile; m >= kSplitRowsFloor && whole_k_units + extra + per_tokens[m] <= g_compute_units; --m) {
             extra += per_tokens[m];
             if (per_tokens[m]) split_min_tokens = m;
         }
@@ -816,13 +970,11 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
 
     order_units_by_xcd(sg->shrink_units);
 
-    sg->off_perm = 0;
-    sg->off_shrink = round_up_sz(sg->perm.size() * sizeof(int32_t), 256);
-    sg->off_prefill = round_up_sz(sg->off_shrink + sg->shrink_units.size() * sizeof(Unit), 256);
-    sg->off_expand = round_up_sz(sg->off_prefill + sg->prefill_units.size() * sizeof(Unit), 256);
-    sg->off_expand_big = round_up_sz(sg->off_expand + sg->expand_units.size() * sizeof(Unit), 256);
-    sg->off_sync = round_up_sz(sg->off_expand_big + sg->expand_big_units.size() * sizeof(Unit), 256);
-    sg->table_bytes = round_up_sz(sg->off_sync + (size_t)(2 * sg->n_sync + 1) * sizeof(unsigned), 256);
+    if (n_projections == 1)
+        finish_decode_fused(sg, pool->in_features);
+    else
+        sg->decode_fused = false;
+    layout_table(sg);
     return LORA_OK;
 }
 
@@ -1011,13 +1163,12 @@ static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const 
     sg->v_floats = v_one * (int64_t)pools.size();
     sg->n_sync = sync_one * (int)pools.size();
     sg->weight_bytes = weight_bytes;
-    sg->off_perm = 0;
-    sg->off_shrink = round_up_sz(sg->perm.size() * sizeof(int32_t), 256);
-    sg->off_prefill = round_up_sz(sg->off_shrink + sg->shrink_units.size() * sizeof(Unit), 256);
-    sg->off_expand = round_up_sz(sg->off_prefill + sg->prefill_units.size() * sizeof(Unit), 256);
-    sg->off_expand_big = round_up_sz(sg->off_expand + sg->expand_units.size() * sizeof(Unit), 256);
-    sg->off_sync = round_up_sz(sg->off_expand_big + sg->expand_big_units.size() * sizeof(Unit), 256);
-    sg->table_bytes = round_up_sz(sg->off_sync + (size_t)(2 * sg->n_sync + 1) * sizeof(unsigned), 256);
+    // (several projections in one launch: the one-launch decode form is planned for single pools only)
+    sg->decode_fused = false;
+    sg->fused_shrink.clear();
+    sg->fused_expand.clear();
+    sg->fused_grid = 0;
+    layout_table(sg);
     return LORA_OK;
 }
 
@@ -1051,10 +1202,59 @@ try {
 }
 API_CATCH
 
+// What the library found out about a device at the first upload there: whether it is the chip the
+// planner's constants describe (gfx950, at least g_compute_units compute units) and, from one probe
+// launch, whether the work groups of one residue mod 8 share an XCD (xcc_map: 4 bits per XCD number, the
+// residue found there).  The one-launch decode form needs both; everything else runs without them.
+struct DeviceProfile {
+    std::atomic<int> state{0};  // 0 unknown, 1 one-launch decode form usable, 2 not usable
+    std::atomic<unsigned> xcc_map{0};
+};
+static DeviceProfile g_profile[lora::kMaxDevices];
+
+static lora_status_t device_profile(hipStream_t s, DeviceProfile **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= lora::kMaxDevices) return fail(LORA_ERR_DEVICE, "device %d outside 0..%d", dev, lora::kMaxDevices - 1);
+    DeviceProfile &p = g_profile[dev];
+    *out = &p;
+    if (p.state.load(std::memory_order_acquire)) return LORA_OK;
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    HIP_TRY(hipStreamIsCapturing(s, &capturing));
+    if (capturing != hipStreamCaptureStatusNone) return LORA_OK;  // no probe under capture: stays unknown
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return fail(LORA_ERR_DEVICE, "device %d is %s: this library's kernels and planner are for gfx950", dev,
+                    prop.gcnArchName);
+    bool ok = prop.multiProcessorCount >= g_compute_units;
+    unsigned map = 0;
+    if (ok) {
+        std::vector<unsigned> xcc((size_t)g_compute_units);
+        HIP_TRY(lora::probe_xcc(xcc.data(), g_compute_units, s));
+        // work groups of one residue mod 8 on one XCD, eight different XCDs numbered 0..7; the map gives
+        // each XCD number the residue it had in this launch (launches may start at another XCD)
+        bool seen[16] = {false};
+        for (int r = 0; r < kXcds && ok; ++r) {
+            for (int b = r; b < g_compute_units; b += kXcds) ok = ok && xcc[b] == xcc[r];
+            ok = ok && xcc[r] < (unsigned)kXcds && !seen[xcc[r] & 15];
+            seen[xcc[r] & 15] = true;
+            if (ok) map |= (unsigned)r << (4 * xcc[r]);
+        }
+    }
+    p.xcc_map.store(map, std::memory_order_relaxed);
+    p.state.store(ok ? 1 : 2, std::memory_order_release);
+    return LORA_OK;
+}
+
 extern "C" lora_status_t lora_segments_upload(lora_segments_t *sg, void *stream)
 try {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     hipStream_t s = (hipStream_t)stream;
+    DeviceProfile *prof = nullptr;
+    lora_status_t pst = device_profile(s, &prof);
+    if (pst != LORA_OK) return pst;
     if (!sg->copied) HIP_TRY(hipEventCreateWithFlags(&sg->copied, hipEventDisableTiming));
     // the previous upload may still be reading the staging buffer
     HIP_TRY(hipEventSynchronize(sg->copied));
@@ -1084,6 +1284,10 @@ try {
         memcpy(sg->staging + sg->off_shrink, sg->shrink_units.data(), sg->shrink_units.size() * sizeof(Unit));
     if (!sg->expand_units.empty())
         memcpy(sg->staging + sg->off_expand, sg->expand_units.data(), sg->expand_units.size() * sizeof(Unit));
+    if (!sg->fused_shrink.empty())
+        memcpy(sg->staging + sg->off_fused_shrink, sg->fused_shrink.data(), sg->fused_shrink.size() * sizeof(Unit));
+    if (!sg->fused_expand.empty())
+        memcpy(sg->staging + sg->off_fused_expand, sg->fused_expand.data(), sg->fused_expand.size() * sizeof(Unit));
     memset(sg->staging + sg->off_sync, 0, sg->table_bytes - sg->off_sync);
     sg->launches = 0;
     if (sg->table_bytes) HIP_TRY(hipMemcpyAsync(sg->dev, sg->staging, sg->table_bytes, hipMemcpyHostToDevice, s));
@@ -1174,6 +1378,8 @@ try {
     info->n_k_slices = sg->n_k_slices;
     info->v_floats = sg->v_floats;
     info->weight_bytes = sg->weight_bytes;
+    info->single_launch = sg->decode_fused ? 1 : 0;
+    info->launch_work_groups = sg->decode_fused ? sg->fused_grid : 0;
     return LORA_OK;
 }
 API_CATCH
@@ -1212,6 +1418,24 @@ try {
         export_units(sg->expand_units, expand_units);
         export_units(sg->expand_big_units, expand_units + 6 * sg->expand_units.size());
     }
+    return LORA_OK;
+}
+API_CATCH
+
+extern "C" lora_status_t lora_segments_export_launch_units(const lora_segments_t *sg, int32_t *shrink_units,
+                                                           int32_t *expand_units)
+try {
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (!sg->decode_fused) return fail(LORA_ERR_INVALID_ARG, "the batch is not planned for the one-launch decode form");
+    auto put = [](const std::vector<Unit> &units, int32_t *dst) {
+        for (size_t i = 0; i < units.size(); ++i) {
+            const Unit &u = units[i];
+            int32_t *d = dst + 7 * i;
+            d[0] = u.seg; d[1] = u.tok0; d[2] = u.ntok; d[3] = u.p0; d[4] = u.pn; d[5] = u.ks; d[6] = u.sync_idx;
+        }
+    };
+    if (shrink_units) put(sg->fused_shrink, shrink_units);
+    if (expand_units) put(sg->fused_expand, expand_units);
     return LORA_OK;
 }
 API_CATCH
@@ -1285,20 +1509,24 @@ static size_t apply_parts_bytes(const lora_segments *sg)
 }
 static size_t apply_packed_bytes(const lora_segments *sg) { return round_up_sz((size_t)sg->v_floats * 2, 256); }
 
-enum UnitKind { kShrink, kPrefill, kExpand, kExpandBig };
+enum UnitKind { kShrink, kPrefill, kExpand, kExpandBig, kFusedShrink, kFusedExpand };
 
 static lora::LaunchCtx ctx_for(const uint16_t *arena, int in_features, int out_features, const lora_segments *sg,
                                 UnitKind kind)
 {
     lora::LaunchCtx c;
-    const size_t off = kind == kShrink    ? sg->off_shrink
-                       : kind == kPrefill ? sg->off_prefill
-                       : kind == kExpand  ? sg->off_expand
-                                          : sg->off_expand_big;
-    const std::vector<Unit> &list = kind == kShrink    ? sg->shrink_units
-                                    : kind == kPrefill ? sg->prefill_units
-                                    : kind == kExpand  ? sg->expand_units
-                                                       : sg->expand_big_units;
+    const size_t off = kind == kShrink        ? sg->off_shrink
+                       : kind == kPrefill     ? sg->off_prefill
+                       : kind == kExpand      ? sg->off_expand
+                       : kind == kExpandBig   ? sg->off_expand_big
+                       : kind == kFusedShrink ? sg->off_fused_shrink
+                                              : sg->off_fused_expand;
+    const std::vector<Unit> &list = kind == kShrink        ? sg->shrink_units
+                                    : kind == kPrefill     ? sg->prefill_units
+                                    : kind == kExpand      ? sg->expand_units
+                                    : kind == kExpandBig   ? sg->expand_big_units
+                                    : kind == kFusedShrink ? sg->fused_shrink
+                                                           : sg->fused_expand;
     c.units = (const Unit *)(sg->dev + off);
     c.perm = (const int32_t *)(sg->dev + sg->off_perm);
     c.arena = arena;
@@ -1404,6 +1632,13 @@ try {
 }
 API_CATCH
 
+extern "C" lora_status_t lora_set_decode_single_launch(int enabled)
+try {
+    g_decode_single_launch = enabled ? 1 : 0;
+    return LORA_OK;
+}
+API_CATCH
+
 extern "C" lora_status_t lora_set_merged_launches(int enabled)
 try {
     g_merged_mixed = enabled ? 1 : 0;
@@ -1428,11 +1663,32 @@ extern "C" lora_status_t lora_segments_check(const lora_segments_t *sg, void *st
 try {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     if (!sg->uploaded || !sg->dev) return LORA_OK;
-    unsigned flag = 0;
-    HIP_TRY(hipMemcpyAsync(&flag, sg->dev + sg->off_sync + (size_t)2 * sg->n_sync * sizeof(unsigned), sizeof flag,
-                           hipMemcpyDeviceToHost, (hipStream_t)stream));
+    std::vector<unsigned> flags(4 + 2 * 256, 0u);
+    HIP_TRY(hipMemcpyAsync(flags.data(), sg->dev + sg->off_sync + (size_t)2 * sg->n_sync * sizeof(unsigned),
+                           flags.size() * sizeof(unsigned), hipMemcpyDeviceToHost, (hipStream_t)stream));
     HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
-    if (flag) return fail(LORA_ERR_DEVICE, "an expand unit of a fused lora_apply gave up waiting for its shrink units");
+    unsigned flag = flags[0];
+    // the last one-launch apply's own record of which places ran on which XCD (earlier ones were looked
+    // at by the launch that followed them)
+    if (sg->decode_fused && sg->launches > 0) {
+        unsigned seen[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int b = 0; b < sg->fused_grid && b < 256; ++b) {
+            const unsigned left = flags[4 + 256 * (sg->launches & 1u) + b];
+            if ((left >> 8) != (sg->launches & 0xFFFFFFu)) continue;  // the last apply took two launches
+            if (left & 0x80u) flag |= 2u;
+            seen[(left >> 4) & 7u] |= 1u << (left & 7u);
+        }
+        for (unsigned q = 0; q < 8; ++q)
+            if (seen[q] & (seen[q] - 1u)) {
+                flag |= 2u;
+                flags[2] = (q << 8) | seen[q];
+            }
+    }
+    if (flag & 2u)
+        return fail(LORA_ERR_DEVICE, "in a one-launch lora_apply, work groups of different places mod 8 ran on one XCD (XCD %u, "
+                                     "differences seen: bits 0x%x): that apply's y is not valid "
+                                     "(lora_set_decode_single_launch(0) selects two launches)", flags[2] >> 8, flags[2] & 255u);
+    if (flag) return fail(LORA_ERR_DEVICE, "an expand unit of a one-launch lora_apply gave up waiting for its shrink units");
     return LORA_OK;
 }
 API_CATCH
@@ -1481,7 +1737,25 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
     if (ev[0]) HIP_TRY(hipEventRecord(ev[0], s));
     // units of more than 16 tokens span several counters, and whole-k shrink units are work groups of
     // another size: such batches always take separate launches
-    if (g_fused_apply && !sg->has_big_units && !sg->wide) {
+    // The one-launch decode form takes its epoch from the host at launch, which a replayed graph would
+    // repeat: under stream capture the batch takes the two launches, which give the same bits.
+    // Nor on a device where the probe launch did not find work group b on the XCD of b mod 8.
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    const DeviceProfile *prof = nullptr;
+    if (g_decode_single_launch && sg->decode_fused) {
+        HIP_TRY(hipStreamIsCapturing(s, &capturing));
+        int dev = -1;
+        HIP_TRY(hipGetDevice(&dev));
+        if (dev >= 0 && dev < lora::kMaxDevices && g_profile[dev].state.load(std::memory_order_acquire) == 1)
+            prof = &g_profile[dev];
+    }
+    if (prof && capturing == hipStreamCaptureStatusNone) {
+        ++msg->launches;
+        HIP_TRY(lora::launch_decode_fused(ctx_for(arena, in, out, sg, kFusedShrink), ctx_for(arena, in, out, sg, kFusedExpand),
+                                          sg->fused_grid, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices,
+                                          (uint16_t *)y, ldy, prof->xcc_map.load(std::memory_order_relaxed), &sa, s));
+        if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
+    } else if (g_fused_apply && !sg->has_big_units && !sg->wide) {
         ++msg->launches;
         HIP_TRY(lora::launch_apply_fused(cs, ce, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride,
                                          (uint16_t *)y, ldy, &sa, s));

@@ -117,6 +117,24 @@ hipError_t launch_apply_fused(const LaunchCtx &shrink, const LaunchCtx &expand, 
                               int k_slice_len, float *parts, int n_slices, int64_t slice_stride, uint16_t *y,
                               int64_t ldy, const SyncArgs *sync, hipStream_t stream);
 
+// A decode-sized batch on the whole-k plan in one launch of `grid` work groups of 16 wavefronts (at most
+// one per compute unit): work group b runs shrink.units[b], then its four groups of four wavefronts run
+// expand.units[4b .. 4b+3]; places with ntok == 0 are empty.  All units of one (group, token tile) sit
+// at places of one residue mod 8, i.e. on one XCD, through whose L2 v (sync->v_hi / v_lo) and the
+// tile's `ready` counter are handed over; the counter grows by an expand unit's sync_n per launch and
+// sync->epoch is the number of such launches since the table was uploaded, this one included.
+// xcc_map: 4 bits per XCD number (0..7), its position in the order in which a launch's work groups are
+// dealt to the XCDs, as a probe launch found it (probe_xcc).  sync->timeout_flag is followed by 3 words
+// of detail and 2 x 256 words the launches' own check of that order uses (see the kernel).  Expand units must be a single
+// column pass (pn <= 512 / 256 / 128 columns up to rank 32 / 64 / beyond).
+hipError_t launch_decode_fused(const LaunchCtx &shrink, const LaunchCtx &expand, int grid, const uint16_t *x,
+                               int64_t ldx, int k_slice_len, int n_slices, uint16_t *y, int64_t ldy,
+                               unsigned xcc_map, const SyncArgs *sync, hipStream_t stream);
+
+// host_out[b] = XCD number (0..15) that work group b of an n-work-group launch ran on (n <= 1024).
+// Synchronises the stream.
+hipError_t probe_xcc(unsigned *host_out, int n_work_groups, hipStream_t stream);
+
 // v[i] = sum over slices, in slice order.
 hipError_t launch_reduce_slices(const float *parts, int n_slices, int64_t slice_stride, float *v,
                                 int64_t n, hipStream_t stream);

@@ -21,6 +21,22 @@
 
 namespace lora {
 
+// Per-work-group device clocks, in builds with -DLORA_WG_CLOCKS only (the measurement build of the
+// library; see lora_debug_clock_buffer): wavefront 0 of a work group writes the 100 MHz wall clock at a
+// few points of its unit into slot (work group, point) of a caller's buffer.  Ordinary builds compile
+// the macro to nothing.
+#ifdef LORA_WG_CLOCKS
+__device__ unsigned long long *g_clock_buf = nullptr;
+__device__ unsigned g_clock_slots = 0;
+#define LORA_CLOCK(point)                                                                              \
+    do {                                                                                               \
+        if (g_clock_buf && threadIdx.x == 0 && blockIdx.x < g_clock_slots)                             \
+            g_clock_buf[(size_t)blockIdx.x * 8 + (point)] = wall_clock64();                            \
+    } while (0)
+#else
+#define LORA_CLOCK(point) do { } while (0)
+#endif
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
@@ -1157,6 +1173,351 @@ static __device__ __forceinline__ void expand_dispatch(const Unit &u, const int3
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Decode apply in one launch.  A decode co-batch is a few tens of megabytes of adapter weights read
+// once: at that size a launch lasts about as long as its first and its last byte take to arrive, and
+// two launches pay that twice.  Here one grid of at most one work group (16 wavefronts) per compute
+// unit does both halves:
+//   * work group b runs shrink unit b exactly as k_shrink_wide does (same tiles, same order of
+//     additions, so v and y are bitwise those of the two launches), then each of its four groups of
+//     four wavefronts runs expand unit 4b + q as k_expand does.  Empty places in either list (ntok
+//     == 0) are skipped.  The expand units' B^T operands and rows of y are requested as soon as the
+//     work group's part of v has been stored, so the chip's loads of B^T follow those of A^T without
+//     the tail, the pause and the ramp of a launch boundary;
+//   * v is handed over inside an XCD.  Each of the chip's XCDs has an L2 of its own, and a store that
+//     must reach memory queues behind everything the chip has requested (several microseconds once
+//     the loads of B^T are out).  The work groups of a launch go to the XCDs in turn (work group b to
+//     the XCD of b mod 8), and the host puts every shrink unit and every expand unit of one (group,
+//     token tile) at places of one residue mod 8: v is then written with plain stores into that XCD's
+//     L2, the tile's ready counter is bumped by an atomic that the L2 executes, the expand units poll it
+//     with a returning atomic (executed by the L2 as well; a plain load could be served by the compute
+//     unit's L1), drop what their L1 holds and read v with plain loads, which the L2 serves.
+//     The counters only grow: the target is epoch * sync_n, epoch = such launches the table has seen.
+//     Every work group checks that the work groups on its XCD all have its residue (see the start of
+//     the kernel); if not it sets bit 1 of the time-out flag: the launch's result is then not valid
+//     and lora_segments_check says so.
+//   * every work group stores its part of v before its first wait, and the grid fits the chip, so
+//     every wait ends; it is bounded all the same (spin_limit polls, then bit 0 of the flag).
+// ------------------------------------------------------------------------------------------------
+constexpr int kDecodeMaxGrid = 256;  // work groups of the launch at most (one per compute unit)
+static_assert(4 * kExpandLds <= kWideWaves * kWideSlab, "the four expand units' partial tiles fit where the x regions were");
+
+// returning atomic OR with 0: the counter's value as the L2 holds it
+static __device__ __forceinline__ unsigned l2_counter_value(unsigned *p)
+{
+    unsigned v;
+    const unsigned zero = 0u;
+    asm volatile("global_atomic_or %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p), "v"(zero) : "memory");
+    return v;
+}
+
+// atomic add executed by the L2, nothing returned
+static __device__ __forceinline__ void l2_counter_add(unsigned *p, unsigned n)
+{
+    asm volatile("global_atomic_add %0, %1, off" : : "v"(p), "v"(n) : "memory");
+}
+
+static __device__ __forceinline__ void l1_invalidate() { asm volatile("buffer_inv sc0" ::: "memory"); }
+
+__global__ __launch_bounds__(kWideThreads) void k_decode_fused(
+    const Unit *__restrict__ s_units, int n_s, const Unit *__restrict__ e_units, int n_e,
+    const uint16_t *__restrict__ arena, const uint16_t *__restrict__ x, int64_t ldx, int in, int k_slice_len,
+    int n_slices, uint16_t *__restrict__ y, int64_t ldy, unsigned xcc_map, Sync sy)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kWideLds + 64];  // + one flag per group of four wavefronts, 8 words of the XCD check
+    const int bid = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int slice = wave >> 2;  // shrink: the k-slice this wavefront works on; expand: its group of four
+    const int wq = wave & 3;      // its place among the four
+    const int i = lane & 15;
+    const int kq = lane >> 4;
+    const uint4 zero = {0u, 0u, 0u, 0u};
+    uint16_t(*slab)[kWideRow] = reinterpret_cast<uint16_t(*)[kWideRow]>(lds + wave * kWideSlab);
+    f32x4(*red)[64] = reinterpret_cast<f32x4(*)[64]>(lds + kWideWaves * kWideSlab);
+    volatile unsigned *qflag = reinterpret_cast<volatile unsigned *>(lds + kWideLds) + slice;
+    if (tid < 4) reinterpret_cast<volatile unsigned *>(lds + kWideLds)[tid] = 0u;
+    // Which XCD do the work groups of each residue run on?  The hardware deals the work groups of a
+    // launch to the XCDs in turn, but not every launch starts at the same XCD: all that the hand-over
+    // needs is that work groups of one residue mod 8 share an XCD, i.e. that every work group on an XCD
+    // finds the same difference d between its place and the XCD's position in the dealing order
+    // (xcc_map: 4 bits per XCD number, its position as a probe launch found it).  Each work group
+    // leaves (epoch, XCD, d) in a word of its own (a plain store: nothing waits for it); the words
+    // alternate between two sets from launch to launch, and the last work group of the following launch
+    // (the one with the lightest shrink unit, where a trip to memory in front of the operand loads
+    // costs the launch nothing) reads what the finished launch left: two values of d on one XCD mean
+    // that its result cannot be trusted (bit 1 of the time-out flag).  The host reads the last launch's
+    // set itself.
+    // hardware register XCC_ID, bits 3:0
+    const unsigned xcc = __builtin_amdgcn_s_getreg(20 | (3 << 11)) & 15u;
+    const unsigned my_d = ((unsigned)bid - ((xcc < 8u ? xcc_map >> (4 * xcc) : 0u) & 15u)) & 7u;
+    unsigned *const xcd_words = sy.timeout_flag + 4;  // [2][kDecodeMaxGrid]
+    if (bid == (int)gridDim.x - 1 && sy.epoch > 1u) {
+        volatile unsigned *seen = reinterpret_cast<volatile unsigned *>(lds + kWideLds) + 4;  // 8 words
+        if (tid < 8) seen[tid] = 0u;
+        __syncthreads();
+        if (tid < (int)gridDim.x) {
+            const unsigned left = xcd_words[kDecodeMaxGrid * ((sy.epoch + 1u) & 1u) + tid];
+            if ((left >> 8) == ((sy.epoch - 1u) & 0xFFFFFFu)) {
+                if ((left & 0x80u) == 0u)
+                    atomicOr(const_cast<unsigned *>(seen) + ((left >> 4) & 7u), 1u << (left & 7u));
+                else
+                    atomicOr(sy.timeout_flag, 2u);  // an XCD number beyond 7
+            }
+        }
+        __syncthreads();
+        if (tid < 8) {
+            const unsigned d_seen = seen[tid];
+            if (d_seen & (d_seen - 1u)) {
+                atomicOr(sy.timeout_flag, 2u);
+                sy.timeout_flag[2] = (tid << 8) | d_seen;  // the XCD and the differences seen there
+            }
+        }
+    }
+    if (tid == 0) xcd_words[kDecodeMaxGrid * (sy.epoch & 1u) + bid] = (sy.epoch << 8) | (xcc << 4) | my_d;
+    LORA_CLOCK(0);
+#ifdef LORA_WG_CLOCKS
+    if (g_clock_buf && tid == 0 && blockIdx.x < g_clock_slots)
+        g_clock_buf[(size_t)blockIdx.x * 8 + 5] = 1000 + (__builtin_amdgcn_s_getreg(20 | (3 << 11)) & 15u);
+#endif
+
+    // ---- the shrink unit ----
+    const Unit &u = s_units[bid < n_s ? bid : 0];
+    const bool s_has = bid < n_s && u.ntok > 0;
+    if (s_has) {
+        const int ntok = u.ntok, pn = u.pn;
+        const bool w_ok = i < pn;
+        const int blk_rows = min(kRowTile, u.r8 - (u.p0 & ~(kRowTile - 1)));
+        const int row0 = u.p0 & (kRowTile - 1);
+        const uint16_t *wrow = arena + u.w_off + (kq * blk_rows + row0 + (w_ok ? i : 0)) * 8;
+        const int half = lane >> 5;
+        const int s_chunk = lane & 31;
+        const uint16_t *xrow[kTokTile / 2];
+#pragma unroll
+        for (int t = 0; t < kTokTile / 2; ++t) xrow[t] = x + (int64_t)(half ? u.tok[2 * t + 1] : u.tok[2 * t]) * ldx;
+        const int kslice_beg = slice * k_slice_len;
+        int kslice_end = kslice_beg + k_slice_len;
+        if (kslice_end > in) kslice_end = in;
+        if (slice >= n_slices) kslice_end = kslice_beg;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int kp = kslice_beg; kp < kslice_end; kp += 4 * kWideK) {
+            const int kbeg = kp + wq * kWideK;  // wavefront-uniform
+            if (kbeg >= kslice_end) break;
+            uint4 a[kShrinkSteps];
+#pragma unroll
+            for (int q = 0; q < kShrinkSteps; ++q) {
+                const int k = kbeg + 32 * q;
+                a[q] = (k < kslice_end) ? ld16_stream(wrow + (int64_t)k * blk_rows) : zero;
+            }
+            int kx = kbeg + 8 * s_chunk;
+            if (kx > in - 8) kx = in - 8;
+            uint4 xs[kTokTile / 2];
+#pragma unroll
+            for (int t = 0; t < kTokTile / 2; ++t)
+                if (2 * t < ntok) xs[t] = ld16(xrow[t] + kx);
+#pragma unroll
+            for (int t = 0; t < kTokTile / 2; ++t)
+                if (2 * t < ntok) *reinterpret_cast<uint4 *>(&slab[2 * t + half][8 * s_chunk]) = xs[t];
+            __atomic_signal_fence(__ATOMIC_SEQ_CST);
+            __builtin_amdgcn_wave_barrier();
+            __atomic_signal_fence(__ATOMIC_SEQ_CST);
+#pragma unroll
+            for (int q = 0; q < kShrinkSteps; ++q) {
+                const int k = kbeg + 32 * q;
+                if (k < kslice_end) {
+                    const uint4 aa = w_ok ? a[q] : zero;
+                    const uint4 bb = *reinterpret_cast<const uint4 *>(&slab[i][32 * q + 8 * kq]);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(aa), as_bf16x8(bb), acc, 0, 0, 0);
+                }
+            }
+            __atomic_signal_fence(__ATOMIC_SEQ_CST);
+            __builtin_amdgcn_wave_barrier();
+            __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        }
+        LORA_CLOCK(1);
+        // the sixteen tiles added in the order of the k-slice plan (inside a slice by wavefront, then the
+        // slices), by wavefront 0 alone: one barrier instead of two
+        red[wave][lane] = acc;
+        __syncthreads();
+        if (wave == 0) {
+            f32x4 t = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int sl = 0; sl < kMaxSlices; ++sl) {
+                if (sl < n_slices) {
+                    f32x4 ts = red[4 * sl][lane];
+                    ts += red[4 * sl + 1][lane];
+                    ts += red[4 * sl + 2][lane];
+                    ts += red[4 * sl + 3][lane];
+                    t = sl ? t + ts : ts;
+                }
+            }
+            if (i < ntok && 4 * kq < pn) {
+                const int64_t off = u.v_off + (int64_t)i * u.r8 + 4 * kq;
+                uint2 h, l;
+                h.x = pack_bf16_rne(t[0], t[1]);
+                h.y = pack_bf16_rne(t[2], t[3]);
+                l.x = pack_bf16_rne(t[0] - bf16_bits_to_f32(h.x & 0xFFFFu), t[1] - __uint_as_float(h.x & 0xFFFF0000u));
+                l.y = pack_bf16_rne(t[2] - bf16_bits_to_f32(h.y & 0xFFFFu), t[3] - __uint_as_float(h.y & 0xFFFF0000u));
+                *reinterpret_cast<uint2 *>(sy.v_hi + off) = h;
+                *reinterpret_cast<uint2 *>(sy.v_lo + off) = l;
+            }
+        }
+        // Nobody requests expand operands before the stores of v have been issued: a compute unit passes
+        // its memory operations on in the order they were issued, and behind 120 KB of requests for B^T
+        // the stores would reach the L2 microseconds later.
+        __syncthreads();
+        LORA_CLOCK(7);
+        if (wave == 0) {
+            stores_done();  // the stores have reached the L2
+            if (lane == 0) l2_counter_add(sy.ready + u.sync_idx, 1u);
+            LORA_CLOCK(2);
+        }
+    } else {
+        __syncthreads();  // the flags in LDS are set
+    }
+
+    // ---- the expand unit of this group of four wavefronts ----
+    const int e_idx = 4 * bid + slice;
+    const Unit *eu = e_units + (e_idx < n_e ? e_idx : 0);
+    const int e_ntok = e_idx < n_e ? eu->ntok : 0;
+    const bool e_has = e_ntok > 0;
+    const int qtid = tid & 255;
+    const int e_tok = qtid >> 4;  // epilogue role: token e_tok of the unit, 8 columns from 8*e_cg of every strip
+    const int e_cg = qtid & 15;
+    float(*part)[kTokTile][kPartRow] = reinterpret_cast<float(*)[kTokTile][kPartRow]>(lds + slice * kExpandLds);
+    const int e_r8 = eu->r8, e_ncols = eu->pn;
+    const int P = e_r8 <= 32 ? 1 : (e_r8 <= 64 ? 2 : 4);  // wavefronts that share a strip, each a part of the rank
+    const int S = 4 / P;                                   // strips per pass
+    const int my_strip = wq / P, my_part = wq % P;
+    const int j0 = 32 * my_part + 8 * kq, j1 = 32 * (my_part + 4) + 8 * kq;
+    const bool j_ok0 = j0 < e_r8, j_ok1 = j1 < e_r8;
+    const int jc0 = j_ok0 ? j0 : 0, jc1 = j_ok1 ? j1 : 0;
+    const bool strip_ok = my_strip * kStrip < e_ncols;
+    uint4 w[8], yv[4];
+    uint16_t *e_y = y;
+    const uint16_t *brow = arena;
+    if (e_has) {
+        // requests that do not need v: the B^T operands of the first k step and the rows of y
+        const int64_t row = eu->tok[e_tok < e_ntok ? e_tok : 0];
+        brow = arena + eu->w_off + (int64_t)(strip_ok ? my_strip * kStrip : 0) * e_r8 + i * 8;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) w[b] = ld16_stream(brow + b * 16 * e_r8 + jc0 * 16);
+        e_y = y + row * ldy + eu->p0 + 8 * e_cg;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            yv[s] = zero;
+            if (s < S && s * kStrip < e_ncols) yv[s] = ld16_stream(e_y + s * kStrip);
+        }
+        // Wait for the tile's v.  The first wavefront of the four polls the tile's counter in the L2 and
+        // tells the other three through LDS.
+        if (wq == 0) {
+            const unsigned target = sy.epoch * (unsigned)eu->sync_n;
+            unsigned spins = 0;
+            // one lane polls (an atomic is executed once per lane, even on one address)
+            for (;;) {
+                unsigned seen = 0u;
+                if (lane == 0) seen = l2_counter_value(sy.ready + eu->sync_idx);
+                seen = __builtin_amdgcn_readfirstlane(seen);
+                if ((int)(seen - target) >= 0) break;
+                if (++spins > sy.spin_limit) {
+                    if (lane == 0) atomicOr(sy.timeout_flag, 1u);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(4);
+            }
+            if (lane == 0) *qflag = 1u;
+        } else {
+            unsigned spins = 0;
+            while (*qflag == 0u) {
+                if (++spins > sy.spin_limit) break;  // the polling wavefront reports the time-out
+                __builtin_amdgcn_s_sleep(2);
+            }
+        }
+        l1_invalidate();
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        LORA_CLOCK(3);
+        const bool ok0 = (i < e_ntok) && j_ok0;
+        const int64_t off0 = eu->v_off + (int64_t)(ok0 ? i : 0) * e_r8 + jc0;
+        uint4 vh0 = ld16(sy.v_hi + off0), vl0 = ld16(sy.v_lo + off0);
+        uint4 vh1 = zero, vl1 = zero;
+        const bool ok1 = (i < e_ntok) && j_ok1;
+        if (e_r8 > 128) {
+            const int64_t off1 = eu->v_off + (int64_t)(ok1 ? i : 0) * e_r8 + jc1;
+            vh1 = ld16(sy.v_hi + off1);
+            vl1 = ld16(sy.v_lo + off1);
+        }
+        if (!ok0) vh0 = vl0 = zero;
+        if (!ok1) vh1 = vl1 = zero;
+        f32x4 acc[8];
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const bf16x8 ww = as_bf16x8(j_ok0 ? w[b] : zero);
+            acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+            acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vh0), ww, acc[b], 0, 0, 0);
+            acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vl0), ww, acc[b], 0, 0, 0);
+        }
+        if (e_r8 > 128) {
+            // the second k step of ranks above 128 re-uses the operand registers
+#pragma unroll
+            for (int b = 0; b < 8; ++b) w[b] = ld16_stream(brow + b * 16 * e_r8 + jc1 * 16);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const bf16x8 ww = as_bf16x8(j_ok1 ? w[b] : zero);
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vh1), ww, acc[b], 0, 0, 0);
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vl1), ww, acc[b], 0, 0, 0);
+            }
+        }
+        if (strip_ok) {
+            // lane (n, kq) holds tokens 4*kq + e, columns 8*n + b
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int tok = 4 * kq + e;
+                if (tok < e_ntok) {
+                    const f32x4 lo = {acc[0][e], acc[1][e], acc[2][e], acc[3][e]};
+                    const f32x4 hi = {acc[4][e], acc[5][e], acc[6][e], acc[7][e]};
+                    *reinterpret_cast<f32x4 *>(&part[wq][tok][8 * i]) = lo;
+                    *reinterpret_cast<f32x4 *>(&part[wq][tok][8 * i + 4]) = hi;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (e_has && e_tok < e_ntok) {
+        const float scale = eu->scale;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            if (s < S && s * kStrip < e_ncols) {
+                f32x4 d0 = *reinterpret_cast<const f32x4 *>(&part[s * P][e_tok][8 * e_cg]);
+                f32x4 d1 = *reinterpret_cast<const f32x4 *>(&part[s * P][e_tok][8 * e_cg + 4]);
+                for (int p = 1; p < P; ++p) {
+                    d0 += *reinterpret_cast<const f32x4 *>(&part[s * P + p][e_tok][8 * e_cg]);
+                    d1 += *reinterpret_cast<const f32x4 *>(&part[s * P + p][e_tok][8 * e_cg + 4]);
+                }
+                const uint4 yy = yv[s];
+                uint4 o;
+                o.x = pack_bf16_rne(bf16_bits_to_f32(yy.x & 0xFFFFu) + scale * d0[0],
+                                    __uint_as_float(yy.x & 0xFFFF0000u) + scale * d0[1]);
+                o.y = pack_bf16_rne(bf16_bits_to_f32(yy.y & 0xFFFFu) + scale * d0[2],
+                                    __uint_as_float(yy.y & 0xFFFF0000u) + scale * d0[3]);
+                o.z = pack_bf16_rne(bf16_bits_to_f32(yy.z & 0xFFFFu) + scale * d1[0],
+                                    __uint_as_float(yy.z & 0xFFFF0000u) + scale * d1[1]);
+                o.w = pack_bf16_rne(bf16_bits_to_f32(yy.w & 0xFFFFu) + scale * d1[2],
+                                    __uint_as_float(yy.w & 0xFFFF0000u) + scale * d1[3]);
+                st16_stream(e_y + s * kStrip, o);
+            }
+        }
+    }
+    LORA_CLOCK(4);
+}
+
+// One work group per place of a launch writes the XCD it runs on (hardware register XCC_ID, bits 3:0).
+__global__ void k_probe_xcc(unsigned *out)
+{
+    if (threadIdx.x == 0) out[blockIdx.x] = __builtin_amdgcn_s_getreg(20 | (3 << 11)) & 15u;
+}
+
 constexpr int kFusedLds = kShrinkLds > kExpandLds ? kShrinkLds : kExpandLds;
 
 __global__ __launch_bounds__(kThreads) void k_shrink(const Unit *__restrict__ units,
@@ -1356,6 +1717,37 @@ hipError_t launch_apply_fused(const LaunchCtx &cs, const LaunchCtx &ce, const ui
     return hipGetLastError();
 }
 
+hipError_t launch_decode_fused(const LaunchCtx &cs, const LaunchCtx &ce, int grid, const uint16_t *x, int64_t ldx,
+                               int k_slice_len, int n_slices, uint16_t *y, int64_t ldy, unsigned xcc_map,
+                               const SyncArgs *sync, hipStream_t stream)
+{
+    if (cs.n_units <= 0 && ce.n_units <= 0) return hipSuccess;
+    if (!sync || grid < 1 || grid > kDecodeMaxGrid || n_slices < 1 || n_slices > kMaxSlices || cs.n_units > grid || ce.n_units > 4 * grid ||
+        cs.n_units < 1 || ce.n_units < 1)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_decode_fused, dim3(grid), dim3(kWideThreads), 0, stream, cs.units, cs.n_units, ce.units,
+                       ce.n_units, cs.arena, x, ldx, cs.in_features, k_slice_len, n_slices, y, ldy, xcc_map,
+                       make_sync(sync, 1));
+    return hipGetLastError();
+}
+
+// Where the work groups of a launch run: host_out[b] = XCD of work group b of an n-work-group launch (n <=
+// kProbeSlots).  Synchronous; its buffer is a device array of this file's own.
+constexpr int kProbeSlots = 1024;
+static __device__ unsigned xcc_probe_buf[kProbeSlots];
+
+hipError_t probe_xcc(unsigned *host_out, int n_work_groups, hipStream_t stream)
+{
+    if (n_work_groups < 1 || n_work_groups > kProbeSlots) return hipErrorInvalidValue;
+    void *buf = nullptr;
+    hipError_t e = hipGetSymbolAddress(&buf, HIP_SYMBOL(xcc_probe_buf));
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_probe_xcc, dim3(n_work_groups), dim3(64), 0, stream, (unsigned *)buf);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = hipStreamSynchronize(stream)) != hipSuccess) return e;
+    return hipMemcpy(host_out, buf, sizeof(unsigned) * (size_t)n_work_groups, hipMemcpyDeviceToHost);
+}
+
 hipError_t launch_shrink_prefill(const LaunchCtx &c, int n_hi, const uint16_t *x, int64_t ldx, uint16_t *v_hi,
                                  uint16_t *v_lo, float *v_f32, int n_slices, int64_t slice_stride, float *parts,
                                  const SyncArgs *sync, hipStream_t stream)
@@ -1450,3 +1842,13 @@ hipError_t launch_pack_adapter(const uint16_t *A, const uint16_t *B, int in, int
 }
 
 }  // namespace lora
+
+#ifdef LORA_WG_CLOCKS
+// Measurement build only: device buffer of 8 clock values per work group for the next launches (NULL = off).
+extern "C" int lora_debug_clock_buffer(unsigned long long *dev_buf, unsigned n_work_groups)
+{
+    hipError_t e = hipMemcpyToSymbol(HIP_SYMBOL(lora::g_clock_buf), &dev_buf, sizeof dev_buf);
+    if (e == hipSuccess) e = hipMemcpyToSymbol(HIP_SYMBOL(lora::g_clock_slots), &n_work_groups, sizeof n_work_groups);
+    return (int)e;
+}
+#endif

@@ -98,6 +98,41 @@ def test_two_launch_apply_matches_fused_apply():
         L.lora_set_whole_k_limit(1024)
 
 
+def test_one_launch_decode_apply_matches_two_launches_bitwise():
+    """A whole-k decode batch runs as one launch by default (shrink units, then expand units that wait
+    for their tile's v, in one grid of at most one work group per compute unit); with
+    lora_set_decode_single_launch(0) as a shrink launch and an expand launch.  Same tiles, same order
+    of additions: same bits.  Applied several times on one table: a launch leaves every counter at zero."""
+    cases = (wl.cfg1_decode(), wl.cfg1_decode(in_features=2048, out_features=640, n_tokens=200),
+             wl.cfg4_skew(0, "1:1", adapters_per_class=8), wl.small_mixed(seed=21, in_features=1024, out_features=384,
+                                                                        decode_tokens=300, prefill_lens=(5, 17, 31)))
+    for b in cases:
+        print(f"[case] one launch vs two on {b.name} T={b.T} in={b.in_features} out={b.out_features}", flush=True)
+        dp = G.DevicePool(b)
+        x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
+        x = G.bits_to_dev(x_bits)
+        seg = L.lora_segments_build(dp.pool, b.token_adapter)
+        assert L.lora_segments_info(seg)["n_k_slices"] == 1, "the case is meant to be on the whole-k plan"
+        ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+        ys = {}
+        for one in (True, False, True):
+            L.lora_set_decode_single_launch(one)
+            try:
+                for rep in range(3):
+                    y = G.bits_to_dev(y0_bits)
+                    L.lora_apply(dp.pool, seg, x, y, ws)
+                    torch.cuda.synchronize()
+                    L.lora_segments_check(seg)
+                    yb = G.dev_to_bits(y)
+                    assert np.array_equal(ys.setdefault("first", yb), yb), f"one launch = {one}, repetition {rep}"
+            finally:
+                L.lora_set_decode_single_launch(True)
+        rows = np.arange(0, b.T, 2, dtype=np.int32)
+        G.check_parity(ys["first"], G.oracle_apply(dp, x_bits, y0_bits, rows=rows), y0_bits, b.token_adapter, rows=rows)
+        L.lora_segments_destroy(seg)
+        dp.close()
+
+
 def test_whole_k_plan_matches_k_slice_plan_bitwise():
     """The two plans of the decode shrink (whole-k units of 16 wavefronts; k-slice units added up
     through counters) do the same arithmetic in the same order: same bits in y and in v."""

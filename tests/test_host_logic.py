@@ -287,6 +287,7 @@ def test_whole_k_limit_switches_the_shrink_plan():
     for a in range(b.n_adapters):
         L.lora_pool_mark_resident(pool, a)
     got = {}
+    L.lora_set_decode_single_launch(False)   # the two-launch plan; the one-launch form has a test of its own below
     try:
         for limit in (1024, 216, 0):
             L.lora_set_whole_k_limit(limit)
@@ -298,6 +299,7 @@ def test_whole_k_limit_switches_the_shrink_plan():
             L.lora_set_whole_k_limit(-1)
     finally:
         L.lora_set_whole_k_limit(1024)
+        L.lora_set_decode_single_launch(True)
     # 217 whole-k units (16 rank rows x <= 16 tokens each) fit the default limit (32 of them, those of
     # 5 tokens and more, cut into two units of 8 rows: 249, within the 256 of one round); below it k is
     # cut in 4
@@ -315,7 +317,11 @@ def test_whole_k_units_of_most_tokens_are_cut_into_row_halves():
         pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
         for a in range(b.n_adapters):
             L.lora_pool_mark_resident(pool, a)
-        seg = L.lora_segments_plan(pool, b.token_adapter)
+        L.lora_set_decode_single_launch(False)
+        try:
+            seg = L.lora_segments_plan(pool, b.token_adapter)
+        finally:
+            L.lora_set_decode_single_launch(True)
         info = L.lora_segments_info(seg)
         if info["n_k_slices"] != 1:
             L.lora_segments_destroy(seg)
@@ -510,3 +516,54 @@ def test_decode_shrink_units_of_a_group_share_an_xcd():
     assert per_xcd.max() <= 1.15 * per_xcd.mean()
     L.lora_segments_destroy(seg)
     L.lora_pool_destroy(pool)
+
+
+def test_one_launch_decode_plan_keeps_every_tile_on_one_xcd():
+    """The one-launch decode form hands v over through the L2 of one XCD, and work group b of a launch
+    runs on the XCD of b mod 8: all units of a (group, token tile) sit at places of one residue mod 8.
+    The shrink units (some cut into row halves) tile every group's (tokens x padded rank rows) exactly,
+    the expand units its (tokens x columns); the launch is one round of at most 256 work groups."""
+    cases = [wl.cfg1_decode(), wl.cfg1_decode(n_tokens=128), wl.cfg1_decode(in_features=2048, out_features=640, n_tokens=200),
+             wl.cfg4_skew(0, "1:1", adapters_per_class=8), wl.cfg1_decode(n_tokens=300, n_adapters=40)]
+    planned = 0
+    for b in cases:
+        n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
+        pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
+        for a in range(b.n_adapters):
+            L.lora_pool_mark_resident(pool, a)
+        seg = L.lora_segments_plan(pool, b.token_adapter)
+        info = L.lora_segments_info(seg)
+        if not info["single_launch"]:
+            L.lora_segments_destroy(seg)
+            L.lora_pool_destroy(pool)
+            continue
+        planned += 1
+        g = info["launch_work_groups"]
+        assert 8 <= g <= 256 and g % 8 == 0 and info["n_k_slices"] == 1
+        lu = L.lora_segments_export_launch_units(seg)
+        su, eu = lu["shrink"], lu["expand"]
+        assert su.shape == (g, 7) and eu.shape == (4 * g, 7)
+        ex = L.lora_segments_export(seg)
+        r8 = (b.ranks[ex["seg_adapter"]] + 7) // 8 * 8
+        xcd_of_tile = {}
+        for place, u in enumerate(su):
+            if u[2] > 0:
+                assert xcd_of_tile.setdefault(int(u[6]), place % 8) == place % 8
+        for place, u in enumerate(eu):
+            if u[2] > 0:
+                assert int(u[6]) in xcd_of_tile, "an expand unit reads a tile no shrink unit writes"
+                assert xcd_of_tile[int(u[6])] == (place // 4) % 8
+        for si in range(info["n_segments"]):
+            ntok = int(ex["seg_start"][si + 1] - ex["seg_start"][si])
+            cover = np.zeros((ntok, int(r8[si])), dtype=np.int32)
+            for _s, tok0, nt, p0, pn, _ks, _t in su[(su[:, 0] == si) & (su[:, 2] > 0)]:
+                assert pn in (8, 16) and tok0 % 16 == 0
+                cover[tok0:tok0 + nt, p0:p0 + pn] += 1
+            assert (cover == 1).all()
+            cols = np.zeros((ntok, b.out_features), dtype=np.int32)
+            for _s, tok0, nt, p0, pn, _ks, _t in eu[(eu[:, 0] == si) & (eu[:, 2] > 0)]:
+                cols[tok0:tok0 + nt, p0:p0 + pn] += 1
+            assert (cols == 1).all()
+        L.lora_segments_destroy(seg)
+        L.lora_pool_destroy(pool)
+    assert planned >= 3
