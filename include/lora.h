@@ -15,10 +15,17 @@
  *
  * Conventions
  *   - bf16 storage (x, y, adapter weights), fp32 accumulation, one round-to-nearest-even to bf16
- *     when y is written.  The shrink result v is fp32 and is never rounded to bf16 in memory.
+ *     when y is written.  lora_shrink returns v as fp32.  Between the two halves of lora_apply, and
+ *     when lora_expand takes the caller's fp32 v, v enters the expand MFMAs as two bf16 terms hi + lo
+ *     (hi = nearest bf16 of v, lo = nearest bf16 of v - hi): 16 mantissa bits, relative error at most
+ *     2^-17 per element, far inside the one bf16 rounding of y (2^-9).
  *   - "device" pointers are HIP device memory of the current device; "host" pointers are ordinary
  *     host memory.  The caller owns every device buffer it passes in (arena, x, y, v, workspace).
- *     The library owns its opaque host objects and one small device table per segment object.
+ *     The library owns its opaque host objects.  Two conveniences allocate on the caller's behalf:
+ *     lora_segments_upload (the object's device table and its pinned host copy) and lora_pool_load
+ *     from a host source (a device staging buffer for the duration of the call); callers that want
+ *     every byte of device memory to be their own use lora_segments_upload_to and
+ *     lora_pool_load_staged instead, which allocate nothing.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernel launches and
  *     copies are asynchronous on it unless a function says otherwise.
  *   - Every function validates its arguments on the host before touching the device and returns a
@@ -27,8 +34,9 @@
  *   - in_features must be a multiple of 64 and out_features of 128; ranks are 1..LORA_MAX_RANK.
  *   - Threads: the objects are not locked.  Calls that touch one pool, or a segment object and the
  *     pools it was planned for, must come from one thread at a time; unrelated objects may be used
- *     from different threads at once.  The lora_set_* knobs are process-wide and are meant to be
- *     set before any planning.  A failed host allocation comes back as LORA_ERR_OOM like any other
+ *     from different threads at once.  Plan settings are per segment object (lora_plan_options_t);
+ *     the lora_set_* calls set the process-wide defaults that fields left at "default" fall back to
+ *     (atomic variables: a setter may run beside planning threads, which see the old or the new value).  A failed host allocation comes back as LORA_ERR_OOM like any other
  *     status (no C++ exception leaves the library).
  */
 #ifndef LORA_GFX950_H
@@ -142,6 +150,15 @@ lora_status_t lora_pool_load(lora_pool_t *pool, int32_t adapter, const void *A_i
 /* Mark an adapter non-resident.  Fixed pool: its bytes stay where they are.  Live pool: its piece
  * returns to the free list, so the caller makes sure no launch that reads it is still running.
  * Segment objects that use the adapter are refused from now on (LORA_ERR_NOT_RESIDENT). */
+/* lora_pool_load from host memory without any allocation or wait of the library's: A and B are copied
+ * into dev_staging (device memory of the caller, 16-byte aligned, at least
+ * lora_pool_load_staging_bytes(pool, adapter) long) and packed from there, all asynchronous on
+ * `stream`.  A, B (pinned host memory if the copies are to overlap anything) and dev_staging must stay
+ * valid and untouched until the stream has passed the call. */
+lora_status_t lora_pool_load_staging_bytes(const lora_pool_t *pool, int32_t adapter, size_t *bytes);
+lora_status_t lora_pool_load_staged(lora_pool_t *pool, int32_t adapter, const void *A_in_by_r, const void *B_r_by_out,
+                                    void *dev_staging, size_t staging_bytes, void *stream);
+
 lora_status_t lora_pool_evict(lora_pool_t *pool, int32_t adapter);
 
 /* Live pool: give the adapter a place without copying anything (no-op in a fixed pool, or if it has
@@ -172,6 +189,21 @@ lora_status_t lora_pool_destroy(lora_pool_t *pool);
 
 /* ---- segments: per-batch grouping of tokens by adapter and the byte-balanced work-unit lists ---- */
 
+/* Plan settings of one segment object, given to the *_opts calls (NULL = all defaults) and kept by the
+ * object: they govern its planning (also every later lora_segments_rebuild) and how lora_apply
+ * launches it.  A switch left at -1 (fused_wait_limit: 0) takes the process-wide default, the value of
+ * the lora_set_* call of the same name, read at the time of use.  The meaning of each setting is
+ * described at that call, further down. */
+typedef struct {
+    int32_t whole_k_limit;        /* -1 or as lora_set_whole_k_limit                  */
+    int32_t merged_launches;      /* -1, 0, 1: lora_set_merged_launches              */
+    int32_t side_stream;          /* -1, 0, 1: lora_set_side_stream                  */
+    int32_t fused_apply;          /* -1, 0, 1: lora_set_fused_apply                  */
+    int32_t decode_single_launch; /* -1, 0, 1: lora_set_decode_single_launch         */
+    uint32_t fused_wait_limit;    /* 0 or polls: lora_set_fused_wait_limit           */
+} lora_plan_options_t;
+#define LORA_PLAN_OPTIONS_DEFAULT {-1, -1, -1, -1, -1, 0u}
+
 /* Host-only half of lora_segments_build: group the T tokens by adapter (stable: tokens of one
  * adapter keep their order), and cut every group into work units whose cost follows that adapter's
  * own bytes.  token_adapter_host[t] in [0, n_adapters) or -1 for "no adapter" (row left untouched).
@@ -180,6 +212,12 @@ lora_status_t lora_pool_destroy(lora_pool_t *pool);
  * lora_segments_upload has run. */
 lora_status_t lora_segments_plan(const lora_pool_t *pool, const int32_t *token_adapter_host, int32_t T,
                                  lora_segments_t **out);
+
+lora_status_t lora_segments_plan_opts(const lora_pool_t *pool, const int32_t *token_adapter_host, int32_t T,
+                                      const lora_plan_options_t *options, lora_segments_t **out);
+
+/* Replaces the object's settings (NULL: all defaults); takes effect at the next rebuild and apply. */
+lora_status_t lora_segments_set_options(lora_segments_t *seg, const lora_plan_options_t *options);
 
 /* Same, from contiguous ranges: tokens seg_start_host[i] .. seg_start_host[i+1]-1 use adapter
  * seg_adapter_host[i] (or none if it is -1); seg_start_host has S+1 non-decreasing entries starting
@@ -191,9 +229,21 @@ lora_status_t lora_segments_plan_ranges(const lora_pool_t *pool, const int32_t *
  * enqueue one host-to-device copy of it on `stream`. */
 lora_status_t lora_segments_upload(lora_segments_t *seg, void *stream);
 
+/* The same with memory of the caller's: the table goes into dev_table (device memory, 256-byte aligned)
+ * through host_staging (host memory, pinned if the copy is to be asynchronous, 16-byte aligned), each
+ * at least lora_segments_table_bytes(seg) long (known after planning).  The object uses both from now
+ * on, for lora_segments_rebuild too (LORA_ERR_OOM, with the sizes, if a later batch needs more), and
+ * never frees them; the caller keeps them alive as long as the object and leaves them alone while
+ * launches that use the object may run.  No allocation is made. */
+lora_status_t lora_segments_table_bytes(const lora_segments_t *seg, size_t *bytes);
+lora_status_t lora_segments_upload_to(lora_segments_t *seg, void *dev_table, size_t dev_bytes, void *host_staging,
+                                      size_t staging_bytes, void *stream);
+
 /* plan + upload. */
 lora_status_t lora_segments_build(const lora_pool_t *pool, const int32_t *token_adapter_host, int32_t T,
                                   void *stream, lora_segments_t **out);
+lora_status_t lora_segments_build_opts(const lora_pool_t *pool, const int32_t *token_adapter_host, int32_t T,
+                                       const lora_plan_options_t *options, void *stream, lora_segments_t **out);
 lora_status_t lora_segments_build_ranges(const lora_pool_t *pool, const int32_t *seg_start_host,
                                          const int32_t *seg_adapter_host, int32_t S, void *stream,
                                          lora_segments_t **out);
@@ -203,6 +253,9 @@ lora_status_t lora_segments_build_ranges(const lora_pool_t *pool, const int32_t 
  * table must no longer be in use by work enqueued on another stream. */
 lora_status_t lora_segments_rebuild(lora_segments_t *seg, const int32_t *token_adapter_host, int32_t T,
                                     void *stream);
+/* (A segment object remembers its pool by handle and id and looks both up among the live pools before
+ * it touches the pool: after lora_pool_destroy, rebuild returns LORA_ERR_STALE_SEGMENTS, and any call
+ * given a destroyed pool handle returns LORA_ERR_INVALID_ARG; no freed memory is read.) */
 
 lora_status_t lora_segments_info(const lora_segments_t *seg, lora_segments_info_t *info);
 
@@ -309,11 +362,19 @@ lora_status_t lora_segments_plan_multi(const lora_pool_t *const *pools, int32_t 
 lora_status_t lora_segments_build_multi(const lora_pool_t *const *pools, int32_t n_pools,
                                         const int32_t *token_adapter_host, int32_t T, void *stream,
                                         lora_segments_t **out);
+lora_status_t lora_segments_plan_multi_opts(const lora_pool_t *const *pools, int32_t n_pools,
+                                            const int32_t *token_adapter_host, int32_t T,
+                                            const lora_plan_options_t *options, lora_segments_t **out);
+lora_status_t lora_segments_build_multi_opts(const lora_pool_t *const *pools, int32_t n_pools,
+                                             const int32_t *token_adapter_host, int32_t T,
+                                             const lora_plan_options_t *options, void *stream,
+                                             lora_segments_t **out);
 lora_status_t lora_apply_multi(const lora_pool_t *const *pools, int32_t n_pools, const lora_segments_t *seg,
                                const void *x, int64_t ldx, void *y, int64_t ldy, void *workspace,
                                size_t ws_bytes, void *stream);
 
-/* Planning knob, process-wide, read by the lora_segments_plan / build / rebuild calls that follow.
+/* Planning knob: the process-wide default of lora_plan_options_t.whole_k_limit, read by the
+ * lora_segments_plan / build / rebuild calls that follow for objects that leave the field at -1.
  * A batch whose decode-sized groups make between 64 and `max_units` shrink units when a unit takes
  * the whole of k (16 rank rows x up to 16 tokens each) is planned that way, if in_features is at most
  * 8192 and the batch is not a mixed one run as merged launches (below): work groups of 16

@@ -25,7 +25,9 @@ STATUS = ("LORA_OK", "LORA_ERR_INVALID_ARG", "LORA_ERR_SHAPE", "LORA_ERR_OOM", "
 EXPORTS = (
     "lora_pool_bytes", "lora_pool_create", "lora_pool_create_live", "lora_pool_load", "lora_pool_evict",
     "lora_pool_reserve", "lora_pool_mark_resident", "lora_pool_space", "lora_pool_compact", "lora_pool_adapter_info",
-    "lora_pool_destroy", "lora_segments_plan", "lora_segments_plan_ranges", "lora_segments_upload",
+    "lora_pool_destroy", "lora_pool_load_staging_bytes", "lora_pool_load_staged", "lora_segments_plan",
+    "lora_segments_plan_opts", "lora_segments_set_options", "lora_segments_table_bytes", "lora_segments_upload_to",
+    "lora_segments_build_opts", "lora_segments_plan_multi_opts", "lora_segments_build_multi_opts", "lora_segments_plan_ranges", "lora_segments_upload",
     "lora_segments_build", "lora_segments_build_ranges", "lora_segments_rebuild", "lora_segments_info",
     "lora_segments_export", "lora_segments_export_units", "lora_segments_export_launch_units", "lora_segments_destroy", "lora_workspace_bytes",
     "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_apply_static",
@@ -61,6 +63,23 @@ class _SegInfo(ctypes.Structure):
                 ("n_shrink_units", ctypes.c_int32), ("n_expand_units", ctypes.c_int32),
                 ("n_k_slices", ctypes.c_int32), ("v_floats", ctypes.c_int64), ("weight_bytes", ctypes.c_int64),
                 ("single_launch", ctypes.c_int32), ("launch_work_groups", ctypes.c_int32)]
+
+
+class _PlanOptions(ctypes.Structure):
+    _fields_ = [("whole_k_limit", ctypes.c_int32), ("merged_launches", ctypes.c_int32), ("side_stream", ctypes.c_int32),
+                ("fused_apply", ctypes.c_int32), ("decode_single_launch", ctypes.c_int32),
+                ("fused_wait_limit", ctypes.c_uint32)]
+
+
+def plan_options(whole_k_limit: int = -1, merged_launches: int = -1, side_stream: int = -1, fused_apply: int = -1,
+                 decode_single_launch: int = -1, fused_wait_limit: int = 0) -> _PlanOptions:
+    """lora_plan_options_t; -1 (0 for the wait limit) = the process-wide default."""
+    return _PlanOptions(int(whole_k_limit), int(merged_launches), int(side_stream), int(fused_apply),
+                        int(decode_single_launch), int(fused_wait_limit))
+
+
+def _opts(options):
+    return ctypes.byref(options) if options is not None else None
 
 
 _lib = None
@@ -223,11 +242,41 @@ def lora_pool_destroy(pool: Pool) -> None:
         pool.handle = ctypes.c_void_p(None)
 
 
-def lora_segments_plan(pool: Pool, token_adapter) -> Segments:
+def lora_segments_plan(pool: Pool, token_adapter, options=None) -> Segments:
     ta = _i32(token_adapter)
     h = ctypes.c_void_p(None)
-    _check(lib().lora_segments_plan(pool.handle, _ptr(ta), ctypes.c_int32(ta.shape[0]), ctypes.byref(h)))
+    _check(lib().lora_segments_plan_opts(pool.handle, _ptr(ta), ctypes.c_int32(ta.shape[0]), _opts(options),
+                                         ctypes.byref(h)))
     return Segments(h, pool)
+
+
+def lora_segments_set_options(seg: Segments, options=None) -> None:
+    _check(lib().lora_segments_set_options(seg.handle, _opts(options)))
+
+
+def lora_segments_table_bytes(seg: Segments) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().lora_segments_table_bytes(seg.handle, ctypes.byref(n)))
+    return int(n.value)
+
+
+def lora_segments_upload_to(seg: Segments, dev_table, host_staging, stream=None) -> None:
+    """dev_table: device tensor; host_staging: pinned host tensor; both at least lora_segments_table_bytes long."""
+    _check(lib().lora_segments_upload_to(seg.handle, _ptr(dev_table), ctypes.c_size_t(_nbytes(dev_table)),
+                                         _ptr(host_staging), ctypes.c_size_t(_nbytes(host_staging)), _stream(stream)))
+    seg.keepalive = (dev_table, host_staging)
+
+
+def lora_pool_load_staging_bytes(pool: Pool, adapter: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().lora_pool_load_staging_bytes(pool.handle, ctypes.c_int32(adapter), ctypes.byref(n)))
+    return int(n.value)
+
+
+def lora_pool_load_staged(pool: Pool, adapter: int, A, B, dev_staging, stream=None) -> None:
+    """A, B: host arrays (numpy uint16 or pinned torch tensors); dev_staging: device tensor of the caller's."""
+    _check(lib().lora_pool_load_staged(pool.handle, ctypes.c_int32(adapter), _ptr(A), _ptr(B), _ptr(dev_staging),
+                                       ctypes.c_size_t(_nbytes(dev_staging)), _stream(stream)))
 
 
 def lora_segments_plan_ranges(pool: Pool, seg_start, seg_adapter) -> Segments:
@@ -243,10 +292,11 @@ def lora_segments_upload(seg: Segments, stream=None) -> None:
     _check(lib().lora_segments_upload(seg.handle, _stream(stream)))
 
 
-def lora_segments_build(pool: Pool, token_adapter, stream=None) -> Segments:
+def lora_segments_build(pool: Pool, token_adapter, stream=None, options=None) -> Segments:
     ta = _i32(token_adapter)
     h = ctypes.c_void_p(None)
-    _check(lib().lora_segments_build(pool.handle, _ptr(ta), ctypes.c_int32(ta.shape[0]), _stream(stream), ctypes.byref(h)))
+    _check(lib().lora_segments_build_opts(pool.handle, _ptr(ta), ctypes.c_int32(ta.shape[0]), _opts(options),
+                                          _stream(stream), ctypes.byref(h)))
     return Segments(h, pool)
 
 
@@ -360,19 +410,20 @@ def _pool_array(pools):
     return arr
 
 
-def lora_segments_plan_multi(pools, token_adapter) -> Segments:
+def lora_segments_plan_multi(pools, token_adapter, options=None) -> Segments:
     ta = _i32(token_adapter)
     h = ctypes.c_void_p(None)
-    _check(lib().lora_segments_plan_multi(_pool_array(pools), ctypes.c_int32(len(pools)), _ptr(ta),
-                                          ctypes.c_int32(ta.shape[0]), ctypes.byref(h)))
+    _check(lib().lora_segments_plan_multi_opts(_pool_array(pools), ctypes.c_int32(len(pools)), _ptr(ta),
+                                               ctypes.c_int32(ta.shape[0]), _opts(options), ctypes.byref(h)))
     return Segments(h, pools[0])
 
 
-def lora_segments_build_multi(pools, token_adapter, stream=None) -> Segments:
+def lora_segments_build_multi(pools, token_adapter, stream=None, options=None) -> Segments:
     ta = _i32(token_adapter)
     h = ctypes.c_void_p(None)
-    _check(lib().lora_segments_build_multi(_pool_array(pools), ctypes.c_int32(len(pools)), _ptr(ta),
-                                           ctypes.c_int32(ta.shape[0]), _stream(stream), ctypes.byref(h)))
+    _check(lib().lora_segments_build_multi_opts(_pool_array(pools), ctypes.c_int32(len(pools)), _ptr(ta),
+                                                ctypes.c_int32(ta.shape[0]), _opts(options), _stream(stream),
+                                                ctypes.byref(h)))
     return Segments(h, pools[0])
 
 

@@ -10,7 +10,10 @@
 #include <cstring>
 #include <map>
 #include <memory>
+#include <mutex>
 #include <new>
+#include <shared_mutex>
+#include <unordered_map>
 #include <vector>
 
 using lora::SegRec;
@@ -107,6 +110,8 @@ struct lora_segments {
     int fused_grid;         // work groups of that launch
     int n_sync;             // counters: one per (group, token tile), then the time-out flag
     unsigned launches;      // fused launches since the table was uploaded (the counters' epoch)
+    bool caller_memory;     // dev / staging belong to the caller (lora_segments_upload_to): never freed, never grown here
+    lora_plan_options_t opts;  // as given at planning (-1 / 0 fields: the process-wide default at the time of use)
     hipEvent_t copied;  // recorded after the upload; guards re-use of `staging`
     // mixed batches: the decode-sized groups' launches go to a stream of the object's own, between a
     // fork and a join event, and run beside the token-heavy groups' launches on the caller's stream
@@ -128,7 +133,25 @@ struct lora_segments {
 static const uint32_t kPoolMagic = 0x4C505231u, kSegMagic = 0x4C534731u;
 static std::atomic<uint64_t> g_next_pool_id{1};
 
-static bool pool_ok(const lora_pool *p) { return p && p->magic == kPoolMagic; }
+// Live pools by address: a pointer is looked up here before it is dereferenced, so a handle that was
+// destroyed (by the caller, or the pool a segment object was planned for) is refused instead of read.
+static std::shared_mutex g_pools_mu;
+static std::unordered_map<const lora_pool *, uint64_t> g_live_pools;  // address -> id
+
+static bool pool_ok(const lora_pool *p)
+{
+    if (!p) return false;
+    std::shared_lock<std::shared_mutex> lk(g_pools_mu);
+    return g_live_pools.find(p) != g_live_pools.end();
+}
+// the pool a segment object remembers: alive, and still the one with that id (not a new pool at the address)
+static bool pool_is(const lora_pool *p, uint64_t id)
+{
+    if (!p) return false;
+    std::shared_lock<std::shared_mutex> lk(g_pools_mu);
+    auto it = g_live_pools.find(p);
+    return it != g_live_pools.end() && it->second == id;
+}
 static bool seg_ok(const lora_segments *s) { return s && s->magic == kSegMagic; }
 
 // ------------------------------------------------------------------------------------------------
@@ -211,6 +234,10 @@ static lora_status_t create_pool(const lora_pool_desc_t *desc, void *dev_arena, 
     if (live) {
         const uint64_t elems = (uint64_t)(arena_bytes / 256) * 128;
         if (elems) p->free_blocks[0] = elems;
+    }
+    {
+        std::unique_lock<std::shared_mutex> lk(g_pools_mu);
+        g_live_pools[p] = p->id;
     }
     *out = p;
     return LORA_OK;
@@ -323,6 +350,26 @@ try {
     for (int a = 0; a < pool->n_adapters; ++a)
         if (pool->a_off[a] != kNoOffset) order.push_back(a);
     std::sort(order.begin(), order.end(), [&](int x, int y) { return pool->a_off[x] < pool->a_off[y]; });
+    // Whatever way this function is left (a copy may fail half-way), the free list is rebuilt from the
+    // places the adapters then have: the gaps between them, in address order.
+    struct FreeListGuard {
+        lora_pool *p;
+        ~FreeListGuard()
+        {
+            std::vector<std::pair<uint64_t, uint64_t>> placed;  // offset, length
+            for (int a = 0; a < p->n_adapters; ++a)
+                if (p->a_off[a] != kNoOffset) placed.push_back({p->a_off[a], block_elems(p, a)});
+            std::sort(placed.begin(), placed.end());
+            p->free_blocks.clear();
+            const uint64_t total = (uint64_t)(p->arena_bytes / 256) * 128;
+            uint64_t at = 0;
+            for (const auto &b : placed) {
+                if (b.first > at) p->free_blocks[at] = b.first - at;
+                at = std::max(at, b.first + b.second);
+            }
+            if (total > at) p->free_blocks[at] = total - at;
+        }
+    } free_list_guard{pool};
     uint64_t cursor = 0;
     int moved = 0;
     for (int a : order) {
@@ -347,9 +394,6 @@ try {
         }
         cursor += len;
     }
-    pool->free_blocks.clear();
-    const uint64_t total = (uint64_t)(pool->arena_bytes / 256) * 128;
-    if (total > cursor) pool->free_blocks[cursor] = total - cursor;
     if (n_moved) *n_moved = moved;
     return LORA_OK;
 }
@@ -367,6 +411,42 @@ try {
     info->rank_padded = pool->r8[adapter];
     info->scale = pool->scale[adapter];
     info->resident = pool->resident[adapter];
+    return LORA_OK;
+}
+API_CATCH
+
+extern "C" lora_status_t lora_pool_load_staging_bytes(const lora_pool_t *pool, int32_t adapter, size_t *bytes)
+try {
+    lora_status_t st = check_adapter(pool, adapter);
+    if (st != LORA_OK) return st;
+    if (!bytes) return fail(LORA_ERR_INVALID_ARG, "bytes is NULL");
+    *bytes = round_up_sz(2 * (size_t)pool->rank[adapter] * ((size_t)pool->in_features + (size_t)pool->out_features), 256);
+    return LORA_OK;
+}
+API_CATCH
+
+extern "C" lora_status_t lora_pool_load_staged(lora_pool_t *pool, int32_t adapter, const void *A, const void *B,
+                                               void *dev_staging, size_t staging_bytes, void *stream)
+try {
+    lora_status_t st = check_adapter(pool, adapter);
+    if (st != LORA_OK) return st;
+    if (!A || !B) return fail(LORA_ERR_INVALID_ARG, "A or B is NULL");
+    const int r = pool->rank[adapter], r8 = pool->r8[adapter];
+    const int in = pool->in_features, out = pool->out_features;
+    const size_t nA = (size_t)in * r, nB = (size_t)r * out;
+    if (!dev_staging || ((uintptr_t)dev_staging) % 16) return fail(LORA_ERR_INVALID_ARG, "dev_staging is NULL or not 16-byte aligned");
+    if (staging_bytes < (nA + nB) * 2)
+        return fail(LORA_ERR_OOM, "dev_staging of %zu bytes is smaller than the %zu the adapter's A and B take", staging_bytes,
+                    (nA + nB) * 2);
+    hipStream_t s = (hipStream_t)stream;
+    if (pool->live && (st = live_place(pool, adapter)) != LORA_OK) return st;
+    uint16_t *tmp = (uint16_t *)dev_staging;
+    HIP_TRY(hipMemcpyAsync(tmp, A, nA * 2, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(tmp + nA, B, nB * 2, hipMemcpyHostToDevice, s));
+    HIP_TRY(lora::launch_pack_adapter(tmp, tmp + nA, in, out, r, r8, pool->arena + pool->a_off[adapter],
+                                      pool->arena + pool->b_off[adapter], s));
+    pool->resident[adapter] = 1;
+    pool->epoch[adapter] = pool->next_epoch++;
     return LORA_OK;
 }
 API_CATCH
@@ -441,7 +521,10 @@ API_CATCH
 extern "C" lora_status_t lora_pool_destroy(lora_pool_t *pool)
 try {
     if (!pool) return LORA_OK;
-    if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "not a pool");
+    {
+        std::unique_lock<std::shared_mutex> lk(g_pools_mu);
+        if (g_live_pools.erase(pool) == 0) return fail(LORA_ERR_INVALID_ARG, "not a pool (or destroyed already)");
+    }
     pool->magic = 0;
     delete pool;
     return LORA_OK;
@@ -482,11 +565,11 @@ static const int kPrefillMinBatch = 1024;
 // Between kWholeKMin and this many whole-k shrink units (four rounds of one work group per compute
 // unit of the chip) the decode shrink runs without k-slices; measured on the rank-skew batches, 442
 // and 544 such units beat their 4 x as many k-slice units by 8 %, 32 units lose 9 % to their 128.
-static int g_whole_k_limit = 1024;
+static std::atomic<int> g_whole_k_limit{1024};
 // Mixed batches (token-heavy groups beside decode-sized ones) in two launches that hold both kinds of
 // unit: the decode-sized groups are then planned in k-slices, whose work groups have the size of the
 // token-heavy ones'.
-static int g_merged_mixed = 1;
+static std::atomic<int> g_merged_mixed{1};
 static const int kSplitRowsFloor = 1;   // fewest tokens of a whole-k unit that may be cut into 8-row halves
 static const int kWholeKMin = 64;  // below this, k-slices are what spreads the batch over the chip
 // A wavefront of a whole-k unit walks in_features / 16 of k in passes of 256, one trip to memory each:
@@ -569,7 +652,19 @@ static void order_units_by_xcd(std::vector<Unit> &units)
 
 static int g_compute_units = 256;  // of the chip: a whole-k launch within this many units is one round
 static const int kXcds = 8;         // XCDs of the chip, each with an L2 of its own; work group b of a launch runs on XCD b mod 8
-static int g_decode_single_launch = 1;
+static std::atomic<int> g_decode_single_launch{1};
+static std::atomic<int> g_side_stream{1};
+static std::atomic<int> g_fused_apply{0};
+static const unsigned kSpinLimit = 1u << 18;  // polls of a waiting expand unit before it gives up
+static std::atomic<unsigned> g_spin_limit{kSpinLimit};
+
+// A segment object's plan settings: what was given at planning, else the process-wide default now.
+static int opt_whole_k_limit(const lora_segments *sg) { return sg->opts.whole_k_limit >= 0 ? sg->opts.whole_k_limit : g_whole_k_limit.load(); }
+static bool opt_merged(const lora_segments *sg) { return (sg->opts.merged_launches >= 0 ? sg->opts.merged_launches : g_merged_mixed.load()) != 0; }
+static bool opt_side_stream(const lora_segments *sg) { return (sg->opts.side_stream >= 0 ? sg->opts.side_stream : g_side_stream.load()) != 0; }
+static bool opt_fused_apply(const lora_segments *sg) { return (sg->opts.fused_apply >= 0 ? sg->opts.fused_apply : g_fused_apply.load()) != 0; }
+static bool opt_decode_single(const lora_segments *sg) { return (sg->opts.decode_single_launch >= 0 ? sg->opts.decode_single_launch : g_decode_single_launch.load()) != 0; }
+static unsigned opt_spin_limit(const lora_segments *sg) { return sg->opts.fused_wait_limit ? sg->opts.fused_wait_limit : g_spin_limit.load(); }
 
 // Offsets of the lists inside the device table.
 static void layout_table(lora_segments *sg)
@@ -603,7 +698,7 @@ static void finish_decode_fused(lora_segments *sg, int in_features)
     sg->fused_expand.clear();
     sg->fused_grid = 0;
     const int cap_s = g_compute_units / kXcds, cap_e = 4 * cap_s;
-    sg->decode_fused = g_decode_single_launch && sg->wide && sg->prefill_units.empty() && sg->expand_big_units.empty() &&
+    sg->decode_fused = opt_decode_single(sg) && sg->wide && sg->prefill_units.empty() && sg->expand_big_units.empty() &&
                        !sg->shrink_units.empty() && !sg->expand_units.empty() && sg->n_sync > 0 &&
                        sg->shrink_units.size() <= (size_t)g_compute_units &&
                        sg->expand_units.size() <= (size_t)(4 * g_compute_units) && g_compute_units % kXcds == 0;
@@ -746,8 +841,8 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     }
     bool heavy_groups = false;
     for (int a = 0; a < N; ++a) heavy_groups |= count[a] >= kPrefillMinTokens && n_active >= kPrefillMinBatch;
-    sg->wide = whole_k_units >= kWholeKMin && whole_k_units <= g_whole_k_limit &&
-               pool->in_features <= kWholeKMaxIn && !(g_merged_mixed && heavy_groups);
+    sg->wide = whole_k_units >= kWholeKMin && whole_k_units <= opt_whole_k_limit(sg) &&
+               pool->in_features <= kWholeKMaxIn && !(opt_merged(sg) && heavy_groups);
     choose_k_slices(pool->in_features, &sg->wide_slices, &sg->wide_slice_len);
     // Whole-k units of many tokens pass up to twice the bytes of the others through their compute unit
     // (x beside A^T) and end the launch.  While the launch stays at one work group per compute unit,
@@ -756,7 +851,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     // us): split_min_tokens is the smallest token count whose units can all be cut within that budget.
     int split_min_tokens = 0;
     // (a batch that may run as one launch gets its row halves per XCD, in finish_decode_fused)
-    const bool want_fused = g_decode_single_launch && sg->wide && !heavy_groups && n_projections == 1 &&
+    const bool want_fused = opt_decode_single(sg) && sg->wide && !heavy_groups && n_projections == 1 &&
                             whole_k_units <= g_compute_units;
     if (sg->wide && !want_fused) {
         int64_t per_tokens[lora::kTokTile + 1] = {0};  // full 16-row units by their token count
@@ -993,6 +1088,8 @@ static lora_segments *new_segments()
     sg->uploaded = false;
     sg->n_sync = 0;
     sg->launches = 0;
+    sg->caller_memory = false;
+    sg->opts = lora_plan_options_t{-1, -1, -1, -1, -1, 0u};
     return sg;
 }
 
@@ -1011,11 +1108,11 @@ try {
     }
     if (seg->fork) (void)hipEventDestroy(seg->fork);
     if (seg->join) (void)hipEventDestroy(seg->join);
-    if (seg->dev) {
+    if (seg->dev && !seg->caller_memory) {
         hipError_t e = hipFree(seg->dev);
         if (e != hipSuccess) st = hip_fail(e, "hipFree(segment table)");
     }
-    if (seg->staging) {
+    if (seg->staging && !seg->caller_memory) {
         hipError_t e = hipHostFree(seg->staging);
         if (e != hipSuccess) st = hip_fail(e, "hipHostFree(segment staging)");
     }
@@ -1044,19 +1141,48 @@ struct SegmentsGuard {
     SegmentsGuard &operator=(const SegmentsGuard &) = delete;
 };
 
-extern "C" lora_status_t lora_segments_plan(const lora_pool_t *pool, const int32_t *ta, int32_t T,
-                                            lora_segments_t **out)
+static lora_status_t check_options(const lora_plan_options_t *o)
+{
+    if (!o) return LORA_OK;
+    if (o->whole_k_limit < -1) return fail(LORA_ERR_INVALID_ARG, "options: whole_k_limit = %d", o->whole_k_limit);
+    const int32_t flags[4] = {o->merged_launches, o->side_stream, o->fused_apply, o->decode_single_launch};
+    for (int32_t f : flags)
+        if (f < -1 || f > 1) return fail(LORA_ERR_INVALID_ARG, "options: a switch is %d, not -1, 0 or 1", f);
+    return LORA_OK;
+}
+
+extern "C" lora_status_t lora_segments_plan_opts(const lora_pool_t *pool, const int32_t *ta, int32_t T,
+                                                 const lora_plan_options_t *options, lora_segments_t **out)
 try {
     if (!out) return fail(LORA_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
     if (!pool_ok(pool)) return fail(LORA_ERR_INVALID_ARG, "pool is NULL or not a pool");
     if (T < 0) return fail(LORA_ERR_INVALID_ARG, "T = %d", T);
     if (T > 0 && !ta) return fail(LORA_ERR_INVALID_ARG, "token_adapter_host is NULL");
+    lora_status_t st = check_options(options);
+    if (st != LORA_OK) return st;
     SegmentsGuard g(new_segments());
     if (!g.sg) return fail(LORA_ERR_OOM, "host allocation failed");
-    lora_status_t st = plan_into(g.sg, pool, ta, T);
+    if (options) g.sg->opts = *options;
+    st = plan_into(g.sg, pool, ta, T);
     if (st != LORA_OK) return st;
     *out = g.release();
+    return LORA_OK;
+}
+API_CATCH
+
+extern "C" lora_status_t lora_segments_plan(const lora_pool_t *pool, const int32_t *ta, int32_t T,
+                                            lora_segments_t **out)
+{
+    return lora_segments_plan_opts(pool, ta, T, nullptr, out);
+}
+
+extern "C" lora_status_t lora_segments_set_options(lora_segments_t *sg, const lora_plan_options_t *options)
+try {
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    lora_status_t st = check_options(options);
+    if (st != LORA_OK) return st;
+    sg->opts = options ? *options : lora_plan_options_t{-1, -1, -1, -1, -1, 0u};
     return LORA_OK;
 }
 API_CATCH
@@ -1133,6 +1259,7 @@ static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const 
     std::unique_ptr<lora_segments> tmp_owner(new (std::nothrow) lora_segments());  // host lists only
     lora_segments *tmp = tmp_owner.get();
     if (!tmp) return fail(LORA_ERR_OOM, "host allocation failed");
+    tmp->opts = sg->opts;
     for (size_t q = 1; q < pools.size(); ++q) {
         st = plan_into(tmp, pools[q], ta, T, (int)pools.size());
         if (st != LORA_OK) break;
@@ -1185,6 +1312,13 @@ static lora_status_t check_pool_list(const lora_pool_t *const *pools, int32_t n,
 
 extern "C" lora_status_t lora_segments_plan_multi(const lora_pool_t *const *pools, int32_t n_pools,
                                                   const int32_t *ta, int32_t T, lora_segments_t **out)
+{
+    return lora_segments_plan_multi_opts(pools, n_pools, ta, T, nullptr, out);
+}
+
+extern "C" lora_status_t lora_segments_plan_multi_opts(const lora_pool_t *const *pools, int32_t n_pools,
+                                                       const int32_t *ta, int32_t T,
+                                                       const lora_plan_options_t *options, lora_segments_t **out)
 try {
     if (!out) return fail(LORA_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
@@ -1193,8 +1327,10 @@ try {
     if (st != LORA_OK) return st;
     if (T < 0) return fail(LORA_ERR_INVALID_ARG, "T = %d", T);
     if (T > 0 && !ta) return fail(LORA_ERR_INVALID_ARG, "token_adapter_host is NULL");
+    if ((st = check_options(options)) != LORA_OK) return st;
     SegmentsGuard g(new_segments());
     if (!g.sg) return fail(LORA_ERR_OOM, "host allocation failed");
+    if (options) g.sg->opts = *options;
     st = plan_multi_into(g.sg, list, ta, T);
     if (st != LORA_OK) return st;
     *out = g.release();
@@ -1248,31 +1384,35 @@ static lora_status_t device_profile(hipStream_t s, DeviceProfile **out)
     return LORA_OK;
 }
 
-extern "C" lora_status_t lora_segments_upload(lora_segments_t *sg, void *stream)
-try {
-    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
-    hipStream_t s = (hipStream_t)stream;
+static lora_status_t upload_table(lora_segments *sg, hipStream_t s)
+{
     DeviceProfile *prof = nullptr;
     lora_status_t pst = device_profile(s, &prof);
     if (pst != LORA_OK) return pst;
     if (!sg->copied) HIP_TRY(hipEventCreateWithFlags(&sg->copied, hipEventDisableTiming));
     // the previous upload may still be reading the staging buffer
     HIP_TRY(hipEventSynchronize(sg->copied));
-    if (sg->table_bytes > sg->staging_capacity) {
-        if (sg->staging) HIP_TRY(hipHostFree(sg->staging));
-        sg->staging = nullptr;
-        sg->staging_capacity = 0;
-        const size_t cap = round_up_sz(sg->table_bytes * 2, 4096);
-        HIP_TRY(hipHostMalloc((void **)&sg->staging, cap, hipHostMallocDefault));
-        sg->staging_capacity = cap;
-    }
-    if (sg->table_bytes > sg->dev_capacity) {
-        if (sg->dev) HIP_TRY(hipFree(sg->dev));
-        sg->dev = nullptr;
-        sg->dev_capacity = 0;
-        const size_t cap = round_up_sz(sg->table_bytes * 2, 4096);
-        HIP_TRY(hipMalloc((void **)&sg->dev, cap));
-        sg->dev_capacity = cap;
+    if (sg->caller_memory) {
+        if (sg->table_bytes > sg->dev_capacity || sg->table_bytes > sg->staging_capacity)
+            return fail(LORA_ERR_OOM, "the batch's table needs %zu bytes; the caller's device table holds %zu, its staging %zu",
+                        sg->table_bytes, sg->dev_capacity, sg->staging_capacity);
+    } else {
+        if (sg->table_bytes > sg->staging_capacity) {
+            if (sg->staging) HIP_TRY(hipHostFree(sg->staging));
+            sg->staging = nullptr;
+            sg->staging_capacity = 0;
+            const size_t cap = round_up_sz(sg->table_bytes * 2, 4096);
+            HIP_TRY(hipHostMalloc((void **)&sg->staging, cap, hipHostMallocDefault));
+            sg->staging_capacity = cap;
+        }
+        if (sg->table_bytes > sg->dev_capacity) {
+            if (sg->dev) HIP_TRY(hipFree(sg->dev));
+            sg->dev = nullptr;
+            sg->dev_capacity = 0;
+            const size_t cap = round_up_sz(sg->table_bytes * 2, 4096);
+            HIP_TRY(hipMalloc((void **)&sg->dev, cap));
+            sg->dev_capacity = cap;
+        }
     }
     if (!sg->perm.empty()) memcpy(sg->staging + sg->off_perm, sg->perm.data(), sg->perm.size() * sizeof(int32_t));
     if (!sg->expand_big_units.empty())
@@ -1295,13 +1435,61 @@ try {
     sg->uploaded = true;
     return LORA_OK;
 }
+
+extern "C" lora_status_t lora_segments_upload(lora_segments_t *sg, void *stream)
+try {
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    return upload_table(sg, (hipStream_t)stream);
+}
+API_CATCH
+
+extern "C" lora_status_t lora_segments_table_bytes(const lora_segments_t *sg, size_t *bytes)
+try {
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (!bytes) return fail(LORA_ERR_INVALID_ARG, "bytes is NULL");
+    *bytes = sg->table_bytes;
+    return LORA_OK;
+}
+API_CATCH
+
+extern "C" lora_status_t lora_segments_upload_to(lora_segments_t *sg, void *dev_table, size_t dev_bytes,
+                                                 void *host_staging, size_t staging_bytes, void *stream)
+try {
+    if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
+    if (!dev_table || ((uintptr_t)dev_table) % 256) return fail(LORA_ERR_INVALID_ARG, "dev_table is NULL or not 256-byte aligned");
+    if (!host_staging || ((uintptr_t)host_staging) % 16) return fail(LORA_ERR_INVALID_ARG, "host_staging is NULL or not 16-byte aligned");
+    if (dev_bytes < sg->table_bytes || staging_bytes < sg->table_bytes)
+        return fail(LORA_ERR_OOM, "the batch's table needs %zu bytes (lora_segments_table_bytes); dev_table holds %zu, host_staging %zu",
+                    sg->table_bytes, dev_bytes, staging_bytes);
+    if (sg->copied) HIP_TRY(hipEventSynchronize(sg->copied));  // an upload from the library's own staging may be in flight
+    if (!sg->caller_memory) {
+        if (sg->dev) HIP_TRY(hipFree(sg->dev));
+        sg->dev = nullptr;
+        if (sg->staging) HIP_TRY(hipHostFree(sg->staging));
+        sg->staging = nullptr;
+    }
+    sg->caller_memory = true;
+    sg->dev = (char *)dev_table;
+    sg->dev_capacity = dev_bytes;
+    sg->staging = (char *)host_staging;
+    sg->staging_capacity = staging_bytes;
+    return upload_table(sg, (hipStream_t)stream);
+}
 API_CATCH
 
 extern "C" lora_status_t lora_segments_build_multi(const lora_pool_t *const *pools, int32_t n_pools,
                                                    const int32_t *ta, int32_t T, void *stream,
                                                    lora_segments_t **out)
+{
+    return lora_segments_build_multi_opts(pools, n_pools, ta, T, nullptr, stream, out);
+}
+
+extern "C" lora_status_t lora_segments_build_multi_opts(const lora_pool_t *const *pools, int32_t n_pools,
+                                                        const int32_t *ta, int32_t T,
+                                                        const lora_plan_options_t *options, void *stream,
+                                                        lora_segments_t **out)
 try {
-    lora_status_t st = lora_segments_plan_multi(pools, n_pools, ta, T, out);
+    lora_status_t st = lora_segments_plan_multi_opts(pools, n_pools, ta, T, options, out);
     if (st != LORA_OK) return st;
     st = lora_segments_upload(*out, stream);
     if (st != LORA_OK) {
@@ -1314,8 +1502,15 @@ API_CATCH
 
 extern "C" lora_status_t lora_segments_build(const lora_pool_t *pool, const int32_t *ta, int32_t T, void *stream,
                                              lora_segments_t **out)
+{
+    return lora_segments_build_opts(pool, ta, T, nullptr, stream, out);
+}
+
+extern "C" lora_status_t lora_segments_build_opts(const lora_pool_t *pool, const int32_t *ta, int32_t T,
+                                                  const lora_plan_options_t *options, void *stream,
+                                                  lora_segments_t **out)
 try {
-    lora_status_t st = lora_segments_plan(pool, ta, T, out);
+    lora_status_t st = lora_segments_plan_opts(pool, ta, T, options, out);
     if (st != LORA_OK) return st;
     st = lora_segments_upload(*out, stream);
     if (st != LORA_OK) {
@@ -1344,7 +1539,7 @@ API_CATCH
 extern "C" lora_status_t lora_segments_rebuild(lora_segments_t *sg, const int32_t *ta, int32_t T, void *stream)
 try {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
-    if (!pool_ok(sg->pool) || sg->pool->id != sg->pool_id)
+    if (!pool_is(sg->pool, sg->pool_id))
         return fail(LORA_ERR_STALE_SEGMENTS, "the pool this segment object was built for no longer exists");
     if (T < 0) return fail(LORA_ERR_INVALID_ARG, "T = %d", T);
     if (T > 0 && !ta) return fail(LORA_ERR_INVALID_ARG, "token_adapter_host is NULL");
@@ -1354,7 +1549,7 @@ try {
     } else {
         const std::vector<const lora_pool *> pools = sg->mpools;
         for (size_t q = 0; q < pools.size(); ++q)
-            if (!pool_ok(pools[q]) || pools[q]->id != sg->mpool_ids[q])
+            if (!pool_is(pools[q], sg->mpool_ids[q]))
                 return fail(LORA_ERR_STALE_SEGMENTS, "a pool this segment object was built for no longer exists");
         st = plan_multi_into(sg, pools, ta, T);
     }
@@ -1362,7 +1557,7 @@ try {
         sg->uploaded = false;
         return st;
     }
-    return lora_segments_upload(sg, stream);
+    return upload_table(sg, (hipStream_t)stream);
 }
 API_CATCH
 
@@ -1619,11 +1814,7 @@ try {
 API_CATCH
 
 static thread_local hipEvent_t g_prof[3] = {nullptr, nullptr, nullptr};
-static int g_side_stream = 1;
 static const int kSideStreamMinUnits = 32;  // decode shrink units below which a second stream is not worth its events
-static int g_fused_apply = 0;
-static const unsigned kSpinLimit = 1u << 18;  // polls of a waiting expand unit before it gives up
-static unsigned g_spin_limit = kSpinLimit;
 
 extern "C" lora_status_t lora_set_fused_apply(int enabled)
 try {
@@ -1655,7 +1846,7 @@ API_CATCH
 
 extern "C" lora_status_t lora_set_fused_wait_limit(uint32_t polls)
 {
-    g_spin_limit = polls ? polls : kSpinLimit;
+    g_spin_limit.store(polls ? polls : kSpinLimit);
     return LORA_OK;
 }
 
@@ -1731,7 +1922,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
     sa.v_hi = (uint16_t *)((char *)workspace + apply_parts_bytes(sg));
     sa.v_lo = (uint16_t *)((char *)workspace + apply_parts_bytes(sg) + apply_packed_bytes(sg));
     sa.epoch = msg->launches + 1;  // read by the single-launch form only, which also advances it
-    sa.spin_limit = g_spin_limit;
+    sa.spin_limit = opt_spin_limit(sg);
     const lora::LaunchCtx cs = ctx_for(arena, in, out, sg, kShrink), cp = ctx_for(arena, in, out, sg, kPrefill),
                           ce = ctx_for(arena, in, out, sg, kExpand), cb = ctx_for(arena, in, out, sg, kExpandBig);
     if (ev[0]) HIP_TRY(hipEventRecord(ev[0], s));
@@ -1742,7 +1933,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
     // Nor on a device where the probe launch did not find work group b on the XCD of b mod 8.
     hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
     const DeviceProfile *prof = nullptr;
-    if (g_decode_single_launch && sg->decode_fused) {
+    if (opt_decode_single(sg) && sg->decode_fused) {
         HIP_TRY(hipStreamIsCapturing(s, &capturing));
         int dev = -1;
         HIP_TRY(hipGetDevice(&dev));
@@ -1755,7 +1946,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
                                           sg->fused_grid, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices,
                                           (uint16_t *)y, ldy, prof->xcc_map.load(std::memory_order_relaxed), &sa, s));
         if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
-    } else if (g_fused_apply && !sg->has_big_units && !sg->wide) {
+    } else if (opt_fused_apply(sg) && !sg->has_big_units && !sg->wide) {
         ++msg->launches;
         HIP_TRY(lora::launch_apply_fused(cs, ce, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride,
                                          (uint16_t *)y, ldy, &sa, s));
@@ -1764,7 +1955,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
         // A mixed batch: the decode-sized groups' two launches are short, latency-bound and touch
         // other tokens (rows of v and y) than the token-heavy groups' two, so they go to a stream of
         // the segment object's own and run beside them; the caller's stream waits for them at the end.
-        if (g_merged_mixed && sg->has_big_units && !sg->wide && cs.n_units > 0) {
+        if (opt_merged(sg) && sg->has_big_units && !sg->wide && cs.n_units > 0) {
             HIP_TRY(lora::launch_shrink_mixed(cp, sg->n_prefill_hi, cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts,
                                               nsl, stride, &sa, s));
             if (ev[1]) HIP_TRY(hipEventRecord(ev[1], s));
@@ -1775,7 +1966,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
         hipStream_t sd = s;
         // not when a token-heavy group's v is read by 16-token expand units (groups above rank 128):
         // those would sit on the side stream, which does not wait for the token-heavy shrink launch
-        const bool split = g_side_stream && sg->has_big_units && !sg->heavy_small_expand &&
+        const bool split = opt_side_stream(sg) && sg->has_big_units && !sg->heavy_small_expand &&
                            cs.n_units >= kSideStreamMinUnits && (may_create || (sg->side && sg->fork && sg->join));
         if (split) {
             if (!msg->side) HIP_TRY(hipStreamCreateWithFlags(&msg->side, hipStreamNonBlocking));

@@ -108,10 +108,20 @@ static __device__ __forceinline__ f32x4 ld_through_f32x4(const float *p)
     return f32x4{lo[0], lo[1], hi[0], hi[1]};
 }
 
+// The s_waitcnt immediate of the gfx9 family (gfx950 included): vmcnt in bits 3:0 and 15:14, expcnt in
+// bits 6:4, lgkmcnt in bits 11:8; a field at its maximum waits for nothing.
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "the hand-built s_waitcnt immediate below is the gfx9 encoding: this file is for gfx950"
+#endif
+constexpr unsigned kWaitcntVmcnt0 = (0u << 0) | (7u << 4) | (15u << 8) | (0u << 14);  // vmcnt(0), nothing else
+static_assert(kWaitcntVmcnt0 == 0x0F70, "vmcnt(0) expcnt(7) lgkmcnt(15)");
+
+// This wavefront's vector memory operations (its stores among them) have completed.  The two signal
+// fences keep the compiler from moving memory operations across the wait in either direction.
 static __device__ __forceinline__ void stores_done()
 {
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's stores have completed
+    __builtin_amdgcn_s_waitcnt(kWaitcntVmcnt0);
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
 }
 
@@ -288,6 +298,8 @@ static __device__ __forceinline__ void shrink_body(const Unit &u, const uint16_t
             unsigned old = 0;
             if (lane == 0) old = atomicAdd(sy.counters + u.sync_idx, 1u);
             old = __builtin_amdgcn_readfirstlane(old);
+            // nothing below (the loads of the other units' partial sums) moves up in front of the arrival
+            __atomic_signal_fence(__ATOMIC_SEQ_CST);
             if (old + 1u == (unsigned)u.sync_n) {
                 // the last of this launch's arrivals at the tile: the counter goes back to zero for the
                 // next launch (nothing else touches it before this launch ends)
@@ -672,6 +684,7 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
     unsigned old = 0;
     if (lane == 0) old = atomicAdd(sy.counters + u.sync_idx, 1u);
     old = __builtin_amdgcn_readfirstlane(old);
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);  // the loads of the slices stay behind the arrival
     if (old + 1u == (unsigned)n_ks) {
         if (lane == 0) atomicExch(sy.counters + u.sync_idx, 0u);  // back to zero for the next launch
         const int tasks = ntok * (u.r8 >> 3);
@@ -1065,7 +1078,7 @@ static __device__ __forceinline__ void expand_big_body(const Unit &u, const int3
     // the copies (and everything else this wavefront has in flight) have landed
 #define LORA_DMA_WAIT()                       \
     __atomic_signal_fence(__ATOMIC_SEQ_CST);  \
-    __builtin_amdgcn_s_waitcnt(0x0F70);       \
+    __builtin_amdgcn_s_waitcnt(kWaitcntVmcnt0); \
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
     uint4 ya[4], yb[4];
     auto fetch_y = [&](int s, uint4 (&yv)[4]) __attribute__((always_inline)) {

@@ -6,6 +6,7 @@
 #include "lora.h"
 #include "lora_placement.h"
 #include "lora_internal.h"
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <random>
@@ -81,7 +82,18 @@ int main(int argc, char **argv){
         std::mt19937 g(100 + t);
         for (int iter = 0; iter < 60 && !rc[t]; ++iter) rc[t] = pool_round(g, iter, false, (uintptr_t)0x10000000 + ((uintptr_t)t << 32));
       });
+    // meanwhile a fifth thread changes the process-wide defaults (atomic variables: allowed beside planners)
+    std::atomic<bool> stop{false};
+    std::thread knobs([&stop]{
+      for (unsigned n = 0; !stop.load(); ++n) {
+        lora_set_whole_k_limit(n % 3 ? 1024 : 0); lora_set_merged_launches(n & 1); lora_set_side_stream((n >> 1) & 1);
+        lora_set_decode_single_launch((n >> 2) & 1); lora_set_fused_apply((n >> 3) & 1); lora_set_fused_wait_limit(n % 5 ? 0 : 7);
+      }
+      lora_set_whole_k_limit(1024); lora_set_merged_launches(1); lora_set_side_stream(1); lora_set_decode_single_launch(1);
+      lora_set_fused_apply(0); lora_set_fused_wait_limit(0);
+    });
     for (auto &x : th) x.join();
+    stop.store(true); knobs.join();
     for (int r : rc) if (r) return 1;
     printf("planner thread run ok\n");
     return 0;
@@ -89,6 +101,34 @@ int main(int argc, char **argv){
   std::mt19937 g(1);
   for (int iter = 0; iter < 300; ++iter)
     if (pool_round(g, iter, true, 0x10000000)) return 1;
+  {
+    // a segment object that outlives its pool, and a pool handle used after lora_pool_destroy: statuses,
+    // not reads of freed memory (this is what the sanitizer is here to see)
+    const int32_t ranks[3] = {8, 64, 200}; const float scales[3] = {0.25f, 0.03125f, 0.01f};
+    lora_pool_desc_t d{512, 256, 3, ranks, scales, LORA_BF16};
+    size_t ab; LK(lora_pool_bytes(&d, &ab));
+    lora_pool_t *pool; LK(lora_pool_create(&d, (void *)0x10000000, ab, &pool));
+    for (int a = 0; a < 3; ++a) LK(lora_pool_mark_resident(pool, a));
+    const int32_t ta[6] = {0, 1, 2, -1, 1, 1};
+    lora_plan_options_t opt = LORA_PLAN_OPTIONS_DEFAULT; opt.whole_k_limit = 0;
+    lora_segments_t *seg; LK(lora_segments_plan_opts(pool, ta, 6, &opt, &seg));
+    LK(lora_pool_destroy(pool));
+    lora_status_t st = lora_segments_rebuild(seg, ta, 6, nullptr);
+    if (st != LORA_ERR_STALE_SEGMENTS) { printf("rebuild after pool destroy: %s\n", lora_status_string(st)); return 1; }
+    st = lora_apply(pool, seg, (void *)0x20000000, 512, (void *)0x30000000, 256, (void *)0x40000000, 1 << 20, nullptr);
+    if (st != LORA_ERR_INVALID_ARG) { printf("apply on a destroyed pool: %s\n", lora_status_string(st)); return 1; }
+    size_t wsb; st = lora_apply_workspace_bytes(pool, seg, &wsb);
+    if (st != LORA_ERR_INVALID_ARG) { printf("workspace size on a destroyed pool: %s\n", lora_status_string(st)); return 1; }
+    st = lora_pool_destroy(pool);
+    if (st != LORA_ERR_INVALID_ARG) { printf("second destroy: %s\n", lora_status_string(st)); return 1; }
+    lora_segments_info_t info; LK(lora_segments_info(seg, &info));   // the object itself is intact
+    // a new pool (perhaps at the old address) is not the old one
+    lora_pool_t *p2; LK(lora_pool_create(&d, (void *)0x10000000, ab, &p2));
+    for (int a = 0; a < 3; ++a) LK(lora_pool_mark_resident(p2, a));
+    st = lora_segments_rebuild(seg, ta, 6, nullptr);
+    if (st != LORA_ERR_STALE_SEGMENTS) { printf("rebuild on a successor pool: %s\n", lora_status_string(st)); return 1; }
+    LK(lora_segments_destroy(seg)); LK(lora_pool_destroy(p2));
+  }
   // the placement routine (host only): random demands, with and without a previous table
   for (int iter = 0; iter < 200; ++iter) {
     const int S = 1 + g() % 12, N = g() % 120;

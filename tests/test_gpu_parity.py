@@ -1188,6 +1188,93 @@ def _with_seed(b, seed):
     return dataclasses.replace(b, seed=seed)
 
 
+def test_callers_own_table_staging_and_load_buffers():
+    """The allocation-free forms: the segment table in device memory and pinned staging of the caller's
+    (lora_segments_upload_to, kept through lora_segments_rebuild), adapters loaded from host memory
+    through a device staging buffer of the caller's (lora_pool_load_staged).  Same bits as the calls
+    that allocate for the caller."""
+    b = wl.small_mixed(seed=31, in_features=1024, out_features=512)
+    dp = G.DevicePool(b)                     # loaded with lora_pool_load (library's staging)
+    n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
+    arena2 = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    pool2 = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, arena2)
+    stage = torch.empty(max(L.lora_pool_load_staging_bytes(pool2, int(a)) for a in b.used_adapters()),
+                        dtype=torch.uint8, device="cuda")
+    for a in b.used_adapters():
+        L.lora_pool_load_staged(pool2, int(a), dp.A[int(a)], dp.B[int(a)], stage)
+        torch.cuda.synchronize()             # one staging buffer for all: wait before it is written again
+    assert torch.equal(arena2, dp.arena)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_load_staged(pool2, int(b.used_adapters()[0]), dp.A[int(b.used_adapters()[0])],
+                                dp.B[int(b.used_adapters()[0])], stage[:64])
+    assert e.value.status_name == "LORA_ERR_OOM"
+
+    x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
+    want = G.apply_on_gpu(dp, x_bits, y0_bits)
+    seg = L.lora_segments_plan(pool2, b.token_adapter)
+    need = L.lora_segments_table_bytes(seg)
+    table = torch.empty(2 * need, dtype=torch.uint8, device="cuda")
+    staging = torch.empty(2 * need, dtype=torch.uint8).pin_memory()
+    with pytest.raises(L.LoraError) as e:
+        L.lora_segments_upload_to(seg, table[:256], staging)
+    assert e.value.status_name == "LORA_ERR_OOM"
+    L.lora_segments_upload_to(seg, table, staging)
+    x = G.bits_to_dev(x_bits)
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(pool2, seg), 256), dtype=torch.uint8, device="cuda")
+    y = G.bits_to_dev(y0_bits)
+    L.lora_apply(pool2, seg, x, y, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(G.dev_to_bits(y), want)
+    # another batch into the same object: the caller's buffers are used again
+    ta2 = np.roll(b.token_adapter, 7)
+    L.lora_segments_rebuild(seg, ta2)
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(pool2, seg), 256), dtype=torch.uint8, device="cuda")
+    y = G.bits_to_dev(y0_bits)
+    L.lora_apply(pool2, seg, x, y, ws)
+    torch.cuda.synchronize()
+    want2 = G.apply_on_gpu(dp, x_bits, y0_bits, token_adapter=ta2)
+    assert np.array_equal(G.dev_to_bits(y), want2)
+    G.check_parity(want2, G.oracle_apply(dp, x_bits, y0_bits, token_adapter=ta2), y0_bits, ta2)
+    # a batch whose table no longer fits the caller's buffers is refused, the object stays usable
+    big = np.concatenate([b.token_adapter] * 40)
+    if L.lora_segments_table_bytes(seg) * 20 > 2 * need:
+        with pytest.raises(L.LoraError) as e:
+            L.lora_segments_rebuild(seg, big)
+        assert e.value.status_name == "LORA_ERR_OOM"
+    L.lora_segments_destroy(seg)
+    L.lora_pool_destroy(pool2)
+    dp.close()
+
+
+def test_plan_options_select_the_launch_form_per_object():
+    """Two segment objects of one pool with different settings, applied one after the other: each keeps
+    its own form (one launch / two launches / k-slices), all give the same bits."""
+    b = wl.cfg1_decode(in_features=2048, out_features=1024, n_tokens=200)
+    dp = G.DevicePool(b)
+    x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
+    x = G.bits_to_dev(x_bits)
+    outs = []
+    segs = [L.lora_segments_build(dp.pool, b.token_adapter, options=o) for o in
+            (L.plan_options(decode_single_launch=1), L.plan_options(decode_single_launch=0), L.plan_options(whole_k_limit=0),
+             L.plan_options(whole_k_limit=0, fused_apply=1))]
+    infos = [L.lora_segments_info(sg) for sg in segs]
+    assert infos[0]["single_launch"] and not infos[1]["single_launch"] and infos[2]["n_k_slices"] > 1
+    for rep in range(2):
+        for sg in segs:
+            ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, sg), 256), dtype=torch.uint8, device="cuda")
+            y = G.bits_to_dev(y0_bits)
+            L.lora_apply(dp.pool, sg, x, y, ws)
+            torch.cuda.synchronize()
+            L.lora_segments_check(sg)
+            outs.append(G.dev_to_bits(y))
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0])
+    G.check_parity(outs[0], G.oracle_apply(dp, x_bits, y0_bits), y0_bits, b.token_adapter)
+    for sg in segs:
+        L.lora_segments_destroy(sg)
+    dp.close()
+
+
 def test_plan_then_upload_and_the_measurement_hook():
     """lora_segments_plan + lora_segments_upload give the object lora_segments_build gives (same bits
     from an apply); a planned object that was never uploaded is refused; the measurement hook records

@@ -567,3 +567,64 @@ def test_one_launch_decode_plan_keeps_every_tile_on_one_xcd():
         L.lora_segments_destroy(seg)
         L.lora_pool_destroy(pool)
     assert planned >= 3
+
+
+def test_plan_options_belong_to_the_object():
+    """Settings given at planning stay with the segment object: two objects planned in one process with
+    different settings differ, whatever the process-wide defaults are, and fields left at their default
+    follow the lora_set_* value of the moment."""
+    b = wl.cfg1_decode()
+    n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
+    pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
+    for a in range(b.n_adapters):
+        L.lora_pool_mark_resident(pool, a)
+    plans = {}
+    for name, opt in (("slices", L.plan_options(whole_k_limit=0)), ("two", L.plan_options(decode_single_launch=0)),
+                      ("one", L.plan_options(decode_single_launch=1)), ("default", None)):
+        seg = L.lora_segments_plan(pool, b.token_adapter, options=opt)
+        plans[name] = L.lora_segments_info(seg)
+        L.lora_segments_destroy(seg)
+    assert plans["slices"]["n_k_slices"] == 4 and not plans["slices"]["single_launch"]
+    assert plans["two"]["n_k_slices"] == 1 and not plans["two"]["single_launch"] and plans["two"]["n_shrink_units"] == 249
+    assert plans["one"]["single_launch"] and plans["one"]["launch_work_groups"] == 256
+    assert plans["default"]["single_launch"]
+    L.lora_set_decode_single_launch(False)
+    try:
+        seg = L.lora_segments_plan(pool, b.token_adapter)
+        assert not L.lora_segments_info(seg)["single_launch"]            # a default field follows the process-wide value
+        L.lora_segments_destroy(seg)
+        seg = L.lora_segments_plan(pool, b.token_adapter, options=L.plan_options(decode_single_launch=1))
+        assert L.lora_segments_info(seg)["single_launch"]                # an explicit field does not
+        L.lora_segments_destroy(seg)
+    finally:
+        L.lora_set_decode_single_launch(True)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_segments_plan(pool, b.token_adapter, options=L.plan_options(merged_launches=5))
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+    L.lora_pool_destroy(pool)
+
+
+def test_handles_that_outlive_their_pool_are_refused():
+    ranks = np.array([8, 64], dtype=np.int32)
+    scales = (2.0 / ranks).astype(np.float32)
+    n = L.lora_pool_bytes(512, 256, ranks, scales)
+    pool = L.lora_pool_create(512, 256, ranks, scales, FAKE_ARENA, n)
+    for a in range(2):
+        L.lora_pool_mark_resident(pool, a)
+    ta = np.array([0, 1, 1, -1], dtype=np.int32)
+    seg = L.lora_segments_plan(pool, ta)
+    assert L.lora_segments_table_bytes(seg) > 0 and L.lora_segments_table_bytes(seg) % 256 == 0
+    handle = pool.handle.value
+    L.lora_pool_destroy(pool)
+    pool.handle = ctypes.c_void_p(handle)          # the stale handle, as a careless caller would keep it
+    with pytest.raises(L.LoraError) as e:
+        L.lora_segments_rebuild(seg, ta)
+    assert e.value.status_name == "LORA_ERR_STALE_SEGMENTS"
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply_workspace_bytes(pool, seg)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+    with pytest.raises(L.LoraError) as e:
+        L.lora_pool_adapter_info(pool, 0)
+    assert e.value.status_name == "LORA_ERR_INVALID_ARG"
+    pool.handle = ctypes.c_void_p(None)
+    L.lora_segments_destroy(seg)
