@@ -17,8 +17,8 @@
  *   - bf16 storage (x, y, adapter weights), fp32 accumulation, one round-to-nearest-even to bf16
  *     when y is written.  lora_shrink returns v as fp32.  Between the two halves of lora_apply, and
  *     when lora_expand takes the caller's fp32 v, v enters the expand MFMAs as two bf16 terms hi + lo
- *     (hi = nearest bf16 of v, lo = nearest bf16 of v - hi): 16 mantissa bits, relative error at most
- *     2^-17 per element, far inside the one bf16 rounding of y (2^-9).
+ *     (hi = nearest bf16 of v, lo = nearest bf16 of v - hi): 16 significant bits, relative error at
+ *     most 2^-16 per element, far inside the one rounding of y to bf16 (2^-8).
  *   - "device" pointers are HIP device memory of the current device; "host" pointers are ordinary
  *     host memory.  The caller owns every device buffer it passes in (arena, x, y, v, workspace).
  *     The library owns its opaque host objects.  Two conveniences allocate on the caller's behalf:

@@ -21,8 +21,9 @@ def _full_parity(batch, y0_kind="zero", ranges=None, tol=G.TOL):
     y_bits = G.apply_on_gpu(dp, x_bits, y0_bits, ranges=ranges)
     y_ref = G.oracle_apply(dp, x_bits, y0_bits)
     worst = G.check_parity(y_bits, y_ref, y0_bits, batch.token_adapter, tol=tol)
+    n, _w, worst_el = G.check_all_rows(dp, x_bits, y0_bits, y_bits, token_adapter=batch.token_adapter, tol=tol)
     dp.close()
-    print(f"[ok] {batch.name}: max row rel-L2 {worst:.3e}", flush=True)
+    print(f"[ok] {batch.name}: {n} rows, max row rel-L2 {worst:.3e}, max element error / bound {worst_el:.3f}", flush=True)
     return worst
 
 
@@ -331,6 +332,53 @@ def test_shrink_and_expand_separately(big):
     dp.close()
 
 
+def test_expand_keeps_sixteen_bits_of_a_wide_ranged_v():
+    """v reaches the expand MFMAs as two bf16 terms hi + lo (16 significant bits).  With a v whose
+    entries span thirty binades (2^-20 .. 2^10, random mantissas, both signs) every element of y must
+    stay within one rounding of y (2^-8) plus (2^-16 + (r + 2) 2^-24) of the sum of the absolute terms:
+    a v cut to bf16 alone (8 bits) would miss that bound by two orders of magnitude on the rows where
+    the large entries cancel."""
+    for b in (wl.small_mixed(seed=41, in_features=256, out_features=640),
+              wl.small_mixed(seed=42, in_features=256, out_features=512, decode_tokens=30, prefill_lens=(300, 500, 260))):
+        dp = G.DevicePool(b)
+        seg = L.lora_segments_build(dp.pool, b.token_adapter)
+        info = L.lora_segments_info(seg)
+        ex = L.lora_segments_export(seg)
+        rng = np.random.default_rng(7)
+        stride = int(b.ranks.max())
+        v_ref = np.zeros((b.T, stride), dtype=np.float64)
+        v_in = np.zeros(max(info["v_floats"], 1), dtype=np.float32)
+        for t in range(b.T):
+            a = b.token_adapter[t]
+            if a < 0:
+                continue
+            r = int(b.ranks[a])
+            vals = (rng.uniform(1.0, 2.0, r) * np.exp2(rng.integers(-20, 11, r)) * rng.choice([-1.0, 1.0], r)).astype(np.float32)
+            v_in[ex["v_offset"][t]: ex["v_offset"][t] + r] = vals
+            v_ref[t, :r] = vals.astype(np.float64)
+        y0_bits = b.y0_bits("zero")
+        y = G.bits_to_dev(y0_bits)
+        L.lora_expand(dp.pool, seg, torch.from_numpy(v_in).cuda(), y)
+        torch.cuda.synchronize()
+        yg = wl.bf16_bits_to_f64(G.dev_to_bits(y))
+        y_ref = oracle.lora_expand(v_ref, b.token_adapter, b.ranks, b.scales, dp.B, b.out_features)
+        mag = oracle.lora_expand(np.abs(v_ref), b.token_adapter, b.ranks, b.scales,
+                                 [None if m is None else G.abs_bits(m) for m in dp.B], b.out_features)
+        act = b.token_adapter >= 0
+        r8 = ((b.ranks.astype(np.int64) + 7) // 8 * 8)[b.token_adapter[act]].astype(np.float64)
+        c = 2.0 ** -16 + (r8 + 2.0) * 2.0 ** -24
+        bound = (G.U_BF16 * np.abs(y_ref[act]) + c[:, None] * mag[act]) * (1.0 + 2.0 ** -7)
+        ratio = np.abs(yg[act] - y_ref[act]) / np.maximum(bound, 1e-300)
+        assert ratio.max() <= 1.0, f"element error {ratio.max():.2f} x the hi + lo bound"
+        # the bound is tight enough to tell 16 bits from 8: with v cut to bf16 the same check fails
+        v_cut = wl.bf16_bits_to_f64(wl.f32_to_bf16_bits(v_ref.astype(np.float32)))
+        y_cut = oracle.lora_expand(v_cut, b.token_adapter, b.ranks, b.scales, dp.B, b.out_features)
+        assert (np.abs(y_cut[act] - y_ref[act]) / np.maximum(bound, 1e-300)).max() > 1.0
+        assert not yg[~act].any()
+        L.lora_segments_destroy(seg)
+        dp.close()
+
+
 def test_ranges_entry_point_matches_token_list():
     b = wl.cfg2_prefill(0, length_scale=0.02)
     b.in_features, b.out_features = 512, 256
@@ -428,13 +476,27 @@ def test_device_source_load_and_stale_segments():
 # launches), checked on sampled rows the oracle computes one by one, plus the property that rows
 # without an adapter and rows outside the sample's groups are untouched where that applies.
 # ------------------------------------------------------------------------------------------------
-def _sampled_parity(batch, n_rows=48, y0_kind="zero", seed=0):
-    print(f"[case] {batch.name} T={batch.T} in={batch.in_features} out={batch.out_features} (sampled)", flush=True)
+def _sampled_parity(batch, n_rows=48, y0_kind="zero", seed=0, quick=False):
+    """A full-size case: every active row against the oracle (row bar and element-wise bound), in row
+    chunks; with --quick-parity only sampled rows (each group's first, middle and last token plus random
+    ones) at the row bar."""
+    print(f"[case] {batch.name} T={batch.T} in={batch.in_features} out={batch.out_features} "
+          f"({'sampled rows' if quick else 'all rows'})", flush=True)
     dp = G.DevicePool(batch)
     x_bits, y0_bits = batch.x_bits(), batch.y0_bits(y0_kind)
     y_bits = G.apply_on_gpu(dp, x_bits, y0_bits)
+    if y0_kind == "zero":
+        # no row is left undone: every active row of a zero y0 must have become non-zero
+        active_rows = batch.token_adapter >= 0
+        assert np.all(y_bits[active_rows].any(axis=1)) and not y_bits[~active_rows].any()
+    if not quick:
+        n, worst_row, worst_el = G.check_all_rows(dp, x_bits, y0_bits, y_bits)
+        assert n == int((batch.token_adapter >= 0).sum())
+        dp.close()
+        print(f"[ok] {batch.name}: {n} rows, max row rel-L2 {worst_row:.3e}, max element error / bound {worst_el:.3f}",
+              flush=True)
+        return
     rng = np.random.default_rng(seed)
-    # sample across groups: first / last token of some groups (tile edges) plus random tokens
     rows = set(rng.integers(0, batch.T, size=n_rows).tolist())
     for a in batch.used_adapters()[:: max(1, len(batch.used_adapters()) // 12)]:
         idx = np.nonzero(batch.token_adapter == a)[0]
@@ -447,24 +509,20 @@ def _sampled_parity(batch, n_rows=48, y0_kind="zero", seed=0):
     assert np.array_equal(y_bits[rows][~act], y0_bits[rows][~act])
     err = G.row_rel_l2(yg[act], y_ref[act])
     assert err.max() <= G.TOL, f"max per-row relative L2 error {err.max():.3e}"
-    # no row is left undone: every active row of a zero y0 must have become non-zero
-    if y0_kind == "zero":
-        active_rows = batch.token_adapter >= 0
-        assert np.all(y_bits[active_rows].any(axis=1)) and not y_bits[~active_rows].any()
     dp.close()
     print(f"[ok] {batch.name}: max row rel-L2 {err.max():.3e} on {act.sum()} sampled rows", flush=True)
 
 
 @pytest.mark.parametrize("shape", [0, 1, 2])
-def test_cfg2_prefill_full_size(shape):
-    _sampled_parity(wl.cfg2_prefill(shape))
+def test_cfg2_prefill_full_size(shape, quick_parity):
+    _sampled_parity(wl.cfg2_prefill(shape), quick=quick_parity)
 
 
 @pytest.mark.parametrize("layer,projection", [(0, 0), (5, 1), (17, 4), (31, 6)])
-def test_cfg3_stack_full_size(layer, projection):
+def test_cfg3_stack_full_size(layer, projection, quick_parity):
     """The mixed batch (8 prefills + 384 decode tokens, 256 adapters) on q, k, gate and down
     projections of four layers; all 224 projections share the token -> adapter map."""
-    _sampled_parity(wl.cfg3_stack(layer=layer, projection=projection), seed=layer)
+    _sampled_parity(wl.cfg3_stack(layer=layer, projection=projection), seed=layer, quick=quick_parity)
 
 
 def test_mixed_batch_forms_give_the_same_bits():
@@ -552,15 +610,15 @@ def test_mixed_batch_with_token_heavy_groups_up_to_rank_64():
 
 
 @pytest.mark.parametrize("shape,split", [(0, "9:1"), (0, "1:1"), (0, "1:9"), (1, "1:1"), (2, "1:1")])
-def test_cfg4_skew_full_size(shape, split):
-    _sampled_parity(wl.cfg4_skew(shape, split), n_rows=64)
+def test_cfg4_skew_full_size(shape, split, quick_parity):
+    _sampled_parity(wl.cfg4_skew(shape, split), n_rows=64, quick=quick_parity)
 
 
 @pytest.mark.parametrize("split", ["9:1", "1:9"])
-def test_cfg4_two_adapter_variant_full_size(split):
+def test_cfg4_two_adapter_variant_full_size(split, quick_parity):
     """One rank-8 and one rank-256 adapter share the 512 tokens (the co-serving pair of the paper's
     motivation, Fig. 1): groups of up to 461 tokens on the decode-sized units."""
-    _sampled_parity(wl.cfg4_skew(0, split, adapters_per_class=1), n_rows=64)
+    _sampled_parity(wl.cfg4_skew(0, split, adapters_per_class=1), n_rows=64, quick=quick_parity)
 
 
 def test_cfg4_isolated_class_equals_mixed_rows():
