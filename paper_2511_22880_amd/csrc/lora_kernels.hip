@@ -28,14 +28,18 @@ namespace lora {
 #ifdef LORA_WG_CLOCKS
 __device__ unsigned long long *g_clock_buf = nullptr;
 __device__ unsigned g_clock_slots = 0;
-#define LORA_CLOCK(point)                                                                              \
+#define LORA_CLOCK_AT(base, point)                                                                     \
     do {                                                                                               \
-        if (g_clock_buf && threadIdx.x == 0 && blockIdx.x < g_clock_slots)                             \
-            g_clock_buf[(size_t)blockIdx.x * 8 + (point)] = wall_clock64();                            \
+        if (g_clock_buf && threadIdx.x == 0 && (base) + blockIdx.x < g_clock_slots)                    \
+            g_clock_buf[((size_t)(base) + blockIdx.x) * 8 + (point)] = wall_clock64();                 \
     } while (0)
 #else
-#define LORA_CLOCK(point) do { } while (0)
+#define LORA_CLOCK_AT(base, point) do { } while (0)
 #endif
+#define LORA_CLOCK(point) LORA_CLOCK_AT(0, point)
+// expand launches keep their clocks behind those of the shrink launch of the same apply
+[[maybe_unused]] constexpr unsigned kClockExpandBase = 32768;
+#define LORA_CLOCK_E(point) LORA_CLOCK_AT(kClockExpandBase, point)
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -348,6 +352,7 @@ __global__ __launch_bounds__(kWideThreads) void k_shrink_wide(const Unit *__rest
                                                               uint16_t *__restrict__ v_lo)
 {
     __shared__ __attribute__((aligned(16))) char lds[kWideLds];
+    LORA_CLOCK(0);
     const Unit &u = units[blockIdx.x];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -454,6 +459,7 @@ __global__ __launch_bounds__(kWideThreads) void k_shrink_wide(const Unit *__rest
                 *reinterpret_cast<f32x4 *>(v_f32 + off) = t;
             }
         }
+        LORA_CLOCK(4);
     }
 }
 
@@ -1540,7 +1546,9 @@ __global__ __launch_bounds__(kThreads) void k_shrink(const Unit *__restrict__ un
                                                      int64_t slice_stride, Sync sy)
 {
     __shared__ __attribute__((aligned(16))) char lds[kShrinkLds];
+    LORA_CLOCK(0);
     shrink_body(units[blockIdx.x], arena, x, ldx, in, k_slice_len, v_out, n_slices, slice_stride, lds, sy);
+    LORA_CLOCK(4);
 }
 
 // BIG: units of up to 64 tokens (token-heavy groups), token indices from perm, the next token block's
@@ -1554,7 +1562,9 @@ __global__ __launch_bounds__(kThreads, BIG ? 2 : 4) void k_expand(const Unit *__
                                                                   int64_t ldy, Sync sy)
 {
     __shared__ __attribute__((aligned(16))) char lds[BIG ? kBigLds : kExpandLds];
+    LORA_CLOCK_E(0);
     expand_dispatch<BIG, VF32>(units[blockIdx.x], perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+    LORA_CLOCK_E(4);
 }
 
 // Both halves in one launch: blocks [0, n_shrink) are shrink units, the rest expand units that wait

@@ -21,9 +21,14 @@ import numpy as np
 
 from . import binding as L
 
-# tokens/s through shrink + expand of one 4096 -> 4096 projection, all adapters of one rank
-MEASURED_OP = {8: 22532 / 119.3e-6, 16: 22532 / 121.3e-6, 32: 22532 / 127.4e-6, 64: 22532 / 144.7e-6,
-               128: 22532 / 198.7e-6}
+def operating_points() -> dict:
+    """{rank: tokens/s one GPU sustains through shrink + expand of a 4096 -> 4096 projection with every
+    adapter at that rank}, measured with bench.py on the MI355X machine and kept in profiles/measured.json."""
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "profiles", "measured.json")
+    with open(path) as f:
+        return {int(k): float(v) for k, v in json.load(f)["placement_operating_points_tokens_per_s"].items()}
 
 
 def utilisation(phi: np.ndarray, ranks: np.ndarray, demand: np.ndarray, op: dict, padded: bool) -> np.ndarray:
@@ -60,22 +65,23 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     g = np.random.default_rng(args.seed)
-    rank_set = np.array(sorted(MEASURED_OP))
+    OP = operating_points()
+    rank_set = np.array(sorted(OP))
     ranks = rank_set[g.permutation(args.adapters) % len(rank_set)].astype(np.int32)
     pop = (np.arange(args.adapters) + 1.0) ** -args.alpha
     pop = pop[g.permutation(args.adapters)]
-    per_token = np.array([1.0 / MEASURED_OP[int(r)] for r in ranks])
+    per_token = np.array([1.0 / OP[int(r)] for r in ranks])
     demand = pop / (pop * per_token).sum() * args.load * args.servers      # tokens/s
     placements = {
-        "rank-aware (lora_place_assign)": L.lora_place_assign(args.servers, ranks, demand, MEASURED_OP)["phi"],
+        "rank-aware (lora_place_assign)": L.lora_place_assign(args.servers, ranks, demand, OP)["phi"],
         "random": static_placement("random", args.servers, ranks, g),
         "contiguous by rank": static_placement("contiguous", args.servers, ranks, g),
     }
     print(f"{args.servers} servers, {args.adapters} adapters, popularity ~ k^-{args.alpha}, load {args.load:.2f}")
     print(f"{'placement':34s} {'ragged: max / mean util':>26s} {'padded: max / mean util':>26s} {'copies':>7s}")
     for name, phi in placements.items():
-        ur = utilisation(phi, ranks, demand, MEASURED_OP, False)
-        up = utilisation(phi, ranks, demand, MEASURED_OP, True)
+        ur = utilisation(phi, ranks, demand, OP, False)
+        up = utilisation(phi, ranks, demand, OP, True)
         print(f"{name:34s} {ur.max():12.3f} / {ur.mean():.3f} {up.max():18.3f} / {up.mean():.3f} {int((phi > 0).sum()):7d}")
     return 0
 

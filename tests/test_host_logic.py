@@ -628,3 +628,28 @@ def test_handles_that_outlive_their_pool_are_refused():
     assert e.value.status_name == "LORA_ERR_INVALID_ARG"
     pool.handle = ctypes.c_void_p(None)
     L.lora_segments_destroy(seg)
+
+
+def test_bench_reads_its_profiler_figures_from_the_data_file():
+    """bench.py carries no profiler figure of its own: HBM traffic per launch, the read ceiling and the
+    placement simulator's operating points come from profiles/measured.json, and the summaries beside
+    it quote the same traffic figures."""
+    import glob
+    import importlib.util
+    import json
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_under_test", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    with open(os.path.join(root, "profiles", "measured.json")) as f:
+        data = json.load(f)
+    assert bench.load_measured() == data
+    assert data["read_ceiling_GBps"] > 0 and data["traffic_bytes"] and data["phase_kernels"]
+    src = open(os.path.join(root, "bench.py")).read()
+    assert "MEASURED_TRAFFIC" not in src and "28.49e6" not in src
+    summaries = "".join(open(p).read() for p in glob.glob(os.path.join(root, "profiles", "*.md")))
+    for key, nbytes in data["traffic_bytes"].items():
+        assert f"{nbytes / 1e6:.2f}" in summaries or f"{nbytes / 1e6:.1f}" in summaries, f"{key}: {nbytes} is not quoted in profiles/*.md"
+    from paper_2511_22880_amd import placement_sim
+    ops = placement_sim.operating_points()
+    assert ops == {int(k): v for k, v in data["placement_operating_points_tokens_per_s"].items()}
