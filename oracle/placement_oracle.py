@@ -50,8 +50,11 @@ def server_budget(rank_util: Dict[int, float], target: float) -> Dict[int, int]:
     return {r: (int(math.floor(u / target + 0.5)) if target > 0 else 0) for r, u in rank_util.items()}
 
 
-def assign(n_servers: int, ranks, demand, op: Dict[int, float], prev_phi: Optional[np.ndarray] = None):
-    """-> dict(phi [n_adapters][n_servers], server_util, server_max_rank, budget, target, phi_unpermuted)."""
+def assign(n_servers: int, ranks, demand, op: Dict[int, float], prev_phi: Optional[np.ndarray] = None,
+           step4: str = "fits"):
+    """-> dict(phi [n_adapters][n_servers], server_util, server_max_rank, budget, target, phi_unpermuted).
+    step4 = "fits" is reading R5; "literal" takes the listing's comment word for word (the server with the
+    highest max rank, the least utilised among those), kept for the comparison in the tests."""
     ranks = [int(r) for r in ranks]
     demand = [float(d) for d in demand]
     n = len(ranks)
@@ -99,6 +102,8 @@ def assign(n_servers: int, ranks, demand, op: Dict[int, float], prev_phi: Option
     for a in leftovers:
         r = ranks[a]
         fits = [s for s in range(n_servers) if max_rank[s] == 0 or max_rank[s] >= r]
+        if step4 == "literal":
+            fits = []
         if fits:
             s = min(fits, key=lambda s: (util[s], -max_rank[s], s))
         else:
