@@ -65,18 +65,19 @@ def test_what_if_script_balances_better_than_the_static_placements():
     """The demonstration script's numbers: under the ragged cost model every placement carries the
     same total utilisation, and the rank-aware one has the lowest peak on skewed popularity."""
     from paper_2511_22880_amd import placement_sim as S
+    op = S.operating_points()
     for seed in (0, 1, 2):
         g = np.random.default_rng(seed)
         servers, n = 8, 200
-        ranks = np.array(sorted(S.MEASURED_OP))[g.permutation(n) % 5].astype(np.int32)
+        ranks = np.array(sorted(op))[g.permutation(n) % 5].astype(np.int32)
         pop = ((np.arange(n) + 1.0) ** -1.1)[g.permutation(n)]
-        per_token = np.array([1.0 / S.MEASURED_OP[int(r)] for r in ranks])
+        per_token = np.array([1.0 / op[int(r)] for r in ranks])
         demand = pop / (pop * per_token).sum() * 0.7 * servers
-        ours = L.lora_place_assign(servers, ranks, demand, S.MEASURED_OP)["phi"]
+        ours = L.lora_place_assign(servers, ranks, demand, op)["phi"]
         peaks = {}
         for name, phi in (("ours", ours), ("random", S.static_placement("random", servers, ranks, g)),
                           ("contiguous", S.static_placement("contiguous", servers, ranks, g))):
-            u = S.utilisation(phi, ranks, demand, S.MEASURED_OP, padded=False)
+            u = S.utilisation(phi, ranks, demand, op, padded=False)
             assert u.sum() == pytest.approx(0.7 * servers)
             peaks[name] = u.max()
         assert peaks["ours"] < peaks["random"] and peaks["ours"] < peaks["contiguous"]
