@@ -154,6 +154,36 @@ def lora_apply(x_bits, token_adapter, ranks, scales, A: Sequence[Optional[np.nda
     return y
 
 
+def lora_linear(x_bits, W_bits, token_adapter, ranks, scales, A: Sequence[Optional[np.ndarray]],
+                B: Sequence[Optional[np.ndarray]], rows=None) -> np.ndarray:
+    """y [n_rows][out] fp64 = x W + s_a (x A_a) B_a per token (rows without adapter: x W).
+
+    x_bits: uint16 [T][in]; W_bits: uint16 [in][out]; A[a]: uint16 [in][r_a]; B[a]: uint16 [r_a][out].
+    """
+    x = _u16(x_bits)
+    W = _u16(W_bits)
+    T, in_f = x.shape
+    if W.ndim != 2 or W.shape[0] != in_f:
+        raise ValueError("W is [in][out]")
+    out_f = int(W.shape[1])
+    ranks, ta, n_rows, rows_p, _keep = _prep(ranks, token_adapter, rows, T)
+    if ta.shape[0] != T:
+        raise ValueError("token_adapter has one entry per row of x")
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    A = [None if m is None else _u16(m) for m in A]
+    B = [None if m is None else _u16(m) for m in B]
+    _check_adapters(A, ranks, ta, lambda r: (in_f, r))
+    _check_adapters(B, ranks, ta, lambda r: (r, out_f))
+    y = np.empty((n_rows, out_f), dtype=np.float64)
+    rc = _load().oracle_lora_linear(n_rows, rows_p, in_f, out_f, x.ctypes.data_as(ctypes.c_void_p),
+                                    W.ctypes.data_as(ctypes.c_void_p), ta.ctypes.data_as(ctypes.c_void_p), len(A),
+                                    ranks.ctypes.data_as(ctypes.c_void_p), scales.ctypes.data_as(ctypes.c_void_p),
+                                    _ptr_table(A), _ptr_table(B), y.ctypes.data_as(ctypes.c_void_p))
+    if rc:
+        raise RuntimeError("oracle_lora_linear rejected its arguments")
+    return y
+
+
 def threads() -> int:
     """OpenMP threads the oracle will use (for the benchmark's 'cores' field)."""
     lib = _load()

@@ -156,3 +156,54 @@ int oracle_lora_apply(int n_rows, const int32_t *rows, int in, int out, const ui
     }
     return bad;
 }
+
+/*
+ * The adapted layer as a whole: base projection plus delta, per token,
+ *
+ *     y[t, o] = sum_{k < in} x[t, k] * W[k, o]  +  s_a * sum_{j < r_a} v[t, j] * B_a[j, o]
+ *
+ * with v as above and the second term absent for tokens without adapter: the frozen base layer and the
+ * low-rank pair added to it (Background, "Low-Rank Adaptation"), which is what a serving system computes
+ * for every adapted projection (Motivation, Fig. 3 measures Q, K, V, O).  W is bf16 bits, row-major
+ * [in][out].  fp64 throughout, k ascending, then j ascending; nothing is rounded.  Pinned by a
+ * hand-worked case with a 3 x 2 base matrix, by the merged dense product x (W + s A B), by W = 0
+ * (which must give oracle_lora_apply's bits) and by numpy's x W on rows without adapter.
+ */
+int oracle_lora_linear(int n_rows, const int32_t *rows, int in, int out, const uint16_t *x, const uint16_t *W,
+                       const int32_t *token_adapter, int n_adapters, const int32_t *ranks,
+                       const float *scales, const uint16_t *const *A, const uint16_t *const *B, double *y)
+{
+    if (check_common(n_rows, in, out, n_adapters, ranks)) return 1;
+    int rmax = 1;
+    for (int a = 0; a < n_adapters; ++a)
+        if (ranks[a] > rmax) rmax = ranks[a];
+    int bad = 0;
+#pragma omp parallel
+    {
+        double *v = (double *)malloc((size_t)rmax * sizeof(double));
+        double *base = (double *)malloc((size_t)out * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int i = 0; i < n_rows; ++i) {
+            int t = rows ? rows[i] : i;
+            int a = token_adapter[t];
+            double *yi = y + (size_t)i * out;
+            const uint16_t *xt = x + (size_t)t * in;
+            if (!v || !base || a >= n_adapters) { bad = 1; continue; }
+            for (int o = 0; o < out; ++o) {
+                double acc = 0.0;
+                for (int k = 0; k < in; ++k)
+                    acc += bf16_value(xt[k]) * bf16_value(W[(size_t)k * out + o]);
+                base[o] = acc;
+            }
+            if (a < 0) {
+                for (int o = 0; o < out; ++o) yi[o] = base[o];
+                continue;
+            }
+            shrink_row(xt, A[a], in, ranks[a], v);
+            expand_row(v, B[a], ranks[a], out, (double)scales[a], base, yi);
+        }
+        free(v);
+        free(base);
+    }
+    return bad;
+}

@@ -241,3 +241,66 @@ def test_oracle_rejects_bad_arguments():
         oracle.lora_apply(x, ta, ranks, scales, [A[0], A[1].T.copy()], B)
     with pytest.raises(TypeError):
         oracle.lora_apply(x.astype(np.float32), ta, ranks, scales, A, B)
+
+
+# ---- the adapted layer as a whole: base projection plus delta (oracle.lora_linear) ----------------------
+def test_linear_hand_worked_example():
+    """tests/golden/hand_worked_linear.txt: the hand-worked delta on top of a 3 x 2 base matrix."""
+    want = np.loadtxt(os.path.join(GOLDEN, "hand_worked_linear.txt"), comments="#")
+    A = [bits([[1], [2], [-1]]), bits([[1, 0], [0, 1], [2, -2]])]
+    B = [bits([[0.5, -1]]), bits([[1, 2], [-4, 0.25]])]
+    x = bits([[1, 2, 3], [2, -1, 4], [5, 5, 5]])
+    W = bits([[1, 0.5], [-2, 1], [0, 3]])
+    y = oracle.lora_linear(x, W, [1, 0, -1], [1, 2], [2.0, 0.5], A, B)
+    assert np.array_equal(y, want[:, 1:])
+    # a subset of rows, in another order
+    assert np.array_equal(oracle.lora_linear(x, W, [1, 0, -1], [1, 2], [2.0, 0.5], A, B, rows=[2, 0]), want[[2, 0], 1:])
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_linear_equals_the_merged_dense_product(seed):
+    """All tokens on one adapter: x W + s (x A) B = x (W + s A B), the merged weight of the paper's remark
+    that an adapter can be folded into the base model; numpy's matmul in fp64 is the textbook routine."""
+    rng = np.random.default_rng(100 + seed)
+    T, in_f, out_f, r = 7, 24, 10, 5
+    x, ta, ranks, scales, A, B = random_problem(rng, T, in_f, out_f, [r], allow_none=False)
+    W = wl.f32_to_bf16_bits(rng.standard_normal((in_f, out_f)).astype(np.float32) * 0.05)
+    y = oracle.lora_linear(x, W, ta, ranks, scales, A, B)
+    Xf, Wf, Af, Bf = (wl.bf16_bits_to_f64(m) for m in (x, W, A[0], B[0]))
+    merged = Xf @ (Wf + float(scales[0]) * (Af @ Bf))
+    assert np.allclose(y, merged, rtol=1e-12, atol=1e-14)
+
+
+def test_linear_with_a_zero_base_is_the_delta_and_rows_without_adapter_are_the_base():
+    rng = np.random.default_rng(7)
+    T, in_f, out_f = 9, 16, 6
+    x, ta, ranks, scales, A, B = random_problem(rng, T, in_f, out_f, [3, 8, 1])
+    ta[0], ta[1] = -1, 2
+    zero_w = np.zeros((in_f, out_f), dtype=np.uint16)
+    assert np.array_equal(oracle.lora_linear(x, zero_w, ta, ranks, scales, A, B), oracle.lora_apply(x, ta, ranks, scales, A, B))
+    W = wl.f32_to_bf16_bits(rng.standard_normal((in_f, out_f)).astype(np.float32))
+    y = oracle.lora_linear(x, W, ta, ranks, scales, A, B)
+    base = wl.bf16_bits_to_f64(x) @ wl.bf16_bits_to_f64(W)
+    none = ta < 0
+    assert none.any() and np.allclose(y[none], base[none], rtol=1e-13, atol=1e-15)
+    # base and delta add: y - x W is the delta on its own
+    assert np.allclose(y - base, oracle.lora_apply(x, ta, ranks, scales, A, B), rtol=0, atol=1e-12)
+    # the base part is linear in W: W scaled by 4 (exact in bf16) scales it by 4
+    W4 = wl.f32_to_bf16_bits((wl.bf16_bits_to_f64(W) * 4.0).astype(np.float32))
+    y4 = oracle.lora_linear(x, W4, ta, ranks, scales, A, B)
+    assert np.allclose(y4 - y, 3.0 * base, rtol=1e-12, atol=1e-13)
+
+
+def test_linear_reads_w_as_in_by_out():
+    """A unit input row picks one row of W (not a column): x = e_k gives W[k, :] plus the delta of e_k."""
+    in_f, out_f = 5, 3
+    rng = np.random.default_rng(3)
+    W = bits(dyadic(rng, (in_f, out_f)))
+    A = [bits(dyadic(rng, (in_f, 2)))]
+    B = [bits(dyadic(rng, (2, out_f)))]
+    for k in range(in_f):
+        e = np.zeros((1, in_f))
+        e[0, k] = 1.0
+        y = oracle.lora_linear(bits(e), W, [0], [2], [0.5], A, B)
+        want = wl.bf16_bits_to_f64(W)[k] + 0.5 * (wl.bf16_bits_to_f64(A[0])[k] @ wl.bf16_bits_to_f64(B[0]))
+        assert np.array_equal(y[0], want)
