@@ -329,6 +329,25 @@ lora_status_t lora_apply_workspace_bytes(const lora_pool_t *pool, const lora_seg
 lora_status_t lora_apply(const lora_pool_t *pool, const lora_segments_t *seg, const void *x, int64_t ldx,
                          void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream);
 
+/* The adapted layer in one pass over y: y[t, :] = bf16(x[t, :] W + s_a v[t, :] B_a) for EVERY token of the
+ * batch (tokens without adapter get x W alone): the base projection with the delta in its epilogue, the
+ * frozen layer plus the low-rank pair of Background, "Low-Rank Adaptation", computed together as a
+ * serving system does for each adapted projection (Motivation, Fig. 3).  y is written once and never
+ * read, where lora_apply reads and re-writes what a separate base GEMM wrote.  Launches: the shrink of
+ * lora_apply (v into the workspace), then one GEMM kernel over 256 x 128 tiles of y whose rows follow
+ * the segment object's grouping (x is gathered and y scattered through it; no copy of either).
+ *   w_packed: the base weight in the kernel's operand order, made once by lora_linear_pack_weight from
+ *             W^T [out][in] row-major bf16 (the layout of a linear layer's weight), in_features *
+ *             out_features * 2 bytes of device memory, 256-byte aligned, owned by the caller;
+ *   x, y, workspace, stream: as for lora_apply (workspace size: lora_apply_workspace_bytes); y need not be
+ *             initialised.  Single-pool segment objects only.
+ * fp32 accumulation of x W and of the delta (each in one accumulator, the delta scaled once), one
+ * rounding to bf16. */
+lora_status_t lora_linear_pack_weight(const void *wt_out_by_in, int32_t in_features, int32_t out_features,
+                                      void *dev_packed, void *stream);
+lora_status_t lora_linear(const lora_pool_t *pool, const lora_segments_t *seg, const void *x, int64_t ldx,
+                          const void *w_packed, void *y, int64_t ldy, void *workspace, size_t ws_bytes, void *stream);
+
 /* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  lora_apply with a workspace of the library's own, a file-scope
  * device array of LORA_STATIC_WORKSPACE_BYTES that every GPU the library runs on holds until the

@@ -30,7 +30,7 @@ EXPORTS = (
     "lora_segments_build_opts", "lora_segments_plan_multi_opts", "lora_segments_build_multi_opts", "lora_segments_plan_ranges", "lora_segments_upload",
     "lora_segments_build", "lora_segments_build_ranges", "lora_segments_rebuild", "lora_segments_info",
     "lora_segments_export", "lora_segments_export_units", "lora_segments_export_launch_units", "lora_segments_destroy", "lora_workspace_bytes",
-    "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_apply_static",
+    "lora_shrink", "lora_expand", "lora_apply_workspace_bytes", "lora_apply", "lora_apply_static", "lora_linear_pack_weight", "lora_linear",
     "lora_profile_next_apply",
     "lora_segments_plan_multi", "lora_segments_build_multi", "lora_apply_multi",
     "lora_set_fused_apply", "lora_set_decode_single_launch", "lora_set_whole_k_limit", "lora_segments_check", "lora_set_side_stream", "lora_set_merged_launches", "lora_set_fused_wait_limit",
@@ -393,6 +393,20 @@ def lora_apply(pool: Pool, seg: Segments, x, y, workspace, stream=None, ldx: Opt
     _check(lib().lora_apply(pool.handle, seg.handle, _ptr(x), ctypes.c_int64(_ld(x, ldx)), _ptr(y),
                             ctypes.c_int64(_ld(y, ldy)), _ptr(workspace),
                             ctypes.c_size_t(_nbytes(workspace) if ws_bytes is None else ws_bytes), _stream(stream)))
+
+
+def lora_linear_pack_weight(wt, in_features: int, out_features: int, dev_packed, stream=None) -> None:
+    """wt: device tensor W^T [out][in] bf16; dev_packed: device tensor of in * out * 2 bytes."""
+    _check(lib().lora_linear_pack_weight(_ptr(wt), ctypes.c_int32(in_features), ctypes.c_int32(out_features),
+                                         _ptr(dev_packed), _stream(stream)))
+
+
+def lora_linear(pool: Pool, seg: Segments, x, w_packed, y, workspace, stream=None, ldx: Optional[int] = None,
+                ldy: Optional[int] = None, ws_bytes: Optional[int] = None) -> None:
+    """y = bf16(x W + delta) for every token, y written once."""
+    _check(lib().lora_linear(pool.handle, seg.handle, _ptr(x), ctypes.c_int64(_ld(x, ldx)), _ptr(w_packed), _ptr(y),
+                             ctypes.c_int64(_ld(y, ldy)), _ptr(workspace),
+                             ctypes.c_size_t(_nbytes(workspace) if ws_bytes is None else ws_bytes), _stream(stream)))
 
 
 LORA_STATIC_WORKSPACE_BYTES = 32 << 20

@@ -16,6 +16,7 @@
 #include <unordered_map>
 #include <vector>
 
+using lora::LinBlock;
 using lora::SegRec;
 using lora::Unit;
 
@@ -93,6 +94,11 @@ struct lora_segments {
     std::vector<Unit> shrink_units, prefill_units, expand_units, expand_big_units;
     // the one-launch decode form's own lists, by place in the launch (empty places have ntok == 0)
     std::vector<Unit> fused_shrink, fused_expand;
+    // the adapted layer's row order (lora_linear): batch row of every place (-1: none) and the adapter of
+    // every 16 places; all T tokens are in it, the ones without adapter last
+    std::vector<int32_t> lin_rows;
+    std::vector<LinBlock> lin_blocks;
+    size_t off_lin_rows, off_lin_blocks;
     // device table: [perm | shrink units | prefill shrink units | expand units | arrival counters,
     // ready counters, time-out flag]
     char *dev;
@@ -676,7 +682,9 @@ static void layout_table(lora_segments *sg)
     sg->off_expand_big = round_up_sz(sg->off_expand + sg->expand_units.size() * sizeof(Unit), 256);
     sg->off_fused_shrink = round_up_sz(sg->off_expand_big + sg->expand_big_units.size() * sizeof(Unit), 256);
     sg->off_fused_expand = round_up_sz(sg->off_fused_shrink + sg->fused_shrink.size() * sizeof(Unit), 256);
-    sg->off_sync = round_up_sz(sg->off_fused_expand + sg->fused_expand.size() * sizeof(Unit), 256);
+    sg->off_lin_rows = round_up_sz(sg->off_fused_expand + sg->fused_expand.size() * sizeof(Unit), 256);
+    sg->off_lin_blocks = round_up_sz(sg->off_lin_rows + sg->lin_rows.size() * sizeof(int32_t), 256);
+    sg->off_sync = round_up_sz(sg->off_lin_blocks + sg->lin_blocks.size() * sizeof(LinBlock), 256);
     sg->table_bytes = round_up_sz(sg->off_sync + (size_t)(2 * sg->n_sync + 4 + 2 * 256) * sizeof(unsigned), 256);
 }
 
@@ -1069,6 +1077,38 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
         finish_decode_fused(sg, pool->in_features);
     else
         sg->decode_fused = false;
+    // row order of the adapted layer: groups in table order, each padded to a multiple of 16 places, then
+    // the tokens without adapter, the whole padded to a multiple of the kernel's row tile
+    sg->lin_rows.clear();
+    sg->lin_blocks.clear();
+    if (n_projections == 1 && T > 0) {
+        auto add_group = [&](const int32_t *toks, int n, const SegRec *r) {
+            for (int t0 = 0; t0 < n; t0 += 16) {
+                LinBlock b;
+                memset(&b, 0, sizeof b);
+                b.ntok = std::min(16, n - t0);
+                if (r) {
+                    b.b_off = r->b_off;
+                    b.v_off = r->v_off + (int64_t)t0 * r->r8;
+                    b.r8 = r->r8;
+                    b.scale = r->scale;
+                }
+                sg->lin_blocks.push_back(b);
+                for (int q = 0; q < 16; ++q) sg->lin_rows.push_back(q < b.ntok ? toks[t0 + q] : -1);
+            }
+        };
+        for (const SegRec &r : sg->segs) add_group(sg->perm.data() + r.tok_start, r.ntok, &r);
+        std::vector<int32_t> none;
+        for (int32_t t = 0; t < T; ++t)
+            if (ta[t] < 0) none.push_back(t);
+        add_group(none.data(), (int)none.size(), nullptr);
+        while (sg->lin_rows.size() % lora::kLinTileM) {
+            LinBlock b;
+            memset(&b, 0, sizeof b);
+            sg->lin_blocks.push_back(b);
+            sg->lin_rows.insert(sg->lin_rows.end(), 16, -1);
+        }
+    }
     layout_table(sg);
     return LORA_OK;
 }
@@ -1295,6 +1335,8 @@ static lora_status_t plan_multi_into(lora_segments *sg, const std::vector<const 
     sg->fused_shrink.clear();
     sg->fused_expand.clear();
     sg->fused_grid = 0;
+    sg->lin_rows.clear();
+    sg->lin_blocks.clear();
     layout_table(sg);
     return LORA_OK;
 }
@@ -1428,6 +1470,10 @@ static lora_status_t upload_table(lora_segments *sg, hipStream_t s)
         memcpy(sg->staging + sg->off_fused_shrink, sg->fused_shrink.data(), sg->fused_shrink.size() * sizeof(Unit));
     if (!sg->fused_expand.empty())
         memcpy(sg->staging + sg->off_fused_expand, sg->fused_expand.data(), sg->fused_expand.size() * sizeof(Unit));
+    if (!sg->lin_rows.empty())
+        memcpy(sg->staging + sg->off_lin_rows, sg->lin_rows.data(), sg->lin_rows.size() * sizeof(int32_t));
+    if (!sg->lin_blocks.empty())
+        memcpy(sg->staging + sg->off_lin_blocks, sg->lin_blocks.data(), sg->lin_blocks.size() * sizeof(LinBlock));
     memset(sg->staging + sg->off_sync, 0, sg->table_bytes - sg->off_sync);
     sg->launches = 0;
     if (sg->table_bytes) HIP_TRY(hipMemcpyAsync(sg->dev, sg->staging, sg->table_bytes, hipMemcpyHostToDevice, s));
@@ -2007,6 +2053,70 @@ try {
     if (sg->n_active == 0) return LORA_OK;
     return run_apply(pool->arena, pool->in_features, pool->out_features, sg, x, ldx, y, ldy, workspace, ws_bytes,
                      stream);
+}
+API_CATCH
+
+// ---- the adapted layer as one pass over y: base GEMM with the delta in its epilogue ----
+extern "C" lora_status_t lora_linear_pack_weight(const void *wt_out_by_in, int32_t in_features, int32_t out_features,
+                                                 void *dev_packed, void *stream)
+try {
+    if (!wt_out_by_in || !dev_packed) return fail(LORA_ERR_INVALID_ARG, "wt_out_by_in or dev_packed is NULL");
+    if (((uintptr_t)dev_packed) % 256) return fail(LORA_ERR_INVALID_ARG, "dev_packed is not 256-byte aligned");
+    if (in_features <= 0 || out_features <= 0 || in_features % 64 || out_features % 128)
+        return fail(LORA_ERR_SHAPE, "in_features (%d) must be a positive multiple of 64 and out_features (%d) of 128",
+                    in_features, out_features);
+    HIP_TRY(lora::launch_pack_weight((const uint16_t *)wt_out_by_in, in_features, out_features, (uint16_t *)dev_packed,
+                                     (hipStream_t)stream));
+    return LORA_OK;
+}
+API_CATCH
+
+extern "C" lora_status_t lora_linear(const lora_pool_t *pool, const lora_segments_t *sg, const void *x, int64_t ldx,
+                                     const void *w_packed, void *y, int64_t ldy, void *workspace, size_t ws_bytes,
+                                     void *stream)
+try {
+    lora_status_t st = check_launchable(pool, sg);
+    if (st != LORA_OK) return st;
+    if (sg->T == 0) return LORA_OK;
+    if (!w_packed || ((uintptr_t)w_packed) % 16) return fail(LORA_ERR_INVALID_ARG, "w_packed is NULL or not 16-byte aligned");
+    const int in = pool->in_features, out = pool->out_features;
+    if ((st = check_matrix(x, ldx, in, "x")) != LORA_OK) return st;
+    if ((st = check_matrix(y, ldy, out, "y")) != LORA_OK) return st;
+    const size_t need = apply_parts_bytes(sg) + 2 * apply_packed_bytes(sg);
+    if (sg->n_active > 0 && (st = check_workspace(workspace, ws_bytes, need)) != LORA_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    float *parts = (float *)workspace;
+    const int nsl = std::max(1, sg->n_k_slices);
+    const int64_t stride = nsl > 1 ? sg->v_floats : 0;
+    lora::SyncArgs sa;
+    sa.counters = (unsigned *)(sg->dev + sg->off_sync);
+    sa.ready = sa.counters + sg->n_sync;
+    sa.timeout_flag = sa.counters + 2 * sg->n_sync;
+    sa.v_hi = (uint16_t *)((char *)workspace + apply_parts_bytes(sg));
+    sa.v_lo = (uint16_t *)((char *)workspace + apply_parts_bytes(sg) + apply_packed_bytes(sg));
+    sa.epoch = 0;
+    sa.spin_limit = opt_spin_limit(sg);
+    if (sg->n_active > 0) {
+        // the shrink half of lora_apply's separate-launch forms: v complete as bf16 hi + lo in the workspace
+        const lora::LaunchCtx cs = ctx_for(pool, sg, kShrink), cp = ctx_for(pool, sg, kPrefill);
+        if (opt_merged(sg) && sg->has_big_units && !sg->wide && cs.n_units > 0) {
+            HIP_TRY(lora::launch_shrink_mixed(cp, sg->n_prefill_hi, cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl,
+                                              stride, &sa, s));
+        } else {
+            HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, sa.v_hi, sa.v_lo, nullptr, nsl,
+                                                stride, parts, &sa, s));
+            if (sg->wide)
+                HIP_TRY(lora::launch_shrink_wide(cs, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, nullptr,
+                                                 sa.v_hi, sa.v_lo, s));
+            else
+                HIP_TRY(lora::launch_shrink(cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride, &sa, s));
+        }
+    }
+    HIP_TRY(lora::launch_linear_lora((const int32_t *)(sg->dev + sg->off_lin_rows),
+                                     (const LinBlock *)(sg->dev + sg->off_lin_blocks), (int)sg->lin_rows.size(), pool->arena,
+                                     (const uint16_t *)w_packed, (const uint16_t *)x, ldx, in, out, sa.v_hi, sa.v_lo,
+                                     (uint16_t *)y, ldy, s));
+    return LORA_OK;
 }
 API_CATCH
 

@@ -45,6 +45,20 @@ struct Unit {
 };
 static_assert(sizeof(Unit) == 128, "Unit is 128 bytes");
 
+// One block of 16 consecutive places of the adapted layer's row order (lora_linear): tokens grouped by
+// adapter, every group padded to a multiple of 16 places, tokens without adapter last.
+struct LinBlock {
+    uint64_t b_off;  // element offset of the group's B^T in the arena
+    int64_t v_off;   // element offset of the v row of the block's first token
+    int32_t r8;      // padded rank; 0 = tokens without adapter (or an empty block)
+    int32_t ntok;    // tokens in the block, 0..16
+    float scale;
+    int32_t pad;
+};
+static_assert(sizeof(LinBlock) == 32, "LinBlock is 32 bytes");
+constexpr int kLinTileM = 256;  // rows of a work group's output tile (the row order is padded to a multiple)
+constexpr int kLinTileN = 128;  // columns of it: one 128-column strip of B^T
+
 #define LORA_MAX_RANK_PADDED 256
 constexpr int kTokTile = 16;   // tokens per MFMA tile (the N of a 16x16x32 MFMA)
 constexpr int kRowTile = 16;   // rank rows / output columns per MFMA tile (the M)
@@ -134,6 +148,19 @@ hipError_t launch_decode_fused(const LaunchCtx &shrink, const LaunchCtx &expand,
 // host_out[b] = XCD number (0..15) that work group b of an n-work-group launch ran on (n <= 1024).
 // Synchronises the stream.
 hipError_t probe_xcc(unsigned *host_out, int n_work_groups, hipStream_t stream);
+
+// The adapted layer in one pass over y: y[row] = bf16(x[row] W + s_a v[row] B_a), W in operand order
+// (launch_pack_weight), v as bf16 hi + lo from a shrink launch, rows[m] = batch row of place m (-1: none),
+// blocks[m / 16] the adapter of places 16 (m / 16) .. +15.  m_pad places, a multiple of kLinTileM.
+hipError_t launch_linear_lora(const int32_t *rows, const LinBlock *blocks, int m_pad, const uint16_t *arena,
+                              const uint16_t *w_packed, const uint16_t *x, int64_t ldx, int in, int out,
+                              const uint16_t *v_hi, const uint16_t *v_lo, uint16_t *y, int64_t ldy,
+                              hipStream_t stream);
+
+// W^T [out][in] row-major bf16 (the layout of a linear layer's weight) -> operand order: for every
+// 128-column strip and every 32-wide k step, eight 1 KB pieces (sub-block b = columns 8n + b), piece
+// (kq, n) holding k = 32 step + 8 kq .. +7 of column 128 strip + 8 n + b.
+hipError_t launch_pack_weight(const uint16_t *wt, int in, int out, uint16_t *dst, hipStream_t stream);
 
 // v[i] = sum over slices, in slice order.
 hipError_t launch_reduce_slices(const float *parts, int n_slices, int64_t slice_stride, float *v,

@@ -1636,6 +1636,195 @@ __global__ __launch_bounds__(256) void k_reduce_slices(const float *__restrict__
     v[idx] = acc;
 }
 
+// ------------------------------------------------------------------------------------------------
+// The adapted layer as one GEMM whose epilogue adds the delta: y = bf16(x W + s_a (x A_a) B_a), y written
+// once and never read (the delta on its own reads y and writes it back: two thirds of its traffic on
+// token-heavy batches).  Rows are taken in the order "tokens grouped by adapter, groups padded to
+// multiples of 16", so that every 16-row MFMA block has one adapter; x is gathered and y scattered
+// through that order, so no copy of either is made.
+//   * One work group (4 wavefronts) computes a 256 x 128 tile, wavefront w the rows 64 w .. 64 w + 63
+//     of it and all 128 columns: 4 x 8 MFMA tiles of 16 x 16, 128 accumulator registers.  With the
+//     columns of sub-block b being 8 n + b, lane n ends up with 8 consecutive columns of 4 tokens per
+//     row block, and y leaves in 16-byte pieces.
+//   * k goes in chunks of 64, double-buffered in LDS.  W comes packed in operand order (1 KB per
+//     wavefront operand, see launch_pack_weight), so a chunk of a strip is 16 KB of consecutive bytes,
+//     copied by loads that write LDS directly.  x rows are 128 consecutive bytes per chunk: 8 lanes
+//     take a row's chunk with 16-byte loads, and the pieces go into LDS in operand order, with the
+//     three low bits of the slot XORed by (2 kq + k step) so that the 64 lanes of a store spread over
+//     all banks; reads apply the same XOR and still cover each 1 KB block exactly.
+//   * After the k loop every row block adds s (v_hi + v_lo) B_a for its adapter: ceil(r8 / 32) more k
+//     steps whose operands come straight from memory (v rows, and B^T in the pool's operand order,
+//     the very pieces the expand kernels read), accumulated apart and scaled once, as the expand does.
+// ------------------------------------------------------------------------------------------------
+constexpr int kLinK = 64;                                   // k per chunk
+constexpr int kLinXBuf = (kLinK / 32) * (kLinTileM / 16) * 1024;  // bytes of x per buffer: 32 KB
+constexpr int kLinWBuf = (kLinK / 32) * 8 * 1024;                 // bytes of W per buffer: 16 KB
+constexpr int kLinLds = 2 * (kLinXBuf + kLinWBuf);
+
+__global__ __launch_bounds__(kThreads, 1) void k_linear_lora(
+    const int32_t *__restrict__ rows, const LinBlock *__restrict__ blocks, int m_tiles, int mt_per_xcd, int n_tiles,
+    const uint16_t *__restrict__ arena, const uint16_t *__restrict__ wp, const uint16_t *__restrict__ x, int64_t ldx,
+    int in, const uint16_t *__restrict__ v_hi, const uint16_t *__restrict__ v_lo, uint16_t *__restrict__ y, int64_t ldy)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kLinLds];
+    // work group b runs on XCD b mod 8: each XCD takes a run of row tiles and walks their column tiles,
+    // so a row tile's x (2 MB at 4096 input features) stays in that XCD's L2 while its columns go by
+    const int xcd = blockIdx.x & 7, jloc = blockIdx.x >> 3;
+    const int mt = xcd * mt_per_xcd + jloc / n_tiles;
+    const int nt = jloc % n_tiles;
+    if (jloc / n_tiles >= mt_per_xcd || mt >= m_tiles) return;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, kq = lane >> 4;
+    const int m0 = mt * kLinTileM;
+    const uint4 zero = {0u, 0u, 0u, 0u};
+    auto xbuf = [&](int which) __attribute__((always_inline)) { return lds + which * kLinXBuf; };
+    auto wbuf = [&](int which) __attribute__((always_inline)) { return lds + 2 * kLinXBuf + which * kLinWBuf; };
+
+    // staging role: 8 lanes per row chunk; thread t takes rows 32 i + t / 8 (i = 0..7), 16-byte piece t % 8
+    const int s_c = tid & 7;
+    const uint16_t *xrow[8];
+    int s_slot[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 32 * i + (tid >> 3);
+        const int row = rows[m0 + r];
+        xrow[i] = x + (int64_t)(row < 0 ? 0 : row) * ldx + 8 * s_c;
+        const int ks = s_c >> 2, q = s_c & 3;
+        // byte offset inside a buffer: (k step, row block) block of 1 KB, slot (kq, n) with its low bits XORed
+        s_slot[i] = ((ks * (kLinTileM / 16) + (r >> 4)) * 64 + ((q * 16 + (r & 15)) ^ ((2 * q + ks) & 7))) * 16;
+    }
+    // this strip's packed W: chunk c is 16 KB at wp + (nt * (in / 32) + 2 c) * 4096 elements
+    const uint4 *wsrc = reinterpret_cast<const uint4 *>(wp + (size_t)nt * (in / 32) * 4096);
+    const int wave_u = wave;
+    auto dma_w = [&](int c, char *dst) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int piece = 4 * wave_u + q;  // 1 KB pieces 0..15 of the chunk
+            dma16_to_lds(wsrc + (size_t)c * 1024 + piece * 64 + lane, reinterpret_cast<const uint4 *>(dst + piece * 1024));
+        }
+    };
+    uint4 xs[8];
+    auto load_x = [&](int c) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) xs[i] = ld16(xrow[i] + c * kLinK);
+    };
+    auto store_x = [&](char *dst) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4 *>(dst + s_slot[i]) = xs[i];
+    };
+
+    f32x4 acc[4][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) acc[i][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int nk = in / kLinK;
+    load_x(0);
+    dma_w(0, wbuf(0));
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __builtin_amdgcn_s_waitcnt(kWaitcntVmcnt0);
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    store_x(xbuf(0));
+    __syncthreads();
+    for (int c = 0; c < nk; ++c) {
+        const int cur = c & 1;
+        if (c + 1 < nk) {
+            load_x(c + 1);
+            dma_w(c + 1, wbuf(cur ^ 1));
+        }
+#pragma unroll
+        for (int ks = 0; ks < kLinK / 32; ++ks) {
+            bf16x8 xo[4], wo[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                xo[i] = as_bf16x8(*reinterpret_cast<const uint4 *>(
+                    xbuf(cur) + ((ks * (kLinTileM / 16) + 4 * wave + i) * 64 + ((kq * 16 + n) ^ ((2 * kq + ks) & 7))) * 16));
+#pragma unroll
+            for (int b = 0; b < 8; ++b)
+                wo[b] = as_bf16x8(*reinterpret_cast<const uint4 *>(wbuf(cur) + ((ks * 8 + b) * 64 + lane) * 16));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int b = 0; b < 8; ++b)
+                    acc[i][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xo[i], wo[b], acc[i][b], 0, 0, 0);
+        }
+        if (c + 1 < nk) {
+            __atomic_signal_fence(__ATOMIC_SEQ_CST);
+            __builtin_amdgcn_s_waitcnt(kWaitcntVmcnt0);  // the next chunk's x is in registers, its W in LDS
+            __atomic_signal_fence(__ATOMIC_SEQ_CST);
+            store_x(xbuf(cur ^ 1));
+        }
+        __syncthreads();
+    }
+
+    // ---- the delta of each row block, then the store of y ----
+    const int c0 = nt * kLinTileN;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int mb = (m0 >> 4) + 4 * wave + i;
+        const LinBlock &bk = blocks[mb];
+        const int r8 = bk.r8;
+        if (r8 > 0) {
+            f32x4 dl[8];
+#pragma unroll
+            for (int b = 0; b < 8; ++b) dl[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const uint16_t *bt = arena + bk.b_off + (size_t)c0 * r8 + n * 8;
+            for (int j = 0; j < r8; j += 32) {
+                const int jj = j + 8 * kq;
+                const bool j_ok = jj < r8;
+                const bool ok = j_ok && n < bk.ntok;
+                const int64_t off = bk.v_off + (int64_t)(ok ? n : 0) * r8 + (j_ok ? jj : 0);
+                uint4 vh = ld16(v_hi + off), vl = ld16(v_lo + off);
+                if (!ok) vh = vl = zero;
+#pragma unroll
+                for (int b = 0; b < 8; ++b) {
+                    // piece (sub-block b, rank piece jj / 8, column slot n) of the strip's B^T tile
+                    const uint4 wv = ld16(bt + (size_t)(b * (r8 >> 3) + (j_ok ? jj >> 3 : 0)) * 128);
+                    dl[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vh), as_bf16x8(wv), dl[b], 0, 0, 0);
+                    dl[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vl), as_bf16x8(wv), dl[b], 0, 0, 0);
+                }
+            }
+            const float scale = bk.scale;
+#pragma unroll
+            for (int b = 0; b < 8; ++b) acc[i][b] += scale * dl[b];
+        }
+        // lane (n, kq) holds tokens 4 kq + e of the block, columns c0 + 8 n .. + 7
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int row = rows[m0 + 64 * wave + 16 * i + 4 * kq + e];
+            if (row >= 0) {
+                uint4 o;
+                o.x = pack_bf16_rne(acc[i][0][e], acc[i][1][e]);
+                o.y = pack_bf16_rne(acc[i][2][e], acc[i][3][e]);
+                o.z = pack_bf16_rne(acc[i][4][e], acc[i][5][e]);
+                o.w = pack_bf16_rne(acc[i][6][e], acc[i][7][e]);
+                st16_stream(y + (int64_t)row * ldy + c0 + 8 * n, o);
+            }
+        }
+    }
+}
+
+// W^T [out][in] row-major -> operand order (see launch_pack_weight).  One thread per destination element.
+__global__ __launch_bounds__(256) void k_pack_w(const uint16_t *__restrict__ wt, int in, int out,
+                                                uint16_t *__restrict__ dst)
+{
+    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (d >= (int64_t)in * out) return;
+    const int ksteps = in / 32;
+    const int e = (int)(d & 7);
+    const int slot = (int)((d >> 3) & 63);
+    const int b = (int)((d >> 9) & 7);
+    const int64_t rest = d >> 12;  // strip * ksteps + kstep
+    const int kstep = (int)(rest % ksteps);
+    const int strip = (int)(rest / ksteps);
+    const int col = 128 * strip + 8 * (slot & 15) + b;
+    const int k = 32 * kstep + 8 * (slot >> 4) + e;
+    dst[d] = wt[(int64_t)col * in + k];
+}
+
 // Writes an adapter's packed form (see the top of this file).  One thread per destination element.
 // A: [in][r] row-major -> dst of r8*in elements.
 __global__ __launch_bounds__(256) void k_pack_a(const uint16_t *__restrict__ A, int in, int r, int r8,
@@ -1815,6 +2004,30 @@ hipError_t launch_expand_mixed(const LaunchCtx &big, const LaunchCtx &c, const f
     if (!sync) return hipErrorInvalidValue;
     hipLaunchKernelGGL(k_expand_mixed, dim3(total), dim3(kThreads), 0, stream, big.units, big.n_units, c.units,
                        c.perm, c.arena, parts, n_slices, slice_stride, y, ldy, make_sync(sync, 0));
+    return hipGetLastError();
+}
+
+hipError_t launch_linear_lora(const int32_t *rows, const LinBlock *blocks, int m_pad, const uint16_t *arena,
+                              const uint16_t *w_packed, const uint16_t *x, int64_t ldx, int in, int out,
+                              const uint16_t *v_hi, const uint16_t *v_lo, uint16_t *y, int64_t ldy,
+                              hipStream_t stream)
+{
+    if (m_pad <= 0) return hipSuccess;
+    if (m_pad % kLinTileM || in % kLinK || out % kLinTileN || in < kLinK) return hipErrorInvalidValue;
+    const int m_tiles = m_pad / kLinTileM, n_tiles = out / kLinTileN;
+    const int mt_per_xcd = (m_tiles + 7) / 8;
+    const int64_t grid = (int64_t)8 * mt_per_xcd * n_tiles;
+    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_linear_lora, dim3((unsigned)grid), dim3(kThreads), 0, stream, rows, blocks, m_tiles, mt_per_xcd,
+                       n_tiles, arena, w_packed, x, ldx, in, v_hi, v_lo, y, ldy);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_weight(const uint16_t *wt, int in, int out, uint16_t *dst, hipStream_t stream)
+{
+    const int64_t n = (int64_t)in * out;
+    if (n <= 0 || in % 32 || out % 128) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_pack_w, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, wt, in, out, dst);
     return hipGetLastError();
 }
 

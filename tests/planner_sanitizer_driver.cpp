@@ -25,6 +25,8 @@ hipError_t launch_reduce_slices(const float *, int, int64_t, float *, int64_t, h
 hipError_t launch_pack_adapter(const uint16_t *, const uint16_t *, int, int, int, int, uint16_t *, uint16_t *, hipStream_t) { return hipSuccess; }
 hipError_t launch_decode_fused(const LaunchCtx &, const LaunchCtx &, int, const uint16_t *, int64_t, int, int, uint16_t *, int64_t, unsigned, const SyncArgs *, hipStream_t) { return hipSuccess; }
 hipError_t probe_xcc(unsigned *, int, hipStream_t) { return hipErrorNoDevice; }
+hipError_t launch_linear_lora(const int32_t *, const LinBlock *, int, const uint16_t *, const uint16_t *, const uint16_t *, int64_t, int, int, const uint16_t *, const uint16_t *, uint16_t *, int64_t, hipStream_t) { return hipSuccess; }
+hipError_t launch_pack_weight(const uint16_t *, int, int, uint16_t *, hipStream_t) { return hipSuccess; }
 hipError_t static_scratch(void **p) { *p = nullptr; return hipErrorNoDevice; }
 }
 #define LK(x) do{lora_status_t s_=(x); if(s_!=LORA_OK){printf("ERR %s: %s %s\n",#x,lora_status_string(s_),lora_last_error()); return 1;} }while(0)

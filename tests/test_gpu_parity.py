@@ -1333,6 +1333,61 @@ def test_plan_options_select_the_launch_form_per_object():
     dp.close()
 
 
+def _linear_case(b, w_sigma, seed=0, check_elements=True):
+    """lora_linear (base GEMM with the delta in its epilogue) against oracle.lora_linear on every row."""
+    print(f"[case] lora_linear {b.name} T={b.T} in={b.in_features} out={b.out_features} sigma_W={w_sigma}", flush=True)
+    dp = G.DevicePool(b)
+    rng = np.random.default_rng([seed, 991])
+    W_bits = wl.f32_to_bf16_bits((rng.standard_normal((b.in_features, b.out_features)) * w_sigma).astype(np.float32))
+    wt = G.bits_to_dev(np.ascontiguousarray(W_bits.T))                      # W^T [out][in], a linear layer's weight
+    wp = torch.empty(b.in_features * b.out_features * 2, dtype=torch.uint8, device="cuda")
+    L.lora_linear_pack_weight(wt, b.in_features, b.out_features, wp)
+    x_bits = b.x_bits()
+    x = G.bits_to_dev(x_bits)
+    y = torch.full((b.T, b.out_features), float("nan"), dtype=torch.bfloat16, device="cuda")   # y need not be initialised
+    seg = L.lora_segments_build(dp.pool, b.token_adapter)
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
+    L.lora_linear(dp.pool, seg, x, wp, y, ws)
+    torch.cuda.synchronize()
+    L.lora_segments_check(seg)
+    yg = wl.bf16_bits_to_f64(G.dev_to_bits(y))
+    assert np.isfinite(yg).all(), "a row of y was not written"
+    y_ref = oracle.lora_linear(x_bits, W_bits, b.token_adapter, b.ranks, b.scales, dp.A, dp.B)
+    nz = np.linalg.norm(y_ref, axis=1) > 0
+    err = G.row_rel_l2(yg[nz], y_ref[nz])
+    assert err.max() <= G.TOL, f"max per-row relative L2 error {err.max():.3e}"
+    assert not yg[~nz].any()
+    worst_el = 0.0
+    if check_elements:
+        mag = oracle.lora_linear(G.abs_bits(x_bits), G.abs_bits(W_bits), b.token_adapter, b.ranks, b.scales,
+                                 [None if m is None else G.abs_bits(m) for m in dp.A],
+                                 [None if m is None else G.abs_bits(m) for m in dp.B])
+        r8 = np.where(b.token_adapter >= 0, ((b.ranks.astype(np.int64) + 7) // 8 * 8)[np.maximum(b.token_adapter, 0)], 0)
+        bound = G.elementwise_bound(y_ref, mag, b.in_features, r8)
+        worst_el = float((np.abs(yg - y_ref) / np.maximum(bound, 1e-300)).max())
+        assert worst_el <= 1.0, f"element error {worst_el:.2f} x the bound"
+    L.lora_segments_destroy(seg)
+    dp.close()
+    print(f"[ok] lora_linear {b.name}: {b.T} rows, max row rel-L2 {err.max():.3e}, max element error / bound {worst_el:.3f}",
+          flush=True)
+
+
+def test_linear_with_delta_in_the_epilogue_small_shapes():
+    """Ragged groups, odd ranks, tokens without adapter, several row tiles and column tiles; with W = 0
+    (the delta alone goes through the epilogue), a small W (base and delta of the same size) and a W of
+    the weights' own scale (the base dominates, as in a model)."""
+    for w_sigma in (0.0, 0.0005, 0.02):
+        _linear_case(wl.small_mixed(seed=51, in_features=256, out_features=384), w_sigma, seed=1)
+        _linear_case(wl.small_mixed(seed=52, in_features=1024, out_features=128, decode_tokens=120,
+                                    prefill_lens=(300, 500, 260, 40, 7)), w_sigma, seed=2)
+    _linear_case(wl.cfg0_tiny(), 0.02)
+    _linear_case(wl.cfg1_decode(in_features=2048, out_features=512, n_tokens=200), 0.0005)
+
+
+def test_linear_on_a_token_heavy_batch_at_model_width():
+    _linear_case(wl.cfg2_prefill(0, length_scale=0.12), 0.02, seed=3)
+
+
 def test_plan_then_upload_and_the_measurement_hook():
     """lora_segments_plan + lora_segments_upload give the object lora_segments_build gives (same bits
     from an apply); a planned object that was never uploaded is refused; the measurement hook records
