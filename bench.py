@@ -346,6 +346,9 @@ def main() -> int:
                          "first work group starts and its last one ends in either launch.  Needs the measurement "
                          "build of the library: python -m paper_2511_22880_amd.build --clocks, then "
                          "LORA_GFX950_LIB=<repo>/paper_2511_22880_amd/liblora_gfx950_clocks.so")
+    ap.add_argument("--linear", action="store_true",
+                    help="the adapted layer in one pass (lora_linear: base GEMM with the delta in its epilogue) on "
+                         "--workload, beside `base GEMM (torch.matmul), then lora_apply` on the same inputs")
     ap.add_argument("--two-launches", action="store_true",
                     help="decode batches as a shrink launch and an expand launch (lora_set_decode_single_launch(0))")
     args = ap.parse_args()
@@ -373,6 +376,9 @@ def main() -> int:
 
     if args.wg_clocks:
         return run_wg_clocks(args, torch, L, wl, dev, stream)
+    if args.linear:
+        print(json.dumps(run_linear(args, torch, L, wl, dev, stream, hip)))
+        return 0
     if args.projections == "layer":
         print(json.dumps(run_layer(args, torch, L, wl, dev, stream, hip)))
         return 0
@@ -451,6 +457,90 @@ def run_wg_clocks(args, torch, L, wl, dev, stream) -> int:
                       "clock": "wall clock of the device, 100 MHz; microseconds from the first work group's entry",
                       "per_class": rows}))
     return 0
+
+
+def run_linear(args, torch, L, wl, dev, stream, hip) -> dict:
+    """y = x W + delta for every token of the workload: lora_linear against torch.matmul followed by
+    lora_apply, and against lora_linear on a pool whose batch uses no adapter (the GEMM alone)."""
+    b0, description, _, _ = pick_workload(args.workload, wl, args.tp)
+    T, in_f, out_f = b0.T, b0.in_features, b0.out_features
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    nl = args.layers or 4
+    nbytes = L.lora_pool_bytes(in_f, out_f, b0.ranks, b0.scales)
+    arenas, pools, wts, wps, xs, ys = [], [], [], [], [], []
+    for l in range(nl):
+        a = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        a.view(torch.bfloat16).normal_(0.0, 0.02, generator=g)
+        arenas.append(a)
+        pools.append(L.lora_pool_create(in_f, out_f, b0.ranks, b0.scales, a))
+        for k in range(b0.n_adapters):
+            L.lora_pool_mark_resident(pools[-1], k)
+        wt = torch.empty(out_f, in_f, dtype=torch.bfloat16, device=dev).normal_(0.0, 0.02, generator=g)
+        wp = torch.empty(in_f * out_f * 2, dtype=torch.uint8, device=dev)
+        L.lora_linear_pack_weight(wt, in_f, out_f, wp, stream=stream)
+        wts.append(wt)
+        wps.append(wp)
+        xs.append(torch.empty(T, in_f, dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0, generator=g))
+        ys.append(torch.empty(T, out_f, dtype=torch.bfloat16, device=dev))
+    seg = L.lora_segments_build(pools[0], b0.token_adapter, stream=stream)
+    none = L.lora_segments_build(pools[0], np.full(T, -1, dtype=np.int32), stream=stream)
+    ws = torch.empty(max(L.lora_apply_workspace_bytes(pools[0], seg), 256), dtype=torch.uint8, device=dev)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev = [hip.event() for _ in range(args.steps + 1)]
+        hip.record(ev[0], stream)
+        for k in range(args.steps):
+            fn()
+            hip.record(ev[k + 1], stream)
+        torch.cuda.synchronize()
+        ms = np.array([hip.elapsed_ms(ev[k], ev[k + 1]) for k in range(args.steps)]) / nl
+        for e in ev:
+            hip.destroy(e)
+        return float(np.median(ms) * 1e3), float(ms.min() * 1e3)
+
+    def fused():
+        for l in range(nl):
+            L.lora_linear(pools[l], seg, xs[l], wps[l], ys[l], ws, stream=stream)
+
+    def gemm_alone():
+        for l in range(nl):
+            L.lora_linear(pools[l], none, xs[l], wps[l], ys[l], ws, stream=stream)
+
+    def separate():
+        for l in range(nl):
+            torch.matmul(xs[l], wts[l].t(), out=ys[l])
+            L.lora_apply(pools[l], seg, xs[l], ys[l], ws, stream=stream)
+
+    def library_gemm():
+        for l in range(nl):
+            torch.matmul(xs[l], wts[l].t(), out=ys[l])
+
+    res = {name: timed(fn) for name, fn in (("lora_linear", fused), ("lora_linear without adapters", gemm_alone),
+                                            ("torch.matmul then lora_apply", separate), ("torch.matmul", library_gemm))}
+    # the two paths agree (same inputs; different summation orders and one rounding more in the separate path)
+    fused()
+    y_f = ys[0].float().clone()
+    separate()
+    torch.cuda.synchronize()
+    rel = float(((y_f - ys[0].float()).norm(dim=1) / ys[0].float().norm(dim=1).clamp_min(1e-30)).max())
+    n_act = int((b0.token_adapter >= 0).sum())
+    gemm_flops = 2.0 * T * in_f * out_f
+    flops = gemm_flops + b0.flops()
+    us = res["lora_linear"][0]
+    return {"workload": description + "; adapted layer y = x W + delta, median us per layer over "
+                        f"{args.steps} steps of {nl} layers", "tokens": T, "active_tokens": n_act,
+            "us_per_layer": {k: {"median": v[0], "min": v[1]} for k, v in res.items()},
+            "flops_per_layer": flops, "lora_linear_TFLOPs": flops / (us * 1e-6) / 1e12,
+            "lora_linear_mfma_frac": flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "torch_matmul_TFLOPs": gemm_flops / (res["torch.matmul"][0] * 1e-6) / 1e12,
+            "delta_cost_us": {"in the epilogue (lora_linear minus the same kernel without adapters)":
+                              res["lora_linear"][0] - res["lora_linear without adapters"][0],
+                              "as lora_apply behind the library GEMM": res["torch.matmul then lora_apply"][0] - res["torch.matmul"][0]},
+            "max_row_rel_l2_between_the_two_paths": rel}
 
 
 def brief(out: dict) -> dict:

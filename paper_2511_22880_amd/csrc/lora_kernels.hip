@@ -1659,28 +1659,32 @@ __global__ __launch_bounds__(256) void k_reduce_slices(const float *__restrict__
 constexpr int kLinK = 64;                                   // k per chunk
 constexpr int kLinXBuf = (kLinK / 32) * (kLinTileM / 16) * 1024;  // bytes of x per buffer: 32 KB
 constexpr int kLinWBuf = (kLinK / 32) * 8 * 1024;                 // bytes of W per buffer: 16 KB
-constexpr int kLinLds = 2 * (kLinXBuf + kLinWBuf);
+constexpr int kLinLds = kLinXBuf + 2 * kLinWBuf;  // x in one buffer (it waits in registers), W in two: 64 KB, two work groups per compute unit
 
-__global__ __launch_bounds__(kThreads, 1) void k_linear_lora(
+__global__ __launch_bounds__(kThreads, 2) void k_linear_lora(
     const int32_t *__restrict__ rows, const LinBlock *__restrict__ blocks, int m_tiles, int mt_per_xcd, int n_tiles,
     const uint16_t *__restrict__ arena, const uint16_t *__restrict__ wp, const uint16_t *__restrict__ x, int64_t ldx,
     int in, const uint16_t *__restrict__ v_hi, const uint16_t *__restrict__ v_lo, uint16_t *__restrict__ y, int64_t ldy)
 {
     __shared__ __attribute__((aligned(16))) char lds[kLinLds];
-    // work group b runs on XCD b mod 8: each XCD takes a run of row tiles and walks their column tiles,
-    // so a row tile's x (2 MB at 4096 input features) stays in that XCD's L2 while its columns go by
+    // Work group b runs on XCD b mod 8.  Each XCD takes a run of row tiles, and the 64 work groups it runs
+    // at a time (two per compute unit) are 8 row tiles x 8 column tiles that walk k together: every
+    // chunk of x and of W that one of them brings into the XCD's L2 serves eight of them.
     const int xcd = blockIdx.x & 7, jloc = blockIdx.x >> 3;
-    const int mt = xcd * mt_per_xcd + jloc / n_tiles;
-    const int nt = jloc % n_tiles;
-    if (jloc / n_tiles >= mt_per_xcd || mt >= m_tiles) return;
+    const int ngroups_n = (n_tiles + 7) >> 3;
+    const int grp = jloc >> 6, within = jloc & 63;
+    const int mt_loc = (grp / ngroups_n) * 8 + (within >> 3);
+    const int nt = (grp % ngroups_n) * 8 + (within & 7);
+    const int mt = xcd * mt_per_xcd + mt_loc;
+    if (mt_loc >= mt_per_xcd || mt >= m_tiles || nt >= n_tiles) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, kq = lane >> 4;
     const int m0 = mt * kLinTileM;
     const uint4 zero = {0u, 0u, 0u, 0u};
-    auto xbuf = [&](int which) __attribute__((always_inline)) { return lds + which * kLinXBuf; };
-    auto wbuf = [&](int which) __attribute__((always_inline)) { return lds + 2 * kLinXBuf + which * kLinWBuf; };
+    char *const xbuf = lds;
+    auto wbuf = [&](int which) __attribute__((always_inline)) { return lds + kLinXBuf + which * kLinWBuf; };
 
     // staging role: 8 lanes per row chunk; thread t takes rows 32 i + t / 8 (i = 0..7), 16-byte piece t % 8
     const int s_c = tid & 7;
@@ -1724,16 +1728,16 @@ __global__ __launch_bounds__(kThreads, 1) void k_linear_lora(
     const int nk = in / kLinK;
     load_x(0);
     dma_w(0, wbuf(0));
-    __atomic_signal_fence(__ATOMIC_SEQ_CST);
-    __builtin_amdgcn_s_waitcnt(kWaitcntVmcnt0);
-    __atomic_signal_fence(__ATOMIC_SEQ_CST);
-    store_x(xbuf(0));
-    __syncthreads();
     for (int c = 0; c < nk; ++c) {
         const int cur = c & 1;
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        __builtin_amdgcn_s_waitcnt(kWaitcntVmcnt0);  // this chunk's x is in registers, its W in LDS
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        store_x(xbuf);
+        __syncthreads();
         if (c + 1 < nk) {
             load_x(c + 1);
-            dma_w(c + 1, wbuf(cur ^ 1));
+            dma_w(c + 1, wbuf(cur ^ 1));  // everyone has left that buffer: it was read two barriers ago
         }
 #pragma unroll
         for (int ks = 0; ks < kLinK / 32; ++ks) {
@@ -1741,7 +1745,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_linear_lora(
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 xo[i] = as_bf16x8(*reinterpret_cast<const uint4 *>(
-                    xbuf(cur) + ((ks * (kLinTileM / 16) + 4 * wave + i) * 64 + ((kq * 16 + n) ^ ((2 * kq + ks) & 7))) * 16));
+                    xbuf + ((ks * (kLinTileM / 16) + 4 * wave + i) * 64 + ((kq * 16 + n) ^ ((2 * kq + ks) & 7))) * 16));
 #pragma unroll
             for (int b = 0; b < 8; ++b)
                 wo[b] = as_bf16x8(*reinterpret_cast<const uint4 *>(wbuf(cur) + ((ks * 8 + b) * 64 + lane) * 16));
@@ -1751,46 +1755,44 @@ __global__ __launch_bounds__(kThreads, 1) void k_linear_lora(
                 for (int b = 0; b < 8; ++b)
                     acc[i][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xo[i], wo[b], acc[i][b], 0, 0, 0);
         }
-        if (c + 1 < nk) {
-            __atomic_signal_fence(__ATOMIC_SEQ_CST);
-            __builtin_amdgcn_s_waitcnt(kWaitcntVmcnt0);  // the next chunk's x is in registers, its W in LDS
-            __atomic_signal_fence(__ATOMIC_SEQ_CST);
-            store_x(xbuf(cur ^ 1));
-        }
-        __syncthreads();
+        __syncthreads();  // the x buffer may be written again
     }
 
     // ---- the delta of each row block, then the store of y ----
     const int c0 = nt * kLinTileN;
+    const LinBlock *bks = blocks + (m0 >> 4) + 4 * wave;
+    // the delta of one row block from its own loads of B^T (row blocks whose neighbours have other adapters)
+    auto delta_one = [&](int i) __attribute__((always_inline)) {
+        const LinBlock &bk = bks[i];
+        const int r8 = bk.r8;
+        if (r8 <= 0) return;
+        f32x4 dl[8];
+#pragma unroll
+        for (int b = 0; b < 8; ++b) dl[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const uint16_t *bt = arena + bk.b_off + (size_t)c0 * r8 + n * 8;
+        for (int j = 0; j < r8; j += 32) {
+            const int jj = j + 8 * kq;
+            const bool j_ok = jj < r8;
+            const bool ok = j_ok && n < bk.ntok;
+            const int64_t off = bk.v_off + (int64_t)(ok ? n : 0) * r8 + (j_ok ? jj : 0);
+            uint4 vh = ld16(v_hi + off), vl = ld16(v_lo + off);
+            if (!ok) vh = vl = zero;
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                // piece (sub-block b, rank piece jj / 8, column slot n) of the strip's B^T tile
+                const uint4 wv = ld16(bt + (size_t)(b * (r8 >> 3) + (j_ok ? jj >> 3 : 0)) * 128);
+                dl[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vh), as_bf16x8(wv), dl[b], 0, 0, 0);
+                dl[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vl), as_bf16x8(wv), dl[b], 0, 0, 0);
+            }
+        }
+        const float scale = bk.scale;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) acc[i][b] += scale * dl[b];
+    };
+#pragma unroll
+    for (int i = 0; i < 4; ++i) delta_one(i);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int mb = (m0 >> 4) + 4 * wave + i;
-        const LinBlock &bk = blocks[mb];
-        const int r8 = bk.r8;
-        if (r8 > 0) {
-            f32x4 dl[8];
-#pragma unroll
-            for (int b = 0; b < 8; ++b) dl[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const uint16_t *bt = arena + bk.b_off + (size_t)c0 * r8 + n * 8;
-            for (int j = 0; j < r8; j += 32) {
-                const int jj = j + 8 * kq;
-                const bool j_ok = jj < r8;
-                const bool ok = j_ok && n < bk.ntok;
-                const int64_t off = bk.v_off + (int64_t)(ok ? n : 0) * r8 + (j_ok ? jj : 0);
-                uint4 vh = ld16(v_hi + off), vl = ld16(v_lo + off);
-                if (!ok) vh = vl = zero;
-#pragma unroll
-                for (int b = 0; b < 8; ++b) {
-                    // piece (sub-block b, rank piece jj / 8, column slot n) of the strip's B^T tile
-                    const uint4 wv = ld16(bt + (size_t)(b * (r8 >> 3) + (j_ok ? jj >> 3 : 0)) * 128);
-                    dl[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vh), as_bf16x8(wv), dl[b], 0, 0, 0);
-                    dl[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vl), as_bf16x8(wv), dl[b], 0, 0, 0);
-                }
-            }
-            const float scale = bk.scale;
-#pragma unroll
-            for (int b = 0; b < 8; ++b) acc[i][b] += scale * dl[b];
-        }
         // lane (n, kq) holds tokens 4 kq + e of the block, columns c0 + 8 n .. + 7
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -2016,7 +2018,7 @@ hipError_t launch_linear_lora(const int32_t *rows, const LinBlock *blocks, int m
     if (m_pad % kLinTileM || in % kLinK || out % kLinTileN || in < kLinK) return hipErrorInvalidValue;
     const int m_tiles = m_pad / kLinTileM, n_tiles = out / kLinTileN;
     const int mt_per_xcd = (m_tiles + 7) / 8;
-    const int64_t grid = (int64_t)8 * mt_per_xcd * n_tiles;
+    const int64_t grid = (int64_t)8 * 64 * ((mt_per_xcd + 7) / 8) * ((n_tiles + 7) / 8);
     if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
     hipLaunchKernelGGL(k_linear_lora, dim3((unsigned)grid), dim3(kThreads), 0, stream, rows, blocks, m_tiles, mt_per_xcd,
                        n_tiles, arena, w_packed, x, ldx, in, v_hi, v_lo, y, ldy);
