@@ -75,6 +75,15 @@ class Hip:
 
 def pick_workload(spec: str, wl, tp: str = None):
     """-> (batch, description, default projections per step, seeded host weights?)"""
+    if "@r" in spec:
+        # <workload>@r<rank>: the same routing with every adapter at one rank (what a placement that
+        # groups adapters by rank gives a server; the operating points of the placement what-if)
+        import dataclasses
+        base, rank = spec.split("@r")
+        b, description, layers, _ = pick_workload(base, wl, tp)
+        ranks = np.full_like(b.ranks, int(rank))
+        b = dataclasses.replace(b, name=f"{b.name}_r{int(rank)}", ranks=ranks, scales=wl._scales_for(ranks))
+        return b, f"{description}; every adapter at rank {int(rank)}", layers, False
     if tp:
         # one GPU's shard of a tensor-parallel layer: a column-parallel layer keeps A_a and holds
         # out/N columns of B_a, a row-parallel layer holds in/N rows of A_a and all of B_a (its v is
@@ -314,7 +323,8 @@ def main() -> int:
                     help="projections per step (default: 32 for cfg1, fewer for the larger workloads)")
     ap.add_argument("--workload", default="cfg1",
                     help="cfg1 (default, the benchmark line) | cfg2:<shape 0..2> | cfg3:<projection 0..6>[:<prompt length scale>] | "
-                         "cfg4:<shape 0..2>:<9to1|1to1|1to9>[:<0|1> only that rank class]")
+                         "cfg4:<shape 0..2>:<9to1|1to1|1to9>[:<0|1> only that rank class]; any of them with @r<rank> appended: "
+                         "every adapter at that rank")
     ap.add_argument("--tp", default=None, metavar="N:col|N:row",
                     help="time one GPU's shard of the workload's projection under N-way tensor parallelism: "
                          "col = out_features/N columns of B (column-parallel layer), row = in_features/N rows of A "
@@ -452,7 +462,11 @@ def run_wg_clocks(args, torch, L, wl, dev, stream) -> int:
             start, end = (clk[sel, 0] - t0) * 0.01, (clk[sel, 4] - t0) * 0.01
             rows.append({"launch": name, "rank": r, "work_groups": int(sel.sum()), "first_start_us": float(start.min()),
                          "median_start_us": float(np.median(start)), "median_duration_us": float(np.median(end - start)),
-                         "last_end_us": float(end.max())})
+                         "max_duration_us": float((end - start).max()), "duration_deciles_us": [round(float(v), 1) for v in
+                         np.percentile(end - start, [10, 30, 50, 70, 90])], "last_end_us": float(end.max())})
+            if name == "shrink launch" and (clk[sel, 1] > 0).any() and (clk[sel, 1] < 10 ** 7).all():
+                # token tiles above rank 32: of the duration, the part between the top of a pass and its barrier's exit
+                rows[-1]["median_wait_for_x_us"] = float(np.median(clk[sel, 1]) * 0.01)
     print(json.dumps({"workload": description, "tokens": T, "single_launch": bool(info["single_launch"]),
                       "clock": "wall clock of the device, 100 MHz; microseconds from the first work group's entry",
                       "per_class": rows}))

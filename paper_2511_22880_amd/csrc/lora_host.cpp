@@ -589,6 +589,10 @@ static const int kWholeKMaxIn = 8192;
 // (measured, shrink launch in us uncut / 2 / 4 slices; 4096: 41 units 32 / 28 / 23, 79 units 33 / 28 /
 // 25, 148 units 33 / 30 / 33, 291 units 37 / 40 / 45; 14336: 41 units 99 / 67 / 52, 79 units 102 / 67 /
 // 59, 148 units 102 / 75 / 77, 291 units 116 / 102 / 109; cfg2's 718 units at 14336: 155 / 155 / 162).
+// Tokens of a token-heavy shrink unit: up to rank 64 the wavefronts split k and hold 32 tokens; above,
+// they split the rank rows and share 64 tokens of x through LDS (A^T is then loaded once per 64
+// tokens); above rank 128, 16 tokens with k split.
+static int heavy_tile(int r8) { return r8 <= 64 ? 32 : (r8 <= 128 ? 64 : 16); }
 static const int kHeavyKCutMaxUnits = 320;
 static const int kHeavyKCutMaxUnitsLongK = 600;
 static const int kBigRunsMaxUnits = 400;  // 64-token expand units of a launch whose groups' columns go in 8 runs
@@ -653,6 +657,70 @@ static void order_units_by_xcd(std::vector<Unit> &units)
     for (size_t j = 0; j < cap; ++j)
         for (int q = 0; q < X; ++q)
             if (j < list[q].size()) out.push_back(units[list[q][j]]);
+    units.swap(out);
+}
+
+// Token-heavy shrink units: the tiles of one adapter on one XCD, so that its A^T comes from memory once
+// instead of once per XCD (cfg2 4096 -> 4096: the eight fetches of every A^T were a quarter of the
+// launch's traffic).  Such a launch runs several rounds, every XCD takes every eighth work group whatever
+// its units cost, and a compute unit passes about 50 GB/s to its work groups whatever they are, so equal
+// numbers of units per XCD would leave the XCD that holds the high ranks running alone at the end.  The
+// eight lists are therefore filled to equal bytes (tokens + rank rows of the unit, each in_features
+// long), heaviest group first, a group cut where a list reaches its share; the shorter lists are padded
+// at their end with units of no tokens, which return at once.
+static void order_heavy_units_by_xcd(std::vector<Unit> &units)
+{
+    const int X = 8;
+    const size_t n = units.size();
+    if (n < 2 * (size_t)X) return;
+    auto cost = [](const Unit &u) { return (int64_t)(u.ntok + u.pn); };  // rows of x and of A^T, each in_features long
+    std::vector<std::pair<size_t, size_t>> groups;  // [first, last): units of a group are adjacent as planned
+    for (size_t i = 0; i < n;) {
+        size_t j = i + 1;
+        while (j < n && units[j].seg == units[i].seg) ++j;
+        groups.push_back({i, j});
+        i = j;
+    }
+    std::vector<int64_t> gw(groups.size(), 0);
+    int64_t total = 0;
+    for (size_t g = 0; g < groups.size(); ++g) {
+        for (size_t i = groups[g].first; i < groups[g].second; ++i) gw[g] += cost(units[i]);
+        total += gw[g];
+    }
+    const int64_t share = total / X + total / (100 * X) + 1;
+    std::vector<size_t> gorder(groups.size());
+    for (size_t g = 0; g < gorder.size(); ++g) gorder[g] = g;
+    std::stable_sort(gorder.begin(), gorder.end(), [&](size_t a, size_t b) { return gw[a] > gw[b]; });
+    std::vector<std::vector<size_t>> list(X);
+    std::vector<int64_t> load(X, 0);
+    for (size_t g : gorder) {
+        size_t i = groups[g].first;
+        while (i < groups[g].second) {
+            int best = 0;
+            for (int q = 1; q < X; ++q)
+                if (load[q] < load[best]) best = q;
+            bool first = true;  // the lightest list takes at least one unit, so the loop ends
+            while (i < groups[g].second && (first || load[best] + cost(units[i]) <= share)) {
+                list[best].push_back(i);
+                load[best] += cost(units[i]);
+                first = false;
+                ++i;
+            }
+        }
+    }
+    size_t longest = 0;
+    for (int q = 0; q < X; ++q) {
+        std::stable_sort(list[q].begin(), list[q].end(),
+                         [&](size_t a, size_t b) { return cost(units[a]) > cost(units[b]); });
+        longest = std::max(longest, list[q].size());
+    }
+    Unit none;
+    memset(&none, 0, sizeof none);  // ntok = 0: the kernels leave such a unit at once
+    none.seg = -1;
+    std::vector<Unit> out;
+    out.reserve(longest * X);
+    for (size_t j = 0; j < longest; ++j)
+        for (int q = 0; q < X; ++q) out.push_back(j < list[q].size() ? units[list[q][j]] : none);
     units.swap(out);
 }
 
@@ -956,7 +1024,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     int64_t heavy_units = 0;
     for (const SegRec &r : sg->segs)
         if (r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch)
-            heavy_units += (r.ntok + (r.r8 <= 128 ? 32 : 16) - 1) / (r.r8 <= 128 ? 32 : 16);
+            heavy_units += (r.ntok + heavy_tile(r.r8) - 1) / heavy_tile(r.r8);
     int heavy_k_slices = 1;
     if (sg->n_k_slices >= 2 && heavy_units > 0) {
         const int64_t limit = pool->in_features > kWholeKMaxIn ? kHeavyKCutMaxUnitsLongK : kHeavyKCutMaxUnits;
@@ -976,11 +1044,12 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
         const bool token_heavy = r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch;
         const int sync_n = ((r.r8 + lora::kRowTile - 1) / lora::kRowTile) * sg->n_k_slices;
         if (token_heavy) {
-            // shrink: tiles of 32 tokens (16 above rank 128), all rank rows, all of k or (heavy_k_slices
-            // > 1) a slice of it, the slices' sums meeting at the counter of the tile's first 16 tokens
+            // shrink: tiles of 32 tokens (64 above rank 64, 16 above rank 128), all rank rows, all of k or
+            // (heavy_k_slices > 1) a slice of it, the slices' sums meeting at the counter of the tile's
+            // first 16 tokens
             sg->has_big_units = true;
             if (r.r8 > 128) sg->heavy_small_expand = true;
-            const int tile = r.r8 <= 128 ? 32 : 16;
+            const int tile = heavy_tile(r.r8);
             for (int tok0 = 0; tok0 < r.ntok; tok0 += tile)
                 for (int ks = 0; ks < heavy_k_slices; ++ks) {
                     Unit u;
@@ -1072,6 +1141,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     }
 
     order_units_by_xcd(sg->shrink_units);
+    order_heavy_units_by_xcd(sg->prefill_units);
 
     if (n_projections == 1)
         finish_decode_fused(sg, pool->in_features);

@@ -29,7 +29,7 @@ struct Unit {
     int64_t v_off;    // float offset of the unit's first v element (shrink: row tok0, column p0;
                       // expand: row tok0, column 0)
     int32_t r8;       // padded rank = row length of v and of B^T
-    int32_t ntok;     // tokens in this unit: 1..16 (decode units), up to 64 (expand) or 32 (prefill shrink)
+    int32_t ntok;     // tokens in this unit: 1..16 (decode units), up to 64 (expand, prefill shrink above rank 64) or 32 (prefill shrink)
     int32_t p0;       // shrink: first rank row; expand: first output column
     int32_t pn;       // shrink: valid rank rows (1..16, multiple of 8 except the tail); expand: columns
     int32_t ks;       // shrink: k-slice index

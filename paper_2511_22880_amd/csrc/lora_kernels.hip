@@ -705,6 +705,225 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
     }
 }
 
+// Token-heavy units above rank 32: 16 * TB tokens, all rank rows, all of k or a slice of it.  Here the
+// four wavefronts split the rank rows (JBW blocks of 16 each) instead of k: every 16-byte piece of
+// A^T is then loaded once per work group, straight into the registers of the one wavefront that owns
+// its rows, and x, which all four need, is staged once per work group in LDS (two buffers of 128 of k,
+// one barrier per pass).  With k split over the wavefronts as above, a unit of 32 tokens loads all of
+// A^T for 32 tokens' worth of x: at rank 128 four times the bytes of x, which made the compute units'
+// vector caches, not memory, the bound (uniform rank 128 on cfg2's routing: 78 us against 35 us at
+// rank 8).  No sums cross wavefronts: each stores the rows of v it owns.
+template <int JBW, int TB, int PD, int WP>
+static __device__ __forceinline__ void shrink_prefill_rowsplit(const Unit &u, const int32_t *__restrict__ perm,
+                                                               const uint16_t *__restrict__ arena,
+                                                               const uint16_t *__restrict__ x, int64_t ldx, int in,
+                                                               uint16_t *__restrict__ v_hi,
+                                                               uint16_t *__restrict__ v_lo, float *__restrict__ v_f32,
+                                                               int n_slices, int64_t slice_stride, char *lds,
+                                                               float *__restrict__ parts, const Sync &sy)
+{
+    constexpr int TOK = 16 * TB;
+    constexpr int SP = kPfPassK / 32;  // k steps of a pass
+    static_assert(PD % 2 == 0 && PD % WP == 0, "the rings are indexed by the pass's place in a round of PD");
+    static_assert(2 * TOK * kPfRow * 2 <= kPrefillLds, "two x buffers fit the LDS");
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint16_t(*buf)[kPfRow] = reinterpret_cast<uint16_t(*)[kPfRow]>(lds);  // [2 * TOK] rows
+    const int n = lane & 15;
+    const int kq = lane >> 4;
+    const int r8 = u.r8;
+    const int ntok = u.ntok;
+
+    // staging: thread (xr, xc) copies 16-byte chunk xc of tokens xr, xr + 16, ...
+    const int xr = threadIdx.x >> 4, xc = threadIdx.x & 15;
+    const uint16_t *xrow[TB];
+#pragma unroll
+    for (int i = 0; i < TB; ++i) xrow[i] = x + (int64_t)perm[u.perm_off + min(xr + 16 * i, ntok - 1)] * ldx;
+
+    // A wavefront whose row blocks lie beyond the padded rank (ranks that are not multiples of 64) works on
+    // the last block that exists instead: its sums are never stored, and the loop needs no branch for it.
+    const uint16_t *wbase = arena + u.w_off;
+    const int nblk = (r8 + 15) >> 4;
+    int woff[JBW], wh[JBW];
+#pragma unroll
+    for (int j = 0; j < JBW; ++j) {
+        const int jb = min(wave * JBW + j, nblk - 1);
+        const int h = min(16, r8 - 16 * jb);
+        wh[j] = h;
+        // lanes n >= 8 of an 8-row block read the piece of row n - 8: they only reach accumulator rows
+        // beyond the padded rank, which are never stored
+        woff[j] = 16 * jb * in + (kq * h + (n & (h - 1))) * 8;
+    }
+
+    f32x4 acc[JBW][TB];
+#pragma unroll
+    for (int j = 0; j < JBW; ++j)
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) acc[j][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int n_ks = u.sync_n > 1 ? u.sync_n : 1;
+    const int ks_len = n_ks > 1 ? ((in / n_ks + 127) / 128) * 128 : in;
+    const int kbeg = min(in, u.ks * ks_len);
+    const int kend = min(in, kbeg + ks_len);
+    const int npass = (kend - kbeg + kPfPassK - 1) / kPfPassK;
+    const int nfull = (kend - kbeg) / kPfPassK;  // passes that hold 128 of k (in is a multiple of 64: the last may hold 64)
+
+    // Loads without conditions (rows of tokens beyond ntok are the last token's, see xrow; a chunk beyond
+    // the row is fetched from the row's last chunk and a k step beyond kend from the last step, neither
+    // enters an MFMA): with a branch around a load the compiler no longer counts the loads in flight and
+    // waits for all of them, the ones requested for later passes included, at every wait.
+    auto x_pass = [&](int k0, uint4(&xs)[TB]) __attribute__((always_inline)) {
+        const int kx = min(k0 + 8 * xc, in - 8);
+#pragma unroll
+        for (int i = 0; i < TB; ++i) xs[i] = ld16_stream(xrow[i] + kx);
+    };
+    auto w_step = [&](int k, int j) __attribute__((always_inline)) {
+        return ld16(wbase + woff[j] + (int64_t)min(k, in - 32) * wh[j]);
+    };
+    auto stage = [&](int base, const uint4(&xs)[TB]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < TB; ++t) *reinterpret_cast<uint4 *>(&buf[base + xr + 16 * t][8 * xc]) = xs[t];
+    };
+    // one 32-wide k step of the pass staged at `base`: rows of tokens beyond ntok hold the last token's x
+    // and only reach accumulator columns that are never stored
+    auto k_step = [&](int base, int d, const uint4(&ws)[JBW]) __attribute__((always_inline)) {
+        bf16x8 xo[TB];
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb)
+            xo[tb] = as_bf16x8(*reinterpret_cast<const uint4 *>(&buf[base + 16 * tb + n][32 * d + 8 * kq]));
+#pragma unroll
+        for (int j = 0; j < JBW; ++j) {
+            const bf16x8 ww = as_bf16x8(ws[j]);
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb)
+                acc[j][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ww, xo[tb], acc[j][tb], 0, 0, 0);
+        }
+    };
+
+    // PD passes of x and WP passes of A^T are in flight per wavefront (registers).  The steady state has
+    // no branch: pass i stages its x, asks for the x of pass i + PD, and after each k step for the rows of
+    // A^T of the same step of pass i + WP.  One barrier per pass: the buffer a pass writes was last read
+    // two passes ago, and every wavefront has passed the previous pass's barrier since those reads.
+    uint4 xs[PD][TB], w[WP][SP][JBW];
+#pragma unroll
+    for (int q = 0; q < PD; ++q) {
+        x_pass(kbeg + min(q, max(npass - 1, 0)) * kPfPassK, xs[q]);
+        if (q < WP) {
+#pragma unroll
+            for (int d = 0; d < SP; ++d)
+#pragma unroll
+                for (int j = 0; j < JBW; ++j) w[q][d][j] = w_step(kbeg + q * kPfPassK + 32 * d, j);
+        }
+    }
+#ifdef LORA_WG_CLOCKS
+    unsigned long long c_wait = 0;  // from the top of a pass to the barrier's exit, summed over the passes
+#endif
+    int i0 = 0;
+    for (; i0 + 2 * PD <= nfull; i0 += PD) {
+#pragma unroll
+        for (int q = 0; q < PD; ++q) {
+            const int k0 = kbeg + (i0 + q) * kPfPassK;
+            const int base = (q & 1) * TOK;
+#ifdef LORA_WG_CLOCKS
+            const unsigned long long c_top = wall_clock64();
+#endif
+            stage(base, xs[q]);
+            x_pass(k0 + PD * kPfPassK, xs[q]);
+            __syncthreads();
+#ifdef LORA_WG_CLOCKS
+            c_wait += wall_clock64() - c_top;
+#endif
+#pragma unroll
+            for (int d = 0; d < SP; ++d) {
+                k_step(base, d, w[q % WP][d]);
+#pragma unroll
+                for (int j = 0; j < JBW; ++j) w[q % WP][d][j] = w_step(k0 + WP * kPfPassK + 32 * d, j);
+            }
+        }
+    }
+    // the last passes (fewer than 2 PD, the last maybe 64 of k): the same, with every request and every k
+    // step under its condition
+#pragma unroll
+    for (int q = 0; q < 2 * PD; ++q) {
+        const int i = i0 + q;
+        if (i < npass) {
+            const int k0 = kbeg + i * kPfPassK;
+            const int base = (q & 1) * TOK;
+            stage(base, xs[q % PD]);
+            if (i + PD < npass) x_pass(k0 + PD * kPfPassK, xs[q % PD]);
+            __syncthreads();
+#pragma unroll
+            for (int d = 0; d < SP; ++d) {
+                if (k0 + 32 * d < kend) k_step(base, d, w[q % WP][d]);
+                if (i + WP < npass) {
+#pragma unroll
+                    for (int j = 0; j < JBW; ++j) w[q % WP][d][j] = w_step(k0 + WP * kPfPassK + 32 * d, j);
+                }
+            }
+        }
+    }
+#ifdef LORA_WG_CLOCKS
+    if (g_clock_buf && threadIdx.x == 0 && blockIdx.x < g_clock_slots) g_clock_buf[(size_t)blockIdx.x * 8 + 1] = c_wait;
+    LORA_CLOCK(2);
+#endif
+    // lane (n, kq) holds, for token block tb and its row block j, v[token 16 tb + n][16 jb + 4 kq + e]
+    if (n_ks == 1) {
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            if (16 * tb + n >= ntok) continue;
+            const int64_t row = u.v_off + (int64_t)(16 * tb + n) * r8;
+#pragma unroll
+            for (int j = 0; j < JBW; ++j) {
+                const int jr = 16 * (wave * JBW + j) + 4 * kq;
+                if (jr < r8) store_v4(acc[j][tb], row + jr, v_hi, v_lo, v_f32, n_slices, slice_stride);
+            }
+        }
+        return;
+    }
+    // A k-slice of the unit's tokens, as in the body above: the sums go to slice u.ks of the fp32
+    // partial sums; the unit that completes the tile adds the slices in slice order.
+    float *dst = v_f32 ? v_f32 : parts;
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        if (16 * tb + n >= ntok) continue;
+        const int64_t row = u.v_off + (int64_t)(16 * tb + n) * r8;
+#pragma unroll
+        for (int j = 0; j < JBW; ++j) {
+            const int jr = 16 * (wave * JBW + j) + 4 * kq;
+            if (jr >= r8) continue;
+            if (v_f32) {
+                *reinterpret_cast<f32x4 *>(dst + (int64_t)u.ks * slice_stride + row + jr) = acc[j][tb];
+                if (u.ks == 0)
+                    for (int sl = n_ks; sl < n_slices; ++sl)
+                        *reinterpret_cast<f32x4 *>(dst + (int64_t)sl * slice_stride + row + jr) =
+                            f32x4{0.f, 0.f, 0.f, 0.f};
+            } else {
+                st_through_f32x4(dst + (int64_t)u.ks * slice_stride + row + jr, acc[j][tb]);
+            }
+        }
+    }
+    if (v_f32) return;
+    stores_done();
+    __syncthreads();  // every wavefront's partial sums are out (and nobody reads the x buffers any more)
+    unsigned *arrived = reinterpret_cast<unsigned *>(lds);
+    if (threadIdx.x == 0) *arrived = atomicAdd(sy.counters + u.sync_idx, 1u);
+    __syncthreads();
+    const unsigned old = *arrived;
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);  // the loads of the slices stay behind the arrival
+    if (old + 1u == (unsigned)n_ks) {
+        if (threadIdx.x == 0) atomicExch(sy.counters + u.sync_idx, 0u);  // back to zero for the next launch
+        const int tasks = ntok * (r8 >> 3);
+        for (int task = threadIdx.x; task < tasks; task += kThreads) {
+            f32x4 f0, f1;
+            sum_slices(parts + u.v_off + 8 * task, n_ks, slice_stride, f0, f1);
+            uint4 ph, pl;
+            split_bf16(f0, f1, ph, pl);
+            st_through_u16x8(v_hi + u.v_off + 8 * task, ph);
+            st_through_u16x8(v_lo + u.v_off + 8 * task, pl);
+        }
+    }
+}
+
 // One wavefront copies 1 KB from memory into LDS without passing through registers: lane l's 16 bytes
 // at gptr (per lane) land at lds_piece + 16*l (lds_piece wave-uniform).  Written as an instruction the
 // compiler does not look into: for its own form of this load it waits until the copy has landed
@@ -747,10 +966,12 @@ static __device__ __forceinline__ void prefill_dispatch(const Unit &u, const int
         shrink_prefill_ksplit<4, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
     else if (r8 <= 64)
         shrink_prefill_ksplit<4, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
-    else if (r8 <= 128)
-        shrink_prefill_ksplit<8, 2, 2>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
-    else
-        shrink_prefill_ksplit<16, 1, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
+    else if constexpr (ANY) {
+        if (r8 <= 128)
+            shrink_prefill_rowsplit<2, 4, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
+        else
+            shrink_prefill_ksplit<16, 1, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
+    }
 }
 
 __global__ __launch_bounds__(kThreads, 4) void k_shrink_prefill(const Unit *__restrict__ units,
@@ -763,8 +984,11 @@ __global__ __launch_bounds__(kThreads, 4) void k_shrink_prefill(const Unit *__re
                                                                 int64_t slice_stride, float *__restrict__ parts, Sync sy)
 {
     __shared__ __attribute__((aligned(16))) char lds[kPrefillLds];
+    if (units[blockIdx.x].ntok <= 0) return;  // a place the planner filled so that every XCD's list has the same length
+    LORA_CLOCK(0);
     prefill_dispatch<false>(units[blockIdx.x], perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride,
                             lds, parts, sy);
+    LORA_CLOCK(4);
 }
 
 // A batch that has units above rank 64 runs all its token-heavy units here, in one launch: two
@@ -780,8 +1004,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_shrink_prefill_any(const Unit *
                                                                     int64_t slice_stride, float *__restrict__ parts, Sync sy)
 {
     __shared__ __attribute__((aligned(16))) char lds[kPrefillLds];
+    if (units[blockIdx.x].ntok <= 0) return;  // a place the planner filled so that every XCD's list has the same length
+    LORA_CLOCK(0);
     prefill_dispatch<true>(units[blockIdx.x], perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride,
                            lds, parts, sy);
+    LORA_CLOCK(4);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1603,6 +1830,7 @@ __global__ __launch_bounds__(kThreads, ANY ? 2 : 4) void k_shrink_mixed(
 {
     __shared__ __attribute__((aligned(16))) char lds[kMixedShrinkLds];
     const int b = blockIdx.x;
+    if (b < n_heavy && heavy_units[b].ntok <= 0) return;  // a place that only pads an XCD's list of token-heavy units
     if (b < n_heavy)
         prefill_dispatch<ANY>(heavy_units[b], perm, arena, x, ldx, in, sy.v_hi, sy.v_lo, nullptr, n_slices,
                               slice_stride, lds, parts, sy);

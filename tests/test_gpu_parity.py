@@ -259,6 +259,7 @@ def test_token_heavy_units_cut_by_k():
     seg = L.lora_segments_build(dp.pool, b.token_adapter)
     units, ex = L.lora_segments_export_units(seg), L.lora_segments_export(seg)
     sh = units["shrink"]
+    sh = sh[sh[:, 0] >= 0]                                       # without the places that only pad an XCD's list
     heavy = sh[np.diff(ex["seg_start"])[sh[:, 0]] >= 32]
     assert set(int(k) for k in heavy[:, 5]) == {0, 1, 2, 3}      # 24 tiles: four slices each
     x_bits, y0_bits = b.x_bits(), b.y0_bits("small")

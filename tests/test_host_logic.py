@@ -201,7 +201,7 @@ def test_planner_matches_brute_force_grouping(maker):
         cover = np.zeros((ntok, rr, cuts), dtype=np.int32)
         for seg_i, tok0, nt, p0, pn, ks in mine:
             if token_heavy:
-                assert 1 <= nt <= 32 and (p0, pn) == (0, rr) and 0 <= ks < cuts
+                assert 1 <= nt <= (32 if rr <= 64 else 64 if rr <= 128 else 16) and (p0, pn) == (0, rr) and 0 <= ks < cuts
                 cover[tok0:tok0 + nt, :, ks] += 1
             else:
                 assert 1 <= nt <= 16 and 1 <= pn <= 16
@@ -266,6 +266,8 @@ def test_token_heavy_units_are_cut_by_k_in_launches_of_few_units():
         seg = L.lora_segments_plan(pool, b.token_adapter)
         ex, units = L.lora_segments_export(seg), L.lora_segments_export_units(seg)
         sh = units["shrink"]
+        assert np.all(sh[sh[:, 0] < 0][:, 2] == 0)              # places that only pad an XCD's list hold no tokens
+        sh = sh[sh[:, 0] >= 0]
         heavy = sh[np.diff(ex["seg_start"])[sh[:, 0]] >= 32]
         tiles = {}
         for s_, tok0, nt, p0, pn, ks in heavy:
@@ -514,6 +516,41 @@ def test_decode_shrink_units_of_a_group_share_an_xcd():
     weight = (su[:, 2] + su[:, 4]).astype(np.int64)          # tokens + rank rows: bytes of x and A^T per k
     per_xcd = np.array([weight[res == q].sum() for q in range(8)])
     assert per_xcd.max() <= 1.15 * per_xcd.mean()
+    L.lora_segments_destroy(seg)
+    L.lora_pool_destroy(pool)
+
+
+def test_token_heavy_shrink_units_of_an_adapter_share_an_xcd_at_equal_cost():
+    """Launch order of the token-heavy shrink units (cfg2): the tiles of one adapter on places of one
+    residue mod 8 (one XCD fetches its A^T), the eight residues carrying the same bytes (tokens + rank
+    rows of the units), the shorter lists padded at their end with places of no tokens."""
+    b = wl.cfg2_prefill(0)
+    n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
+    pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
+    for a in range(b.n_adapters):
+        L.lora_pool_mark_resident(pool, a)
+    seg = L.lora_segments_plan(pool, b.token_adapter)
+    ex, info = L.lora_segments_export(seg), L.lora_segments_info(seg)
+    su = L.lora_segments_export_units(seg)["shrink"]
+    count = np.diff(ex["seg_start"])
+    n_small = int(np.sum((su[:, 0] >= 0) & (count[np.maximum(su[:, 0], 0)] < 32)))   # the small groups' units come first
+    heavy = su[n_small:]
+    assert len(heavy) % 8 == 0
+    res = np.arange(len(heavy)) % 8
+    real = heavy[:, 0] >= 0
+    assert np.all(heavy[~real][:, 2] == 0) and np.all(heavy[real][:, 2] >= 1)
+    for q in range(8):                                        # padding only at the end of a list
+        mine = real[res == q]
+        assert not np.any(mine[int(mine.sum()):])
+    r8 = ((b.ranks + 7) // 8 * 8)[ex["seg_adapter"]]
+    cost = np.where(real, heavy[:, 2] + heavy[:, 4], 0).astype(np.int64)       # rows of x + rows of A^T
+    per_xcd = np.array([cost[res == q].sum() for q in range(8)])
+    assert per_xcd.max() <= 1.03 * per_xcd.mean()
+    groups = np.unique(heavy[real][:, 0])
+    pairs = sum(len(np.unique(res[real & (heavy[:, 0] == g)])) for g in groups)
+    assert pairs <= 1.35 * len(groups)                        # A^T fetched by 1.35 XCDs on average, not by 8
+    tile = np.where(r8 <= 64, 32, 64)                       # tokens per unit: 64 above rank 64
+    assert real.sum() == sum((c + t - 1) // t for c, t in zip(count, tile) if c >= 32)
     L.lora_segments_destroy(seg)
     L.lora_pool_destroy(pool)
 
