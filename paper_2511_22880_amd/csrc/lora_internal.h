@@ -57,7 +57,7 @@ struct LinBlock {
 };
 static_assert(sizeof(LinBlock) == 32, "LinBlock is 32 bytes");
 constexpr int kLinTileM = 256;  // rows of a work group's output tile (the row order is padded to a multiple)
-constexpr int kLinTileN = 128;  // columns of it: one 128-column strip of B^T
+constexpr int kLinTileN = 256;  // columns of it: two 128-column strips of B^T (the last tile of a row may hold one)
 
 #define LORA_MAX_RANK_PADDED 256
 constexpr int kTokTile = 16;   // tokens per MFMA tile (the N of a 16x16x32 MFMA)

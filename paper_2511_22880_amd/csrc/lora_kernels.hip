@@ -1870,81 +1870,90 @@ __global__ __launch_bounds__(256) void k_reduce_slices(const float *__restrict__
 // token-heavy batches).  Rows are taken in the order "tokens grouped by adapter, groups padded to
 // multiples of 16", so that every 16-row MFMA block has one adapter; x is gathered and y scattered
 // through that order, so no copy of either is made.
-//   * One work group (4 wavefronts) computes a 256 x 128 tile, wavefront w the rows 64 w .. 64 w + 63
-//     of it and all 128 columns: 4 x 8 MFMA tiles of 16 x 16, 128 accumulator registers.  With the
-//     columns of sub-block b being 8 n + b, lane n ends up with 8 consecutive columns of 4 tokens per
-//     row block, and y leaves in 16-byte pieces.
-//   * k goes in chunks of 64, double-buffered in LDS.  W comes packed in operand order (1 KB per
-//     wavefront operand, see launch_pack_weight), so a chunk of a strip is 16 KB of consecutive bytes,
-//     copied by loads that write LDS directly.  x rows are 128 consecutive bytes per chunk: 8 lanes
-//     take a row's chunk with 16-byte loads, and the pieces go into LDS in operand order, with the
-//     three low bits of the slot XORed by (2 kq + k step) so that the 64 lanes of a store spread over
-//     all banks; reads apply the same XOR and still cover each 1 KB block exactly.
+//   * One work group (8 wavefronts) computes a 256 x 256 tile, wavefront w the rows 64 (w mod 4) .. + 63
+//     of it and the 128-column strip w / 4: 4 x 8 MFMA tiles of 16 x 16, 128 accumulator registers.  With
+//     the columns of sub-block b being 8 n + b, lane n ends up with 8 consecutive columns of 4 tokens per
+//     row block, and y leaves in 16-byte pieces.  (A compute unit takes about 50 GB/s from the L2s
+//     whatever it runs; a 256 x 128 tile draws 48 KB per 64 of k and sat exactly at that rate, 720 us for
+//     cfg2's 22.5 k x 4096 x 4096; two strips per tile share the 32 KB of x.)
+//   * k goes in chunks of 32 (one MFMA k step) through a ring of four LDS buffers, everything copied by
+//     loads that write LDS directly, three chunks ahead (a chunk's 32 MFMAs per wavefront last about
+//     0.25 us, a trip to the L2 under load several times that), one barrier per chunk.  W comes packed in
+//     operand order (1 KB per wavefront operand, see launch_pack_weight), so a chunk of a strip is 8 KB of
+//     consecutive bytes.  x is gathered in operand order by the copy itself: the 64 lanes of one copy
+//     fetch the 16-byte pieces (row n, k quarter kq) of a 16-row block and land them in one 1 KB block,
+//     piece (kq, n) in slot (16 kq + n) XOR (2 kq) so that the 64 lanes of an operand read spread over
+//     all banks.  No request passes through registers the compiler tracks, so the waits are exact:
+//     every wavefront issues four copies per chunk and waits until at most eight are in flight.
 //   * After the k loop every row block adds s (v_hi + v_lo) B_a for its adapter: ceil(r8 / 32) more k
 //     steps whose operands come straight from memory (v rows, and B^T in the pool's operand order,
 //     the very pieces the expand kernels read), accumulated apart and scaled once, as the expand does.
 // ------------------------------------------------------------------------------------------------
-constexpr int kLinK = 64;                                   // k per chunk
-constexpr int kLinXBuf = (kLinK / 32) * (kLinTileM / 16) * 1024;  // bytes of x per buffer: 32 KB
-constexpr int kLinWBuf = (kLinK / 32) * 8 * 1024;                 // bytes of W per buffer: 16 KB
-constexpr int kLinLds = kLinXBuf + 2 * kLinWBuf;  // x in one buffer (it waits in registers), W in two: 64 KB, two work groups per compute unit
+constexpr int kLinK = 32;                                   // k per chunk
+constexpr int kLinThreads = 512;
+constexpr int kLinRing = 4;
+constexpr int kLinXBuf = (kLinTileM / 16) * 1024;       // bytes of x per chunk: 16 KB
+constexpr int kLinWBuf = 8 * 1024 * (kLinTileN / 128);  // bytes of W per chunk: 2 strips x 8 KB
+constexpr int kLinLds = kLinRing * (kLinXBuf + kLinWBuf);  // 128 KB: one work group per compute unit
+static_assert(kLinTileM == 256 && kLinTileN == 256, "the wavefront roles below are written for 256 x 256");
 
-__global__ __launch_bounds__(kThreads, 2) void k_linear_lora(
+__global__ __launch_bounds__(kLinThreads, 1) void k_linear_lora(
     const int32_t *__restrict__ rows, const LinBlock *__restrict__ blocks, int m_tiles, int mt_per_xcd, int n_tiles,
     const uint16_t *__restrict__ arena, const uint16_t *__restrict__ wp, const uint16_t *__restrict__ x, int64_t ldx,
-    int in, const uint16_t *__restrict__ v_hi, const uint16_t *__restrict__ v_lo, uint16_t *__restrict__ y, int64_t ldy)
+    int in, int out, const uint16_t *__restrict__ v_hi, const uint16_t *__restrict__ v_lo, uint16_t *__restrict__ y,
+    int64_t ldy)
 {
     __shared__ __attribute__((aligned(16))) char lds[kLinLds];
-    // Work group b runs on XCD b mod 8.  Each XCD takes a run of row tiles, and the 64 work groups it runs
-    // at a time (two per compute unit) are 8 row tiles x 8 column tiles that walk k together: every
-    // chunk of x and of W that one of them brings into the XCD's L2 serves eight of them.
+    // Work group b runs on XCD b mod 8.  Each XCD takes a run of row tiles, and the 32 work groups it runs
+    // at a time (one per compute unit) are 8 row tiles x 4 column tiles that walk k together: every
+    // chunk of x and of W that one of them brings into the XCD's L2 serves four or eight of them.
     const int xcd = blockIdx.x & 7, jloc = blockIdx.x >> 3;
-    const int ngroups_n = (n_tiles + 7) >> 3;
-    const int grp = jloc >> 6, within = jloc & 63;
-    const int mt_loc = (grp / ngroups_n) * 8 + (within >> 3);
-    const int nt = (grp % ngroups_n) * 8 + (within & 7);
+    const int ngroups_n = (n_tiles + 3) >> 2;
+    const int grp = jloc >> 5, within = jloc & 31;
+    const int mt_loc = (grp / ngroups_n) * 8 + (within >> 2);
+    const int nt = (grp % ngroups_n) * 4 + (within & 3);
     const int mt = xcd * mt_per_xcd + mt_loc;
     if (mt_loc >= mt_per_xcd || mt >= m_tiles || nt >= n_tiles) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rw = wave & 3;                     // rows 64 rw .. 64 rw + 63 of the tile
+    const int strip = 2 * nt + (wave >> 2);      // this wavefront's 128-column strip
+    const bool has_strip = strip * 128 < out;    // out is a multiple of 128: the last tile may hold one strip
     const int n = lane & 15, kq = lane >> 4;
     const int m0 = mt * kLinTileM;
     const uint4 zero = {0u, 0u, 0u, 0u};
-    char *const xbuf = lds;
-    auto wbuf = [&](int which) __attribute__((always_inline)) { return lds + kLinXBuf + which * kLinWBuf; };
+    auto xbuf = [&](int which) __attribute__((always_inline)) { return lds + which * (kLinXBuf + kLinWBuf); };
+    auto wbuf = [&](int which) __attribute__((always_inline)) { return lds + which * (kLinXBuf + kLinWBuf) + kLinXBuf; };
 
-    // staging role: 8 lanes per row chunk; thread t takes rows 32 i + t / 8 (i = 0..7), 16-byte piece t % 8
-    const int s_c = tid & 7;
-    const uint16_t *xrow[8];
-    int s_slot[8];
+    // copies of x: this wavefront fills the 16-row blocks 2 wave and 2 wave + 1; its lane s fills slot s of a
+    // block, which holds the piece (kq = s / 16, row n = (s mod 16) XOR (2 kq)) of the block
+    const uint16_t *xsrc[2];
+    {
+        const int nn = n ^ ((2 * kq) & 7);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int r = 32 * i + (tid >> 3);
-        const int row = rows[m0 + r];
-        xrow[i] = x + (int64_t)(row < 0 ? 0 : row) * ldx + 8 * s_c;
-        const int ks = s_c >> 2, q = s_c & 3;
-        // byte offset inside a buffer: (k step, row block) block of 1 KB, slot (kq, n) with its low bits XORed
-        s_slot[i] = ((ks * (kLinTileM / 16) + (r >> 4)) * 64 + ((q * 16 + (r & 15)) ^ ((2 * q + ks) & 7))) * 16;
-    }
-    // this strip's packed W: chunk c is 16 KB at wp + (nt * (in / 32) + 2 c) * 4096 elements
-    const uint4 *wsrc = reinterpret_cast<const uint4 *>(wp + (size_t)nt * (in / 32) * 4096);
-    const int wave_u = wave;
-    auto dma_w = [&](int c, char *dst) __attribute__((always_inline)) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int piece = 4 * wave_u + q;  // 1 KB pieces 0..15 of the chunk
-            dma16_to_lds(wsrc + (size_t)c * 1024 + piece * 64 + lane, reinterpret_cast<const uint4 *>(dst + piece * 1024));
+        for (int j = 0; j < 2; ++j) {
+            const int row = rows[m0 + 16 * (2 * wave + j) + nn];
+            xsrc[j] = x + (int64_t)(row < 0 ? 0 : row) * ldx + 8 * kq;
         }
-    };
-    uint4 xs[8];
-    auto load_x = [&](int c) __attribute__((always_inline)) {
+    }
+    // copies of W: chunk c of a strip is 8 KB at wp + (strip * (in / 32) + c) * 4096 elements; the four
+    // wavefronts of a strip copy two of its eight 1 KB pieces each.  (The wavefronts of a strip the matrix
+    // does not have copy strip 0's pieces into their unused half: every wavefront then has the same
+    // number of copies in flight, which the waits below count.)
+    const uint4 *wsrc = reinterpret_cast<const uint4 *>(wp + (size_t)(has_strip ? strip : 0) * (in / 32) * 4096);
+    const int w_half = (wave >> 2) * (kLinWBuf / 2);
+    auto issue = [&](int c, int which) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) xs[i] = ld16(xrow[i] + c * kLinK);
-    };
-    auto store_x = [&](char *dst) __attribute__((always_inline)) {
+        for (int j = 0; j < 2; ++j)
+            dma16_to_lds(reinterpret_cast<const uint4 *>(xsrc[j] + c * kLinK),
+                         reinterpret_cast<const uint4 *>(xbuf(which) + (2 * wave + j) * 1024));
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4 *>(dst + s_slot[i]) = xs[i];
+        for (int q = 0; q < 2; ++q) {
+            const int piece = 2 * rw + q;
+            dma16_to_lds(wsrc + (size_t)c * 512 + piece * 64 + lane,
+                         reinterpret_cast<const uint4 *>(wbuf(which) + w_half + piece * 1024));
+        }
     };
 
     f32x4 acc[4][8];
@@ -1954,41 +1963,47 @@ __global__ __launch_bounds__(kThreads, 2) void k_linear_lora(
         for (int b = 0; b < 8; ++b) acc[i][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int nk = in / kLinK;
-    load_x(0);
-    dma_w(0, wbuf(0));
-    for (int c = 0; c < nk; ++c) {
-        const int cur = c & 1;
-        __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        __builtin_amdgcn_s_waitcnt(kWaitcntVmcnt0);  // this chunk's x is in registers, its W in LDS
-        __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        store_x(xbuf);
-        __syncthreads();
-        if (c + 1 < nk) {
-            load_x(c + 1);
-            dma_w(c + 1, wbuf(cur ^ 1));  // everyone has left that buffer: it was read two barriers ago
-        }
 #pragma unroll
-        for (int ks = 0; ks < kLinK / 32; ++ks) {
+    for (int c = 0; c < kLinRing - 1; ++c)
+        if (c < nk) issue(c, c);
+    for (int c = 0; c < nk; ++c) {
+        // chunk c has landed when at most the copies of the chunks after it are in flight: 4 per chunk,
+        // up to two chunks (fewer at the end of k)
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        const int after = min(nk - 1 - c, kLinRing - 2);
+        if (after >= 2)
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if (after == 1)
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        // one barrier per chunk: everyone's copies of chunk c have landed, and everyone has left the buffer
+        // of chunk c - 1, which the copies of chunk c + 3 now fill
+        __syncthreads();
+        if (c + kLinRing - 1 < nk) issue(c + kLinRing - 1, (c + kLinRing - 1) % kLinRing);
+        if (has_strip) {
+            const char *xcur = xbuf(c % kLinRing);
+            const char *wcur = wbuf(c % kLinRing) + w_half;
             bf16x8 xo[4], wo[8];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                xo[i] = as_bf16x8(*reinterpret_cast<const uint4 *>(
-                    xbuf + ((ks * (kLinTileM / 16) + 4 * wave + i) * 64 + ((kq * 16 + n) ^ ((2 * kq + ks) & 7))) * 16));
+                xo[i] = as_bf16x8(*reinterpret_cast<const uint4 *>(xcur + ((4 * rw + i) * 64 + ((kq * 16 + n) ^ ((2 * kq) & 7))) * 16));
 #pragma unroll
             for (int b = 0; b < 8; ++b)
-                wo[b] = as_bf16x8(*reinterpret_cast<const uint4 *>(wbuf(cur) + ((ks * 8 + b) * 64 + lane) * 16));
+                wo[b] = as_bf16x8(*reinterpret_cast<const uint4 *>(wcur + (b * 64 + lane) * 16));
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int b = 0; b < 8; ++b)
                     acc[i][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xo[i], wo[b], acc[i][b], 0, 0, 0);
         }
-        __syncthreads();  // the x buffer may be written again
     }
+    if (!has_strip) return;
 
     // ---- the delta of each row block, then the store of y ----
-    const int c0 = nt * kLinTileN;
-    const LinBlock *bks = blocks + (m0 >> 4) + 4 * wave;
+    const int c0 = strip * 128;
+    const LinBlock *bks = blocks + (m0 >> 4) + 4 * rw;
     // the delta of one row block from its own loads of B^T (row blocks whose neighbours have other adapters)
     auto delta_one = [&](int i) __attribute__((always_inline)) {
         const LinBlock &bk = bks[i];
@@ -2024,7 +2039,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_linear_lora(
         // lane (n, kq) holds tokens 4 kq + e of the block, columns c0 + 8 n .. + 7
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int row = rows[m0 + 64 * wave + 16 * i + 4 * kq + e];
+            const int row = rows[m0 + 64 * rw + 16 * i + 4 * kq + e];
             if (row >= 0) {
                 uint4 o;
                 o.x = pack_bf16_rne(acc[i][0][e], acc[i][1][e]);
@@ -2243,13 +2258,14 @@ hipError_t launch_linear_lora(const int32_t *rows, const LinBlock *blocks, int m
                               hipStream_t stream)
 {
     if (m_pad <= 0) return hipSuccess;
-    if (m_pad % kLinTileM || in % kLinK || out % kLinTileN || in < kLinK) return hipErrorInvalidValue;
-    const int m_tiles = m_pad / kLinTileM, n_tiles = out / kLinTileN;
+    if (m_pad % kLinTileM || in % kLinK || out % 128 || out <= 0 || in < kLinK) return hipErrorInvalidValue;
+    const int m_tiles = m_pad / kLinTileM, n_tiles = (out + kLinTileN - 1) / kLinTileN;
     const int mt_per_xcd = (m_tiles + 7) / 8;
-    const int64_t grid = (int64_t)8 * 64 * ((mt_per_xcd + 7) / 8) * ((n_tiles + 7) / 8);
+    // per XCD: groups of 32 work groups = 8 row tiles x 4 column tiles (see the kernel)
+    const int64_t grid = (int64_t)8 * 32 * ((mt_per_xcd + 7) / 8) * ((n_tiles + 3) / 4);
     if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k_linear_lora, dim3((unsigned)grid), dim3(kThreads), 0, stream, rows, blocks, m_tiles, mt_per_xcd,
-                       n_tiles, arena, w_packed, x, ldx, in, v_hi, v_lo, y, ldy);
+    hipLaunchKernelGGL(k_linear_lora, dim3((unsigned)grid), dim3(kLinThreads), 0, stream, rows, blocks, m_tiles,
+                       mt_per_xcd, n_tiles, arena, w_packed, x, ldx, in, out, v_hi, v_lo, y, ldy);
     return hipGetLastError();
 }
 
