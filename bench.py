@@ -99,6 +99,21 @@ def pick_workload(spec: str, wl, tp: str = None):
         return b, f"{description}; tensor-parallel shard 1/{n} ({kind}): {in_f}->{out_f}", layers, seeded
     parts = spec.split(":")
     kind = parts[0]
+    if kind == "groups":
+        # groups:<in>x<out>:<count>x<tokens>[r<rank>]+...   e.g. groups:4096x4096:1x40r64+960x1
+        in_f, out_f = (int(v) for v in parts[1].split("x"))
+        groups = []
+        for g in parts[2].split("+"):
+            body, _, rank = g.partition("r")
+            count, tokens = (int(v) for v in body.split("x"))
+            groups.append((count, tokens, int(rank) if rank else 0))
+        b = wl.groups_batch(in_f, out_f, groups)
+        return (b, f"groups {parts[2]} (count x tokens, one adapter each), {in_f}->{out_f}, T={b.T}", 4, False)
+    if kind == "cfg1" and len(parts) > 1:
+        # cfg1:<in>x<out>: the same routing on another projection shape
+        in_f, out_f = (int(v) for v in parts[1].split("x"))
+        return (wl.cfg1_decode(layer=0, in_features=in_f, out_features=out_f), f"cfg1's routing (T=256, 128 adapters ranks "
+                f"{{8,16,32,64,128}}, Zipf(1.1)) on {in_f}->{out_f}", 32, False)
     if kind == "cfg1":
         return (wl.cfg1_decode(layer=0), "cfg1 decode co-batch, Llama-3-8B q_proj 4096->4096, T=256, 128 adapters "
                 "ranks {8,16,32,64,128}, Zipf(1.1)", 32, True)
@@ -323,8 +338,12 @@ def main() -> int:
                     help="projections per step (default: 32 for cfg1, fewer for the larger workloads)")
     ap.add_argument("--workload", default="cfg1",
                     help="cfg1 (default, the benchmark line) | cfg2:<shape 0..2> | cfg3:<projection 0..6>[:<prompt length scale>] | "
-                         "cfg4:<shape 0..2>:<9to1|1to1|1to9>[:<0|1> only that rank class]; any of them with @r<rank> appended: "
+                         "cfg4:<shape 0..2>:<9to1|1to1|1to9>[:<0|1> only that rank class] | groups:<in>x<out>:<count>x<tokens>[r<rank>]+...; "
+                         "any of them with @r<rank> appended: "
                          "every adapter at that rank")
+    ap.add_argument("--plan", default=None, metavar="NAME=VALUE[,...]",
+                    help="fields of lora_plan_options_t for the timed object, e.g. heavy_k_cut_max_units=0,whole_k_max_in=16384 "
+                         "(a planner rule measured on the other side of its threshold)")
     ap.add_argument("--tp", default=None, metavar="N:col|N:row",
                     help="time one GPU's shard of the workload's projection under N-way tensor parallelism: "
                          "col = out_features/N columns of B (column-parallel layer), row = in_features/N rows of A "
@@ -630,7 +649,10 @@ def run_workload(args, torch, L, wl, dev, stream, hip, workload, layers, steps, 
             L.lora_pool_mark_resident(pools[l], a)
     ys = [torch.zeros(T, out_f, dtype=torch.bfloat16, device=dev) for _ in range(nl)]
 
-    seg = L.lora_segments_build(pools[0], b0.token_adapter, stream=stream)
+    plan = None
+    if getattr(args, "plan", None):
+        plan = L.plan_options(**{k: int(v) for k, v in (kv.split("=") for kv in args.plan.split(","))})
+    seg = L.lora_segments_build(pools[0], b0.token_adapter, stream=stream, options=plan)
     info = L.lora_segments_info(seg)
     ws = torch.empty(max(L.lora_apply_workspace_bytes(pools[0], seg), 256), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()

@@ -201,8 +201,19 @@ typedef struct {
     int32_t fused_apply;          /* -1, 0, 1: lora_set_fused_apply                  */
     int32_t decode_single_launch; /* -1, 0, 1: lora_set_decode_single_launch         */
     uint32_t fused_wait_limit;    /* 0 or polls: lora_set_fused_wait_limit           */
+    /* The planner's size thresholds, each found by a sweep on one MI355X (the measured points are listed
+     * beside the built-in values in the host source); -1 = built in.  They exist so that a caller, or a
+     * bench, can measure a plan on either side of a threshold; results do not depend on them beyond the
+     * order of fp32 sums. */
+    int32_t whole_k_max_in;        /* largest in_features planned without k-slices (built in: 18432)      */
+    int32_t heavy_min_tokens;      /* a group of at least this many tokens is token-heavy (32) ...        */
+    int32_t heavy_min_batch;       /* ... in a batch of at least this many active tokens (1024)           */
+    int32_t heavy_k_cut_max_units; /* token-heavy shrink units are cut along k while the cut units stay    *
+                                    * within this count (320; 750 beyond in_features 8192)                 */
+    int32_t big_runs_max_units;    /* 64-token expand units take their columns in 8 runs, not 4, while     *
+                                    * the launch stays within this many of them (two per compute unit: 512) */
 } lora_plan_options_t;
-#define LORA_PLAN_OPTIONS_DEFAULT {-1, -1, -1, -1, -1, 0u}
+#define LORA_PLAN_OPTIONS_DEFAULT {-1, -1, -1, -1, -1, 0u, -1, -1, -1, -1, -1}
 
 /* Host-only half of lora_segments_build: group the T tokens by adapter (stable: tokens of one
  * adapter keep their order), and cut every group into work units whose cost follows that adapter's
@@ -396,7 +407,7 @@ lora_status_t lora_apply_multi(const lora_pool_t *const *pools, int32_t n_pools,
  * lora_segments_plan / build / rebuild calls that follow for objects that leave the field at -1.
  * A batch whose decode-sized groups make between 64 and `max_units` shrink units when a unit takes
  * the whole of k (16 rank rows x up to 16 tokens each) is planned that way, if in_features is at most
- * 8192 and the batch is not a mixed one run as merged launches (below): work groups of 16
+ * 18432 and the batch is not a mixed one run as merged launches (below): work groups of 16
  * wavefronts, v complete when the unit ends.  Other batches cut k into up to 4 slices per unit (more,
  * smaller units spread a small batch over the chip and fill the last round of a large one better) and
  * add the slices up through counters.  Both plans give bitwise the same v for these groups
@@ -438,7 +449,7 @@ lora_status_t lora_set_fused_apply(int enabled);
  * by side and everything later on `stream` is ordered behind both.  lora_set_side_stream(0) keeps all
  * four launches on `stream`.  y is bitwise the same in all three forms, except where the merged
  * form's plan also cuts the token-heavy shrink units along k (launches of few such units: at most
- * 160 of them, 300 beyond 8192 input features; the sums of v are then grouped differently, within
+ * 160 of them, 375 beyond 8192 input features; the sums of v are then grouped differently, within
  * the same tolerance).
  * Process-wide. */
 lora_status_t lora_set_merged_launches(int enabled);

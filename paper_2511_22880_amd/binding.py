@@ -68,14 +68,19 @@ class _SegInfo(ctypes.Structure):
 class _PlanOptions(ctypes.Structure):
     _fields_ = [("whole_k_limit", ctypes.c_int32), ("merged_launches", ctypes.c_int32), ("side_stream", ctypes.c_int32),
                 ("fused_apply", ctypes.c_int32), ("decode_single_launch", ctypes.c_int32),
-                ("fused_wait_limit", ctypes.c_uint32)]
+                ("fused_wait_limit", ctypes.c_uint32), ("whole_k_max_in", ctypes.c_int32),
+                ("heavy_min_tokens", ctypes.c_int32), ("heavy_min_batch", ctypes.c_int32),
+                ("heavy_k_cut_max_units", ctypes.c_int32), ("big_runs_max_units", ctypes.c_int32)]
 
 
 def plan_options(whole_k_limit: int = -1, merged_launches: int = -1, side_stream: int = -1, fused_apply: int = -1,
-                 decode_single_launch: int = -1, fused_wait_limit: int = 0) -> _PlanOptions:
-    """lora_plan_options_t; -1 (0 for the wait limit) = the process-wide default."""
+                 decode_single_launch: int = -1, fused_wait_limit: int = 0, whole_k_max_in: int = -1,
+                 heavy_min_tokens: int = -1, heavy_min_batch: int = -1, heavy_k_cut_max_units: int = -1,
+                 big_runs_max_units: int = -1) -> _PlanOptions:
+    """lora_plan_options_t; -1 (0 for the wait limit) = the process-wide default or the built-in threshold."""
     return _PlanOptions(int(whole_k_limit), int(merged_launches), int(side_stream), int(fused_apply),
-                        int(decode_single_launch), int(fused_wait_limit))
+                        int(decode_single_launch), int(fused_wait_limit), int(whole_k_max_in), int(heavy_min_tokens),
+                        int(heavy_min_batch), int(heavy_k_cut_max_units), int(big_runs_max_units))
 
 
 def _opts(options):

@@ -579,23 +579,36 @@ static std::atomic<int> g_merged_mixed{1};
 static const int kSplitRowsFloor = 1;   // fewest tokens of a whole-k unit that may be cut into 8-row halves
 static const int kWholeKMin = 64;  // below this, k-slices are what spreads the batch over the chip
 // A wavefront of a whole-k unit walks in_features / 16 of k in passes of 256, one trip to memory each:
-// beyond this many input features the k-slice units win (cfg1's routing, shrink launch: 14.4 vs 15.5 us
-// at 8192, 23.5 vs 22.4 us at 14336, 41.8 vs 38.8 us at 28672; the rank-skew batch at 28672: 96 vs 86 us).
-static const int kWholeKMaxIn = 8192;
-// Likewise a token-heavy shrink unit: a wavefront takes a quarter of k in passes of 128, and a launch of
-// few such units lasts as long as one unit's walk (cfg3's routing scaled to 1.5 k .. 9.5 k tokens: 32-37
-// us at 4096 input features, 99-116 us at 14336, whatever the number of tokens).  In a batch planned
-// in k-slices such units are cut into 4 or 2 slices along k while the cut units stay below these counts
-// (measured, shrink launch in us uncut / 2 / 4 slices; 4096: 41 units 32 / 28 / 23, 79 units 33 / 28 /
-// 25, 148 units 33 / 30 / 33, 291 units 37 / 40 / 45; 14336: 41 units 99 / 67 / 52, 79 units 102 / 67 /
-// 59, 148 units 102 / 75 / 77, 291 units 116 / 102 / 109; cfg2's 718 units at 14336: 155 / 155 / 162).
+// beyond this many input features the k-slice units win.  cfg1's routing, ms per step of 32 projections,
+// whole-k (one launch per apply) against k-slices (two launches): 0.663 / 0.744 at 8192 input features,
+// 0.668 / 0.769 at 8256, 0.942 / 0.963 at 14336, 1.002 / 1.041 at 16384, 1.038 / 1.079 at 16448, 1.290 /
+// 1.228 at 20480, 1.442 / 1.380 at 24576, 1.592 / 1.533 at 28672; the rank-skew batch at 28672: 1.024 /
+// 0.951.  (Before the one-launch form the shrink launches alone crossed at 8192.)
+static const int kWholeKMaxIn = 18432;
 // Tokens of a token-heavy shrink unit: up to rank 64 the wavefronts split k and hold 32 tokens; above,
 // they split the rank rows and share 64 tokens of x through LDS (A^T is then loaded once per 64
 // tokens); above rank 128, 16 tokens with k split.
 static int heavy_tile(int r8) { return r8 <= 64 ? 32 : (r8 <= 128 ? 64 : 16); }
+// A token-heavy shrink unit is one walk through k (a wavefront takes a quarter of k in passes of 128, one
+// trip to memory each), and a launch of few such units lasts as long as one unit's walk (cfg3's routing
+// scaled to 1.5 k .. 9.5 k tokens: 32-37 us at 4096 input features, 99-116 us at 14336, whatever the
+// number of tokens).  In a batch planned in k-slices such units are cut into 4 or 2 slices along k while
+// the cut units stay within these counts.  Measured, shrink launch in us uncut / 2 / 4 slices; 4096: 41
+// units 32 / 28 / 23, 79 units 33 / 28 / 25, 148 units 33 / 30 / 33, 161 units 19.5 / 21.4, 291 units
+// 37 / 40 / 45, 321 units 28.2 / 28.2; 8192: 250 units 38.7 / 38.9; 14336: 41 units 99 / 67 / 52, 79
+// units 102 / 67 / 59, 148 units 102 / 75 / 77, 291 units 116 / 102 / 109, 301 units 85.6 / 75.7, 450
+// units 94 / 101.5, 600 units 126.6 / 126.3, cfg2's 718 units 155 / 155 / 162.  So two slices pay up
+// to about 320 cut units at 4096 .. 8192 input features and up to 600 .. 900 at 14336, where a unit's
+// walk is 3.5 times as long.
 static const int kHeavyKCutMaxUnits = 320;
-static const int kHeavyKCutMaxUnitsLongK = 600;
-static const int kBigRunsMaxUnits = 400;  // 64-token expand units of a launch whose groups' columns go in 8 runs
+static const int kHeavyKCutLongK = 8192;          // beyond this many input features:
+static const int kHeavyKCutMaxUnitsLongK = 750;
+// 64-token expand units take a group's columns in 8 runs instead of 4 while the launch stays within one
+// round of work groups (two per compute unit): expand launch, 4 / 8 runs, 50 tiles of 64 tokens 15.3 /
+// 14.0 us, 51 tiles 15.7 / 14.2, 64 tiles 17.2 / 15.9, 72 tiles 21.7 / 21.9; cfg3's routing at 1.5 k /
+// 2.7 k tokens 25.7 -> 19.5 / 26.6 -> 23.1 us at 4096 columns, 78.6 -> 60.8 / 80.5 -> 72.8 us at 14336;
+// at 4.9 k tokens and beyond 8 runs are level or lose.
+static const int kBigRunsWorkGroupsPerComputeUnit = 2;
 
 extern "C" lora_status_t lora_set_whole_k_limit(int32_t max_units)
 try {
@@ -725,6 +738,10 @@ static void order_heavy_units_by_xcd(std::vector<Unit> &units)
 }
 
 static int g_compute_units = 256;  // of the chip: a whole-k launch within this many units is one round
+static int opt_big_runs_max_units(const lora_segments *sg)
+{
+    return sg->opts.big_runs_max_units >= 0 ? sg->opts.big_runs_max_units : kBigRunsWorkGroupsPerComputeUnit * g_compute_units;
+}
 static const int kXcds = 8;         // XCDs of the chip, each with an L2 of its own; work group b of a launch runs on XCD b mod 8
 static std::atomic<int> g_decode_single_launch{1};
 static std::atomic<int> g_side_stream{1};
@@ -733,11 +750,21 @@ static const unsigned kSpinLimit = 1u << 18;  // polls of a waiting expand unit 
 static std::atomic<unsigned> g_spin_limit{kSpinLimit};
 
 // A segment object's plan settings: what was given at planning, else the process-wide default now.
+static const lora_plan_options_t kDefaultOptions = LORA_PLAN_OPTIONS_DEFAULT;
 static int opt_whole_k_limit(const lora_segments *sg) { return sg->opts.whole_k_limit >= 0 ? sg->opts.whole_k_limit : g_whole_k_limit.load(); }
 static bool opt_merged(const lora_segments *sg) { return (sg->opts.merged_launches >= 0 ? sg->opts.merged_launches : g_merged_mixed.load()) != 0; }
 static bool opt_side_stream(const lora_segments *sg) { return (sg->opts.side_stream >= 0 ? sg->opts.side_stream : g_side_stream.load()) != 0; }
 static bool opt_fused_apply(const lora_segments *sg) { return (sg->opts.fused_apply >= 0 ? sg->opts.fused_apply : g_fused_apply.load()) != 0; }
 static bool opt_decode_single(const lora_segments *sg) { return (sg->opts.decode_single_launch >= 0 ? sg->opts.decode_single_launch : g_decode_single_launch.load()) != 0; }
+static int opt_whole_k_max_in(const lora_segments *sg) { return sg->opts.whole_k_max_in >= 0 ? sg->opts.whole_k_max_in : kWholeKMaxIn; }
+static int opt_heavy_min_tokens(const lora_segments *sg) { return sg->opts.heavy_min_tokens >= 0 ? sg->opts.heavy_min_tokens : kPrefillMinTokens; }
+static int opt_heavy_min_batch(const lora_segments *sg) { return sg->opts.heavy_min_batch >= 0 ? sg->opts.heavy_min_batch : kPrefillMinBatch; }
+static int opt_big_runs_max_units(const lora_segments *sg);
+static int opt_heavy_k_cut_max_units(const lora_segments *sg, int in_features)
+{
+    if (sg->opts.heavy_k_cut_max_units >= 0) return sg->opts.heavy_k_cut_max_units;
+    return in_features > kHeavyKCutLongK ? kHeavyKCutMaxUnitsLongK : kHeavyKCutMaxUnits;
+}
 static unsigned opt_spin_limit(const lora_segments *sg) { return sg->opts.fused_wait_limit ? sg->opts.fused_wait_limit : g_spin_limit.load(); }
 
 // Offsets of the lists inside the device table.
@@ -899,6 +926,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
         ++count[a];
         ++n_active;
     }
+    const int heavy_min_tokens = opt_heavy_min_tokens(sg), heavy_min_batch = opt_heavy_min_batch(sg);
     sg->pool = pool;
     sg->pool_id = pool->id;
     sg->layout_in = pool->in_features;
@@ -911,14 +939,14 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     // units and fill the last round of a large one better.
     int64_t whole_k_units = 0;
     for (int a = 0; a < N; ++a) {
-        if (!count[a] || (count[a] >= kPrefillMinTokens && n_active >= kPrefillMinBatch)) continue;
+        if (!count[a] || (count[a] >= heavy_min_tokens && n_active >= heavy_min_batch)) continue;
         whole_k_units += (int64_t)((pool->r8[a] + lora::kRowTile - 1) / lora::kRowTile) *
                          ((count[a] + lora::kTokTile - 1) / lora::kTokTile);
     }
     bool heavy_groups = false;
-    for (int a = 0; a < N; ++a) heavy_groups |= count[a] >= kPrefillMinTokens && n_active >= kPrefillMinBatch;
+    for (int a = 0; a < N; ++a) heavy_groups |= count[a] >= heavy_min_tokens && n_active >= heavy_min_batch;
     sg->wide = whole_k_units >= kWholeKMin && whole_k_units <= opt_whole_k_limit(sg) &&
-               pool->in_features <= kWholeKMaxIn && !(opt_merged(sg) && heavy_groups);
+               pool->in_features <= opt_whole_k_max_in(sg) && !(opt_merged(sg) && heavy_groups);
     choose_k_slices(pool->in_features, &sg->wide_slices, &sg->wide_slice_len);
     // Whole-k units of many tokens pass up to twice the bytes of the others through their compute unit
     // (x beside A^T) and end the launch.  While the launch stays at one work group per compute unit,
@@ -932,7 +960,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     if (sg->wide && !want_fused) {
         int64_t per_tokens[lora::kTokTile + 1] = {0};  // full 16-row units by their token count
         for (int a = 0; a < N; ++a) {
-            if (!count[a] || (count[a] >= kPrefillMinTokens && n_active >= kPrefillMinBatch)) continue;
+            if (!count[a] || (count[a] >= heavy_min_tokens && n_active >= heavy_min_batch)) continue;
             for (int tok0 = 0; tok0 < count[a]; tok0 += lora::kTokTile)
                 per_tokens[std::min(lora::kTokTile, count[a] - tok0)] += pool->r8[a] / lora::kRowTile;
         }
@@ -1023,11 +1051,11 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     // takes a quarter of k in passes of 128, one trip to memory each); such units are cut into k-slices.
     int64_t heavy_units = 0;
     for (const SegRec &r : sg->segs)
-        if (r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch)
+        if (r.ntok >= heavy_min_tokens && n_active >= heavy_min_batch)
             heavy_units += (r.ntok + heavy_tile(r.r8) - 1) / heavy_tile(r.r8);
     int heavy_k_slices = 1;
     if (sg->n_k_slices >= 2 && heavy_units > 0) {
-        const int64_t limit = pool->in_features > kWholeKMaxIn ? kHeavyKCutMaxUnitsLongK : kHeavyKCutMaxUnits;
+        const int64_t limit = opt_heavy_k_cut_max_units(sg, pool->in_features);
         for (int c = std::min(4, sg->n_k_slices); c >= 2 && heavy_k_slices == 1; c /= 2)
             if (heavy_units * c <= limit) heavy_k_slices = c;  // per projection: lora_apply_multi gives the bits of separate applies
     }
@@ -1037,11 +1065,11 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     // us at 14336; at 4.9 k tokens and beyond 8 runs are level or lose).
     int64_t big_tiles = 0;
     for (const SegRec &r : sg->segs)
-        if (r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch && r.r8 <= 128) big_tiles += (r.ntok + 63) / 64;
-    const int big_runs = big_tiles * 8 * n_projections <= kBigRunsMaxUnits ? 8 : 4;
+        if (r.ntok >= heavy_min_tokens && n_active >= heavy_min_batch && r.r8 <= 128) big_tiles += (r.ntok + 63) / 64;
+    const int big_runs = big_tiles * 8 * n_projections <= opt_big_runs_max_units(sg) ? 8 : 4;
     for (int32_t si : order) {
         const SegRec &r = sg->segs[si];
-        const bool token_heavy = r.ntok >= kPrefillMinTokens && n_active >= kPrefillMinBatch;
+        const bool token_heavy = r.ntok >= heavy_min_tokens && n_active >= heavy_min_batch;
         const int sync_n = ((r.r8 + lora::kRowTile - 1) / lora::kRowTile) * sg->n_k_slices;
         if (token_heavy) {
             // shrink: tiles of 32 tokens (64 above rank 64, 16 above rank 128), all rank rows, all of k or
@@ -1199,7 +1227,7 @@ static lora_segments *new_segments()
     sg->n_sync = 0;
     sg->launches = 0;
     sg->caller_memory = false;
-    sg->opts = lora_plan_options_t{-1, -1, -1, -1, -1, 0u};
+    sg->opts = kDefaultOptions;
     return sg;
 }
 
@@ -1255,6 +1283,11 @@ static lora_status_t check_options(const lora_plan_options_t *o)
 {
     if (!o) return LORA_OK;
     if (o->whole_k_limit < -1) return fail(LORA_ERR_INVALID_ARG, "options: whole_k_limit = %d", o->whole_k_limit);
+    const int32_t sizes[5] = {o->whole_k_max_in, o->heavy_min_tokens, o->heavy_min_batch, o->heavy_k_cut_max_units,
+                              o->big_runs_max_units};
+    for (int32_t v : sizes)
+        if (v < -1) return fail(LORA_ERR_INVALID_ARG, "options: a threshold is %d (-1 = built in)", v);
+    if (o->heavy_min_tokens == 0) return fail(LORA_ERR_INVALID_ARG, "options: heavy_min_tokens = 0");
     const int32_t flags[4] = {o->merged_launches, o->side_stream, o->fused_apply, o->decode_single_launch};
     for (int32_t f : flags)
         if (f < -1 || f > 1) return fail(LORA_ERR_INVALID_ARG, "options: a switch is %d, not -1, 0 or 1", f);
@@ -1292,7 +1325,7 @@ try {
     if (!seg_ok(sg)) return fail(LORA_ERR_INVALID_ARG, "seg is NULL or not a segment object");
     lora_status_t st = check_options(options);
     if (st != LORA_OK) return st;
-    sg->opts = options ? *options : lora_plan_options_t{-1, -1, -1, -1, -1, 0u};
+    sg->opts = options ? *options : kDefaultOptions;
     return LORA_OK;
 }
 API_CATCH

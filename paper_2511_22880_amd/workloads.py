@@ -186,6 +186,21 @@ def _from_requests(name: str, in_f: int, out_f: int, ranks: np.ndarray, req_len:
     return CoBatch(name, in_f, out_f, ranks, _scales_for(ranks), ta, requests=reqs, **kw)
 
 
+def groups_batch(in_features: int, out_features: int, groups: Sequence[Tuple[int, int, int]], seed: int = 0) -> CoBatch:
+    """A batch given by its groups: (how many groups, tokens of each, rank of their adapters or 0 = the
+    rank set in turn), every group with an adapter of its own and its tokens side by side.  For
+    measurements at chosen sizes (a planner rule on either side of its threshold), not one of the
+    paper's workloads."""
+    lens, ranks = [], []
+    for count, tokens, rank in groups:
+        for _ in range(int(count)):
+            lens.append(int(tokens))
+            ranks.append(int(rank) if rank else RANK_SET[len(ranks) % len(RANK_SET)])
+    ranks = np.asarray(ranks, dtype=np.int32)
+    return _from_requests(f"groups_{in_features}x{out_features}_{len(lens)}", in_features, out_features, ranks, lens,
+                          np.arange(len(lens)), seed=seed, config=9)
+
+
 def cfg2_prefill(shape: int = 0, seed: int = 0, length_scale: float = 1.0) -> CoBatch:
     """32 prefill requests, prompt lengths lognormal (median 512, sigma 1, clipped 16..4096), one
     distinct adapter per request, ranks balanced over {8..128}.  ``shape`` indexes CFG2_SHAPES.

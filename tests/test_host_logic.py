@@ -253,7 +253,7 @@ def test_column_runs_of_64_token_expand_units_meet_few_xcds():
 
 def test_token_heavy_units_are_cut_by_k_in_launches_of_few_units():
     """A mixed batch planned in k-slices: every 32-token tile of a token-heavy group gets 4 or 2 units
-    (k-slices of the same rows) while the cut units stay at or below 320 (600 beyond 8192 input
+    (k-slices of the same rows) while the cut units stay at or below 320 (750 beyond 8192 input
     features), else one."""
     cases = ((wl.cfg3_stack(projection=6), 2), (wl.cfg3_stack(projection=0), 1), (wl.cfg2_prefill(2), 1),
              (wl.cfg3_stack(projection=0, length_scale=0.5), 2), (wl.cfg3_stack(projection=0, length_scale=0.25), 4),
@@ -273,7 +273,7 @@ def test_token_heavy_units_are_cut_by_k_in_launches_of_few_units():
         for s_, tok0, nt, p0, pn, ks in heavy:
             tiles.setdefault((int(s_), int(tok0), int(nt), int(p0), int(pn)), []).append(int(ks))
         assert len(tiles) > 0
-        limit = 600 if b.in_features > 8192 else 320
+        limit = 750 if b.in_features > 8192 else 320
         assert len(tiles) * cuts <= limit or cuts == 1
         assert cuts == 4 or len(tiles) * cuts * 2 > limit
         for ks_list in tiles.values():
@@ -639,6 +639,46 @@ def test_plan_options_belong_to_the_object():
         L.lora_segments_plan(pool, b.token_adapter, options=L.plan_options(merged_launches=5))
     assert e.value.status_name == "LORA_ERR_INVALID_ARG"
     L.lora_pool_destroy(pool)
+
+
+def test_planner_thresholds_can_be_moved_per_object():
+    """The size thresholds of the planner are fields of lora_plan_options_t: a batch can be planned on
+    either side of each (what bench.py --plan does); -1 keeps the built-in value, anything below is refused."""
+    def plan(b, **kw):
+        n = L.lora_pool_bytes(b.in_features, b.out_features, b.ranks, b.scales)
+        pool = L.lora_pool_create(b.in_features, b.out_features, b.ranks, b.scales, FAKE_ARENA, n)
+        for a in range(b.n_adapters):
+            L.lora_pool_mark_resident(pool, a)
+        seg = L.lora_segments_plan(pool, b.token_adapter, options=L.plan_options(**kw) if kw else None)
+        info, units = L.lora_segments_info(seg), L.lora_segments_export_units(seg)
+        L.lora_segments_destroy(seg)
+        L.lora_pool_destroy(pool)
+        return info, units
+    # in_features beyond the built-in limit of the whole-k plan: k-slices, unless the limit is raised
+    b = wl.cfg1_decode(in_features=18496, out_features=512)
+    assert plan(b)[0]["n_k_slices"] > 1 and plan(b, whole_k_max_in=32768)[0]["n_k_slices"] == 1
+    b = wl.cfg1_decode(in_features=18432, out_features=512)
+    assert plan(b)[0]["n_k_slices"] == 1 and plan(b, whole_k_max_in=4096)[0]["n_k_slices"] > 1
+    # a 40-token group in a batch of 1000 tokens is cut like the small groups, unless the batch size that
+    # makes groups token-heavy is lowered; in a batch of 1030 it is token-heavy, unless that size is raised
+    for extra, kw in ((960, {"heavy_min_batch": 1000}), (990, {"heavy_min_batch": 100000})):
+        b = wl.groups_batch(256, 256, [(1, 40, 64), (extra, 1, 0)])
+        base, moved = plan(b)[1]["shrink"], plan(b, **kw)[1]["shrink"]
+        big = lambda u: int((u[:, 2] > 16).sum())
+        assert (big(base) > 0) == (extra == 990) and (big(moved) > 0) == (extra == 960)
+    # groups of 31 tokens become token-heavy when the token threshold is lowered
+    b = wl.groups_batch(256, 256, [(40, 31, 64), (800, 1, 0)])
+    assert int((plan(b)[1]["shrink"][:, 2] > 16).sum()) == 0
+    assert int((plan(b, heavy_min_tokens=31)[1]["shrink"][:, 2] > 16).sum()) == 40
+    # 64-token expand units: 8 column runs within one round of work groups (512 units), else 4
+    b = wl.groups_batch(256, 4096, [(4, 1024, 32)])
+    assert len(plan(b)[1]["expand"]) == 64 * 8 and len(plan(b, big_runs_max_units=511)[1]["expand"]) == 64 * 4
+    b = wl.groups_batch(256, 4096, [(5, 832, 32)])
+    assert len(plan(b)[1]["expand"]) == 65 * 4 and len(plan(b, big_runs_max_units=520)[1]["expand"]) == 65 * 8
+    with pytest.raises(L.LoraError):
+        plan(b, heavy_k_cut_max_units=-2)
+    with pytest.raises(L.LoraError):
+        plan(b, heavy_min_tokens=0)
 
 
 def test_handles_that_outlive_their_pool_are_refused():
