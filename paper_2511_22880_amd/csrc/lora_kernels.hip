@@ -1464,7 +1464,10 @@ static __device__ __forceinline__ void l2_counter_add(unsigned *p, unsigned n)
     asm volatile("global_atomic_add %0, %1, off" : : "v"(p), "v"(n) : "memory");
 }
 
-static __device__ __forceinline__ void l1_invalidate() { asm volatile("buffer_inv sc0" ::: "memory"); }
+// Drops this compute unit's vector cache lines, so that the loads that follow see what other compute
+// units have stored (through the XCD's L2) since the lines were fetched.  Agent scope: at work-group
+// scope the instruction does nothing unless the work group is split over compute units.
+static __device__ __forceinline__ void l1_invalidate() { asm volatile("buffer_inv sc1" ::: "memory"); }
 
 __global__ __launch_bounds__(kWideThreads) void k_decode_fused(
     const Unit *__restrict__ s_units, int n_s, const Unit *__restrict__ e_units, int n_e,
@@ -1686,13 +1689,17 @@ __global__ __launch_bounds__(kWideThreads) void k_decode_fused(
         LORA_CLOCK(3);
         const bool ok0 = (i < e_ntok) && j_ok0;
         const int64_t off0 = eu->v_off + (int64_t)(ok0 ? i : 0) * e_r8 + jc0;
-        uint4 vh0 = ld16(sy.v_hi + off0), vl0 = ld16(sy.v_lo + off0);
+        // Loads that do not stop at this compute unit's vector cache: a 128-byte line of v can hold rows of
+        // two token tiles, and another unit of this work group may have fetched the line for its own tile
+        // before this tile's rows were stored (seen as rows without their delta, on a first, cold launch
+        // at 14,336 input features, where the shrink units end far apart).
+        uint4 vh0 = ld_through_u16x8(sy.v_hi + off0), vl0 = ld_through_u16x8(sy.v_lo + off0);
         uint4 vh1 = zero, vl1 = zero;
         const bool ok1 = (i < e_ntok) && j_ok1;
         if (e_r8 > 128) {
             const int64_t off1 = eu->v_off + (int64_t)(ok1 ? i : 0) * e_r8 + jc1;
-            vh1 = ld16(sy.v_hi + off1);
-            vl1 = ld16(sy.v_lo + off1);
+            vh1 = ld_through_u16x8(sy.v_hi + off1);
+            vl1 = ld_through_u16x8(sy.v_lo + off1);
         }
         if (!ok0) vh0 = vl0 = zero;
         if (!ok1) vh1 = vl1 = zero;

@@ -42,6 +42,24 @@ def test_small_mixed_ragged():
     _full_parity(wl.small_mixed(seed=3, in_features=1280, out_features=640), y0_kind="small")
 
 
+def test_decode_batches_up_to_the_widest_whole_k_plan():
+    """Decode co-batches whose units take the whole of k up to 18,432 input features (the one-launch form
+    and the two launches), and just beyond, where the planner goes to k-slices."""
+    for in_f in (14336, 18432, 18496):
+        b = wl.cfg1_decode(in_features=in_f, out_features=512, n_tokens=200)
+        dp = G.DevicePool(b)
+        seg = L.lora_segments_plan(dp.pool, b.token_adapter)
+        assert (L.lora_segments_info(seg)["n_k_slices"] == 1) == (in_f <= 18432)
+        L.lora_segments_destroy(seg)
+        dp.close()
+        _full_parity(b)
+        L.lora_set_decode_single_launch(False)
+        try:
+            _full_parity(b, y0_kind="small")
+        finally:
+            L.lora_set_decode_single_launch(True)
+
+
 def test_padded_control_pool():
     """The control layout (every adapter stored zero-padded at the largest rank, what a kernel sized to
     the largest rank needs) goes through the same entry points and gives the same rows."""
