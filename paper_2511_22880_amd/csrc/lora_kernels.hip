@@ -1438,7 +1438,11 @@ static __device__ __forceinline__ void expand_dispatch(const Unit &u, const int3
 //     token tile) at places of one residue mod 8: v is then written with plain stores into that XCD's
 //     L2, the tile's ready counter is bumped by an atomic that the L2 executes, the expand units poll it
 //     with a returning atomic (executed by the L2 as well; a plain load could be served by the compute
-//     unit's L1), drop what their L1 holds and read v with plain loads, which the L2 serves.
+//     unit's L1) and read v with agent-scope loads, which pass the compute unit's L1 and are served
+//     by the L2.  (Not plain loads behind an L1 invalidate: at work-group scope the invalidate does
+//     nothing here, and a 128-byte line of v can hold rows of two tiles, so that a unit of the same work
+//     group may have fetched the line before this tile's rows were stored; the agent-scope
+//     invalidate, which does drop the lines, made the launch 2.6 times as long.)
 //     The counters only grow: the target is epoch * sync_n, epoch = such launches the table has seen.
 //     Every work group checks that the work groups on its XCD all have its residue (see the start of
 //     the kernel); if not it sets bit 1 of the time-out flag: the launch's result is then not valid
@@ -1463,11 +1467,6 @@ static __device__ __forceinline__ void l2_counter_add(unsigned *p, unsigned n)
 {
     asm volatile("global_atomic_add %0, %1, off" : : "v"(p), "v"(n) : "memory");
 }
-
-// Drops this compute unit's vector cache lines, so that the loads that follow see what other compute
-// units have stored (through the XCD's L2) since the lines were fetched.  Agent scope: at work-group
-// scope the instruction does nothing unless the work group is split over compute units.
-static __device__ __forceinline__ void l1_invalidate() { asm volatile("buffer_inv sc1" ::: "memory"); }
 
 __global__ __launch_bounds__(kWideThreads) void k_decode_fused(
     const Unit *__restrict__ s_units, int n_s, const Unit *__restrict__ e_units, int n_e,
@@ -1684,15 +1683,14 @@ __global__ __launch_bounds__(kWideThreads) void k_decode_fused(
                 __builtin_amdgcn_s_sleep(2);
             }
         }
-        l1_invalidate();
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
         LORA_CLOCK(3);
         const bool ok0 = (i < e_ntok) && j_ok0;
         const int64_t off0 = eu->v_off + (int64_t)(ok0 ? i : 0) * e_r8 + jc0;
-        // Loads that do not stop at this compute unit's vector cache: a 128-byte line of v can hold rows of
-        // two token tiles, and another unit of this work group may have fetched the line for its own tile
-        // before this tile's rows were stored (seen as rows without their delta, on a first, cold launch
-        // at 14,336 input features, where the shrink units end far apart).
+        // Agent-scope loads, which do not stop at this compute unit's vector cache: a 128-byte line of v
+        // can hold rows of two token tiles, and another unit of this work group may have fetched the line
+        // for its own tile before this tile's rows were stored (seen as rows without their delta, on a
+        // first, cold launch at 14,336 input features, where the shrink units end far apart).
         uint4 vh0 = ld_through_u16x8(sy.v_hi + off0), vl0 = ld_through_u16x8(sy.v_lo + off0);
         uint4 vh1 = zero, vl1 = zero;
         const bool ok1 = (i < e_ntok) && j_ok1;
