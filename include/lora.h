@@ -281,12 +281,15 @@ lora_status_t lora_segments_export(const lora_segments_t *seg, int32_t *perm, in
  * group), token count, first row (shrink) or first column (expand), row or column count,
  * k-slice (shrink) or 0}.  Groups of fewer than 32 tokens are cut into shrink units of <= 16 tokens x
  * 16 rank rows x one k-slice (in a whole-k plan of at most 256 units, the units of the most tokens
- * come as two units of 8 rank rows each, as many token counts as fit 256 units); token-heavy groups into shrink units of up to 32 tokens x all rank
+ * come as two units of 8 rank rows each, as many token counts as fit 256 units); token-heavy groups
+ * into shrink units of up to 32 tokens (64 for ranks 65..128, 16 above rank 128) x all rank
  * rows x all of k (listed after the others, k-slice 0; in a batch planned in k-slices with few such
  * units, two or four k-slices each) and into expand units of up to 64 tokens.
  * The order is the launch order: the decode shrink units of one group take places of one residue
  * mod 8 where the counts allow it (the launch's work groups go to the chip's 8 XCDs in turn, and the
- * group's rows of x then stay in one XCD's L2); the 64-token expand units (listed after the others)
+ * group's rows of x then stay in one XCD's L2); the token-heavy shrink units of one adapter likewise
+ * (its A^T then enters one L2), the eight lists filled to equal bytes and the shorter ones padded at
+ * their end with places that hold no work: segment -1, token count 0; the 64-token expand units (listed after the others)
  * of one group (its columns in 4 runs, 8 in a launch of few such units) come in rows of 8, each
  * column run with 8 / (column runs) consecutive token tiles, so that a column run's part of B^T is
  * fetched by that many XCDs instead of all 8.  Either output may be NULL. */
