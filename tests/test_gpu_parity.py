@@ -1045,6 +1045,32 @@ def test_random_cobatches_under_random_plan_settings(seed):
         L.lora_set_side_stream(True)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_decode_batches_at_long_k(seed):
+    """Seeded decode-sized co-batches (1..300 tokens over 4..64 adapters, uniform to very skewed
+    popularity) at 2,048 .. 20,480 input features, mostly through the one-launch form, every launch the
+    first on its pool: shrink units that end far apart, tiles of v that share cache lines."""
+    rng = np.random.default_rng(99_000 + seed)
+    in_f = 64 * int(rng.integers(32, 321))
+    out_f = 128 * int(rng.integers(1, 9))
+    n_ad = int(rng.integers(4, 65))
+    ranks = np.where(rng.random(n_ad) < 0.6, rng.choice([8, 16, 32, 64, 128], n_ad), rng.integers(1, 257, n_ad))
+    ntok = int(rng.integers(1, 301))
+    p = (np.arange(n_ad) + 1.0) ** -float(rng.choice([0.0, 1.1, 2.0]))
+    ta = rng.choice(n_ad, size=ntok, p=p / p.sum()).astype(np.int32)
+    ta[rng.random(ntok) < 0.03] = -1
+    b = _custom(f"long_k_decode_{seed}", in_f, out_f, ranks, ta, seed=seed)
+    single, limit = bool(rng.integers(0, 4)), int(rng.choice([1024, 1024, 0]))
+    print(f"[settings] decode_single_launch={single} whole_k_limit={limit}", flush=True)
+    L.lora_set_decode_single_launch(single)
+    L.lora_set_whole_k_limit(limit)
+    try:
+        _full_parity(b, y0_kind="small" if seed % 2 else "zero")
+    finally:
+        L.lora_set_decode_single_launch(True)
+        L.lora_set_whole_k_limit(1024)
+
+
 @pytest.mark.parametrize("seed", range(100, 112))
 def test_random_cobatches_through_every_entry_point(seed):
     """Seeded random co-batches under seeded plan settings, through the calls a server makes on one
