@@ -1378,8 +1378,9 @@ def test_plan_options_select_the_launch_form_per_object():
     dp.close()
 
 
-def _linear_case(b, w_sigma, seed=0, check_elements=True):
-    """lora_linear (base GEMM with the delta in its epilogue) against oracle.lora_linear on every row."""
+def _linear_case(b, w_sigma, seed=0, check_elements=True, rows=None):
+    """lora_linear (base GEMM with the delta in its epilogue) against oracle.lora_linear on every row
+    (or, at sizes where the fp64 layer takes minutes, on the rows given)."""
     print(f"[case] lora_linear {b.name} T={b.T} in={b.in_features} out={b.out_features} sigma_W={w_sigma}", flush=True)
     dp = G.DevicePool(b)
     rng = np.random.default_rng([seed, 991])
@@ -1397,7 +1398,11 @@ def _linear_case(b, w_sigma, seed=0, check_elements=True):
     L.lora_segments_check(seg)
     yg = wl.bf16_bits_to_f64(G.dev_to_bits(y))
     assert np.isfinite(yg).all(), "a row of y was not written"
-    y_ref = oracle.lora_linear(x_bits, W_bits, b.token_adapter, b.ranks, b.scales, dp.A, dp.B)
+    ta_all = b.token_adapter
+    if rows is not None:
+        rows = np.asarray(rows, dtype=np.int32)
+        yg = yg[rows]
+    y_ref = oracle.lora_linear(x_bits, W_bits, b.token_adapter, b.ranks, b.scales, dp.A, dp.B, rows=rows)
     nz = np.linalg.norm(y_ref, axis=1) > 0
     err = G.row_rel_l2(yg[nz], y_ref[nz])
     assert err.max() <= G.TOL, f"max per-row relative L2 error {err.max():.3e}"
@@ -1406,14 +1411,15 @@ def _linear_case(b, w_sigma, seed=0, check_elements=True):
     if check_elements:
         mag = oracle.lora_linear(G.abs_bits(x_bits), G.abs_bits(W_bits), b.token_adapter, b.ranks, b.scales,
                                  [None if m is None else G.abs_bits(m) for m in dp.A],
-                                 [None if m is None else G.abs_bits(m) for m in dp.B])
-        r8 = np.where(b.token_adapter >= 0, ((b.ranks.astype(np.int64) + 7) // 8 * 8)[np.maximum(b.token_adapter, 0)], 0)
+                                 [None if m is None else G.abs_bits(m) for m in dp.B], rows=rows)
+        ta_sel = ta_all if rows is None else ta_all[rows]
+        r8 = np.where(ta_sel >= 0, ((b.ranks.astype(np.int64) + 7) // 8 * 8)[np.maximum(ta_sel, 0)], 0)
         bound = G.elementwise_bound(y_ref, mag, b.in_features, r8)
         worst_el = float((np.abs(yg - y_ref) / np.maximum(bound, 1e-300)).max())
         assert worst_el <= 1.0, f"element error {worst_el:.2f} x the bound"
     L.lora_segments_destroy(seg)
     dp.close()
-    print(f"[ok] lora_linear {b.name}: {b.T} rows, max row rel-L2 {err.max():.3e}, max element error / bound {worst_el:.3f}",
+    print(f"[ok] lora_linear {b.name}: {len(yg)} rows, max row rel-L2 {err.max():.3e}, max element error / bound {worst_el:.3f}",
           flush=True)
 
 
@@ -1431,6 +1437,17 @@ def test_linear_with_delta_in_the_epilogue_small_shapes():
 
 def test_linear_on_a_token_heavy_batch_at_model_width():
     _linear_case(wl.cfg2_prefill(0, length_scale=0.12), 0.02, seed=3)
+
+
+def test_linear_at_full_size_on_sampled_rows():
+    """The shape bench.py --linear times (cfg2's 22,532 tokens, 4096 -> 4096): every group's first, middle
+    and last row, the padded tail of the row order and every 61st row against the fp64 layer."""
+    b = wl.cfg2_prefill(0)
+    rows = set(range(0, b.T, 61)) | {b.T - 1}
+    for a in b.used_adapters():
+        idx = np.nonzero(b.token_adapter == a)[0]
+        rows.update([int(idx[0]), int(idx[-1]), int(idx[len(idx) // 2])])
+    _linear_case(b, 0.02, seed=4, rows=sorted(rows))
 
 
 def test_plan_then_upload_and_the_measurement_hook():
