@@ -607,7 +607,7 @@ def run_secondary(args, torch, L, wl, dev, stream, hip) -> list:
     torch.cuda.empty_cache()
     # the adapted layer y = x W + delta in one GEMM (MFMA-bound: its roofline is the bf16 MFMA peak)
     sub = argparse.Namespace(**vars(args))
-    sub.workload, sub.layers, sub.steps, sub.warmup = "cfg2:0", 4, 5, 2
+    sub.workload, sub.layers, sub.steps, sub.warmup = "cfg2:0", 4, 10, 2
     lin = run_linear(sub, torch, L, wl, dev, stream, hip)
     res.append({"workload": lin["workload"], "tokens": lin["tokens"], "us_per_layer": lin["us_per_layer"],
                 "roofline": {"bound": "mfma", "achieved": lin["lora_linear_TFLOPs"], "peak": 2500.0, "unit": "TFLOP/s",
