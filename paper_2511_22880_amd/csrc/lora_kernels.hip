@@ -705,14 +705,15 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
     }
 }
 
-// Token-heavy units above rank 32: 16 * TB tokens, all rank rows, all of k or a slice of it.  Here the
+// Token-heavy units of ranks 65..128: 16 * TB tokens, all rank rows, all of k or a slice of it.  Here the
 // four wavefronts split the rank rows (JBW blocks of 16 each) instead of k: every 16-byte piece of
 // A^T is then loaded once per work group, straight into the registers of the one wavefront that owns
 // its rows, and x, which all four need, is staged once per work group in LDS (two buffers of 128 of k,
 // one barrier per pass).  With k split over the wavefronts as above, a unit of 32 tokens loads all of
 // A^T for 32 tokens' worth of x: at rank 128 four times the bytes of x, which made the compute units'
 // vector caches, not memory, the bound (uniform rank 128 on cfg2's routing: 78 us against 35 us at
-// rank 8).  No sums cross wavefronts: each stores the rows of v it owns.
+// rank 8; 62 us with this body).  No sums cross wavefronts: each stores the rows of v it owns.  (Up to
+// rank 64 the k-split body of 32 tokens stayed as fast or faster: 50 us at uniform rank 64 either way.)
 template <int JBW, int TB, int PD, int WP>
 static __device__ __forceinline__ void shrink_prefill_rowsplit(const Unit &u, const int32_t *__restrict__ perm,
                                                                const uint16_t *__restrict__ arena,
@@ -945,9 +946,9 @@ static __device__ __forceinline__ void dma16_to_lds(const uint4 *gptr, const uin
 }
 
 // Picks the body by the unit's rank rows.  ANY = false: the launch holds no unit above rank 64 and the
-// bodies fit 128 registers (four work groups per compute unit).  ANY = true: any rank; above rank 64
-// the accumulator tiles alone take 64 registers (two work groups per compute unit), units above rank
-// 128 hold 16 tokens.
+// bodies fit 128 registers (four work groups per compute unit).  ANY = true: any rank (two work groups
+// per compute unit); ranks 65..128 take the row-split body with 64 tokens, units above rank 128 hold
+// 16 tokens.
 template <bool ANY>
 static __device__ __forceinline__ void prefill_dispatch(const Unit &u, const int32_t *__restrict__ perm,
                                                         const uint16_t *__restrict__ arena,
