@@ -1882,25 +1882,25 @@ __global__ __launch_bounds__(256) void k_reduce_slices(const float *__restrict__
 //     row block, and y leaves in 16-byte pieces.  (A compute unit takes about 50 GB/s from the L2s
 //     whatever it runs; a 256 x 128 tile draws 48 KB per 64 of k and sat exactly at that rate, 720 us for
 //     cfg2's 22.5 k x 4096 x 4096; two strips per tile share the 32 KB of x.)
-//   * k goes in chunks of 32 (one MFMA k step) through a ring of four LDS buffers, everything copied by
-//     loads that write LDS directly, three chunks ahead (a chunk's 32 MFMAs per wavefront last about
-//     0.25 us, a trip to the L2 under load several times that), one barrier per chunk.  W comes packed in
-//     operand order (1 KB per wavefront operand, see launch_pack_weight), so a chunk of a strip is 8 KB of
-//     consecutive bytes.  x is gathered in operand order by the copy itself: the 64 lanes of one copy
-//     fetch the 16-byte pieces (row n, k quarter kq) of a 16-row block and land them in one 1 KB block,
-//     piece (kq, n) in slot (16 kq + n) XOR (2 kq) so that the 64 lanes of an operand read spread over
-//     all banks.  No request passes through registers the compiler tracks, so the waits are exact:
-//     every wavefront issues four copies per chunk and waits until at most eight are in flight.
+//   * Everything is copied by loads that write LDS directly, through a ring of five 32 KB slots (all of a
+//     compute unit's LDS), so no request passes through registers the compiler tracks and the waits are
+//     exact: every wavefront issues four copies per slot and waits until at most four are in flight.
+//     W comes packed in operand order (1 KB per wavefront operand, see launch_pack_weight), so a 32-wide
+//     k step of a strip is 8 KB of consecutive bytes.  x is gathered in operand order by the copy itself,
+//     in full cache lines: a copy takes 128 bytes (64 of k) of 8 rows (64 bytes of 16 rows took twice as
+//     long to arrive), so a slot holds, of x, one half of the tile's rows for a pair of k steps and, of
+//     W, one k step; pair j is computed from slots 2 j and 2 j + 1 while the copies of the next three
+//     slots are in flight, one barrier per pair.  Inside a 1 KB block of x, piece p of row r sits in
+//     slot 8 r + (p XOR r), so that the 8 lanes that read one piece of 8 rows meet 8 bank groups.
 //   * After the k loop every row block adds s (v_hi + v_lo) B_a for its adapter: ceil(r8 / 32) more k
 //     steps whose operands come straight from memory (v rows, and B^T in the pool's operand order,
 //     the very pieces the expand kernels read), accumulated apart and scaled once, as the expand does.
 // ------------------------------------------------------------------------------------------------
-constexpr int kLinK = 32;                                   // k per chunk
 constexpr int kLinThreads = 512;
-constexpr int kLinRing = 4;
-constexpr int kLinXBuf = (kLinTileM / 16) * 1024;       // bytes of x per chunk: 16 KB
-constexpr int kLinWBuf = 8 * 1024 * (kLinTileN / 128);  // bytes of W per chunk: 2 strips x 8 KB
-constexpr int kLinLds = kLinRing * (kLinXBuf + kLinWBuf);  // 128 KB: one work group per compute unit
+constexpr int kLinRing = 5;
+constexpr int kLinXBuf = (kLinTileM / 16) * 1024;       // bytes of x per slot: 128 rows x 128 bytes = 16 KB
+constexpr int kLinWBuf = 8 * 1024 * (kLinTileN / 128);  // bytes of W per slot: one k step of 2 strips, 8 KB each
+constexpr int kLinLds = kLinRing * (kLinXBuf + kLinWBuf);  // 160 KB, all of a compute unit's LDS: one work group per compute unit
 static_assert(kLinTileM == 256 && kLinTileN == 256, "the wavefront roles below are written for 256 x 256");
 
 __global__ __launch_bounds__(kLinThreads, 1) void k_linear_lora(
@@ -1932,32 +1932,39 @@ __global__ __launch_bounds__(kLinThreads, 1) void k_linear_lora(
     auto xbuf = [&](int which) __attribute__((always_inline)) { return lds + which * (kLinXBuf + kLinWBuf); };
     auto wbuf = [&](int which) __attribute__((always_inline)) { return lds + which * (kLinXBuf + kLinWBuf) + kLinXBuf; };
 
-    // copies of x: this wavefront fills the 16-row blocks 2 wave and 2 wave + 1; its lane s fills slot s of a
-    // block, which holds the piece (kq = s / 16, row n = (s mod 16) XOR (2 kq)) of the block
-    const uint16_t *xsrc[2];
+    // Copies of x.  A copy takes 8 rows x 128 bytes (64 of k): full cache lines; with 64 bytes of 16 rows per
+    // copy the same bytes took twice as long to arrive (0.57 against 0.33 us per 32 of k and compute unit
+    // in a kernel that only copies).  One ring slot ("half stage" h) therefore holds, of x, the 128 rows
+    // of row half h mod 2 for the 64 of k of pair h / 2, as 16 blocks of 1 KB; this wavefront fills blocks
+    // 2 wave and 2 wave + 1, its lane l the slot l of a block with piece (l mod 8) XOR (l / 8) of row l / 8,
+    // so that the 8 lanes that read one piece of 8 rows meet 8 different bank groups.
+    const uint16_t *xsrc[2][2];
     {
-        const int nn = n ^ ((2 * kq) & 7);
+        const int r = lane >> 3, piece = (lane & 7) ^ r;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int row = rows[m0 + 16 * (2 * wave + j) + nn];
-            xsrc[j] = x + (int64_t)(row < 0 ? 0 : row) * ldx + 8 * kq;
-        }
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int row = rows[m0 + 128 * hf + 8 * (2 * wave + j) + r];
+                xsrc[hf][j] = x + (int64_t)(row < 0 ? 0 : row) * ldx + 8 * piece;
+            }
     }
-    // copies of W: chunk c of a strip is 8 KB at wp + (strip * (in / 32) + c) * 4096 elements; the four
+    // copies of W: k step h of a strip is 8 KB at wp + (strip * (in / 32) + h) * 4096 elements; the four
     // wavefronts of a strip copy two of its eight 1 KB pieces each.  (The wavefronts of a strip the matrix
     // does not have copy strip 0's pieces into their unused half: every wavefront then has the same
     // number of copies in flight, which the waits below count.)
     const uint4 *wsrc = reinterpret_cast<const uint4 *>(wp + (size_t)(has_strip ? strip : 0) * (in / 32) * 4096);
     const int w_half = (wave >> 2) * (kLinWBuf / 2);
-    auto issue = [&](int c, int which) __attribute__((always_inline)) {
+    auto issue = [&](int h, int which) __attribute__((always_inline)) {
+        const int hf = h & 1;
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-            dma16_to_lds(reinterpret_cast<const uint4 *>(xsrc[j] + c * kLinK),
+            dma16_to_lds(reinterpret_cast<const uint4 *>((hf ? xsrc[1][j] : xsrc[0][j]) + (h >> 1) * 64),
                          reinterpret_cast<const uint4 *>(xbuf(which) + (2 * wave + j) * 1024));
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const int piece = 2 * rw + q;
-            dma16_to_lds(wsrc + (size_t)c * 512 + piece * 64 + lane,
+            dma16_to_lds(wsrc + (size_t)h * 512 + piece * 64 + lane,
                          reinterpret_cast<const uint4 *>(wbuf(which) + w_half + piece * 1024));
         }
     };
@@ -1968,41 +1975,52 @@ __global__ __launch_bounds__(kLinThreads, 1) void k_linear_lora(
 #pragma unroll
         for (int b = 0; b < 8; ++b) acc[i][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int nk = in / kLinK;
+    // Pair j (64 of k) is computed from half stages 2 j and 2 j + 1; while it is, the copies of 2 j + 2 ..
+    // 2 j + 4 are in flight (a ring of five slots, all of the LDS).  One barrier per pair.
+    const int nh = in / 32;   // half stages; in is a multiple of 64, so nh is even
+    static_assert(kLinRing == 5, "the schedule below is written for five slots");
 #pragma unroll
-    for (int c = 0; c < kLinRing - 1; ++c)
-        if (c < nk) issue(c, c);
-    for (int c = 0; c < nk; ++c) {
-        // chunk c has landed when at most the copies of the chunks after it are in flight: 4 per chunk,
-        // up to two chunks (fewer at the end of k)
+    for (int h = 0; h < 3; ++h)
+        if (h < nh) issue(h, h);
+    // this wavefront's rows 64 rw .. 64 rw + 63 lie in row half rw / 2, blocks 8 (rw mod 2) .. + 7 of its 16
+    const int x_half = rw >> 1;
+    const int x_blk0 = 8 * (rw & 1);
+    for (int j = 0; 2 * j < nh; ++j) {
+        // half stages 2 j and 2 j + 1 have landed when at most the copies of 2 j + 2 are in flight (4 per half
+        // stage and wavefront)
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        const int after = min(nk - 1 - c, kLinRing - 2);
-        if (after >= 2)
-            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else if (after == 1)
+        if (2 * j + 2 < nh)
             asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         else
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        // one barrier per chunk: everyone's copies of chunk c have landed, and everyone has left the buffer
-        // of chunk c - 1, which the copies of chunk c + 3 now fill
+        // everyone's copies have landed, and everyone has left the slots of pair j - 1, which the copies of
+        // half stages 2 j + 3 and 2 j + 4 now fill
         __syncthreads();
-        if (c + kLinRing - 1 < nk) issue(c + kLinRing - 1, (c + kLinRing - 1) % kLinRing);
+        if (2 * j + 3 < nh) issue(2 * j + 3, (2 * j + 3) % kLinRing);
+        if (2 * j + 4 < nh) issue(2 * j + 4, (2 * j + 4) % kLinRing);
         if (has_strip) {
-            const char *xcur = xbuf(c % kLinRing);
-            const char *wcur = wbuf(c % kLinRing) + w_half;
-            bf16x8 xo[4], wo[8];
+            const char *xcur = xbuf((2 * j + x_half) % kLinRing);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                xo[i] = as_bf16x8(*reinterpret_cast<const uint4 *>(xcur + ((4 * rw + i) * 64 + ((kq * 16 + n) ^ ((2 * kq) & 7))) * 16));
+            for (int ks = 0; ks < 2; ++ks) {
+                const char *wcur = wbuf((2 * j + ks) % kLinRing) + w_half;
+                bf16x8 xo[4], wo[8];
 #pragma unroll
-            for (int b = 0; b < 8; ++b)
-                wo[b] = as_bf16x8(*reinterpret_cast<const uint4 *>(wcur + (b * 64 + lane) * 16));
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < 4; ++i) {
+                    // row 16 i + n of this wavefront's rows: block x_blk0 + 2 i + n / 8, row n mod 8 of it, piece 4 ks + kq
+                    const int r = n & 7, p = 4 * ks + kq;
+                    xo[i] = as_bf16x8(*reinterpret_cast<const uint4 *>(
+                        xcur + (x_blk0 + 2 * i + (n >> 3)) * 1024 + (r * 8 + (p ^ r)) * 16));
+                }
 #pragma unroll
                 for (int b = 0; b < 8; ++b)
-                    acc[i][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xo[i], wo[b], acc[i][b], 0, 0, 0);
+                    wo[b] = as_bf16x8(*reinterpret_cast<const uint4 *>(wcur + (b * 64 + lane) * 16));
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int b = 0; b < 8; ++b)
+                        acc[i][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xo[i], wo[b], acc[i][b], 0, 0, 0);
+            }
         }
     }
     if (!has_strip) return;
@@ -2264,7 +2282,7 @@ hipError_t launch_linear_lora(const int32_t *rows, const LinBlock *blocks, int m
                               hipStream_t stream)
 {
     if (m_pad <= 0) return hipSuccess;
-    if (m_pad % kLinTileM || in % kLinK || out % 128 || out <= 0 || in < kLinK) return hipErrorInvalidValue;
+    if (m_pad % kLinTileM || in % 64 || out % 128 || out <= 0 || in < 64) return hipErrorInvalidValue;
     const int m_tiles = m_pad / kLinTileM, n_tiles = (out + kLinTileN - 1) / kLinTileN;
     const int mt_per_xcd = (m_tiles + 7) / 8;
     // per XCD: groups of 32 work groups = 8 row tiles x 4 column tiles (see the kernel)
