@@ -1926,7 +1926,7 @@ try {
     hipStream_t s = (hipStream_t)stream;
     const lora::LaunchCtx c = ctx_for(pool, sg, kShrink), cp = ctx_for(pool, sg, kPrefill);
     if (sg->wide) {
-        HIP_TRY(lora::launch_shrink_wide(c, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, v, nullptr,
+        HIP_TRY(lora::launch_shrink_wide(c, c.n_units > g_compute_units, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, v, nullptr,
                                          nullptr, s));
         HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, nullptr, nullptr, v, 1, 0, nullptr,
                                             nullptr, s));
@@ -2132,7 +2132,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
         HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, sa.v_hi, sa.v_lo, nullptr,
                                             nsl, stride, parts, &sa, s));
         if (sg->wide)
-            HIP_TRY(lora::launch_shrink_wide(cs, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, nullptr,
+            HIP_TRY(lora::launch_shrink_wide(cs, cs.n_units > g_compute_units, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, nullptr,
                                              sa.v_hi, sa.v_lo, sd));
         else
             HIP_TRY(lora::launch_shrink(cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride, &sa, sd));
@@ -2209,7 +2209,7 @@ try {
             HIP_TRY(lora::launch_shrink_prefill(cp, sg->n_prefill_hi, (const uint16_t *)x, ldx, sa.v_hi, sa.v_lo, nullptr, nsl,
                                                 stride, parts, &sa, s));
             if (sg->wide)
-                HIP_TRY(lora::launch_shrink_wide(cs, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, nullptr,
+                HIP_TRY(lora::launch_shrink_wide(cs, cs.n_units > g_compute_units, (const uint16_t *)x, ldx, sg->wide_slice_len, sg->wide_slices, nullptr,
                                                  sa.v_hi, sa.v_lo, s));
             else
                 HIP_TRY(lora::launch_shrink(cs, (const uint16_t *)x, ldx, sg->k_slice_len, parts, nsl, stride, &sa, s));

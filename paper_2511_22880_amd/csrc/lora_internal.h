@@ -93,9 +93,12 @@ hipError_t launch_shrink(const LaunchCtx &c, const uint16_t *x, int64_t ldx, int
 
 // Whole-k shrink units: work groups of 16 wavefronts, four per k-slice of k_slice_len (n_slices <= 4
 // slices cover in_features); v written complete, either as fp32 into v_f32 or (v_hi != NULL) as bf16
-// hi + lo, bitwise what the k-slice units of launch_shrink give.
-hipError_t launch_shrink_wide(const LaunchCtx &c, const uint16_t *x, int64_t ldx, int k_slice_len, int n_slices,
-                              float *v_f32, uint16_t *v_hi, uint16_t *v_lo, hipStream_t stream);
+// hi + lo, bitwise what the k-slice units of launch_shrink give.  more_than_one_round: the launch has more
+// units than the chip has compute units; it then runs as work groups of 8 wavefronts, two per compute unit
+// (same bits).
+hipError_t launch_shrink_wide(const LaunchCtx &c, bool more_than_one_round, const uint16_t *x, int64_t ldx,
+                              int k_slice_len, int n_slices, float *v_f32, uint16_t *v_hi, uint16_t *v_lo,
+                              hipStream_t stream);
 
 // Without `sync`: v_in holds n_slices fp32 partial sums slice_stride floats apart (n_slices = 1: v
 // itself).  With `sync`: v comes from sync->v_hi / v_lo (written by a shrink launch of the same epoch).

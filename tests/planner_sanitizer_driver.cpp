@@ -15,7 +15,7 @@
 #include <vector>
 namespace lora {
 hipError_t launch_shrink(const LaunchCtx &, const uint16_t *, int64_t, int, float *, int, int64_t, const SyncArgs *, hipStream_t) { return hipSuccess; }
-hipError_t launch_shrink_wide(const LaunchCtx &, const uint16_t *, int64_t, int, int, float *, uint16_t *, uint16_t *, hipStream_t) { return hipSuccess; }
+hipError_t launch_shrink_wide(const LaunchCtx &, bool, const uint16_t *, int64_t, int, int, float *, uint16_t *, uint16_t *, hipStream_t) { return hipSuccess; }
 hipError_t launch_expand(const LaunchCtx &, bool, const float *, int, int64_t, uint16_t *, int64_t, const SyncArgs *, hipStream_t) { return hipSuccess; }
 hipError_t launch_shrink_prefill(const LaunchCtx &, int, const uint16_t *, int64_t, uint16_t *, uint16_t *, float *, int, int64_t, float *, const SyncArgs *, hipStream_t) { return hipSuccess; }
 hipError_t launch_shrink_mixed(const LaunchCtx &, int, const LaunchCtx &, const uint16_t *, int64_t, int, float *, int, int64_t, const SyncArgs *, hipStream_t) { return hipSuccess; }

@@ -155,8 +155,12 @@ def test_one_launch_decode_apply_matches_two_launches_bitwise():
 def test_whole_k_plan_matches_k_slice_plan_bitwise():
     """The two plans of the decode shrink (whole-k units of 16 wavefronts; k-slice units added up
     through counters) do the same arithmetic in the same order: same bits in y and in v."""
-    for b in (wl.small_mixed(seed=5, in_features=2048), wl.cfg1_decode(in_features=4096, out_features=256, n_tokens=96),
-              wl.cfg1_decode(in_features=3200, out_features=128, n_tokens=40)):
+    # the last case has more whole-k units than the chip has compute units: those launches run as work
+    # groups of 8 wavefronts, two per compute unit, each wavefront in two of the sixteen roles
+    for b, more_than_a_round in ((wl.small_mixed(seed=5, in_features=2048), False),
+                                 (wl.cfg1_decode(in_features=4096, out_features=256, n_tokens=96), False),
+                                 (wl.cfg1_decode(in_features=3200, out_features=128, n_tokens=40), False),
+                                 (wl.cfg1_decode(in_features=6144, out_features=128, n_tokens=512), True)):
         print(f"[case] plans on {b.name} T={b.T} in={b.in_features}", flush=True)
         dp = G.DevicePool(b)
         x_bits, y0_bits = b.x_bits(), b.y0_bits("small")
@@ -168,6 +172,8 @@ def test_whole_k_plan_matches_k_slice_plan_bitwise():
                 seg = L.lora_segments_build(dp.pool, b.token_adapter)
                 info = L.lora_segments_info(seg)
                 assert (info["n_k_slices"] == 1) == (limit == 1024)
+                if limit == 1024:
+                    assert (info["n_shrink_units"] > 256) == more_than_a_round, info["n_shrink_units"]
                 v = torch.zeros(max(info["v_floats"], 1), dtype=torch.float32, device="cuda")
                 ws = torch.empty(max(L.lora_workspace_bytes(dp.pool, seg), 256), dtype=torch.uint8, device="cuda")
                 L.lora_shrink(dp.pool, seg, G.bits_to_dev(x_bits), v, ws)
