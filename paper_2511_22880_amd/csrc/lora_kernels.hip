@@ -325,6 +325,26 @@ static __device__ __forceinline__ void shrink_body(const Unit &u, const uint16_t
     }
 }
 
+// A unit record read with one 128-byte request per wavefront: word w of the record in lane w (and w + 32).
+// Its fields are then taken from that register (unit_word), so that a unit's operand loads are one trip to
+// memory behind the start of its work group, not two (the token list after the token count).  Used by the
+// one-launch decode kernel for its shrink units, every one of which is on the launch's critical path (15.4 ->
+// 15.0 us on a 256-token batch; for its expand units' records, which are read while the shrink units run,
+// 15.0 -> 15.2 us); in the launches of several rounds (k_shrink_wide, k_expand) it changed nothing or
+// cost a little (28.9 -> 29.3 us for 2,560 expand units), so they read the record field by field.
+static_assert(offsetof(Unit, w_off) == 0 && offsetof(Unit, v_off) == 8 && offsetof(Unit, r8) == 16 &&
+                  offsetof(Unit, ntok) == 20 && offsetof(Unit, p0) == 24 && offsetof(Unit, pn) == 28 &&
+                  offsetof(Unit, sync_idx) == 48 && offsetof(Unit, tok) == 64,
+              "the words of a unit record as unit_word's callers number them");
+static __device__ __forceinline__ uint32_t load_unit_words(const Unit *u)
+{
+    return reinterpret_cast<const uint32_t *>(u)[threadIdx.x & 31];
+}
+static __device__ __forceinline__ uint32_t unit_word(uint32_t rec, int w)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)rec, w);
+}
+
 // ------------------------------------------------------------------------------------------------
 // shrink, whole-k units: one unit = (group, <=16 tokens, 16 rank rows or one half of them, all of k), one work group of
 // 16 wavefronts.  Used when the batch's units fit the chip in one round: each compute unit then
@@ -1516,6 +1536,8 @@ __global__ __launch_bounds__(kWideThreads) void k_decode_fused(
     f32x4(*red)[64] = reinterpret_cast<f32x4(*)[64]>(lds + kWideWaves * kWideSlab);
     volatile unsigned *qflag = reinterpret_cast<volatile unsigned *>(lds + kWideLds) + slice;
     if (tid < 4) reinterpret_cast<volatile unsigned *>(lds + kWideLds)[tid] = 0u;
+    // the shrink unit's record, one request (load_unit_words)
+    const uint32_t s_rec = load_unit_words(s_units + (bid < n_s ? bid : 0));
     // Which XCD do the work groups of each residue run on?  The hardware deals the work groups of a
     // launch to the XCDs in turn, but not every launch starts at the same XCD: all that the hand-over
     // needs is that work groups of one residue mod 8 share an XCD, i.e. that every work group on an XCD
@@ -1561,19 +1583,25 @@ __global__ __launch_bounds__(kWideThreads) void k_decode_fused(
 #endif
 
     // ---- the shrink unit ----
-    const Unit &u = s_units[bid < n_s ? bid : 0];
-    const bool s_has = bid < n_s && u.ntok > 0;
+    auto s_word = [&](int w) __attribute__((always_inline)) { return unit_word(s_rec, w); };
+    const int ntok = (int)s_word(5), pn = (int)s_word(7);
+    const bool s_has = bid < n_s && ntok > 0;
     if (s_has) {
-        const int ntok = u.ntok, pn = u.pn;
+        const uint64_t u_w_off = s_word(0) | ((uint64_t)s_word(1) << 32);
+        const int64_t u_v_off = (int64_t)(s_word(2) | ((uint64_t)s_word(3) << 32));
+        const int u_r8 = (int)s_word(4), u_p0 = (int)s_word(6), u_sync_idx = (int)s_word(12);
         const bool w_ok = i < pn;
-        const int blk_rows = min(kRowTile, u.r8 - (u.p0 & ~(kRowTile - 1)));
-        const int row0 = u.p0 & (kRowTile - 1);
-        const uint16_t *wrow = arena + u.w_off + (kq * blk_rows + row0 + (w_ok ? i : 0)) * 8;
+        const int blk_rows = min(kRowTile, u_r8 - (u_p0 & ~(kRowTile - 1)));
+        const int row0 = u_p0 & (kRowTile - 1);
+        const uint16_t *wrow = arena + u_w_off + (kq * blk_rows + row0 + (w_ok ? i : 0)) * 8;
         const int half = lane >> 5;
         const int s_chunk = lane & 31;
         const uint16_t *xrow[kTokTile / 2];
 #pragma unroll
-        for (int t = 0; t < kTokTile / 2; ++t) xrow[t] = x + (int64_t)(half ? u.tok[2 * t + 1] : u.tok[2 * t]) * ldx;
+        for (int t = 0; t < kTokTile / 2; ++t) {
+            const int tok_even = (int)s_word(16 + 2 * t), tok_odd = (int)s_word(17 + 2 * t);
+            xrow[t] = x + (int64_t)(half ? tok_odd : tok_even) * ldx;
+        }
         const int kslice_beg = slice * k_slice_len;
         int kslice_end = kslice_beg + k_slice_len;
         if (kslice_end > in) kslice_end = in;
@@ -1631,7 +1659,7 @@ __global__ __launch_bounds__(kWideThreads) void k_decode_fused(
                 }
             }
             if (i < ntok && 4 * kq < pn) {
-                const int64_t off = u.v_off + (int64_t)i * u.r8 + 4 * kq;
+                const int64_t off = u_v_off + (int64_t)i * u_r8 + 4 * kq;
                 uint2 h, l;
                 h.x = pack_bf16_rne(t[0], t[1]);
                 h.y = pack_bf16_rne(t[2], t[3]);
@@ -1648,7 +1676,7 @@ __global__ __launch_bounds__(kWideThreads) void k_decode_fused(
         LORA_CLOCK(7);
         if (wave == 0) {
             stores_done();  // the stores have reached the L2
-            if (lane == 0) l2_counter_add(sy.ready + u.sync_idx, 1u);
+            if (lane == 0) l2_counter_add(sy.ready + u_sync_idx, 1u);
             LORA_CLOCK(2);
         }
     } else {
