@@ -463,6 +463,7 @@ def run_wg_clocks(args, torch, L, wl, dev, stream) -> int:
     ex = L.lora_segments_export(seg)
     rank_of_seg = b0.ranks[ex["seg_adapter"]]
     rows = []
+    heavy_seg = np.zeros(len(rank_of_seg), dtype=bool)
     if info["single_launch"]:
         lu = L.lora_segments_export_launch_units(seg)
         n = info["launch_work_groups"]
@@ -471,15 +472,31 @@ def run_wg_clocks(args, torch, L, wl, dev, stream) -> int:
     else:
         units = L.lora_segments_export_units(seg)
         ns, ne = len(units["shrink"]), len(units["expand"])
+        # The export holds the decode-sized groups' list first and the token-heavy groups' list behind it; a
+        # launch that holds both runs the token-heavy list first.  (Token-heavy: 32 tokens or more in a batch
+        # of 1024 or more, the planner's default; such a group's expand units are in the second list up to
+        # rank 128; places that only pad the token-heavy shrink list have segment -1.)
+        seg_ntok = np.diff(ex["seg_start"])
+        heavy_seg = (seg_ntok >= 32) & (int(seg_ntok.sum()) >= 1024)
+
+        def launch_order(ulist, second):
+            n_first = next((k for k, u in enumerate(ulist) if second(u)), len(ulist))
+            return np.concatenate([ulist[n_first:], ulist[:n_first]]) if 0 < n_first < len(ulist) else ulist
+
+        shrink_list = launch_order(units["shrink"], lambda u: u[0] < 0 or heavy_seg[u[0]])
+        expand_list = launch_order(units["expand"], lambda u: heavy_seg[u[0]] and rank_of_seg[u[0]] <= 128)
         t0 = h[:ns, 0][h[:ns, 0] > 0].min()
-        lists = [("shrink launch", units["shrink"], h[:ns]), ("expand launch", units["expand"], h[E_BASE:E_BASE + ne])]
+        lists = [("shrink launch", shrink_list, h[:ns]), ("expand launch", expand_list, h[E_BASE:E_BASE + ne])]
     for name, ulist, clk in lists:
-        for r in sorted(set(int(v) for v in rank_of_seg)):
-            sel = np.array([u[2] > 0 and rank_of_seg[u[0]] == r for u in ulist]) & (clk[:, 0] > 0) & (clk[:, 4] > 0)
+        # classes: the adapter's rank, and whether the unit's group is token-heavy
+        for r, heavy in [(r, h) for r in sorted(set(int(v) for v in rank_of_seg)) for h in (False, True)]:
+            sel = np.array([u[2] > 0 and rank_of_seg[u[0]] == r and bool(heavy_seg[u[0]]) == heavy for u in ulist]) & \
+                (clk[:, 0] > 0) & (clk[:, 4] > 0)
             if not sel.any():
                 continue
             start, end = (clk[sel, 0] - t0) * 0.01, (clk[sel, 4] - t0) * 0.01
-            rows.append({"launch": name, "rank": r, "work_groups": int(sel.sum()), "first_start_us": float(start.min()),
+            rows.append({"launch": name, "rank": r, "token_heavy_units": heavy, "work_groups": int(sel.sum()),
+                         "first_start_us": float(start.min()),
                          "median_start_us": float(np.median(start)), "median_duration_us": float(np.median(end - start)),
                          "max_duration_us": float((end - start).max()), "duration_deciles_us": [round(float(v), 1) for v in
                          np.percentile(end - start, [10, 30, 50, 70, 90])], "last_end_us": float(end.max())})

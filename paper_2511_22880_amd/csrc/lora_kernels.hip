@@ -1893,11 +1893,13 @@ __global__ __launch_bounds__(kThreads, ANY ? 2 : 4) void k_shrink_mixed(
     __shared__ __attribute__((aligned(16))) char lds[kMixedShrinkLds];
     const int b = blockIdx.x;
     if (b < n_heavy && heavy_units[b].ntok <= 0) return;  // a place that only pads an XCD's list of token-heavy units
+    LORA_CLOCK(0);
     if (b < n_heavy)
         prefill_dispatch<ANY>(heavy_units[b], perm, arena, x, ldx, in, sy.v_hi, sy.v_lo, nullptr, n_slices,
                               slice_stride, lds, parts, sy);
     else
         shrink_body(units[b - n_heavy], arena, x, ldx, in, k_slice_len, parts, n_slices, slice_stride, lds, sy);
+    LORA_CLOCK(4);
 }
 
 __global__ __launch_bounds__(kThreads, 2) void k_expand_mixed(const Unit *__restrict__ big_units, int n_big,
@@ -1910,10 +1912,12 @@ __global__ __launch_bounds__(kThreads, 2) void k_expand_mixed(const Unit *__rest
 {
     __shared__ __attribute__((aligned(16))) char lds[kMixedExpandLds];
     const int b = blockIdx.x;
+    LORA_CLOCK_E(0);
     if (b < n_big)
         expand_dispatch<true, false>(big_units[b], perm, arena, parts, n_slices, slice_stride, y, ldy, lds, sy);
     else
         expand_dispatch<false, false>(units[b - n_big], perm, arena, parts, n_slices, slice_stride, y, ldy, lds, sy);
+    LORA_CLOCK_E(4);
 }
 
 __global__ __launch_bounds__(256) void k_reduce_slices(const float *__restrict__ parts, int n_slices,
