@@ -550,7 +550,7 @@ static __device__ __forceinline__ void store_v4(f32x4 f, int64_t at, uint16_t *_
     }
 }
 
-template <int JB, int TB, int WD>
+template <int JB, int TB, int WD, int XD = 1>
 static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, const int32_t *__restrict__ perm,
                                                              const uint16_t *__restrict__ arena,
                                                              const uint16_t *__restrict__ x, int64_t ldx, int in,
@@ -587,13 +587,18 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
     const uint4 zero = {0u, 0u, 0u, 0u};
     int woff[JB];  // element offset of this lane's 16-byte piece in k step 0 of row block jb
     int wh[JB];    // rows in block jb (16, or 8 for the last block of a padded rank that is 8 mod 16)
+    // Up to four row blocks the loop below has no branch: a block beyond the padded rank (ranks 33..48 of
+    // the bucket up to 64) is worked as a copy of the last block that exists, and its sums are never stored.
+    constexpr bool kNoBranch = JB <= 4;
+    const int nblk = (r8 + 15) >> 4;
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) {
-        const int h = min(16, r8 - 16 * jb);
+        const int jbc = kNoBranch ? min(jb, nblk - 1) : jb;
+        const int h = min(16, r8 - 16 * jbc);
         wh[jb] = h > 0 ? h : 16;
         // lanes n >= 8 of an 8-row block read the piece of row n - 8: they only reach accumulator rows
         // beyond the padded rank, which are never stored
-        woff[jb] = 16 * jb * in + (kq * wh[jb] + (n & (wh[jb] - 1))) * 8;
+        woff[jb] = 16 * jbc * in + (kq * wh[jb] + (n & (wh[jb] - 1))) * 8;
     }
 
     f32x4 acc[JB][TB];
@@ -621,6 +626,96 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
             if (4 * t < ntok) xs[t] = ld16_stream(xrow[t] + kx);
     };
 
+    if constexpr (kNoBranch) {
+        // Loads without conditions (rows of tokens beyond ntok are the last token's, see xrow; a chunk beyond
+        // the row is fetched from the row's last chunk and a k step beyond the row from its last step; none
+        // of them enters an MFMA whose sums are stored): with a branch around a load the compiler no
+        // longer counts the loads in flight and waits for all of them at every wait, the x of the passes
+        // ahead included, so that every pass of 128 of k took a whole trip to memory.
+        const int npass = kend > kbeg ? (kend - kbeg + kPfPassK - 1) / kPfPassK : 0;
+        const int nfull = kend > kbeg ? (kend - kbeg) / kPfPassK : 0;
+        auto x_all = [&](int k0, uint4(&xq)[NL]) __attribute__((always_inline)) {
+            const int kx = min(k0 + 8 * n, in - 8);
+#pragma unroll
+            for (int t = 0; t < NL; ++t) xq[t] = ld16_stream(xrow[t] + kx);
+        };
+        auto w_step = [&](int k, int jb) __attribute__((always_inline)) {
+            return ld16(wbase + woff[jb] + (int64_t)min(k, in - 32) * wh[jb]);
+        };
+        auto stage = [&](const uint4(&xq)[NL]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int t = 0; t < NL; ++t) *reinterpret_cast<uint4 *>(&slab[4 * t + kq][8 * n]) = xq[t];
+        };
+        auto k_step = [&](int d, const uint4(&wd)[JB]) __attribute__((always_inline)) {
+            bf16x8 xo[TB];
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb)
+                xo[tb] = as_bf16x8(*reinterpret_cast<const uint4 *>(&slab[16 * tb + n][32 * d + 8 * kq]));
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) {
+                const bf16x8 ww = as_bf16x8(wd[jb]);
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb)
+                    acc[jb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ww, xo[tb], acc[jb][tb], 0, 0, 0);
+            }
+        };
+        auto wave_sync = [&]() __attribute__((always_inline)) {
+            // the region is private to this wavefront and LDS operations of a wavefront complete in order
+            __atomic_signal_fence(__ATOMIC_SEQ_CST);
+            __builtin_amdgcn_wave_barrier();
+            __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        };
+        // XD passes of x and WD k steps of A^T are in flight per wavefront (registers)
+        uint4 xq[XD][NL], w[WD][JB];
+#pragma unroll
+        for (int q = 0; q < XD; ++q) x_all(kbeg + min(q, max(npass - 1, 0)) * kPfPassK, xq[q]);
+#pragma unroll
+        for (int d = 0; d < WD; ++d)
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) w[d][jb] = w_step(kbeg + 32 * d, jb);
+        int i0 = 0;
+        for (; i0 + 2 * XD <= nfull; i0 += XD) {
+#pragma unroll
+            for (int q = 0; q < XD; ++q) {
+                const int k0 = kbeg + (i0 + q) * kPfPassK;
+                stage(xq[q]);
+                x_all(k0 + XD * kPfPassK, xq[q]);
+                wave_sync();
+#pragma unroll
+                for (int d = 0; d < kPfPassK / 32; ++d) {
+                    k_step(d, w[d % WD]);
+#pragma unroll
+                    for (int jb = 0; jb < JB; ++jb) w[d % WD][jb] = w_step(k0 + 32 * (d + WD), jb);
+                }
+                wave_sync();
+            }
+        }
+        // the last passes (fewer than 2 XD full ones and maybe a shorter one): the same under conditions
+        for (; i0 < npass; i0 += XD) {
+#pragma unroll
+        for (int q = 0; q < XD; ++q) {
+            const int i = i0 + q;
+            if (i < npass) {
+                const int k0 = kbeg + i * kPfPassK;
+                stage(xq[q]);
+                if (i + XD < npass) x_all(k0 + XD * kPfPassK, xq[q]);
+                wave_sync();
+#pragma unroll
+                for (int d = 0; d < kPfPassK / 32; ++d) {
+                    const int k = k0 + 32 * d;
+                    if (k < kend) {
+                        k_step(d, w[d % WD]);
+                        if (k + 32 * WD < kend) {
+#pragma unroll
+                            for (int jb = 0; jb < JB; ++jb) w[d % WD][jb] = w_step(k + 32 * WD, jb);
+                        }
+                    }
+                }
+                wave_sync();
+            }
+        }
+        }
+    } else {
     uint4 xs[NL], w[WD][JB];
     if (kbeg < kend) x_pass(kbeg, xs);
 #pragma unroll
@@ -665,6 +760,7 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
         __builtin_amdgcn_wave_barrier();
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    }
     }
 
     // sum the four k-quarters: (wave 2 -> 0, wave 3 -> 1), then (wave 1 -> 0)
@@ -1007,14 +1103,16 @@ static __device__ __forceinline__ void prefill_dispatch(const Unit &u, const int
                                                         float *__restrict__ parts, const Sync &sy)
 {
     const int r8 = u.r8;
+    // (three in flight for ranks up to 32: cfg2 4096 -> 4096 shrink 48.3 against 43.9 us)
+    constexpr int XD = ANY ? 2 : 1;  // passes of x in flight per wavefront: two where two work groups share a compute unit
     if (r8 <= 16)
-        shrink_prefill_ksplit<1, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
+        shrink_prefill_ksplit<1, 2, 4, XD>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
     else if (r8 <= 32)
-        shrink_prefill_ksplit<2, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
+        shrink_prefill_ksplit<2, 2, 4, XD>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
     else if (!ANY)  // the launcher takes this form only for batches whose token-heavy units are all up to rank 64
         shrink_prefill_ksplit<4, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
     else if (r8 <= 64)
-        shrink_prefill_ksplit<4, 2, 4>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
+        shrink_prefill_ksplit<4, 2, 4, XD>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
     else if constexpr (ANY) {
         if (r8 <= 128)
             shrink_prefill_rowsplit<2, 4, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
