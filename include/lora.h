@@ -282,7 +282,7 @@ lora_status_t lora_segments_export(const lora_segments_t *seg, int32_t *perm, in
  * k-slice (shrink) or 0}.  Groups of fewer than 32 tokens are cut into shrink units of <= 16 tokens x
  * 16 rank rows x one k-slice (in a whole-k plan of at most 256 units, the units of the most tokens
  * come as two units of 8 rank rows each, as many token counts as fit 256 units); token-heavy groups
- * into shrink units of up to 32 tokens (64 for ranks 65..128, 16 above rank 128) x all rank
+ * into shrink units of up to 32 tokens (64 for ranks 65..192) x all rank
  * rows x all of k (listed after the others, k-slice 0; in a batch planned in k-slices with few such
  * units, two or four k-slices each) and into expand units of up to 64 tokens.
  * The order is the launch order: the decode shrink units of one group take places of one residue

@@ -108,7 +108,7 @@ struct lora_segments {
     size_t off_perm, off_shrink, off_prefill, off_expand, off_expand_big, off_fused_shrink, off_fused_expand, off_sync,
         table_bytes;
     bool has_big_units;     // some unit holds more than 16 tokens (token-heavy groups)
-    bool heavy_small_expand;  // a token-heavy group above rank 128: shrunk by token-heavy units, expanded by 16-token units
+    bool heavy_small_expand;  // a token-heavy group above kBigExpandMaxRank (none, as the pool's ranks stand): shrunk by token-heavy units, expanded by 16-token units
     bool wide;              // decode shrink units span all of k (work groups of 16 wavefronts, no partial sums)
     int wide_slices, wide_slice_len;  // the k-slices such a work group's wavefronts divide k into
     int n_prefill_hi;       // how many of prefill_units are above rank 64
@@ -587,8 +587,12 @@ static const int kWholeKMin = 64;  // below this, k-slices are what spreads the 
 static const int kWholeKMaxIn = 18432;
 // Tokens of a token-heavy shrink unit: up to rank 64 the wavefronts split k and hold 32 tokens; above,
 // they split the rank rows and share 64 tokens of x through LDS (A^T is then loaded once per 64
-// tokens); above rank 128, 16 tokens with k split.
-static int heavy_tile(int r8) { return r8 <= 64 ? 32 : (r8 <= 128 ? 64 : 16); }
+// tokens); above rank 192, 32 tokens (the accumulators of 64 tokens x 256 rank rows do not fit the registers).
+static int heavy_tile(int r8) { return r8 <= 64 || r8 > 192 ? 32 : 64; }
+// token-heavy groups take 64-token expand units up to this padded rank (a strip's tile of B^T, 128 columns x
+// rank, must fit the kernel's 64 KiB of LDS): every rank the pool holds
+static const int kBigExpandMaxRank = 256;
+static_assert(kBigExpandMaxRank >= LORA_MAX_RANK_PADDED, "the 16-token expand units of token-heavy groups are gone");
 // A token-heavy shrink unit is one walk through k (a wavefront takes a quarter of k in passes of 128, one
 // trip to memory each), and a launch of few such units lasts as long as one unit's walk (cfg3's routing
 // scaled to 1.5 k .. 9.5 k tokens: 32-37 us at 4096 input features, 99-116 us at 14336, whatever the
@@ -1065,18 +1069,18 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
     // us at 14336; at 4.9 k tokens and beyond 8 runs are level or lose).
     int64_t big_tiles = 0;
     for (const SegRec &r : sg->segs)
-        if (r.ntok >= heavy_min_tokens && n_active >= heavy_min_batch && r.r8 <= 128) big_tiles += (r.ntok + 63) / 64;
+        if (r.ntok >= heavy_min_tokens && n_active >= heavy_min_batch && r.r8 <= kBigExpandMaxRank) big_tiles += (r.ntok + 63) / 64;
     const int big_runs = big_tiles * 8 * n_projections <= opt_big_runs_max_units(sg) ? 8 : 4;
     for (int32_t si : order) {
         const SegRec &r = sg->segs[si];
         const bool token_heavy = r.ntok >= heavy_min_tokens && n_active >= heavy_min_batch;
         const int sync_n = ((r.r8 + lora::kRowTile - 1) / lora::kRowTile) * sg->n_k_slices;
         if (token_heavy) {
-            // shrink: tiles of 32 tokens (64 above rank 64, 16 above rank 128), all rank rows, all of k or
+            // shrink: tiles of 32 tokens (64 for ranks 65..192), all rank rows, all of k or
             // (heavy_k_slices > 1) a slice of it, the slices' sums meeting at the counter of the tile's
             // first 16 tokens
             sg->has_big_units = true;
-            if (r.r8 > 128) sg->heavy_small_expand = true;
+            if (r.r8 > kBigExpandMaxRank) sg->heavy_small_expand = true;
             const int tile = heavy_tile(r.r8);
             for (int tok0 = 0; tok0 < r.ntok; tok0 += tile)
                 for (int ks = 0; ks < heavy_k_slices; ++ks) {
@@ -1130,7 +1134,7 @@ static lora_status_t plan_into(lora_segments *sg, const lora_pool *pool, const i
         // (16 per wavefront, v kept in registers) and a quarter (or an eighth) of the columns, at least 512
         int cols = expand_cols_per_unit(r.r8, out);
         int etile = lora::kTokTile;
-        if (token_heavy && r.r8 <= 128) {  // above rank 128 a strip's tile does not fit the kernel's LDS buffer
+        if (token_heavy && r.r8 <= kBigExpandMaxRank) {
             etile = 64;
             cols = std::min(out, std::max(512, (out / big_runs + 127) / 128 * 128));
         }
@@ -2113,7 +2117,7 @@ static lora_status_t run_apply(const uint16_t *arena, int in, int out, const lor
             return LORA_OK;
         }
         hipStream_t sd = s;
-        // not when a token-heavy group's v is read by 16-token expand units (groups above rank 128):
+        // not when a token-heavy group's v is read by 16-token expand units (groups above kBigExpandMaxRank):
         // those would sit on the side stream, which does not wait for the token-heavy shrink launch
         const bool split = opt_side_stream(sg) && sg->has_big_units && !sg->heavy_small_expand &&
                            cs.n_units >= kSideStreamMinUnits && (may_create || (sg->side && sg->fork && sg->join));

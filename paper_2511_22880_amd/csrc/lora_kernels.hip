@@ -512,17 +512,17 @@ __global__ __launch_bounds__(64 * WAVES, kWideWaves / WAVES) void k_shrink_wide(
 }
 
 // ------------------------------------------------------------------------------------------------
-// shrink of token-heavy groups (prefill): one unit = (group, 32 tokens (16 above rank 128), all rank
+// shrink of token-heavy groups (prefill) up to rank 64: one unit = (group, 32 tokens, all rank
 // rows, all of k).  The four wavefronts split k into quarters; each streams its quarter of the
 // tokens' x rows exactly once.  x comes from HBM with coalesced loads (a wavefront load covers 256
-// bytes of each of 4 tokens), one pass of 128 k ahead, and is turned into MFMA operand order through
+// bytes of each of 4 tokens), XD passes of 128 k ahead, and is turned into MFMA operand order through
 // an LDS region private to the wavefront, so no work-group barrier sits in the k loop.  (Loading the
 // token operand straight from memory, 16 rows x 64 bytes per load, costs the address path 3.7 times
 // as much per byte.)  The rows of A^T come from L2 (every token tile of the group re-reads them),
 // requested WD k steps ahead because a step of a low rank is far shorter than a round trip to L2,
 // and are shared by the TB token blocks in registers.  The four partial tiles are summed through
 // LDS (re-using the x regions) in a fixed order (3+1, 2+0, then 1+0) and v leaves complete: as bf16
-// hi + lo for the expand, or as fp32.  JB = 16-row blocks of A^T (1, 2, 4, 8, 16).
+// hi + lo for the expand, or as fp32.  JB = 16-row blocks of A^T (1, 2, 4).
 // ------------------------------------------------------------------------------------------------
 constexpr int kPfTokens = 32;
 constexpr int kPfPassK = 128;                 // k per pass of a wavefront
@@ -584,16 +584,15 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
     // blocks that always exist (with a branch per block the same loop ran 2.4 times slower).
     __builtin_assume(r8 <= 16 * JB && (JB == 1 ? r8 >= 8 : r8 > 8 * JB));
     const uint16_t *wbase = arena + u.w_off;
-    const uint4 zero = {0u, 0u, 0u, 0u};
     int woff[JB];  // element offset of this lane's 16-byte piece in k step 0 of row block jb
     int wh[JB];    // rows in block jb (16, or 8 for the last block of a padded rank that is 8 mod 16)
-    // Up to four row blocks the loop below has no branch: a block beyond the padded rank (ranks 33..48 of
-    // the bucket up to 64) is worked as a copy of the last block that exists, and its sums are never stored.
-    constexpr bool kNoBranch = JB <= 4;
+    // The loop below has no branch: a block beyond the padded rank (ranks 33..48 of the bucket up to 64) is
+    // worked as a copy of the last block that exists, and its sums are never stored.
+    static_assert(JB <= 4, "ranks above 64 take the row-split body");
     const int nblk = (r8 + 15) >> 4;
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) {
-        const int jbc = kNoBranch ? min(jb, nblk - 1) : jb;
+        const int jbc = min(jb, nblk - 1);
         const int h = min(16, r8 - 16 * jbc);
         wh[jb] = h > 0 ? h : 16;
         // lanes n >= 8 of an 8-row block read the piece of row n - 8: they only reach accumulator rows
@@ -617,16 +616,7 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
     const int kbeg = ks_beg + wave * kquarter;
     const int kend = min(ks_end, kbeg + kquarter);
 
-    // in is a multiple of 64, so a 16-byte chunk lies inside the row or wholly beyond it; a chunk
-    // beyond the row is fetched from the row's last chunk instead and never enters an MFMA
-    auto x_pass = [&](int k0, uint4(&xs)[NL]) __attribute__((always_inline)) {
-        const int kx = min(k0 + 8 * n, in - 8);
-#pragma unroll
-        for (int t = 0; t < NL; ++t)
-            if (4 * t < ntok) xs[t] = ld16_stream(xrow[t] + kx);
-    };
-
-    if constexpr (kNoBranch) {
+    {
         // Loads without conditions (rows of tokens beyond ntok are the last token's, see xrow; a chunk beyond
         // the row is fetched from the row's last chunk and a k step beyond the row from its last step; none
         // of them enters an MFMA whose sums are stored): with a branch around a load the compiler no
@@ -715,52 +705,6 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
             }
         }
         }
-    } else {
-    uint4 xs[NL], w[WD][JB];
-    if (kbeg < kend) x_pass(kbeg, xs);
-#pragma unroll
-    for (int d = 0; d < WD; ++d)
-#pragma unroll
-        for (int jb = 0; jb < JB; ++jb) {
-            w[d][jb] = zero;
-            if (16 * jb < r8 && kbeg + 32 * d < kend) w[d][jb] = ld16(wbase + woff[jb] + (int64_t)(kbeg + 32 * d) * wh[jb]);
-        }
-
-    for (int k0 = kbeg; k0 < kend; k0 += kPfPassK) {
-#pragma unroll
-        for (int t = 0; t < NL; ++t)
-            if (4 * t < ntok) *reinterpret_cast<uint4 *>(&slab[4 * t + kq][8 * n]) = xs[t];
-        if (k0 + kPfPassK < kend) x_pass(k0 + kPfPassK, xs);
-        // the region is private to this wavefront and LDS operations of a wavefront complete in order
-        __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        __builtin_amdgcn_wave_barrier();
-        __atomic_signal_fence(__ATOMIC_SEQ_CST);
-#pragma unroll
-        for (int d = 0; d < kPfPassK / 32; ++d) {
-            const int k = k0 + 32 * d;
-            if (k < kend) {
-                bf16x8 xo[TB];
-#pragma unroll
-                for (int tb = 0; tb < TB; ++tb)
-                    // rows of tokens beyond ntok hold a copy of the last token or whatever LDS held: they
-                    // only reach accumulator columns that are never stored
-                    xo[tb] = as_bf16x8(*reinterpret_cast<const uint4 *>(&slab[16 * tb + n][32 * d + 8 * kq]));
-#pragma unroll
-                for (int jb = 0; jb < JB; ++jb) {
-                    if (16 * jb < r8) {
-                        const bf16x8 ww = as_bf16x8(w[d % WD][jb]);
-#pragma unroll
-                        for (int tb = 0; tb < TB; ++tb)
-                            acc[jb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ww, xo[tb], acc[jb][tb], 0, 0, 0);
-                        if (k + 32 * WD < kend) w[d % WD][jb] = ld16(wbase + woff[jb] + (int64_t)(k + 32 * WD) * wh[jb]);
-                    }
-                }
-            }
-        }
-        __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        __builtin_amdgcn_wave_barrier();
-        __atomic_signal_fence(__ATOMIC_SEQ_CST);
-    }
     }
 
     // sum the four k-quarters: (wave 2 -> 0, wave 3 -> 1), then (wave 1 -> 0)
@@ -849,7 +793,7 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
     }
 }
 
-// Token-heavy units of ranks 65..128: 16 * TB tokens, all rank rows, all of k or a slice of it.  Here the
+// Token-heavy units above rank 64: 16 * TB tokens, all rank rows, all of k or a slice of it.  Here the
 // four wavefronts split the rank rows (JBW blocks of 16 each) instead of k: every 16-byte piece of
 // A^T is then loaded once per work group, straight into the registers of the one wavefront that owns
 // its rows, and x, which all four need, is staged once per work group in LDS (two buffers of 128 of k,
@@ -857,7 +801,10 @@ static __device__ __forceinline__ void shrink_prefill_ksplit(const Unit &u, cons
 // A^T for 32 tokens' worth of x: at rank 128 four times the bytes of x, which made the compute units'
 // vector caches, not memory, the bound (uniform rank 128 on cfg2's routing: 78 us against 35 us at
 // rank 8; 62 us with this body).  No sums cross wavefronts: each stores the rows of v it owns.  (Up to
-// rank 64 the k-split body of 32 tokens stayed as fast or faster: 50 us at uniform rank 64 either way.)
+// rank 64 the k-split body of 32 tokens stayed as fast or faster: 50 us at uniform rank 64 either way.
+// Ranks 129..192 take three row blocks per wavefront and 64 tokens, ranks 193..256 four and 32 tokens, the
+// accumulators of 64 not fitting the registers: against units of 16 tokens with k split, the shrink
+// launch at uniform rank 160 / 192 / 256 went from 105 / 121 / 156 us to 78 / 86 / 112.)
 template <int JBW, int TB, int PD, int WP>
 static __device__ __forceinline__ void shrink_prefill_rowsplit(const Unit &u, const int32_t *__restrict__ perm,
                                                                const uint16_t *__restrict__ arena,
@@ -1091,8 +1038,7 @@ static __device__ __forceinline__ void dma16_to_lds(const uint4 *gptr, const uin
 
 // Picks the body by the unit's rank rows.  ANY = false: the launch holds no unit above rank 64 and the
 // bodies fit 128 registers (four work groups per compute unit).  ANY = true: any rank (two work groups
-// per compute unit); ranks 65..128 take the row-split body with 64 tokens, units above rank 128 hold
-// 16 tokens.
+// per compute unit); ranks above 64 take the row-split body, with 64 tokens up to rank 192 and 32 above.
 template <bool ANY>
 static __device__ __forceinline__ void prefill_dispatch(const Unit &u, const int32_t *__restrict__ perm,
                                                         const uint16_t *__restrict__ arena,
@@ -1116,8 +1062,10 @@ static __device__ __forceinline__ void prefill_dispatch(const Unit &u, const int
     else if constexpr (ANY) {
         if (r8 <= 128)
             shrink_prefill_rowsplit<2, 4, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
-        else
-            shrink_prefill_ksplit<16, 1, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
+        else if (r8 <= 192)
+            shrink_prefill_rowsplit<3, 4, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
+        else  // 32 tokens: the 16 accumulator tiles of 64 tokens x 64 rank rows per wavefront do not fit the registers
+            shrink_prefill_rowsplit<4, 2, 2, 1>(u, perm, arena, x, ldx, in, v_hi, v_lo, v_f32, n_slices, slice_stride, lds, parts, sy);
     }
 }
 
@@ -1391,9 +1339,10 @@ static __device__ __forceinline__ void expand_big_body(const Unit &u, const int3
                                                        int64_t slice_stride, uint16_t *__restrict__ y,
                                                        int64_t ldy, char *lds, const Sync &sy)
 {
-    // the tile of one strip is 128 * r8 * 2 bytes <= 32 KiB up to rank 128: two buffers of 32 KiB
-    static_assert(KSTEPS <= 4, "token-heavy expand units exist up to rank 128");
-    constexpr bool DB = true;
+    // the tile of one strip is 128 * r8 * 2 bytes: <= 32 KiB up to rank 128, two buffers of 32 KiB; above,
+    // one buffer of 64 KiB, filled between two strips
+    static_assert(KSTEPS <= 8, "token-heavy expand units exist up to rank 256");
+    constexpr bool DB = KSTEPS <= 4;
     constexpr int WREG = 2 * KSTEPS;  // 16-byte pieces of a tile per thread (256 threads): 128*32*KSTEPS*2 / 4096
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -1552,8 +1501,10 @@ static __device__ __forceinline__ void expand_dispatch(const Unit &u, const int3
             expand_big_body<1, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
         else if (r8 <= 64)
             expand_big_body<2, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
-        else  // the planner makes such units only up to rank 128
+        else if (r8 <= 128)
             expand_big_body<4, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
+        else
+            expand_big_body<8, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);
     } else {
         if (r8 <= 32)
             expand_body<1, false, VF32>(u, perm, arena, v_in, n_slices, slice_stride, y, ldy, lds, sy);

@@ -250,11 +250,11 @@ def test_token_heavy_batches_small():
 @pytest.mark.parametrize("in_features", [2048, 3072, 4096])
 def test_token_heavy_groups_of_every_rank_bucket(in_features):
     """One token-heavy group per rank bucket of the token-tile shrink (ranks that are no multiple of
-    16 give an 8-row last block; 72..120 leave row blocks beyond the rank) at in_features of several
-    k passes per wavefront, groups whose last unit is short, decode tokens beside them; all rows
-    checked."""
-    ranks = (8, 3, 12, 16, 24, 32, 40, 56, 64, 72, 100, 120, 128, 1)
-    lens = (33, 47, 64, 32, 95, 130, 40, 70, 36, 50, 65, 100, 81, 37)
+    16 give an 8-row last block; 72..120, 136 and 200 leave row blocks beyond the rank; 64-token units
+    up to rank 192, 32-token units above) at in_features of several k passes per wavefront, groups
+    whose last unit is short, decode tokens beside them; all rows checked."""
+    ranks = (8, 3, 12, 16, 24, 32, 40, 56, 64, 72, 100, 120, 128, 1, 136, 192, 200, 256, 161)
+    lens = (33, 47, 64, 32, 95, 130, 40, 70, 36, 50, 65, 100, 81, 37, 70, 129, 45, 97, 64)
     b0 = wl.small_mixed(seed=in_features, in_features=in_features, out_features=256, n_adapters=len(ranks),
                         ranks=ranks, decode_tokens=240, prefill_lens=())
     ta = np.concatenate([np.full(n, a, dtype=np.int32) for a, n in enumerate(lens)] + [b0.token_adapter])

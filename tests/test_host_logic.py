@@ -555,6 +555,39 @@ def test_token_heavy_shrink_units_of_an_adapter_share_an_xcd_at_equal_cost():
     L.lora_pool_destroy(pool)
 
 
+def test_token_heavy_units_above_rank_128():
+    """Token-heavy groups above rank 128 are cut like the others: shrink units of 64 tokens up to rank 192
+    and of 32 above, all rank rows each; expand units of up to 64 tokens (none of 16)."""
+    ranks = np.array([160, 192, 256, 200, 8], dtype=np.int32)
+    lens = [300, 260, 250, 130, 200]
+    ta = np.concatenate([np.full(n, a, dtype=np.int32) for a, n in enumerate(lens)])
+    pool = L.lora_pool_create(4096, 1024, ranks, (2.0 / ranks).astype(np.float32), FAKE_ARENA,
+                              L.lora_pool_bytes(4096, 1024, ranks, (2.0 / ranks).astype(np.float32)))
+    for a in range(len(ranks)):
+        L.lora_pool_mark_resident(pool, a)
+    seg = L.lora_segments_plan(pool, ta)
+    ex = L.lora_segments_export(seg)
+    units = L.lora_segments_export_units(seg)
+    su = units["shrink"][units["shrink"][:, 0] >= 0]
+    eu = units["expand"]
+    rank_of = ranks[ex["seg_adapter"]]
+    for g, r in enumerate(rank_of):
+        n = lens[int(ex["seg_adapter"][g])]
+        mine = su[su[:, 0] == g]
+        tile = 32 if (r <= 64 or r > 192) else 64
+        assert np.all(mine[:, 4] == (r + 7) // 8 * 8), (r, mine)
+        slices = len(np.unique(mine[:, 5]))                   # a launch of few such units cuts each along k
+        first = mine[mine[:, 5] == 0]
+        assert len(mine) == slices * len(first)
+        assert sorted(first[:, 1]) == list(range(0, n, tile)) and first[:, 2].sum() == n
+        e = eu[eu[:, 0] == g]
+        assert e[:, 2].max() > 16 and np.all(e[:, 2] <= 64)
+        cols = np.unique(e[:, 3])
+        assert sum(e[e[:, 3] == c][:, 2].sum() for c in cols) == n * len(cols)
+    L.lora_segments_destroy(seg)
+    L.lora_pool_destroy(pool)
+
+
 def test_one_launch_decode_plan_keeps_every_tile_on_one_xcd():
     """The one-launch decode form hands v over through the L2 of one XCD, and work group b of a launch
     runs on the XCD of b mod 8: all units of a (group, token tile) sit at places of one residue mod 8.
