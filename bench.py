@@ -503,9 +503,23 @@ def run_wg_clocks(args, torch, L, wl, dev, stream) -> int:
             if name == "shrink launch" and (clk[sel, 1] > 0).any() and (clk[sel, 1] < 10 ** 7).all():
                 # token tiles above rank 32: of the duration, the part between the top of a pass and its barrier's exit
                 rows[-1]["median_wait_for_x_us"] = float(np.median(clk[sel, 1]) * 0.01)
-    print(json.dumps({"workload": description, "tokens": T, "single_launch": bool(info["single_launch"]),
-                      "clock": "wall clock of the device, 100 MHz; microseconds from the first work group's entry",
-                      "per_class": rows}))
+    out = {"workload": description, "tokens": T, "single_launch": bool(info["single_launch"]),
+           "clock": "wall clock of the device, 100 MHz; microseconds from the first work group's entry",
+           "per_class": rows}
+    if info["single_launch"]:
+        # the one-launch decode kernel also records where a work group stands inside its two halves
+        n = info["launch_work_groups"]
+        t0 = h[:n, 0][h[:n, 0] > 0].min()
+        points = {}
+        for slot, name in ((0, "entry"), (1, "shrink loop done (wavefront 0)"), (7, "v stored (behind the work group's barrier)"),
+                           (2, "stores of v acknowledged, counter bumped"), (3, "tile's v seen by the expand unit"), (4, "end")):
+            v = h[:n, slot]
+            v = v[v > 0]
+            if len(v):
+                points[name] = {k: round(float(q), 2) for k, q in
+                                zip(("p10", "median", "p90", "last"), (np.percentile(v, [10, 50, 90, 100]) - t0) * 0.01)}
+        out["points_us"] = points
+    print(json.dumps(out))
     return 0
 
 
